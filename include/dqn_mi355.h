@@ -1,0 +1,198 @@
+/*
+ * dqn_mi355.h -- C boundary of the MI355X (gfx950) DQN hot-path library.
+ *
+ * The calls follow the problem statement of "Human-Level Control without Server-Grade Hardware"
+ * (Daley & Amato): Section 2.1 (Q-network, Eq. 1, replay memory D, target network, epsilon-greedy),
+ * Section 3 (Concurrent Training: actions from the target parameters, experiences buffered until
+ * the synchronisation point), Section 4 (Synchronized Execution: one minibatch of W states per act
+ * step), Algorithm 1 (flush + target update every C timesteps), Appendix B / Table 5 (RMSProp
+ * constants, gamma, minibatch size).
+ *
+ * Conventions
+ *   - Every pointer is a DEVICE pointer unless its name starts with host_.  The caller owns every
+ *     buffer it passes in; the library owns what lives inside the opaque handles.
+ *   - Streams are hipStream_t values passed as void*.  Calls only ENQUEUE work on their stream and
+ *     return; they do not synchronise with the host, except dqn_get_params, dqn_get_train_q,
+ *     dqn_set_params, and dqn_sync_target / replay_flush with blocking != 0.
+ *   - Every call returns DQN_OK or a negative code, never throws, aborts or prints;
+ *     dqn_last_error() returns a thread-local message for the last failing call.  Arguments are
+ *     validated on the host before anything is launched; a failing call launches nothing.
+ *   - Image tensors are uint8 [n, 4, 84, 84] (stacked states) or [n, 84, 84] (single frames),
+ *     densely packed, 16-byte aligned.
+ *   - Parameter blobs are flat float32 in this order and layout:
+ *       conv1.w [32,4,8,8], conv1.b [32], conv2.w [64,32,4,4], conv2.b [64], conv3.w [64,64,3,3],
+ *       conv3.b [64], fc1.w [512,3136] (input index = c*49 + h*7 + w), fc1.b [512],
+ *       fc2.w [A,512], fc2.b [A].
+ */
+#ifndef DQN_MI355_H
+#define DQN_MI355_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#pragma GCC visibility push(default)
+#endif
+
+enum { DQN_OK = 0, DQN_EINVAL = -1, DQN_EHIP = -2, DQN_ENOMEM = -3, DQN_ESTATE = -4 };
+
+enum { DQN_PRECISION_FP32 = 0, DQN_PRECISION_BF16 = 1 };
+
+/* dqn_get_params / dqn_set_params selector */
+enum {
+    DQN_PARAMS_ONLINE = 0,   /* theta                                   */
+    DQN_PARAMS_TARGET = 1,   /* theta^-                                 */
+    DQN_PARAMS_RMS_V = 2,    /* RMSProp second-moment accumulator       */
+    DQN_PARAMS_RMS_M = 3,    /* RMSProp first-moment accumulator        */
+    DQN_PARAMS_GRAD = 4      /* gradient of the last train step (get only) */
+};
+
+typedef struct dqn_ctx dqn_ctx;
+typedef struct replay replay;
+
+typedef struct {
+    int32_t num_actions;   /* A, 1..64 (the paper's games use 4..18)                              */
+    int32_t max_batch;     /* largest minibatch dqn_train_step will see (Table 5: 32)              */
+    int32_t max_envs;      /* largest W dqn_act will see (Section 4)                              */
+    int32_t precision;     /* DQN_PRECISION_FP32: fp32 operands on fp32 MFMA;
+                              DQN_PRECISION_BF16: bf16 operands on bf16 MFMA, fp32 accumulation,
+                              fp32 master parameters and optimiser state                           */
+    int32_t double_dqn;    /* 0: Eq. 1 (max over theta^-); 1: argmax from theta, value from theta^- */
+    int32_t centered;      /* 1: centered RMSProp (Appendix B); 0: plain RMSProp                   */
+    float gamma;           /* discount, Table 5: 0.99                                              */
+    float huber_delta;     /* error-clipping threshold of the adopted setup: 1                     */
+    float lr;              /* Appendix B: 2.5e-4                                                   */
+    float rms_alpha;       /* Appendix B: 0.95 for both moments                                    */
+    float rms_eps;         /* Appendix B: 0.01, added to the denominator outside the square root   */
+    uint64_t seed;         /* key of the counter-based generator used by the epsilon-greedy draws  */
+} dqn_config;
+
+/* ---- lifetime ------------------------------------------------------------------------------- */
+
+/* Creates a context on the current device.  Parameters start at zero; load them with
+ * dqn_set_params.  act_stream carries dqn_act, train_stream carries dqn_train_step (Section 3:
+ * the two run concurrently between synchronisation points).  Errors: DQN_EINVAL (bad config,
+ * null pointer), DQN_ENOMEM, DQN_EHIP. */
+int dqn_create(const dqn_config* host_cfg, void* act_stream, void* train_stream, dqn_ctx** host_out);
+int dqn_destroy(dqn_ctx* ctx);
+
+size_t dqn_num_params(const dqn_ctx* ctx);
+
+/* Copies a float32 blob (layout above) from / to host memory.  n must equal dqn_num_params().
+ * Both wait for the context's two streams first.  Setting DQN_PARAMS_ONLINE or DQN_PARAMS_TARGET
+ * also refreshes that network's low-precision operand copy.  DQN_PARAMS_GRAD cannot be set. */
+int dqn_set_params(dqn_ctx* ctx, int which, const float* host_src, size_t n);
+int dqn_get_params(dqn_ctx* ctx, int which, float* host_dst, size_t n);
+
+/* ---- act step (Sections 3 and 4, Algorithm 1's batched Q evaluation) --------------------- */
+
+/* Evaluates Q(s^(j), .) for the W states in one minibatch and picks one action per environment:
+ * with probability epsilon a uniformly random action, otherwise argmax_a Q (lowest index on
+ * ties).  Environment j at call counter act_step uses the Philox4x32-10 outputs (x0, x1, ..) for
+ * key = (seed lo, seed hi), counter = (j, 1, act_step lo, act_step hi): it explores iff
+ * float(x0 >> 8) * 2^-24 < epsilon (float32 compare), and the random action is (x1 * A) >> 32.
+ *   states   [W,4,84,84] uint8, scaled by 1/255 inside.
+ *   use_target  1: parameters theta^- (Concurrent Training, Section 3); 0: theta (standard DQN);
+ *               with 0 the call first waits, on the device, for the last enqueued train step.
+ *   actions  [W] int32 out.   q_out  [W,A] float32 out, or NULL.
+ * Runs on act_stream.  Errors: DQN_EINVAL (W < 1, W > max_envs, null/misaligned pointer,
+ * epsilon outside [0,1]). */
+int dqn_act(dqn_ctx* ctx, const uint8_t* states, int32_t W, float epsilon, uint64_t act_step,
+            int32_t use_target, int32_t* actions, float* q_out);
+
+/* ---- minibatch train step (Section 2.1, Eq. 1; Appendix B) -------------------------------- */
+
+/* One gradient update of theta on a minibatch of B transitions:
+ *   y_b = r_b + gamma (1 - done_b) max_a' Q(s2_b, a'; theta^-)        (double_dqn: Q(s2_b, a*; theta^-),
+ *                                                                        a* = argmax_a Q(s2_b, a; theta))
+ *   delta_b = Q(s_b, a_b; theta) - y_b;  loss = mean_b huber(delta_b);  no gradient through y
+ *   theta <- RMSProp(theta, dloss/dtheta).   theta^- is not touched.
+ *   s, s2 [B,4,84,84] uint8;  a [B] int32 in [0,A);  r, done [B] float32 (done is 0 or 1);
+ *   loss_out: device float32 scalar, or NULL.
+ * Runs on train_stream.  Errors: DQN_EINVAL (B < 1, B > max_batch, null/misaligned pointer). */
+int dqn_train_step(dqn_ctx* ctx, const uint8_t* s, const int32_t* a, const float* r,
+                   const uint8_t* s2, const float* done, int32_t B, float* loss_out);
+
+/* Q rows computed inside the last dqn_train_step, copied to host memory after waiting for
+ * train_stream: host_q_online [B,A] = Q(s,.;theta) (before the update), host_q_next_target [B,A] =
+ * Q(s2,.;theta^-), host_q_next_online [B,A] = Q(s2,.;theta) (double_dqn only, else untouched).
+ * Any pointer may be NULL.  Errors: DQN_ESTATE if no train step has run. */
+int dqn_get_train_q(dqn_ctx* ctx, float* host_q_online, float* host_q_next_target,
+                    float* host_q_next_online);
+
+/* ---- synchronisation point (Algorithm 1: wait, flush, theta^- <- theta) ------------------- */
+
+/* On the device: train_stream waits for everything enqueued on act_stream (and on rb's push
+ * stream), then rb's staged experiences are flushed into D (if rb != NULL), then theta^- <- theta
+ * (bitwise, plus the operand copy); act_stream (and rb's push stream) then wait for that.
+ * blocking != 0 additionally waits on the host.  Must not be called concurrently with another
+ * call on the same ctx / rb. */
+int dqn_sync_target(dqn_ctx* ctx, replay* rb, int32_t blocking);
+
+/* ---- replay memory D (Section 2.1; buffering of Section 3) -------------------------------- */
+
+/* D holds capacity_frames single frames with (action, reward, terminal) each, split into `lanes`
+ * equal rings (one per sampler; capacity_frames % lanes == 0, 1 <= lanes <= 64).  A terminal flag
+ * means the episode ended after that frame's action.  staging_per_lane (1..capacity_frames/lanes)
+ * is the number of experiences a lane can buffer between two flushes.  push_stream carries
+ * replay_push, sample_stream carries replay_sample_gather and the flush.  seed keys the sampling
+ * generator. */
+int replay_create(int64_t capacity_frames, int32_t lanes, int64_t staging_per_lane, uint64_t seed,
+                  void* push_stream, void* sample_stream, replay** host_out);
+int replay_destroy(replay* rb);
+
+/* Appends n experiences of one lane to that lane's temporary buffer; they stay invisible to
+ * sampling until the next flush (Section 3).  frames [n,84,84] uint8; actions [n] int32;
+ * rewards [n] float32; terminals [n] uint8.  Errors: DQN_EINVAL (lane out of range, n < 0,
+ * null/misaligned pointer), DQN_ESTATE (temporary buffer would overflow). */
+int replay_push(replay* rb, int32_t lane, const uint8_t* frames, const int32_t* actions,
+                const float* rewards, const uint8_t* terminals, int32_t n);
+
+/* Moves every lane's buffered experiences into D in push order, overwriting the oldest. */
+int replay_flush(replay* rb, int32_t blocking);
+
+/* Number of transitions that can currently be sampled (host-side bookkeeping, no device work). */
+int64_t replay_num_valid(const replay* rb);
+
+/* Draws B transitions uniformly with replacement (or takes them from idx_in) and assembles the
+ * minibatch.  Indexing: within lane l the visible frames are numbered by age j = 0 (oldest) ..
+ * count_l - 1; the global index of a transition is l * (capacity_frames / lanes) + j, valid iff
+ * 3 <= j <= count_l - 2.  Draw i at counter sample_step uses the Philox4x32-10 outputs for
+ * key = (seed lo, seed hi), counter = (i, 2, sample_step lo, sample_step hi):
+ * k = ((x1:x0) * V) >> 64 with V the number of valid transitions, lanes walked in order.
+ *   s  [B,4,84,84]: frames of ages j-3..j;  s2: ages j-2..j+1;  a stacked frame is all zeros if a
+ *   terminal flag lies between it (inclusive) and the stack's newest frame (exclusive).
+ *   a [B] int32, r [B] float32, done [B] float32 (0/1) of the frame at age j.
+ *   idx_in [B] int64 or NULL;  idx_out [B] int64 or NULL.
+ * Runs on sample_stream.  Errors: DQN_EINVAL (B < 1, null/misaligned pointer), DQN_ESTATE (no
+ * valid transition).  Indices passed through idx_in are range-checked on the device: an invalid
+ * one yields all-zero stacks and a = -1 for that row instead of an out-of-range read. */
+int replay_sample_gather(replay* rb, int32_t B, uint64_t sample_step, const int64_t* idx_in,
+                         uint8_t* s, uint8_t* s2, int32_t* a, float* r, float* done,
+                         int64_t* idx_out);
+
+/* ---- seeded synthetic inputs (benchmark support; stands in for emulator output) ----------- */
+
+/* Frame i of the call gets id = id0 + i * id_step and is written to dst[i] ([n,84,84] uint8):
+ * with mix64 the SplitMix64 output function, GAMMA = 0x9E3779B97F4A7C15 and
+ * word(id, g) = mix64(mix64(mix64(seed + GAMMA*(stream_tag+1)) + id) + GAMMA*(g+1)), pixel p takes
+ * w32 = 32-bit half (p & 1) of word(id, p >> 1) and is (w32 & 255) if (w32 >> 8) < pix_threshold,
+ * else `background`. */
+int synth_frames(uint8_t* dst, int64_t n, uint64_t id0, uint64_t id_step, uint64_t seed,
+                 uint32_t stream_tag, uint32_t pix_threshold, uint32_t background, void* stream);
+
+/* Transition i (id as above): w = word(id, 0) with stream_tag 1;  rb = w & 0xFFFFFF,
+ * tb = (w >> 24) & 0xFFFFFF, ab = w >> 48;  reward = -1 if rb < t_neg, +1 if rb >= 2^24 - t_pos,
+ * else 0;  terminal = tb < t_term;  action = (ab * num_actions) >> 16. */
+int synth_transitions(int32_t* actions, float* rewards, uint8_t* terminals, int64_t n,
+                      uint64_t id0, uint64_t id_step, uint64_t seed, int32_t num_actions,
+                      uint32_t t_neg, uint32_t t_pos, uint32_t t_term, void* stream);
+
+const char* dqn_last_error(void);
+
+#ifdef __cplusplus
+#pragma GCC visibility pop
+}
+#endif
+#endif /* DQN_MI355_H */

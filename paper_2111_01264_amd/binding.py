@@ -1,0 +1,188 @@
+"""ctypes binding of libdqn_mi355.so: argument marshalling only.
+
+Every function has the name and argument order of its C declaration in include/dqn_mi355.h.
+Device buffers are torch tensors (their data_ptr() is passed), streams are torch.cuda.Stream
+objects (their cuda_stream handle is passed) or None for the default stream.  A non-zero return
+code raises DqnError with the library's message.  There is no fallback: if the shared library is
+missing, importing this module fails.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+import torch  # noqa: F401  -- imported first on purpose: the library must bind to the HIP runtime
+              # that PyTorch has loaded, so that tensors, streams and kernels share one runtime
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libdqn_mi355.so")
+
+DQN_OK, DQN_EINVAL, DQN_EHIP, DQN_ENOMEM, DQN_ESTATE = 0, -1, -2, -3, -4
+DQN_PRECISION_FP32, DQN_PRECISION_BF16 = 0, 1
+DQN_PARAMS_ONLINE, DQN_PARAMS_TARGET, DQN_PARAMS_RMS_V, DQN_PARAMS_RMS_M, DQN_PARAMS_GRAD = range(5)
+
+
+class DqnError(RuntimeError):
+    def __init__(self, code, message):
+        super().__init__("dqn_mi355 error %d: %s" % (code, message))
+        self.code = code
+
+
+class dqn_config(C.Structure):
+    _fields_ = [
+        ("num_actions", C.c_int32), ("max_batch", C.c_int32), ("max_envs", C.c_int32),
+        ("precision", C.c_int32), ("double_dqn", C.c_int32), ("centered", C.c_int32),
+        ("gamma", C.c_float), ("huber_delta", C.c_float), ("lr", C.c_float),
+        ("rms_alpha", C.c_float), ("rms_eps", C.c_float), ("seed", C.c_uint64),
+    ]
+
+
+EXPORTS = {
+    "dqn_create": (C.c_int, [C.POINTER(dqn_config), C.c_void_p, C.c_void_p, C.POINTER(C.c_void_p)]),
+    "dqn_destroy": (C.c_int, [C.c_void_p]),
+    "dqn_num_params": (C.c_size_t, [C.c_void_p]),
+    "dqn_set_params": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_size_t]),
+    "dqn_get_params": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_size_t]),
+    "dqn_act": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_float, C.c_uint64, C.c_int32,
+                          C.c_void_p, C.c_void_p]),
+    "dqn_train_step": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                 C.c_void_p, C.c_int32, C.c_void_p]),
+    "dqn_get_train_q": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
+    "dqn_sync_target": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32]),
+    "replay_create": (C.c_int, [C.c_int64, C.c_int32, C.c_int64, C.c_uint64, C.c_void_p, C.c_void_p,
+                                C.POINTER(C.c_void_p)]),
+    "replay_destroy": (C.c_int, [C.c_void_p]),
+    "replay_push": (C.c_int, [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                              C.c_int32]),
+    "replay_flush": (C.c_int, [C.c_void_p, C.c_int32]),
+    "replay_num_valid": (C.c_int64, [C.c_void_p]),
+    "replay_sample_gather": (C.c_int, [C.c_void_p, C.c_int32, C.c_uint64, C.c_void_p, C.c_void_p,
+                                       C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
+    "synth_frames": (C.c_int, [C.c_void_p, C.c_int64, C.c_uint64, C.c_uint64, C.c_uint64, C.c_uint32,
+                               C.c_uint32, C.c_uint32, C.c_void_p]),
+    "synth_transitions": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_uint64,
+                                    C.c_uint64, C.c_uint64, C.c_int32, C.c_uint32, C.c_uint32,
+                                    C.c_uint32, C.c_void_p]),
+    "dqn_last_error": (C.c_char_p, []),
+}
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError("%s is missing: build it with `python -m paper_2111_01264_amd.build` "
+                      "(there is no CPU fallback)" % LIB_PATH)
+_lib = C.CDLL(LIB_PATH)
+for _name, (_res, _args) in EXPORTS.items():
+    _fn = getattr(_lib, _name)
+    _fn.restype = _res
+    _fn.argtypes = _args
+
+
+def _check(rc):
+    if rc != DQN_OK:
+        raise DqnError(rc, _lib.dqn_last_error().decode())
+
+
+def _ptr(t):
+    """torch tensor (device) -> address, None -> NULL."""
+    if t is None:
+        return None
+    assert t.is_contiguous(), "tensors handed to the library must be contiguous"
+    return t.data_ptr()
+
+
+def _stream(s):
+    return None if s is None else s.cuda_stream
+
+
+def _host(a, dtype):
+    a = np.ascontiguousarray(a, dtype=dtype)
+    return a, a.ctypes.data
+
+
+def dqn_last_error():
+    return _lib.dqn_last_error().decode()
+
+
+def dqn_create(cfg: dqn_config, act_stream, train_stream):
+    out = C.c_void_p()
+    _check(_lib.dqn_create(C.byref(cfg), _stream(act_stream), _stream(train_stream), C.byref(out)))
+    return out
+
+
+def dqn_destroy(ctx):
+    _check(_lib.dqn_destroy(ctx))
+
+
+def dqn_num_params(ctx):
+    return int(_lib.dqn_num_params(ctx))
+
+
+def dqn_set_params(ctx, which, host_src):
+    a, p = _host(host_src, np.float32)
+    _check(_lib.dqn_set_params(ctx, which, p, a.size))
+
+
+def dqn_get_params(ctx, which):
+    out = np.empty(dqn_num_params(ctx), dtype=np.float32)
+    _check(_lib.dqn_get_params(ctx, which, out.ctypes.data, out.size))
+    return out
+
+
+def dqn_act(ctx, states, W, epsilon, act_step, use_target, actions, q_out=None):
+    _check(_lib.dqn_act(ctx, _ptr(states), W, epsilon, act_step, use_target, _ptr(actions), _ptr(q_out)))
+
+
+def dqn_train_step(ctx, s, a, r, s2, done, B, loss_out=None):
+    _check(_lib.dqn_train_step(ctx, _ptr(s), _ptr(a), _ptr(r), _ptr(s2), _ptr(done), B, _ptr(loss_out)))
+
+
+def dqn_get_train_q(ctx, B, A, double_dqn=False):
+    q_on = np.empty((B, A), dtype=np.float32)
+    q_nt = np.empty((B, A), dtype=np.float32)
+    q_no = np.empty((B, A), dtype=np.float32) if double_dqn else None
+    _check(_lib.dqn_get_train_q(ctx, q_on.ctypes.data, q_nt.ctypes.data,
+                                q_no.ctypes.data if double_dqn else None))
+    return q_on, q_nt, q_no
+
+
+def dqn_sync_target(ctx, rb, blocking):
+    _check(_lib.dqn_sync_target(ctx, rb, blocking))
+
+
+def replay_create(capacity_frames, lanes, staging_per_lane, seed, push_stream, sample_stream):
+    out = C.c_void_p()
+    _check(_lib.replay_create(capacity_frames, lanes, staging_per_lane, seed, _stream(push_stream),
+                              _stream(sample_stream), C.byref(out)))
+    return out
+
+
+def replay_destroy(rb):
+    _check(_lib.replay_destroy(rb))
+
+
+def replay_push(rb, lane, frames, actions, rewards, terminals, n):
+    _check(_lib.replay_push(rb, lane, _ptr(frames), _ptr(actions), _ptr(rewards), _ptr(terminals), n))
+
+
+def replay_flush(rb, blocking):
+    _check(_lib.replay_flush(rb, blocking))
+
+
+def replay_num_valid(rb):
+    return int(_lib.replay_num_valid(rb))
+
+
+def replay_sample_gather(rb, B, sample_step, idx_in, s, s2, a, r, done, idx_out=None):
+    _check(_lib.replay_sample_gather(rb, B, sample_step, _ptr(idx_in), _ptr(s), _ptr(s2), _ptr(a),
+                                     _ptr(r), _ptr(done), _ptr(idx_out)))
+
+
+def synth_frames(dst, n, id0, id_step, seed, stream_tag, pix_threshold, background, stream):
+    _check(_lib.synth_frames(_ptr(dst), n, id0, id_step, seed, stream_tag, pix_threshold, background,
+                             _stream(stream)))
+
+
+def synth_transitions(actions, rewards, terminals, n, id0, id_step, seed, num_actions, t_neg, t_pos,
+                      t_term, stream):
+    _check(_lib.synth_transitions(_ptr(actions), _ptr(rewards), _ptr(terminals), n, id0, id_step, seed,
+                                  num_actions, t_neg, t_pos, t_term, _stream(stream)))
