@@ -1,0 +1,331 @@
+#!/usr/bin/env python3
+"""Throughput of the DQN hot path on one MI355X: train steps/sec (batch 32) with the act steps
+that belong to them running concurrently on a second stream, on seeded synthetic data shaped like
+the paper's workload (Table 5: replay of 1,000,000 frames, minibatch 32, C = 10,000; Section 5.1:
+W = 8 samplers, epsilon = 0.1).
+
+One "step" = 4 act steps (W states each: Q evaluation, epsilon-greedy, push of W experiences) on the
+act stream + one replay sample/gather and one train step on the train stream; every `sync_every`
+train steps the synchronisation point of Algorithm 1 (flush, theta^- <- theta).
+
+Prints ONE JSON line.  `--sweep` instead prints the batch/W sweep table (bf16 MFMA utilisation per
+kernel and gather bandwidth) as plain text.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK = {"hbm": (8000.0, "GB/s"), "bf16": (2500.0, "TFLOP/s"), "f32": (157.3, "TFLOP/s")}
+N_PARAMS_BASE = 1684128
+
+
+def kernel_work(name, B, A, groups, precision):
+    """Algorithmic (flops, bytes) of one launch of a train-step kernel.  GEMM flops are
+    2*M*N*K of the layer; bytes are what the method must move for that layer (operands once)."""
+    e = 2 if precision == "bf16" else 4
+    n_par = N_PARAMS_BASE + 513 * A
+    G = groups
+    t = {
+        "conv1_fwd": (2.0 * G * B * 400 * 32 * 256, G * B * (28224 + 12800 * e)),
+        "conv2_fwd": (2.0 * G * B * 81 * 64 * 512, G * B * (12800 + 5184) * e),
+        "conv3_fwd": (2.0 * G * B * 49 * 64 * 576, G * B * (5184 + 3136) * e),
+        "fc1_fwd": (2.0 * G * B * 512 * 3136, G * (B * (3136 + 512) * e) + min(G, 2) * 512 * 3136 * e),
+        "fc2_td": (2.0 * G * B * A * 512, G * B * 512 * e),
+        "td_head_bwd": (2.0 * B * 512 * 2, B * 512 * e * 2 + A * 512 * 4),
+        "fc1_wgrad": (2.0 * 512 * 3136 * B, 512 * 3136 * 4 + B * (3136 + 512) * e),
+        "fc1_dgrad": (2.0 * B * 3136 * 512, 512 * 3136 * e + B * (3136 * 2 + 512) * e),
+        "conv3_wgrad": (2.0 * 64 * 576 * B * 49, B * (5184 + 3136) * e + 64 * 576 * 4),
+        "conv3_dgrad": (2.0 * B * 81 * 64 * 576, B * (3136 + 2 * 5184) * e),
+        "conv2_wgrad": (2.0 * 64 * 512 * B * 81, B * (12800 + 5184) * e + 64 * 512 * 4),
+        "conv2_dgrad": (2.0 * B * 400 * 32 * 256, B * (5184 + 2 * 12800) * e),
+        "conv1_wgrad": (2.0 * 32 * 256 * B * 400, B * (28224 + 12800 * e) + 32 * 256 * 4),
+        "bias_grad": (1.0 * B * (12800 + 5184 + 3136 + 512), B * (12800 + 5184 + 3136 + 512) * e),
+        "rmsprop": (10.0 * n_par, n_par * (28 + (2 if precision == "bf16" else 0))),
+    }
+    return t[name]
+
+
+def roofline_for(name, avg_ms, B, A, groups, precision):
+    flops, nbytes = kernel_work(name, B, A, groups, precision)
+    peak_f = PEAK["bf16" if precision == "bf16" else "f32"][0]
+    ridge = peak_f * 1e12 / (PEAK["hbm"][0] * 1e9)
+    sec = avg_ms * 1e-3
+    if flops / max(nbytes, 1) >= ridge * 0.25 and name not in ("rmsprop", "bias_grad", "td_head_bwd", "fc2_td"):
+        ach = flops / sec / 1e12
+        return {"kernel": name, "bound": "mfma", "achieved": ach, "peak": peak_f, "unit": "TFLOP/s",
+                "frac": ach / peak_f, "traffic": None, "avg_launch_us": avg_ms * 1e3}
+    ach = nbytes / sec / 1e9
+    return {"kernel": name, "bound": "hbm", "achieved": ach, "peak": PEAK["hbm"][0], "unit": "GB/s",
+            "frac": ach / PEAK["hbm"][0], "traffic": None, "avg_launch_us": avg_ms * 1e3}
+
+
+class Workload:
+    """Device-resident state of one benchmark configuration."""
+
+    def __init__(self, args):
+        import torch
+        import paper_2111_01264_amd as P
+        from datagen import synth
+        self.torch, self.P, self.synth = torch, P, synth
+        self.A, self.B, self.W = args.actions, args.batch, args.envs
+        self.lanes = args.lanes
+        self.seed = args.seed
+        self.precision = args.precision
+        self.acts_per_train = args.acts_per_train
+        self.sync_every = args.sync_every
+        self.double = int(args.double_dqn)
+        torch.cuda.set_device(0)
+        self.act_stream, self.train_stream = torch.cuda.Stream(), torch.cuda.Stream()
+        cfg = P.dqn_config()
+        cfg.num_actions, cfg.max_batch, cfg.max_envs = self.A, self.B, self.W
+        cfg.precision = P.DQN_PRECISION_BF16 if args.precision == "bf16" else P.DQN_PRECISION_FP32
+        cfg.double_dqn, cfg.centered = self.double, 1
+        cfg.gamma, cfg.huber_delta, cfg.lr, cfg.rms_alpha, cfg.rms_eps = 0.99, 1.0, 2.5e-4, 0.95, 0.01
+        cfg.seed = self.seed
+        self.ctx = P.dqn_create(cfg, self.act_stream, self.train_stream)
+        theta = synth.init_params(self.seed, self.A)
+        P.dqn_set_params(self.ctx, P.DQN_PARAMS_ONLINE, theta)
+        P.dqn_set_params(self.ctx, P.DQN_PARAMS_TARGET, theta)
+        per_lane = args.frames // self.lanes
+        staging = min(per_lane, max(self.acts_per_train * self.sync_every, 5000))
+        self.rb = P.replay_create(args.frames, self.lanes, staging, self.seed, self.act_stream, self.train_stream)
+        self._fill(per_lane, args)
+        # pools of act-step inputs: states, the new frame each sampler produced, reward, terminal
+        pool = 16
+        self.pool = pool
+        dev = "cuda"
+        self.states = torch.empty((pool, self.W, 4, 84, 84), dtype=torch.uint8, device=dev)
+        P.synth_frames(self.states, pool * self.W * 4, 0, 1, self.seed, synth.STREAM_ACT, synth.PIX_T,
+                       synth.BACKGROUND, None)
+        self.new_frames = torch.empty((pool, self.lanes, 84, 84), dtype=torch.uint8, device=dev)
+        P.synth_frames(self.new_frames, pool * self.lanes, 1 << 40, 1, self.seed, synth.STREAM_ACT, synth.PIX_T,
+                       synth.BACKGROUND, None)
+        self.rew = torch.empty((pool, self.lanes), dtype=torch.float32, device=dev)
+        self.term = torch.empty((pool, self.lanes), dtype=torch.uint8, device=dev)
+        scratch_a = torch.empty((pool, self.lanes), dtype=torch.int32, device=dev)
+        tn, tp, tt = synth.thresholds(args.p_reward, args.p_reward, args.p_term)
+        P.synth_transitions(scratch_a, self.rew, self.term, pool * self.lanes, 1 << 41, 1, self.seed, self.A, tn, tp,
+                            tt, None)
+        self.actions = torch.zeros(max(self.W, self.lanes), dtype=torch.int32, device=dev)
+        self.s = torch.empty((self.B, 4, 84, 84), dtype=torch.uint8, device=dev)
+        self.s2 = torch.empty_like(self.s)
+        self.a = torch.empty(self.B, dtype=torch.int32, device=dev)
+        self.r = torch.empty(self.B, dtype=torch.float32, device=dev)
+        self.d = torch.empty(self.B, dtype=torch.float32, device=dev)
+        self.loss = torch.zeros(1, dtype=torch.float32, device=dev)
+        torch.cuda.synchronize()
+        self.train_steps = 0
+        self.act_steps = 0
+
+    def _fill(self, per_lane, args):
+        torch, P, synth = self.torch, self.P, self.synth
+        chunk = min(5000, per_lane)
+        buf = torch.empty((chunk, 84, 84), dtype=torch.uint8, device="cuda")
+        a = torch.empty(chunk, dtype=torch.int32, device="cuda")
+        r = torch.empty(chunk, dtype=torch.float32, device="cuda")
+        t = torch.empty(chunk, dtype=torch.uint8, device="cuda")
+        tn, tp, tt = synth.thresholds(args.p_reward, args.p_reward, args.p_term)
+        with torch.cuda.stream(self.act_stream):
+            for lo in range(0, per_lane, chunk):
+                n = min(chunk, per_lane - lo)
+                for lane in range(self.lanes):
+                    # frame id of (lane, time) = time * lanes + lane
+                    P.synth_frames(buf, n, lo * self.lanes + lane, self.lanes, self.seed, synth.STREAM_REPLAY,
+                                   synth.PIX_T, synth.BACKGROUND, self.act_stream)
+                    P.synth_transitions(a, r, t, n, lo * self.lanes + lane, self.lanes, self.seed, self.A, tn, tp, tt,
+                                        self.act_stream)
+                    P.replay_push(self.rb, lane, buf, a, r, t, n)
+                P.replay_flush(self.rb, 1)
+        torch.cuda.synchronize()
+
+    def step(self):
+        """Enqueue one benchmark step (no host synchronisation)."""
+        P = self.P
+        if self.train_steps % self.sync_every == 0:
+            P.dqn_sync_target(self.ctx, self.rb, 0)
+        for _ in range(self.acts_per_train):
+            k = self.act_steps % self.pool
+            P.dqn_act(self.ctx, self.states[k], self.W, 0.1, self.act_steps, 1, self.actions, None)
+            if self.W == self.lanes:
+                P.replay_push_step(self.rb, self.new_frames[k], self.actions, self.rew[k], self.term[k])
+            self.act_steps += 1
+        P.replay_sample_gather(self.rb, self.B, self.train_steps, None, self.s, self.s2, self.a, self.r, self.d, None)
+        P.dqn_train_step(self.ctx, self.s, self.a, self.r, self.s2, self.d, self.B, self.loss)
+        self.train_steps += 1
+
+    def close(self):
+        self.torch.cuda.synchronize()
+        self.P.replay_destroy(self.rb)
+        self.P.dqn_destroy(self.ctx)
+
+
+def time_steps(wl, steps):
+    torch = wl.torch
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        wl.step()
+    torch.cuda.synchronize()
+    return time.perf_counter() - t0
+
+
+def kernel_breakdown(wl, steps_each):
+    """Average launch duration (ms) of every train-step kernel, one kernel at a time."""
+    P = wl.P
+    out = {}
+    for kid in range(1, P.dqn_profile_kernel_count() + 1):
+        P.dqn_profile_select(wl.ctx, kid)
+        for _ in range(steps_each):
+            wl.step()
+        ms, n = P.dqn_profile_read(wl.ctx)
+        out[P.dqn_profile_kernel_name(kid)] = ms / max(n, 1)
+    P.dqn_profile_select(wl.ctx, 0)
+    return out
+
+
+def cpu_baseline(args):
+    """The oracle, as it stands, on the host cores: same step composition, bounded sample."""
+    from datagen import synth
+    from oracle import dqn as odqn
+    from oracle.replay import OracleReplay
+    A, B, W, lanes, seed = args.actions, args.batch, args.envs, args.lanes, args.seed
+    n_frames = 64 * lanes                       # a small ring is enough for a timing sample
+    rep = OracleReplay(n_frames, lanes, seed)
+    for lane in range(lanes):
+        ids = np.arange(64, dtype=np.uint64) * np.uint64(lanes) + np.uint64(lane)
+        a, r, d = synth.transitions(seed, ids, A)
+        rep.push(lane, synth.frames(seed, synth.STREAM_REPLAY, ids), a, r, d)
+    rep.flush()
+    agent = odqn.OracleDQN(A, synth.init_params(seed, A), seed=seed, double_dqn=bool(args.double_dqn))
+    states = synth.act_states(seed, 0, W)
+    budget, done_steps = args.cpu_seconds, 0
+    t0 = time.perf_counter()
+    while True:
+        for k in range(args.acts_per_train):
+            agent.act(states, 0.1, done_steps * args.acts_per_train + k, use_target=True)
+        s, s2, a, r, d = rep.gather(rep.sample_indices(B, done_steps))
+        agent.train_step(s, a, r, s2, d)
+        done_steps += 1
+        el = time.perf_counter() - t0
+        if el >= budget or done_steps >= 50:
+            break
+    return {"value": done_steps / el, "unit": "train steps/s", "cores": odqn.max_threads(), "kind": "oracle",
+            "sample": "%d steps (each: %d act steps of W=%d + gather + train step at batch %d) in %.1f s"
+                      % (done_steps, args.acts_per_train, W, B, el)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10000)
+    ap.add_argument("--warmup", type=int, default=500)
+    ap.add_argument("--precision", choices=["bf16", "fp32"], default="bf16")
+    ap.add_argument("--actions", type=int, default=18)
+    ap.add_argument("--batch", type=int, default=32)
+    ap.add_argument("--envs", type=int, default=8)
+    ap.add_argument("--lanes", type=int, default=8)
+    ap.add_argument("--frames", type=int, default=1000000)
+    ap.add_argument("--acts-per-train", type=int, default=4)
+    ap.add_argument("--sync-every", type=int, default=10000)
+    ap.add_argument("--double-dqn", action="store_true")
+    ap.add_argument("--p-reward", type=float, default=0.05)
+    ap.add_argument("--p-term", type=float, default=0.001)
+    ap.add_argument("--seed", type=int, default=211101264 + 2)
+    ap.add_argument("--cpu-seconds", type=float, default=12.0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--sweep", action="store_true", help="print the batch/W roofline sweep instead of the JSON line")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one MI355X: this build has no multi-GPU path, run with --gpus 1", file=sys.stderr)
+        return 2
+
+    if args.sweep:
+        return sweep(args)
+
+    wl = Workload(args)
+    groups = 3 if args.double_dqn else 2
+    time_steps(wl, max(args.warmup // 2, 1))
+    # find the dominant train-step kernel before the timed region, then time it inside the region
+    breakdown = kernel_breakdown(wl, max(min(args.warmup // 30, 50), 5))
+    dominant = max(breakdown, key=breakdown.get)
+    time_steps(wl, max(args.warmup // 2, 1))
+    kid = [wl.P.dqn_profile_kernel_name(i) for i in range(wl.P.dqn_profile_kernel_count() + 1)].index(dominant)
+    wl.P.dqn_profile_select(wl.ctx, kid)
+    elapsed = time_steps(wl, args.steps)
+    ms, n = wl.P.dqn_profile_read(wl.ctx)
+    wl.P.dqn_profile_select(wl.ctx, 0)
+    roof = roofline_for(dominant, ms / max(n, 1), args.batch, args.actions, groups, args.precision)
+    roof["timed_launches"] = n
+    wl.close()
+
+    out = {
+        "metric": "train steps/sec (batch %d) + act states/sec" % args.batch,
+        "value": args.steps / elapsed,
+        "unit": "train steps/s",
+        "act_states_per_sec": args.steps * args.acts_per_train * args.envs / elapsed,
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": 1e3 * elapsed / args.steps,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if args.precision == "bf16" else "f32",
+        "data": "synthetic",
+        "config": {"workload": "paper-shaped slice: A=%d, W=%d envs, replay %d frames in %d lanes, batch %d, "
+                               "%d act steps per train step on a concurrent stream, target sync every %d train steps"
+                               % (args.actions, args.envs, args.frames, args.lanes, args.batch, args.acts_per_train,
+                                  args.sync_every),
+                   "double_dqn": bool(args.double_dqn), "seed": args.seed},
+        "kernel_avg_us": {k: round(v * 1e3, 2) for k, v in breakdown.items()},
+        "roofline": roof,
+        "context": "paper: 25 h -> 9 h for 200M frames on one GTX 1080 (end to end, emulator included)",
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(args)
+    print(json.dumps(out))
+    return 0
+
+
+def sweep(args):
+    """Batch in {128,256,512} x W in {32,64,128}, bf16: per-kernel time and roofline fractions."""
+    import copy
+    rows = []
+    for B, W in ((128, 32), (256, 64), (512, 128)):
+        a = copy.copy(args)
+        a.batch, a.envs, a.acts_per_train = B, W, 1
+        a.frames = min(args.frames, 200000)
+        wl = Workload(a)
+        groups = 3 if a.double_dqn else 2
+        time_steps(wl, 20)
+        br = kernel_breakdown(wl, 20)
+        steps = 200
+        el = time_steps(wl, steps)
+        torch = wl.torch
+        # gather alone, timed with events on the train stream
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(wl.train_stream)
+        for i in range(50):
+            wl.P.replay_sample_gather(wl.rb, B, i, None, wl.s, wl.s2, wl.a, wl.r, wl.d, None)
+        e1.record(wl.train_stream)
+        torch.cuda.synchronize()
+        g_ms = e0.elapsed_time(e1) / 50
+        wl.close()
+        print("B=%d W=%d  %.1f train steps/s  %.1f us/step  gather %.1f us = %.0f GB/s" %
+              (B, W, steps / el, 1e6 * el / steps, g_ms * 1e3, 91728 * B / (g_ms * 1e-3) / 1e9))
+        for name, ms in br.items():
+            r = roofline_for(name, ms, B, a.actions, groups, a.precision)
+            print("   %-12s %8.1f us  %-4s %9.1f %-7s  %5.1f %%" % (name, ms * 1e3, r["bound"], r["achieved"],
+                                                                   r["unit"], 100 * r["frac"]))
+        rows.append((B, W))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

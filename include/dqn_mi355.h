@@ -149,6 +149,13 @@ int replay_destroy(replay* rb);
 int replay_push(replay* rb, int32_t lane, const uint8_t* frames, const int32_t* actions,
                 const float* rewards, const uint8_t* terminals, int32_t n);
 
+/* Synchronized Execution (Section 4): all W = lanes samplers have stepped once; appends one
+ * experience to every lane's temporary buffer in a single launch.  frames [lanes,84,84] uint8 (row l
+ * goes to lane l); actions [lanes] int32; rewards [lanes] float32; terminals [lanes] uint8.
+ * Errors as replay_push. */
+int replay_push_step(replay* rb, const uint8_t* frames, const int32_t* actions, const float* rewards,
+                     const uint8_t* terminals);
+
 /* Moves every lane's buffered experiences into D in push order, overwriting the oldest. */
 int replay_flush(replay* rb, int32_t blocking);
 
@@ -188,6 +195,21 @@ int synth_frames(uint8_t* dst, int64_t n, uint64_t id0, uint64_t id_step, uint64
 int synth_transitions(int32_t* actions, float* rewards, uint8_t* terminals, int64_t n,
                       uint64_t id0, uint64_t id_step, uint64_t seed, int32_t num_actions,
                       uint32_t t_neg, uint32_t t_pos, uint32_t t_term, void* stream);
+
+/* ---- per-kernel timing (measurement support) ------------------------------------------------- */
+
+/* Number of distinct kernels a train step launches, and their names (id 1 .. count). */
+int dqn_profile_kernel_count(void);
+const char* dqn_profile_kernel_name(int kernel_id);
+
+/* Selects one kernel of dqn_train_step (0 = none): from now on each of its launches is bracketed
+ * by a pair of HIP events on train_stream (up to 4096 launches are kept, later ones are not
+ * timed).  Selecting resets the collected data. */
+int dqn_profile_select(dqn_ctx* ctx, int kernel_id);
+
+/* Waits for train_stream, then returns the summed duration in milliseconds and the number of
+ * timed launches of the selected kernel since dqn_profile_select. */
+int dqn_profile_read(dqn_ctx* ctx, double* host_total_ms, int64_t* host_launches);
 
 const char* dqn_last_error(void);
 

@@ -73,8 +73,14 @@ def lib():
         L.rmsprop_step.restype = None
         L.rmsprop_step.argtypes = [dp, dp, dp, dp, C.c_size_t, C.c_double, C.c_double, C.c_double,
                                    C.c_int]
+        L.oracle_max_threads.restype = C.c_int
+        L.oracle_max_threads.argtypes = []
         _lib = L
     return _lib
+
+
+def max_threads() -> int:
+    return int(lib().oracle_max_threads())
 
 
 def _dp(a):

@@ -320,3 +320,11 @@ void rmsprop_step(double *theta, const double *g, double *v, double *m, size_t n
         theta[i] -= lr * g[i] / (sqrt(var) + eps);
     }
 }
+
+/* Number of threads the OpenMP loops above will use (reported by the benchmark's CPU leg). */
+#ifdef _OPENMP
+#include <omp.h>
+int oracle_max_threads(void) { return omp_get_max_threads(); }
+#else
+int oracle_max_threads(void) { return 1; }
+#endif

@@ -55,6 +55,7 @@ EXPORTS = {
     "replay_destroy": (C.c_int, [C.c_void_p]),
     "replay_push": (C.c_int, [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                               C.c_int32]),
+    "replay_push_step": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
     "replay_flush": (C.c_int, [C.c_void_p, C.c_int32]),
     "replay_num_valid": (C.c_int64, [C.c_void_p]),
     "replay_sample_gather": (C.c_int, [C.c_void_p, C.c_int32, C.c_uint64, C.c_void_p, C.c_void_p,
@@ -64,6 +65,10 @@ EXPORTS = {
     "synth_transitions": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_uint64,
                                     C.c_uint64, C.c_uint64, C.c_int32, C.c_uint32, C.c_uint32,
                                     C.c_uint32, C.c_void_p]),
+    "dqn_profile_kernel_count": (C.c_int, []),
+    "dqn_profile_kernel_name": (C.c_char_p, [C.c_int]),
+    "dqn_profile_select": (C.c_int, [C.c_void_p, C.c_int]),
+    "dqn_profile_read": (C.c_int, [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_int64)]),
     "dqn_last_error": (C.c_char_p, []),
 }
 
@@ -164,6 +169,10 @@ def replay_push(rb, lane, frames, actions, rewards, terminals, n):
     _check(_lib.replay_push(rb, lane, _ptr(frames), _ptr(actions), _ptr(rewards), _ptr(terminals), n))
 
 
+def replay_push_step(rb, frames, actions, rewards, terminals):
+    _check(_lib.replay_push_step(rb, _ptr(frames), _ptr(actions), _ptr(rewards), _ptr(terminals)))
+
+
 def replay_flush(rb, blocking):
     _check(_lib.replay_flush(rb, blocking))
 
@@ -186,3 +195,22 @@ def synth_transitions(actions, rewards, terminals, n, id0, id_step, seed, num_ac
                       t_term, stream):
     _check(_lib.synth_transitions(_ptr(actions), _ptr(rewards), _ptr(terminals), n, id0, id_step, seed,
                                   num_actions, t_neg, t_pos, t_term, _stream(stream)))
+
+
+def dqn_profile_kernel_count():
+    return int(_lib.dqn_profile_kernel_count())
+
+
+def dqn_profile_kernel_name(kernel_id):
+    r = _lib.dqn_profile_kernel_name(kernel_id)
+    return r.decode() if r else None
+
+
+def dqn_profile_select(ctx, kernel_id):
+    _check(_lib.dqn_profile_select(ctx, kernel_id))
+
+
+def dqn_profile_read(ctx):
+    ms, n = C.c_double(), C.c_int64()
+    _check(_lib.dqn_profile_read(ctx, C.byref(ms), C.byref(n)))
+    return ms.value, n.value

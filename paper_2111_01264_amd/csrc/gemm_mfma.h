@@ -213,7 +213,8 @@ __global__ __launch_bounds__(256) void splitk_finalize_kernel(EP ep, const float
 // groups * splits * M * N floats when splits > 1 (capacity given in floats).
 template <typename T, int BM, int BN, int BK, int WGM, class AL, class BL, class EP>
 inline hipError_t launch_gemm(hipStream_t st, const AL& al, const BL& bl, const EP& ep, int M, int N, int K,
-                              int groups, int want_splits, float* partial, size_t partial_capacity)
+                              int groups, int want_splits, float* partial, size_t partial_capacity,
+                              hipEvent_t ev_begin = nullptr, hipEvent_t ev_end = nullptr)
 {
     const int m_tiles = (M + BM - 1) / BM, n_tiles = (N + BN - 1) / BN;
     int splits = want_splits < 1 ? 1 : want_splits;
@@ -224,9 +225,11 @@ inline hipError_t launch_gemm(hipStream_t st, const AL& al, const BL& bl, const 
         splits = (K + kps - 1) / kps;
     }
     if (splits == 1) kps = (K + BK - 1) / BK * BK;
+    if (ev_begin) (void)hipEventRecord(ev_begin, st);   // optional timing of the main kernel only
     hipLaunchKernelGGL((gemm_nt_kernel<T, AL, BL, EP, BM, BN, BK, WGM>), dim3(m_tiles * n_tiles, splits, groups),
                        dim3(kGemmThreads), 0, st, al, bl, ep, M, N, K, kps, n_tiles, partial);
     hipError_t e = hipGetLastError();
+    if (ev_end) (void)hipEventRecord(ev_end, st);
     if (e != hipSuccess) return e;
     if (splits > 1) {
         const size_t mn = static_cast<size_t>(M) * N;

@@ -29,6 +29,17 @@ static Offsets make_offsets(int A)
     return o;
 }
 
+enum KernelId {
+    K_NONE = 0, K_CONV1_FWD, K_CONV2_FWD, K_CONV3_FWD, K_FC1_FWD, K_FC2_TD, K_TD_HEAD_BWD, K_FC1_WGRAD,
+    K_FC1_DGRAD, K_CONV3_WGRAD, K_CONV3_DGRAD, K_CONV2_WGRAD, K_CONV2_DGRAD, K_CONV1_WGRAD, K_BIAS_GRAD,
+    K_RMSPROP, K_COUNT
+};
+static const char* const kKernelNames[K_COUNT] = {
+    "none", "conv1_fwd", "conv2_fwd", "conv3_fwd", "fc1_fwd", "fc2_td", "td_head_bwd", "fc1_wgrad",
+    "fc1_dgrad", "conv3_wgrad", "conv3_dgrad", "conv2_wgrad", "conv2_dgrad", "conv1_wgrad", "bias_grad",
+    "rmsprop"};
+constexpr size_t kProfPairs = 4096;
+
 constexpr int kMaxBatch = 1024;
 constexpr int kMaxActions = 64;
 
@@ -307,6 +318,10 @@ struct dqn_ctx {
     hipEvent_t ev_train = nullptr, ev_act = nullptr, ev_sync = nullptr;
     bool act_reads_online = false;   // an act step with use_target = 0 is in flight
     int last_B = 0;
+    // per-kernel timing (dqn_profile_*)
+    int prof_id = 0;
+    std::vector<hipEvent_t> prof_events;   // pairs
+    size_t prof_used = 0;                  // pairs recorded since the last select
 };
 
 namespace dqn {
@@ -345,6 +360,19 @@ static void free_ws(Workspace& ws)
     (void)hipFree(ws.q); (void)hipFree(ws.partial);
 }
 
+// Event pair for a launch of kernel `id`, or nulls if that kernel is not the selected one.
+struct ProfPair { hipEvent_t begin = nullptr, end = nullptr; };
+static ProfPair prof_pair(dqn_ctx* c, int id)
+{
+    ProfPair p;
+    if (c->prof_id == id && c->prof_used < c->prof_events.size() / 2) {
+        p.begin = c->prof_events[2 * c->prof_used];
+        p.end = c->prof_events[2 * c->prof_used + 1];
+        ++c->prof_used;
+    }
+    return p;
+}
+
 static int pick_splits(int tiles, int groups, int K, int BK, int max_splits)
 {
     const int target = 512;   // about two workgroups per compute unit
@@ -358,8 +386,9 @@ static int pick_splits(int tiles, int groups, int K, int BK, int max_splits)
 // Forward pass of `groups` independent (input, parameter set) pairs with n samples each, up to h.
 template <typename T>
 static int forward_to_h(dqn_ctx* c, hipStream_t st, Workspace& ws, int groups, const uint8_t* const* x,
-                        const void* const* shadow, const float* const* master, int n)
+                        const void* const* shadow, const float* const* master, int n, bool timed)
 {
+    auto pp = [&](int id) { return timed ? prof_pair(c, id) : ProfPair(); };
     const Offsets& o = c->off;
     const size_t e_act1 = static_cast<size_t>(n) * 12800, e_act2 = static_cast<size_t>(n) * 5184;
     const size_t e_act3 = static_cast<size_t>(n) * 3136, e_h = static_cast<size_t>(n) * 512;
@@ -373,7 +402,9 @@ static int forward_to_h(dqn_ctx* c, hipStream_t st, Workspace& ws, int groups, c
             ep.out[g] = act1 + g * e_act1; ep.bias[g] = master[g] + o.b1;
         }
         bl.ld = 256; ep.ld = 32; ep.scale = 1.f / 255.f;
-        DQN_HIP((launch_gemm<T, 128, 32, 32, 4>(st, al, bl, ep, n * 400, 32, 256, groups, 1, ws.partial, ws.partial_cap)));
+        const ProfPair pr = pp(K_CONV1_FWD);
+        DQN_HIP((launch_gemm<T, 128, 32, 32, 4>(st, al, bl, ep, n * 400, 32, 256, groups, 1, ws.partial, ws.partial_cap,
+                                                 pr.begin, pr.end)));
     }
     {   // conv2
         ConvA<T, 32, 20, 20, 9, 9, 4, 2> al{}; DenseK<T> bl{}; EpiBiasAct<T, true> ep{};
@@ -384,8 +415,9 @@ static int forward_to_h(dqn_ctx* c, hipStream_t st, Workspace& ws, int groups, c
         }
         bl.ld = 512; ep.ld = 64; ep.scale = 1.f;
         const int M = n * 81, tiles = (M + 63) / 64;
+        const ProfPair pr = pp(K_CONV2_FWD);
         DQN_HIP((launch_gemm<T, 64, 64, 32, 2>(st, al, bl, ep, M, 64, 512, groups, pick_splits(tiles, groups, 512, 32, 8),
-                                                ws.partial, ws.partial_cap)));
+                                                ws.partial, ws.partial_cap, pr.begin, pr.end)));
     }
     {   // conv3
         ConvA<T, 64, 9, 9, 7, 7, 3, 1> al{}; DenseK<T> bl{}; EpiBiasAct<T, true> ep{};
@@ -396,8 +428,9 @@ static int forward_to_h(dqn_ctx* c, hipStream_t st, Workspace& ws, int groups, c
         }
         bl.ld = 576; ep.ld = 64; ep.scale = 1.f;
         const int M = n * 49, tiles = (M + 63) / 64;
+        const ProfPair pr = pp(K_CONV3_FWD);
         DQN_HIP((launch_gemm<T, 64, 64, 32, 2>(st, al, bl, ep, M, 64, 576, groups, pick_splits(tiles, groups, 576, 32, 8),
-                                                ws.partial, ws.partial_cap)));
+                                                ws.partial, ws.partial_cap, pr.begin, pr.end)));
     }
     {   // fc1
         DenseK<T> al{}; DenseK<T> bl{}; EpiBiasAct<T, true> ep{};
@@ -408,8 +441,9 @@ static int forward_to_h(dqn_ctx* c, hipStream_t st, Workspace& ws, int groups, c
         }
         al.ld = 3136; bl.ld = 3136; ep.ld = 512; ep.scale = 1.f;
         const int tiles = ((n + 31) / 32) * 4;
+        const ProfPair pr = pp(K_FC1_FWD);
         DQN_HIP((launch_gemm<T, 32, 128, 32, 1>(st, al, bl, ep, n, 512, 3136, groups, pick_splits(tiles, groups, 3136, 32, 64),
-                                                 ws.partial, ws.partial_cap)));
+                                                 ws.partial, ws.partial_cap, pr.begin, pr.end)));
     }
     return DQN_OK;
 }
@@ -421,7 +455,7 @@ static int act_impl(dqn_ctx* c, const uint8_t* states, int W, float epsilon, uin
     const uint8_t* x[1] = {states};
     const void* shadow[1] = {use_target ? c->sh_t : c->sh};
     const float* master[1] = {use_target ? c->theta_t : c->theta};
-    const int rc = forward_to_h<T>(c, c->act_stream, c->act_ws, 1, x, shadow, master, W);
+    const int rc = forward_to_h<T>(c, c->act_stream, c->act_ws, 1, x, shadow, master, W, false);
     if (rc != DQN_OK) return rc;
     hipLaunchKernelGGL((fc2_act_kernel<T>), dim3((W + 3) / 4), dim3(256), 0, c->act_stream,
                        static_cast<const T*>(c->act_ws.h), static_cast<const T*>(shadow[0]) + c->off.wf2,
@@ -441,7 +475,7 @@ static int train_impl(dqn_ctx* c, const uint8_t* s, const int32_t* a, const floa
     const uint8_t* x[3] = {s, s2, s2};
     const void* shadow[3] = {c->sh, c->sh_t, c->sh};
     const float* master[3] = {c->theta, c->theta_t, c->theta};
-    int rc = forward_to_h<T>(c, st, ws, groups, x, shadow, master, B);
+    int rc = forward_to_h<T>(c, st, ws, groups, x, shadow, master, B, true);
     if (rc != DQN_OK) return rc;
 
     const T* sh = static_cast<const T*>(c->sh);
@@ -451,54 +485,71 @@ static int train_impl(dqn_ctx* c, const uint8_t* s, const int32_t* a, const floa
     T* dzh = static_cast<T*>(c->dzh); T* dz3 = static_cast<T*>(c->dz3);
     T* dz2 = static_cast<T*>(c->dz2); T* dz1 = static_cast<T*>(c->dz1);
 
-    hipLaunchKernelGGL((fc2_td_kernel<T>), dim3((B + 3) / 4), dim3(256), 0, st, h, sh + o.wf2, sh_t + o.wf2,
+    {
+        const ProfPair pr = prof_pair(c, K_FC2_TD);
+        if (pr.begin) (void)hipEventRecord(pr.begin, st);
+        hipLaunchKernelGGL((fc2_td_kernel<T>), dim3((B + 3) / 4), dim3(256), 0, st, h, sh + o.wf2, sh_t + o.wf2,
                        c->theta + o.bf2, c->theta_t + o.bf2, B, c->A, c->cfg.double_dqn, a, r, done, c->cfg.gamma,
                        c->cfg.huber_delta, ws.q, c->dqv, c->lossv);
-    DQN_LAUNCH_CHECK();
-    hipLaunchKernelGGL((td_head_bwd_kernel<T>), dim3(8), dim3(256), 0, st, h, sh + o.wf2, a, c->dqv, c->lossv, B, c->A,
+    if (pr.end) (void)hipEventRecord(pr.end, st);
+        DQN_LAUNCH_CHECK();
+    }
+    {
+        const ProfPair pr = prof_pair(c, K_TD_HEAD_BWD);
+        if (pr.begin) (void)hipEventRecord(pr.begin, st);
+        hipLaunchKernelGGL((td_head_bwd_kernel<T>), dim3(8), dim3(256), 0, st, h, sh + o.wf2, a, c->dqv, c->lossv, B, c->A,
                        dzh, c->grad + o.wf2, c->grad + o.bf2, loss_out, c->loss_keep);
-    DQN_LAUNCH_CHECK();
+    if (pr.end) (void)hipEventRecord(pr.end, st);
+        DQN_LAUNCH_CHECK();
+    }
     {   // fc1 weight gradient: dW[o][f] = sum_b dZ[b][o] act3[b][f]
         DenseM<T> al{}; DenseM<T> bl{}; EpiGrad ep{c->grad + o.wf1, 3136, 1.f};
         al.p[0] = dzh; al.ld = 512; bl.p[0] = act3; bl.ld = 3136;
-        DQN_HIP((launch_gemm<T, 64, 128, 32, 2>(st, al, bl, ep, 512, 3136, B, 1, 1, ws.partial, ws.partial_cap)));
+        const ProfPair pr = prof_pair(c, K_FC1_WGRAD);
+        DQN_HIP((launch_gemm<T, 64, 128, 32, 2>(st, al, bl, ep, 512, 3136, B, 1, 1, ws.partial, ws.partial_cap, pr.begin, pr.end)));
     }
     {   // fc1 data gradient through conv3's ReLU
         DenseK<T> al{}; DenseM<T> bl{}; EpiMaskDense<T> ep{dz3, act3, 3136};
         al.p[0] = dzh; al.ld = 512; bl.p[0] = sh + o.wf1; bl.ld = 3136;
         const int tiles = ((B + 31) / 32) * 25;
+        const ProfPair pr = prof_pair(c, K_FC1_DGRAD);
         DQN_HIP((launch_gemm<T, 32, 128, 32, 1>(st, al, bl, ep, B, 3136, 512, 1, pick_splits(tiles, 1, 512, 32, 16),
-                                                 ws.partial, ws.partial_cap)));
+                                                 ws.partial, ws.partial_cap, pr.begin, pr.end)));
     }
     {   // conv3 weight gradient
         DenseM<T> al{}; WgradB<T, 64, 9, 9, 7, 7, 3, 1> bl{act2}; EpiGrad ep{c->grad + o.w3, 576, 1.f};
         al.p[0] = dz3; al.ld = 64;
+        const ProfPair pr = prof_pair(c, K_CONV3_WGRAD);
         DQN_HIP((launch_gemm<T, 64, 64, 32, 2>(st, al, bl, ep, 64, 576, B * 49, 1, pick_splits(9, 1, B * 49, 32, 512),
-                                                ws.partial, ws.partial_cap)));
+                                                ws.partial, ws.partial_cap, pr.begin, pr.end)));
     }
     {   // conv3 data gradient through conv2's ReLU
         DgradA<T, 64, 7, 7, 9, 9, 3, 1> al{dz3}; DgradB<T, 64, 64, 3, 1> bl{sh + o.w3};
         EpiDgradMask<T, 9, 9, 64, 1> ep{dz2, act2};
         const int M = B * 81, tiles = (M + 63) / 64;
+        const ProfPair pr = prof_pair(c, K_CONV3_DGRAD);
         DQN_HIP((launch_gemm<T, 64, 64, 32, 2>(st, al, bl, ep, M, 64, 576, 1, pick_splits(tiles, 1, 576, 32, 8),
-                                                ws.partial, ws.partial_cap)));
+                                                ws.partial, ws.partial_cap, pr.begin, pr.end)));
     }
     {   // conv2 weight gradient
         DenseM<T> al{}; WgradB<T, 32, 20, 20, 9, 9, 4, 2> bl{act1}; EpiGrad ep{c->grad + o.w2, 512, 1.f};
         al.p[0] = dz2; al.ld = 64;
+        const ProfPair pr = prof_pair(c, K_CONV2_WGRAD);
         DQN_HIP((launch_gemm<T, 64, 64, 32, 2>(st, al, bl, ep, 64, 512, B * 81, 1, pick_splits(8, 1, B * 81, 32, 512),
-                                                ws.partial, ws.partial_cap)));
+                                                ws.partial, ws.partial_cap, pr.begin, pr.end)));
     }
     {   // conv2 data gradient through conv1's ReLU: four stride-parity classes
         DgradA<T, 64, 9, 9, 20, 20, 4, 2> al{dz2}; DgradB<T, 32, 64, 4, 2> bl{sh + o.w2};
         EpiDgradMask<T, 20, 20, 32, 2> ep{dz1, act1};
-        DQN_HIP((launch_gemm<T, 128, 32, 32, 4>(st, al, bl, ep, B * 100, 32, 256, 4, 1, ws.partial, ws.partial_cap)));
+        const ProfPair pr = prof_pair(c, K_CONV2_DGRAD);
+        DQN_HIP((launch_gemm<T, 128, 32, 32, 4>(st, al, bl, ep, B * 100, 32, 256, 4, 1, ws.partial, ws.partial_cap, pr.begin, pr.end)));
     }
     {   // conv1 weight gradient (input scale 1/255 folded into the epilogue)
         DenseM<T> al{}; Conv1WgradB<T> bl{s}; EpiGrad ep{c->grad + o.w1, 256, 1.f / 255.f};
         al.p[0] = dz1; al.ld = 32;
+        const ProfPair pr = prof_pair(c, K_CONV1_WGRAD);
         DQN_HIP((launch_gemm<T, 32, 128, 32, 1>(st, al, bl, ep, 32, 256, B * 400, 1, pick_splits(2, 1, B * 400, 32, 512),
-                                                 ws.partial, ws.partial_cap)));
+                                                 ws.partial, ws.partial_cap, pr.begin, pr.end)));
     }
     {
         BiasGradArgs args;
@@ -508,15 +559,25 @@ static int train_impl(dqn_ctx* c, const uint8_t* s, const int32_t* a, const floa
         args.dz[3] = dzh; args.out[3] = c->grad + o.bf1; args.rows[3] = B;      args.chans[3] = 512;
         args.first_block[0] = 0;
         for (int l = 0; l < 4; ++l) args.first_block[l + 1] = args.first_block[l] + args.chans[l] / 8;
+        {
+        const ProfPair pr = prof_pair(c, K_BIAS_GRAD);
+        if (pr.begin) (void)hipEventRecord(pr.begin, st);
         hipLaunchKernelGGL((bias_grad_kernel<T>), dim3(args.first_block[4]), dim3(256), 0, st, args);
+        if (pr.end) (void)hipEventRecord(pr.end, st);
         DQN_LAUNCH_CHECK();
+    }
     }
     {
         const size_t n = o.total, threads = n / 4 + 4;
+        {
+        const ProfPair pr = prof_pair(c, K_RMSPROP);
+        if (pr.begin) (void)hipEventRecord(pr.begin, st);
         hipLaunchKernelGGL((rmsprop_kernel<T, SHADOW>), dim3(static_cast<unsigned>((threads + 255) / 256)), dim3(256), 0,
                            st, c->theta, c->grad, c->v, c->m, static_cast<T*>(c->sh), n, c->cfg.lr, c->cfg.rms_alpha,
                            c->cfg.rms_eps, c->cfg.centered);
+        if (pr.end) (void)hipEventRecord(pr.end, st);
         DQN_LAUNCH_CHECK();
+    }
     }
     return DQN_OK;
 }
@@ -652,6 +713,7 @@ int dqn_destroy(dqn_ctx* c)
     if (c->ev_train) (void)hipEventDestroy(c->ev_train);
     if (c->ev_act) (void)hipEventDestroy(c->ev_act);
     if (c->ev_sync) (void)hipEventDestroy(c->ev_sync);
+    for (hipEvent_t e : c->prof_events) (void)hipEventDestroy(e);
     delete c;
     return DQN_OK;
 }
@@ -747,6 +809,46 @@ int dqn_get_train_q(dqn_ctx* c, float* host_q_online, float* host_q_next_target,
     if (host_q_next_target) DQN_HIP(hipMemcpy(host_q_next_target, c->train_ws.q + row, row * 4, hipMemcpyDeviceToHost));
     if (host_q_next_online && c->cfg.double_dqn)
         DQN_HIP(hipMemcpy(host_q_next_online, c->train_ws.q + 2 * row, row * 4, hipMemcpyDeviceToHost));
+    return DQN_OK;
+}
+
+int dqn_profile_kernel_count(void) { return K_COUNT - 1; }
+
+const char* dqn_profile_kernel_name(int kernel_id)
+{
+    return kernel_id >= 1 && kernel_id < K_COUNT ? kKernelNames[kernel_id] : nullptr;
+}
+
+int dqn_profile_select(dqn_ctx* c, int kernel_id)
+{
+    if (!c) return fail(DQN_EINVAL, "dqn_profile_select: ctx is null");
+    if (kernel_id < 0 || kernel_id >= K_COUNT) return fail(DQN_EINVAL, "dqn_profile_select: kernel id %d", kernel_id);
+    DQN_HIP(hipStreamSynchronize(c->train_stream));
+    if (kernel_id != 0 && c->prof_events.empty()) {
+        c->prof_events.reserve(2 * kProfPairs);
+        for (size_t i = 0; i < 2 * kProfPairs; ++i) {
+            hipEvent_t e;
+            DQN_HIP(hipEventCreate(&e));
+            c->prof_events.push_back(e);
+        }
+    }
+    c->prof_id = kernel_id;
+    c->prof_used = 0;
+    return DQN_OK;
+}
+
+int dqn_profile_read(dqn_ctx* c, double* host_total_ms, int64_t* host_launches)
+{
+    if (!c || !host_total_ms || !host_launches) return fail(DQN_EINVAL, "dqn_profile_read: null pointer");
+    DQN_HIP(hipStreamSynchronize(c->train_stream));
+    double total = 0.0;
+    for (size_t i = 0; i < c->prof_used; ++i) {
+        float ms = 0.f;
+        DQN_HIP(hipEventElapsedTime(&ms, c->prof_events[2 * i], c->prof_events[2 * i + 1]));
+        total += ms;
+    }
+    *host_total_ms = total;
+    *host_launches = static_cast<int64_t>(c->prof_used);
     return DQN_OK;
 }
 

@@ -65,6 +65,23 @@ __global__ __launch_bounds__(256) void push_kernel(
     }
 }
 
+// One experience per lane: row l of the call goes to staging slot l * S + staged[l].
+__global__ __launch_bounds__(256) void push_step_kernel(
+    const uint8_t* __restrict__ frames, const int32_t* __restrict__ actions,
+    const float* __restrict__ rewards, const uint8_t* __restrict__ terminals,
+    uint8_t* __restrict__ st_frames, int32_t* __restrict__ st_actions, float* __restrict__ st_rewards,
+    uint8_t* __restrict__ st_terminals, LaneTable staged, int64_t S)
+{
+    const int64_t l = blockIdx.x;
+    const int64_t dst = l * S + staged.count[l];
+    copy_frame(st_frames + dst * kFrameBytes, frames + l * kFrameBytes);
+    if (threadIdx.x == 0) {
+        st_actions[dst] = actions[l];
+        st_rewards[dst] = rewards[l];
+        st_terminals[dst] = terminals[l];
+    }
+}
+
 // Flush: staged experience number blockIdx.x (lanes concatenated) moves to its ring slot.
 __global__ __launch_bounds__(256) void flush_kernel(
     const uint8_t* __restrict__ st_frames, const int32_t* __restrict__ st_actions,
@@ -301,6 +318,26 @@ int replay_push(replay* rb, int32_t lane, const uint8_t* frames, const int32_t* 
                        terminals, rb->st_frames, rb->st_actions, rb->st_rewards, rb->st_terminals, first);
     DQN_LAUNCH_CHECK();
     rb->staged[lane] += n;
+    return DQN_OK;
+}
+
+int replay_push_step(replay* rb, const uint8_t* frames, const int32_t* actions, const float* rewards,
+                     const uint8_t* terminals)
+{
+    if (!rb) return fail(DQN_EINVAL, "replay_push_step: rb is null");
+    if (!frames || !actions || !rewards || !terminals) return fail(DQN_EINVAL, "replay_push_step: null pointer");
+    if (!aligned16(frames)) return fail(DQN_EINVAL, "replay_push_step: frames not 16-byte aligned");
+    LaneTable staged;
+    for (int l = 0; l < rb->L; ++l) {
+        if (rb->staged[l] + 1 > rb->S)
+            return fail(DQN_ESTATE, "replay_push_step: lane %d buffer is full (%lld experiences); flush first", l,
+                        (long long)rb->S);
+        staged.count[l] = (int32_t)rb->staged[l];
+    }
+    hipLaunchKernelGGL(push_step_kernel, dim3(rb->L), dim3(256), 0, rb->push_stream, frames, actions, rewards,
+                       terminals, rb->st_frames, rb->st_actions, rb->st_rewards, rb->st_terminals, staged, rb->S);
+    DQN_LAUNCH_CHECK();
+    for (int l = 0; l < rb->L; ++l) rb->staged[l] += 1;
     return DQN_OK;
 }
 
