@@ -52,7 +52,7 @@ typedef struct dqn_ctx dqn_ctx;
 typedef struct replay replay;
 
 typedef struct {
-    int32_t num_actions;   /* A, 1..64 (the paper's games use 4..18)                              */
+    int32_t num_actions;   /* A, 1..32 (the paper's games use 4..18)                              */
     int32_t max_batch;     /* largest minibatch dqn_train_step will see (Table 5: 32)              */
     int32_t max_envs;      /* largest W dqn_act will see (Section 4)                              */
     int32_t precision;     /* DQN_PRECISION_FP32: fp32 operands on fp32 MFMA;

@@ -1,0 +1,154 @@
+// Activation-stationary GEMM for the fully connected layer fc1 (512 x 3136) and its data gradient.
+//
+//   out[b][n] = sum_k X[b][k] * W[n][k]        X: [M][ldx] activations (few rows), W: [N][ldw] weights
+//
+// With at most a few hundred rows of X the layer is bound by streaming W once, so the roles are
+// the reverse of the convolution kernel: a workgroup parks a [32*TB][KC] slab of X in LDS and every
+// wavefront streams 32 rows of W straight from global memory in MFMA operand layout (eight
+// consecutive k per lane).  MFMA A = weights (row i = output feature), B = samples (column j = b),
+// so lane l ends up with sample (l % 32) and four consecutive features per register quad.
+//
+// K may be split over blockIdx.z: each slice then writes fp32 partial sums [slice][b][n], which the
+// consumer kernel adds in slice order while it loads them (no separate reduction pass).
+#pragma once
+#include "conv_ws.h"
+
+namespace dqn {
+
+template <typename T> struct FcAsArgs {
+    const T* x[kMaxGroups];      // [M][ldx]
+    const T* w[kMaxGroups];      // [N][ldw]
+    float* partial;              // kFcPartial: [group][slice][M][N] fp32
+    T* dz;                       // kFcReluMask: [M][N]
+    const T* mask;               // kFcReluMask: activation indexed like dz
+    int M, N, K, ldx, ldw;      // K is a multiple of 64
+    int kc;                      // k per slice, multiple of 64 (the last slice may be shorter)
+    int slices;
+};
+
+constexpr int kFcPartial = 0, kFcReluMask = 1;
+
+template <typename T, int EPI, int TB, int WAVES>
+__global__ __launch_bounds__(WAVES * 64) void fc_as_kernel(FcAsArgs<T> a)
+{
+    typedef typename Vec8<T>::type V8;
+    extern __shared__ __attribute__((aligned(32))) unsigned char as_smem[];
+    T* sX = reinterpret_cast<T*>(as_smem);
+    const int ldk = a.kc + 8;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int g = blockIdx.z / a.slices, slice = blockIdx.z % a.slices;
+    const int m0 = blockIdx.y * (TB * 32);
+    const int k0 = slice * a.kc;
+    const int klen = min(a.kc, a.K - k0);
+    {
+        const T* xg = a.x[g];
+        const int vec_per_row = klen / 8;
+        for (int v = tid; v < TB * 32 * vec_per_row; v += WAVES * 64) {
+            const int r = v / vec_per_row, kc8 = v % vec_per_row;
+            V8 val = vec8_zero<T>();
+            if (m0 + r < a.M) val = *reinterpret_cast<const V8*>(xg + static_cast<size_t>(m0 + r) * a.ldx + k0 + kc8 * 8);
+            *reinterpret_cast<V8*>(&sX[r * ldk + kc8 * 8]) = val;
+        }
+    }
+    __syncthreads();
+
+    const int lane_r = lane & 31, kg = lane >> 5;
+    const int n = (blockIdx.x * WAVES + wave) * 32 + lane_r;
+    const bool n_ok = n < a.N;
+    const T* wp = a.w[g] + static_cast<size_t>(n_ok ? n : 0) * a.ldw + k0 + kg * 8;
+
+    f32x16 acc[TB];
+#pragma unroll
+    for (int t = 0; t < TB; ++t)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[t][v] = 0.f;
+
+    // four k-steps (64 k) per iteration, the next iteration's weight fragments already in flight
+    V8 cur[4], nxt[4];
+#pragma unroll
+    for (int s = 0; s < 4; ++s) cur[s] = *reinterpret_cast<const V8*>(wp + s * 16);
+    for (int kk = 0; kk < klen; kk += 64) {
+        if (kk + 64 < klen) {
+#pragma unroll
+            for (int s = 0; s < 4; ++s) nxt[s] = *reinterpret_cast<const V8*>(wp + kk + 64 + s * 16);
+        }
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+#pragma unroll
+            for (int t = 0; t < TB; ++t) {
+                const V8 xf = *reinterpret_cast<const V8*>(&sX[(t * 32 + lane_r) * ldk + kk + s * 16 + kg * 8]);
+                mma_32x32x16(acc[t], cur[s], xf);
+            }
+        }
+#pragma unroll
+        for (int s = 0; s < 4; ++s) cur[s] = nxt[s];
+    }
+
+    // lane: sample b = m0 + t*32 + lane_r; values: features 8*q + 4*kg + e of this wavefront's 32
+    const int n_base = (blockIdx.x * WAVES + wave) * 32;
+#pragma unroll
+    for (int t = 0; t < TB; ++t) {
+        const int b = m0 + t * 32 + lane_r;
+        if (b >= a.M) continue;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int nn = n_base + 8 * q + 4 * kg;
+            if (nn >= a.N) continue;   // N is a multiple of 4
+            if constexpr (EPI == kFcPartial) {
+                float* dst = a.partial + ((static_cast<size_t>(g) * a.slices + slice) * a.M + b) * a.N + nn;
+                *reinterpret_cast<float4*>(dst) = make_float4(acc[t][4 * q], acc[t][4 * q + 1], acc[t][4 * q + 2], acc[t][4 * q + 3]);
+            } else {
+                const size_t idx = static_cast<size_t>(b) * a.N + nn;
+                float m[4];
+                load4<T>(a.mask + idx, m);
+                store4<T>(a.dz + idx, m[0] > 0.f ? acc[t][4 * q] : 0.f, m[1] > 0.f ? acc[t][4 * q + 1] : 0.f,
+                          m[2] > 0.f ? acc[t][4 * q + 2] : 0.f, m[3] > 0.f ? acc[t][4 * q + 3] : 0.f);
+            }
+        }
+    }
+}
+
+template <typename T, int EPI>
+inline hipError_t launch_fc_as(hipStream_t st, FcAsArgs<T> a, int K, int groups, int want_slices, int* slices_used,
+                               hipEvent_t ev_begin = nullptr, hipEvent_t ev_end = nullptr)
+{
+    constexpr int WAVES = 4;
+    int slices = want_slices < 1 ? 1 : want_slices;
+    int kc = ((K + slices - 1) / slices + 63) / 64 * 64;
+    slices = (K + kc - 1) / kc;
+    if (slices_used) *slices_used = slices;
+    a.K = K;
+    a.kc = kc;
+    a.slices = slices;
+    const int n_blocks = (a.N + WAVES * 32 - 1) / (WAVES * 32);
+    hipError_t e = hipSuccess;
+    if (ev_begin) (void)hipEventRecord(ev_begin, st);
+    if (a.M > 32) {
+        constexpr int TB = 2;
+        const size_t smem = static_cast<size_t>(TB) * 32 * (kc + 8) * sizeof(T);
+        auto kern = fc_as_kernel<T, EPI, TB, WAVES>;
+        static size_t attr_smem = 0;
+        if (smem > attr_smem) {
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+            if (e != hipSuccess) return e;
+            attr_smem = smem;
+        }
+        hipLaunchKernelGGL(kern, dim3(n_blocks, (a.M + TB * 32 - 1) / (TB * 32), groups * slices), dim3(WAVES * 64), smem, st, a);
+    } else {
+        constexpr int TB = 1;
+        const size_t smem = static_cast<size_t>(TB) * 32 * (kc + 8) * sizeof(T);
+        auto kern = fc_as_kernel<T, EPI, TB, WAVES>;
+        static size_t attr_smem = 0;
+        if (smem > attr_smem) {
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+            if (e != hipSuccess) return e;
+            attr_smem = smem;
+        }
+        hipLaunchKernelGGL(kern, dim3(n_blocks, 1, groups * slices), dim3(WAVES * 64), smem, st, a);
+    }
+    e = hipGetLastError();
+    if (ev_end) (void)hipEventRecord(ev_end, st);
+    return e;
+}
+
+}  // namespace dqn

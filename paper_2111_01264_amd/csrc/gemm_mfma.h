@@ -67,6 +67,7 @@ __device__ inline void mma_32x32x16(f32x16& acc, const f32x8& a, const f32x8& b)
     for (int t = 0; t < 8; ++t) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[t], b[t], acc, 0, 0, 0);
 }
 
+constexpr int kMaxGroups = 4;   // independent problems per launch (online/target nets, parity classes)
 constexpr int kGemmThreads = 256;
 constexpr int kLdsPad = 8;  // elements of padding per LDS row
 

@@ -14,8 +14,6 @@
 
 namespace dqn {
 
-constexpr int kMaxGroups = 4;
-
 // ---- forward A-operands -------------------------------------------------------------------------
 
 // conv1 im2col on the raw uint8 state: rows (b, i, j) over the 20x20 output, k = (c, p, q).

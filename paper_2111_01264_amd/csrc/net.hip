@@ -8,26 +8,11 @@
 #include <vector>
 
 #include "common.h"
+#include "fc_as.h"
+#include "head_kernels.h"
 #include "layers.h"
-#include "philox.h"
 
 namespace dqn {
-
-// Offsets of the tensors inside a parameter blob (identical for the public and the device layout).
-struct Offsets {
-    size_t w1, b1, w2, b2, w3, b3, wf1, bf1, wf2, bf2, total;
-};
-static Offsets make_offsets(int A)
-{
-    Offsets o;
-    o.w1 = 0;            o.b1 = o.w1 + 32 * 256;
-    o.w2 = o.b1 + 32;    o.b2 = o.w2 + 64 * 512;
-    o.w3 = o.b2 + 64;    o.b3 = o.w3 + 64 * 576;
-    o.wf1 = o.b3 + 64;   o.bf1 = o.wf1 + 512 * 3136;
-    o.wf2 = o.bf1 + 512; o.bf2 = o.wf2 + static_cast<size_t>(A) * 512;
-    o.total = o.bf2 + A;
-    return o;
-}
 
 enum KernelId {
     K_NONE = 0, K_CONV1_FWD, K_CONV2_FWD, K_CONV3_FWD, K_FC1_FWD, K_FC2_TD, K_TD_HEAD_BWD, K_FC1_WGRAD,
@@ -40,267 +25,24 @@ static const char* const kKernelNames[K_COUNT] = {
     "rmsprop"};
 constexpr size_t kProfPairs = 4096;
 
-constexpr int kMaxBatch = 1024;
-constexpr int kMaxActions = 64;
-
-// ---- small kernels ------------------------------------------------------------------------------
-
-// Dot products of one 512-vector with the A rows of fc2, one wavefront per call: lane l owns
-// k = 8l .. 8l+7; butterfly reduction (fixed order, so the result does not depend on the launch).
-// Returns Q[a] in lane a (a < A) and -inf in the other lanes.
-template <typename T>
-__device__ inline float fc2_row(const T* __restrict__ h, const T* __restrict__ w2, const float* __restrict__ b2,
-                                int A, int lane)
-{
-    typedef typename Vec8<T>::type V8;
-    const V8 hv = *reinterpret_cast<const V8*>(h + lane * 8);
-    float mine = -INFINITY;
-    for (int a = 0; a < A; ++a) {
-        const V8 wv = *reinterpret_cast<const V8*>(w2 + static_cast<size_t>(a) * 512 + lane * 8);
-        float acc = 0.f;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) acc += to_float(hv[e]) * to_float(wv[e]);
-#pragma unroll
-        for (int off = 32; off >= 1; off >>= 1) acc += __shfl_xor(acc, off, 64);
-        if (lane == a) mine = acc + b2[a];
-    }
-    return mine;
-}
-
-// argmax over the lanes of a wavefront, lowest lane on ties; result uniform across the wavefront.
-__device__ inline int wave_argmax_lowest(float v, int lane)
-{
-    int idx = lane;
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) {
-        const float ov = __shfl_xor(v, off, 64);
-        const int oi = __shfl_xor(idx, off, 64);
-        if (ov > v || (ov == v && oi < idx)) { v = ov; idx = oi; }
-    }
-    return idx;
-}
-
-// Act step tail: fc2 + epsilon-greedy, one wavefront per environment.
-template <typename T>
-__global__ __launch_bounds__(256) void fc2_act_kernel(const T* __restrict__ h, const T* __restrict__ w2,
-                                                      const float* __restrict__ b2, int W, int A, float epsilon,
-                                                      uint64_t seed, uint64_t act_step,
-                                                      int32_t* __restrict__ actions, float* __restrict__ q_out)
-{
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int j = blockIdx.x * 4 + wave;
-    if (j >= W) return;
-    const float q = fc2_row<T>(h + static_cast<size_t>(j) * 512, w2, b2, A, lane);
-    if (q_out && lane < A) q_out[static_cast<size_t>(j) * A + lane] = q;
-    const int greedy = wave_argmax_lowest(q, lane);
-    if (lane == 0) {
-        const Philox4 d = philox_draw(seed, kTagAct, act_step, static_cast<uint32_t>(j));
-        const float u = static_cast<float>(d.x[0] >> 8) * 0x1p-24f;
-        int act = greedy;
-        if (u < epsilon) act = static_cast<int>((static_cast<uint64_t>(d.x[1]) * static_cast<uint32_t>(A)) >> 32);
-        actions[j] = act;
-    }
-}
-
-// Train step head, forward half: fc2 for Q(s,.;theta), Q(s',.;theta^-) [and Q(s',.;theta)], then
-// per sample the TD target, the error, its clipped gradient and its loss term (Eq. 1).
-template <typename T>
-__global__ __launch_bounds__(256) void fc2_td_kernel(
-    const T* __restrict__ h, const T* __restrict__ w2_online, const T* __restrict__ w2_target,
-    const float* __restrict__ b2_online, const float* __restrict__ b2_target, int B, int A, int double_dqn,
-    const int32_t* __restrict__ act, const float* __restrict__ rew, const float* __restrict__ done,
-    float gamma, float huber, float* __restrict__ q_all, float* __restrict__ dqv, float* __restrict__ lossv)
-{
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int b = blockIdx.x * 4 + wave;
-    if (b >= B) return;
-    const float q_on = fc2_row<T>(h + static_cast<size_t>(b) * 512, w2_online, b2_online, A, lane);
-    const float q_nt = fc2_row<T>(h + static_cast<size_t>(B + b) * 512, w2_target, b2_target, A, lane);
-    int astar;
-    if (double_dqn) {
-        const float q_no = fc2_row<T>(h + static_cast<size_t>(2 * B + b) * 512, w2_online, b2_online, A, lane);
-        if (lane < A) q_all[(static_cast<size_t>(2) * B + b) * A + lane] = q_no;
-        astar = wave_argmax_lowest(q_no, lane);
-    } else {
-        astar = wave_argmax_lowest(q_nt, lane);
-    }
-    if (lane < A) {
-        q_all[static_cast<size_t>(b) * A + lane] = q_on;
-        q_all[(static_cast<size_t>(B) + b) * A + lane] = q_nt;
-    }
-    const float boot = __shfl(q_nt, astar, 64);
-    const float q_sa = __shfl(q_on, act[b], 64);
-    if (lane == 0) {
-        const float y = rew[b] + gamma * (1.f - done[b]) * boot;
-        const float delta = q_sa - y;
-        const float ad = fabsf(delta);
-        lossv[b] = ad <= huber ? 0.5f * delta * delta : huber * (ad - 0.5f * huber);
-        const float clipped = fminf(fmaxf(delta, -huber), huber);
-        dqv[b] = clipped / static_cast<float>(B);
-    }
-}
-
-// Train step head, backward half.  dQ has one non-zero per row (the taken action), so fc2's
-// backward is a gather: dZ_fc1[b][o] = dq_b * W2[a_b][o] * [h[b][o] > 0];
-// dW2[a][o] = sum_{b: a_b = a} dq_b h[b][o];  db2[a] = sum_{b: a_b = a} dq_b;  loss = mean_b loss_b.
-// Each block owns 64 columns o; all sums run over b in increasing order.
-template <typename T>
-__global__ __launch_bounds__(256) void td_head_bwd_kernel(
-    const T* __restrict__ h, const T* __restrict__ w2, const int32_t* __restrict__ act,
-    const float* __restrict__ dqv, const float* __restrict__ lossv, int B, int A, T* __restrict__ dzh,
-    float* __restrict__ g_w2, float* __restrict__ g_b2, float* __restrict__ loss_out, float* __restrict__ loss_keep)
-{
-    __shared__ float s_dq[kMaxBatch];
-    __shared__ int s_a[kMaxBatch];
-    for (int b = threadIdx.x; b < B; b += blockDim.x) { s_dq[b] = dqv[b]; s_a[b] = act[b]; }
-    __syncthreads();
-    const int o = blockIdx.x * 64 + (threadIdx.x & 63);
-    const int part = threadIdx.x >> 6;
-    for (int b = part; b < B; b += 4) {
-        const size_t idx = static_cast<size_t>(b) * 512 + o;
-        const float hv = to_float(h[idx]);
-        const float g = s_dq[b] * to_float(w2[static_cast<size_t>(s_a[b]) * 512 + o]);
-        dzh[idx] = hv > 0.f ? from_float<T>(g) : from_float<T>(0.f);
-    }
-    for (int a = part; a < A; a += 4) {
-        float acc = 0.f;
-        for (int b = 0; b < B; ++b)
-            if (s_a[b] == a) acc += s_dq[b] * to_float(h[static_cast<size_t>(b) * 512 + o]);
-        g_w2[static_cast<size_t>(a) * 512 + o] = acc;
-    }
-    if (blockIdx.x == 0) {
-        for (int a = threadIdx.x; a < A; a += blockDim.x) {
-            float acc = 0.f;
-            for (int b = 0; b < B; ++b)
-                if (s_a[b] == a) acc += s_dq[b];
-            g_b2[a] = acc;
-        }
-        if (threadIdx.x == 0) {
-            float acc = 0.f;
-            for (int b = 0; b < B; ++b) acc += lossv[b];
-            acc /= static_cast<float>(B);
-            *loss_keep = acc;
-            if (loss_out) *loss_out = acc;
-        }
-    }
-}
-
-// Bias gradients = column sums of the four dZ matrices ([rows][C], T).  One block per
-// (layer, group of eight channels); rows are strided over the threads and combined by a fixed tree.
-struct BiasGradArgs {
-    const void* dz[4];
-    float* out[4];
-    int rows[4];
-    int chans[4];
-    int first_block[5];
-};
-template <typename T>
-__global__ __launch_bounds__(256) void bias_grad_kernel(BiasGradArgs args)
-{
-    typedef typename Vec8<T>::type V8;
-    __shared__ float red[256][9];
-    int layer = 0;
-    while (layer < 3 && static_cast<int>(blockIdx.x) >= args.first_block[layer + 1]) ++layer;
-    const int cg = blockIdx.x - args.first_block[layer];
-    const T* dz = static_cast<const T*>(args.dz[layer]) + cg * 8;
-    const int C = args.chans[layer], rows = args.rows[layer];
-    float acc[8];
-#pragma unroll
-    for (int e = 0; e < 8; ++e) acc[e] = 0.f;
-    for (int r = threadIdx.x; r < rows; r += 256) {
-        const V8 v = *reinterpret_cast<const V8*>(dz + static_cast<size_t>(r) * C);
-#pragma unroll
-        for (int e = 0; e < 8; ++e) acc[e] += to_float(v[e]);
-    }
-#pragma unroll
-    for (int e = 0; e < 8; ++e) red[threadIdx.x][e] = acc[e];
-    __syncthreads();
-    for (int stride = 128; stride >= 1; stride >>= 1) {
-        if (static_cast<int>(threadIdx.x) < stride)
-#pragma unroll
-            for (int e = 0; e < 8; ++e) red[threadIdx.x][e] += red[threadIdx.x + stride][e];
-        __syncthreads();
-    }
-    if (threadIdx.x < 8) args.out[layer][cg * 8 + threadIdx.x] = red[0][threadIdx.x];
-}
-
-// Centered RMSProp (Appendix B) fused with the refresh of the low-precision operand copy.
-template <typename T, bool SHADOW>
-__global__ __launch_bounds__(256) void rmsprop_kernel(float* __restrict__ theta, const float* __restrict__ grad,
-                                                      float* __restrict__ v, float* __restrict__ m,
-                                                      T* __restrict__ shadow, size_t n, float lr, float alpha,
-                                                      float eps, int centered)
-{
-    const size_t n4 = n / 4;
-    const size_t i = blockIdx.x * static_cast<size_t>(blockDim.x) + threadIdx.x;
-    auto update = [&](float& th, float g, float& vv, float& mm) {
-        vv = alpha * vv + (1.f - alpha) * g * g;
-        float var = vv;
-        if (centered) {
-            mm = alpha * mm + (1.f - alpha) * g;
-            var = fmaxf(vv - mm * mm, 0.f);
-        }
-        th -= lr * g / (sqrtf(var) + eps);
-    };
-    if (i < n4) {
-        float4 th = reinterpret_cast<float4*>(theta)[i];
-        const float4 g = reinterpret_cast<const float4*>(grad)[i];
-        float4 vv = reinterpret_cast<float4*>(v)[i];
-        float4 mm = reinterpret_cast<float4*>(m)[i];
-        update(th.x, g.x, vv.x, mm.x);
-        update(th.y, g.y, vv.y, mm.y);
-        update(th.z, g.z, vv.z, mm.z);
-        update(th.w, g.w, vv.w, mm.w);
-        reinterpret_cast<float4*>(theta)[i] = th;
-        reinterpret_cast<float4*>(v)[i] = vv;
-        if (centered) reinterpret_cast<float4*>(m)[i] = mm;
-        if (SHADOW) {
-            shadow[4 * i + 0] = from_float<T>(th.x);
-            shadow[4 * i + 1] = from_float<T>(th.y);
-            shadow[4 * i + 2] = from_float<T>(th.z);
-            shadow[4 * i + 3] = from_float<T>(th.w);
-        }
-    } else if (i < n4 + (n - 4 * n4)) {
-        const size_t e = 4 * n4 + (i - n4);
-        float th = theta[e], vv = v[e], mm = m[e];
-        update(th, grad[e], vv, mm);
-        theta[e] = th; v[e] = vv;
-        if (centered) m[e] = mm;
-        if (SHADOW) shadow[e] = from_float<T>(th);
-    }
-}
-
-template <typename T>
-__global__ __launch_bounds__(256) void shadow_cast_kernel(const float* __restrict__ src, T* __restrict__ dst, size_t n)
-{
-    const size_t i = blockIdx.x * static_cast<size_t>(blockDim.x) + threadIdx.x;
-    if (i < n) dst[i] = from_float<T>(src[i]);
-}
-
-// theta^- <- theta: fp32 master (bitwise) and, if present, the operand copy.
-template <typename T, bool SHADOW>
-__global__ __launch_bounds__(256) void target_copy_kernel(const float* __restrict__ theta, float* __restrict__ theta_t,
-                                                          const T* __restrict__ sh, T* __restrict__ sh_t, size_t n)
-{
-    const size_t i = blockIdx.x * static_cast<size_t>(blockDim.x) + threadIdx.x;
-    if (i < n) {
-        theta_t[i] = theta[i];
-        if (SHADOW) sh_t[i] = sh[i];
-    }
-}
+// Layer geometries (Section 5: the Nature-DQN network).
+template <typename T> using Conv2Geo = FwdGeo<T, 32, 20, 20, 64, 9, 9, 4, 2>;
+template <typename T> using Conv3Geo = FwdGeo<T, 64, 9, 9, 64, 7, 7, 3, 1>;
+template <typename T> using Conv3DgradGeo = DgradGeo<T, 64, 9, 9, 64, 7, 7, 3, 1>;
+template <typename T> using Conv2DgradGeo = DgradGeo<T, 32, 20, 20, 64, 9, 9, 4, 2>;
 
 }  // namespace dqn
 
 using namespace dqn;
 
-// Activations / gradients of one forward+backward workspace, sized for `cap` samples per group.
+// Activations of one forward workspace, sized for `cap` samples in each of `groups` groups.
 struct Workspace {
     void* act1 = nullptr;   // [G*cap][20][20][32]
     void* act2 = nullptr;   // [G*cap][9][9][64]
     void* act3 = nullptr;   // [G*cap][7][7][64]
-    void* h = nullptr;      // [G*cap][512]
+    void* h = nullptr;      // [cap][512]  (online pass on s only)
     float* q = nullptr;     // [G*cap][A]
-    float* partial = nullptr;
+    float* partial = nullptr;   // fc1 slices [G][slices][cap][512]; split-K scratch of the weight gradients
     size_t partial_cap = 0;
 };
 
@@ -311,10 +53,13 @@ struct dqn_ctx {
     size_t esize;           // bytes per operand element
     hipStream_t act_stream, train_stream;
     float *theta = nullptr, *theta_t = nullptr, *v = nullptr, *m = nullptr, *grad = nullptr;
-    void *sh = nullptr, *sh_t = nullptr;   // operand copies; alias theta / theta_t in fp32 mode
+    void *sh = nullptr, *sh_t = nullptr;   // forward operand copies; alias theta / theta_t in fp32 mode
+    void* bsh = nullptr;                   // backward operand copies of theta
     Workspace train_ws, act_ws;
     void *dzh = nullptr, *dz3 = nullptr, *dz2 = nullptr, *dz1 = nullptr;
     float *dqv = nullptr, *lossv = nullptr, *loss_keep = nullptr;
+    float* bias_partial = nullptr;
+    unsigned int* bias_tickets = nullptr;
     hipEvent_t ev_train = nullptr, ev_act = nullptr, ev_sync = nullptr;
     bool act_reads_online = false;   // an act step with use_target = 0 is in flight
     int last_B = 0;
@@ -326,30 +71,19 @@ struct dqn_ctx {
 
 namespace dqn {
 
-static size_t partial_floats(int n, int groups)
-{
-    // generous bound: the largest split-K product used below (see pick_splits)
-    const size_t fwd = static_cast<size_t>(groups) * 64 * n * 512;          // fc1 forward, <= 64 splits
-    const size_t wg = static_cast<size_t>(512) * 64 * 576;                  // conv weight grads, <= 512 splits
-    const size_t dg = static_cast<size_t>(16) * n * 3136;                   // fc1 dgrad
-    const size_t cv = static_cast<size_t>(groups) * 8 * n * 81 * 64;        // conv2/3 forward
-    size_t best = fwd;
-    if (wg > best) best = wg;
-    if (dg > best) best = dg;
-    if (cv > best) best = cv;
-    return best;
-}
+constexpr int kMaxFc1Slices = 49;
 
-static int alloc_ws(Workspace& ws, int cap, int groups, int A, size_t esize, bool with_partial_bwd)
+static int alloc_ws(Workspace& ws, int cap, int groups, int A, size_t esize, bool training)
 {
-    (void)with_partial_bwd;
     const size_t n = static_cast<size_t>(cap) * groups;
     DQN_HIP(hipMalloc(&ws.act1, n * 12800 * esize));
     DQN_HIP(hipMalloc(&ws.act2, n * 5184 * esize));
     DQN_HIP(hipMalloc(&ws.act3, n * 3136 * esize));
-    DQN_HIP(hipMalloc(&ws.h, n * 512 * esize));
+    DQN_HIP(hipMalloc(&ws.h, static_cast<size_t>(cap) * 512 * esize));
     DQN_HIP(hipMalloc((void**)&ws.q, n * A * sizeof(float)));
-    ws.partial_cap = partial_floats(cap, groups);
+    ws.partial_cap = n * kMaxFc1Slices * 512;
+    const size_t wgrad = static_cast<size_t>(256) * 64 * 576;   // up to 256 split-K slices of the largest filter
+    if (training && ws.partial_cap < wgrad) ws.partial_cap = wgrad;
     DQN_HIP(hipMalloc((void**)&ws.partial, ws.partial_cap * sizeof(float)));
     return DQN_OK;
 }
@@ -373,77 +107,88 @@ static ProfPair prof_pair(dqn_ctx* c, int id)
     return p;
 }
 
-static int pick_splits(int tiles, int groups, int K, int BK, int max_splits)
+static int pick_splits(int tiles, int K, int BK, int max_splits)
 {
     const int target = 512;   // about two workgroups per compute unit
-    int s = target / (tiles * groups > 0 ? tiles * groups : 1);
+    int s = target / (tiles > 0 ? tiles : 1);
     const int by_k = K / (2 * BK) > 0 ? K / (2 * BK) : 1;
     if (s > by_k) s = by_k;
     if (s > max_splits) s = max_splits;
     return s < 1 ? 1 : s;
 }
 
-// Forward pass of `groups` independent (input, parameter set) pairs with n samples each, up to h.
-template <typename T>
-static int forward_to_h(dqn_ctx* c, hipStream_t st, Workspace& ws, int groups, const uint8_t* const* x,
-                        const void* const* shadow, const float* const* master, int n, bool timed)
+// Number of fc1 k-slices for n rows per group: enough workgroups to fill the chip, few enough that
+// the consumer's slice sum stays small.
+static int fc1_slices(int n, int groups)
 {
-    auto pp = [&](int id) { return timed ? prof_pair(c, id) : ProfPair(); };
+    const int row_tiles = n > 32 ? (n + 63) / 64 : 1;
+    const int blocks = 4 * row_tiles * groups;
+    int s = 256 / blocks;
+    if (s < 7) s = 7;            // 3136 / 7 = 448 columns of X per workgroup fit in LDS
+    if (s > kMaxFc1Slices) s = kMaxFc1Slices;
+    return s;
+}
+
+// Forward pass of `groups` independent (input, parameter set) pairs with n samples each, up to the
+// fc1 partial slices.  Returns the number of slices through *slices_out.
+template <typename T>
+static int forward_to_fc1(dqn_ctx* c, hipStream_t st, Workspace& ws, int groups, const uint8_t* const* x,
+                          const void* const* shadow, const float* const* master, int n, bool timed, int* slices_out)
+{
     const Offsets& o = c->off;
+    auto pp = [&](int id) { return timed ? prof_pair(c, id) : ProfPair(); };
     const size_t e_act1 = static_cast<size_t>(n) * 12800, e_act2 = static_cast<size_t>(n) * 5184;
-    const size_t e_act3 = static_cast<size_t>(n) * 3136, e_h = static_cast<size_t>(n) * 512;
-    T* act1 = static_cast<T*>(ws.act1); T* act2 = static_cast<T*>(ws.act2);
-    T* act3 = static_cast<T*>(ws.act3); T* h = static_cast<T*>(ws.h);
-    {   // conv1: [n*400, 32] = im2col(u8)[n*400, 256] x W1^T, (1/255) scale + bias + ReLU
-        Conv1A<T> al{}; DenseK<T> bl{}; EpiBiasAct<T, true> ep{};
+    const size_t e_act3 = static_cast<size_t>(n) * 3136;
+    T* act1 = static_cast<T*>(ws.act1); T* act2 = static_cast<T*>(ws.act2); T* act3 = static_cast<T*>(ws.act3);
+    {   // conv1 on the uint8 state, 1/255 folded into the epilogue
+        ConvWsArgs<T, Conv1Geo<T>> a{};
         for (int g = 0; g < groups; ++g) {
-            al.x[g] = x[g];
-            bl.p[g] = static_cast<const T*>(shadow[g]) + o.w1;
-            ep.out[g] = act1 + g * e_act1; ep.bias[g] = master[g] + o.b1;
+            a.x[g] = x[g];
+            a.w[g] = static_cast<const T*>(shadow[g]) + o.w1;
+            a.bias[g] = master[g] + o.b1;
+            a.out[g] = act1 + g * e_act1;
         }
-        bl.ld = 256; ep.ld = 32; ep.scale = 1.f / 255.f;
+        a.M = n * 400; a.scale = 1.f / 255.f;
         const ProfPair pr = pp(K_CONV1_FWD);
-        DQN_HIP((launch_gemm<T, 128, 32, 32, 4>(st, al, bl, ep, n * 400, 32, 256, groups, 1, ws.partial, ws.partial_cap,
-                                                 pr.begin, pr.end)));
+        DQN_HIP((launch_conv_ws<T, Conv1Geo<T>, kEpiBiasRelu>(st, a, groups, pr.begin, pr.end)));
     }
-    {   // conv2
-        ConvA<T, 32, 20, 20, 9, 9, 4, 2> al{}; DenseK<T> bl{}; EpiBiasAct<T, true> ep{};
+    {
+        ConvWsArgs<T, Conv2Geo<T>> a{};
         for (int g = 0; g < groups; ++g) {
-            al.x[g] = act1 + g * e_act1;
-            bl.p[g] = static_cast<const T*>(shadow[g]) + o.w2;
-            ep.out[g] = act2 + g * e_act2; ep.bias[g] = master[g] + o.b2;
+            a.x[g] = act1 + g * e_act1;
+            a.w[g] = static_cast<const T*>(shadow[g]) + o.w2;
+            a.bias[g] = master[g] + o.b2;
+            a.out[g] = act2 + g * e_act2;
         }
-        bl.ld = 512; ep.ld = 64; ep.scale = 1.f;
-        const int M = n * 81, tiles = (M + 63) / 64;
+        a.M = n * 81; a.scale = 1.f;
         const ProfPair pr = pp(K_CONV2_FWD);
-        DQN_HIP((launch_gemm<T, 64, 64, 32, 2>(st, al, bl, ep, M, 64, 512, groups, pick_splits(tiles, groups, 512, 32, 8),
-                                                ws.partial, ws.partial_cap, pr.begin, pr.end)));
+        DQN_HIP((launch_conv_ws<T, Conv2Geo<T>, kEpiBiasRelu>(st, a, groups, pr.begin, pr.end)));
     }
-    {   // conv3
-        ConvA<T, 64, 9, 9, 7, 7, 3, 1> al{}; DenseK<T> bl{}; EpiBiasAct<T, true> ep{};
+    {
+        ConvWsArgs<T, Conv3Geo<T>> a{};
         for (int g = 0; g < groups; ++g) {
-            al.x[g] = act2 + g * e_act2;
-            bl.p[g] = static_cast<const T*>(shadow[g]) + o.w3;
-            ep.out[g] = act3 + g * e_act3; ep.bias[g] = master[g] + o.b3;
+            a.x[g] = act2 + g * e_act2;
+            a.w[g] = static_cast<const T*>(shadow[g]) + o.w3;
+            a.bias[g] = master[g] + o.b3;
+            a.out[g] = act3 + g * e_act3;
         }
-        bl.ld = 576; ep.ld = 64; ep.scale = 1.f;
-        const int M = n * 49, tiles = (M + 63) / 64;
+        a.M = n * 49; a.scale = 1.f;
         const ProfPair pr = pp(K_CONV3_FWD);
-        DQN_HIP((launch_gemm<T, 64, 64, 32, 2>(st, al, bl, ep, M, 64, 576, groups, pick_splits(tiles, groups, 576, 32, 8),
-                                                ws.partial, ws.partial_cap, pr.begin, pr.end)));
+        DQN_HIP((launch_conv_ws<T, Conv3Geo<T>, kEpiBiasRelu>(st, a, groups, pr.begin, pr.end)));
     }
-    {   // fc1
-        DenseK<T> al{}; DenseK<T> bl{}; EpiBiasAct<T, true> ep{};
+    {   // fc1: k-slices of fp32 partial sums, finished by the fc2 kernels
+        FcAsArgs<T> a{};
         for (int g = 0; g < groups; ++g) {
-            al.p[g] = act3 + g * e_act3;
-            bl.p[g] = static_cast<const T*>(shadow[g]) + o.wf1;
-            ep.out[g] = h + g * e_h; ep.bias[g] = master[g] + o.bf1;
+            a.x[g] = act3 + g * e_act3;
+            a.w[g] = static_cast<const T*>(shadow[g]) + o.wf1;
         }
-        al.ld = 3136; bl.ld = 3136; ep.ld = 512; ep.scale = 1.f;
-        const int tiles = ((n + 31) / 32) * 4;
+        a.partial = ws.partial;
+        a.M = n; a.N = 512; a.ldx = 3136; a.ldw = 3136;
+        const int slices = fc1_slices(n, groups);
         const ProfPair pr = pp(K_FC1_FWD);
-        DQN_HIP((launch_gemm<T, 32, 128, 32, 1>(st, al, bl, ep, n, 512, 3136, groups, pick_splits(tiles, groups, 3136, 32, 64),
-                                                 ws.partial, ws.partial_cap, pr.begin, pr.end)));
+        int used = 0;
+        DQN_HIP((launch_fc_as<T, kFcPartial>(st, a, 3136, groups, slices, &used, pr.begin, pr.end)));
+        *slices_out = used;
     }
     return DQN_OK;
 }
@@ -455,11 +200,12 @@ static int act_impl(dqn_ctx* c, const uint8_t* states, int W, float epsilon, uin
     const uint8_t* x[1] = {states};
     const void* shadow[1] = {use_target ? c->sh_t : c->sh};
     const float* master[1] = {use_target ? c->theta_t : c->theta};
-    const int rc = forward_to_h<T>(c, c->act_stream, c->act_ws, 1, x, shadow, master, W, false);
+    int slices = 0;
+    const int rc = forward_to_fc1<T>(c, c->act_stream, c->act_ws, 1, x, shadow, master, W, false, &slices);
     if (rc != DQN_OK) return rc;
-    hipLaunchKernelGGL((fc2_act_kernel<T>), dim3((W + 3) / 4), dim3(256), 0, c->act_stream,
-                       static_cast<const T*>(c->act_ws.h), static_cast<const T*>(shadow[0]) + c->off.wf2,
-                       master[0] + c->off.bf2, W, c->A, epsilon, c->cfg.seed, act_step, actions, q_out);
+    hipLaunchKernelGGL((fc2_act_kernel<T>), dim3((W + 3) / 4), dim3(256), 0, c->act_stream, c->act_ws.partial, slices,
+                       master[0] + c->off.bf1, static_cast<const T*>(shadow[0]) + c->off.wf2, master[0] + c->off.bf2, W,
+                       c->A, epsilon, c->cfg.seed, act_step, actions, q_out);
     DQN_LAUNCH_CHECK();
     return DQN_OK;
 }
@@ -475,31 +221,33 @@ static int train_impl(dqn_ctx* c, const uint8_t* s, const int32_t* a, const floa
     const uint8_t* x[3] = {s, s2, s2};
     const void* shadow[3] = {c->sh, c->sh_t, c->sh};
     const float* master[3] = {c->theta, c->theta_t, c->theta};
-    int rc = forward_to_h<T>(c, st, ws, groups, x, shadow, master, B, true);
+    int slices = 0;
+    int rc = forward_to_fc1<T>(c, st, ws, groups, x, shadow, master, B, true, &slices);
     if (rc != DQN_OK) return rc;
 
     const T* sh = static_cast<const T*>(c->sh);
     const T* sh_t = static_cast<const T*>(c->sh_t);
+    const T* bsh = static_cast<const T*>(c->bsh);
     const T* act1 = static_cast<const T*>(ws.act1); const T* act2 = static_cast<const T*>(ws.act2);
-    const T* act3 = static_cast<const T*>(ws.act3); const T* h = static_cast<const T*>(ws.h);
+    const T* act3 = static_cast<const T*>(ws.act3); T* h = static_cast<T*>(ws.h);
     T* dzh = static_cast<T*>(c->dzh); T* dz3 = static_cast<T*>(c->dz3);
     T* dz2 = static_cast<T*>(c->dz2); T* dz1 = static_cast<T*>(c->dz1);
 
     {
         const ProfPair pr = prof_pair(c, K_FC2_TD);
         if (pr.begin) (void)hipEventRecord(pr.begin, st);
-        hipLaunchKernelGGL((fc2_td_kernel<T>), dim3((B + 3) / 4), dim3(256), 0, st, h, sh + o.wf2, sh_t + o.wf2,
-                       c->theta + o.bf2, c->theta_t + o.bf2, B, c->A, c->cfg.double_dqn, a, r, done, c->cfg.gamma,
-                       c->cfg.huber_delta, ws.q, c->dqv, c->lossv);
-    if (pr.end) (void)hipEventRecord(pr.end, st);
+        hipLaunchKernelGGL((fc2_td_kernel<T>), dim3((B + 3) / 4), dim3(256), 0, st, ws.partial, slices, c->theta + o.bf1,
+                           c->theta_t + o.bf1, sh + o.wf2, sh_t + o.wf2, c->theta + o.bf2, c->theta_t + o.bf2, B, c->A,
+                           c->cfg.double_dqn, a, r, done, c->cfg.gamma, c->cfg.huber_delta, h, ws.q, c->dqv, c->lossv);
+        if (pr.end) (void)hipEventRecord(pr.end, st);
         DQN_LAUNCH_CHECK();
     }
     {
         const ProfPair pr = prof_pair(c, K_TD_HEAD_BWD);
         if (pr.begin) (void)hipEventRecord(pr.begin, st);
         hipLaunchKernelGGL((td_head_bwd_kernel<T>), dim3(8), dim3(256), 0, st, h, sh + o.wf2, a, c->dqv, c->lossv, B, c->A,
-                       dzh, c->grad + o.wf2, c->grad + o.bf2, loss_out, c->loss_keep);
-    if (pr.end) (void)hipEventRecord(pr.end, st);
+                           dzh, c->grad + o.wf2, c->grad + o.bf2, loss_out, c->loss_keep);
+        if (pr.end) (void)hipEventRecord(pr.end, st);
         DQN_LAUNCH_CHECK();
     }
     {   // fc1 weight gradient: dW[o][f] = sum_b dZ[b][o] act3[b][f]
@@ -508,47 +256,50 @@ static int train_impl(dqn_ctx* c, const uint8_t* s, const int32_t* a, const floa
         const ProfPair pr = prof_pair(c, K_FC1_WGRAD);
         DQN_HIP((launch_gemm<T, 64, 128, 32, 2>(st, al, bl, ep, 512, 3136, B, 1, 1, ws.partial, ws.partial_cap, pr.begin, pr.end)));
     }
-    {   // fc1 data gradient through conv3's ReLU
-        DenseK<T> al{}; DenseM<T> bl{}; EpiMaskDense<T> ep{dz3, act3, 3136};
-        al.p[0] = dzh; al.ld = 512; bl.p[0] = sh + o.wf1; bl.ld = 3136;
-        const int tiles = ((B + 31) / 32) * 25;
+    {   // fc1 data gradient through conv3's ReLU: dz3[b][f] = [act3 > 0] sum_o dZ[b][o] W1[o][f]
+        FcAsArgs<T> fa{};
+        fa.x[0] = dzh; fa.w[0] = bsh + kBshWf1;
+        fa.dz = dz3; fa.mask = act3;
+        fa.M = B; fa.N = 3136; fa.ldx = 512; fa.ldw = 512;
         const ProfPair pr = prof_pair(c, K_FC1_DGRAD);
-        DQN_HIP((launch_gemm<T, 32, 128, 32, 1>(st, al, bl, ep, B, 3136, 512, 1, pick_splits(tiles, 1, 512, 32, 16),
-                                                 ws.partial, ws.partial_cap, pr.begin, pr.end)));
+        int used = 0;
+        DQN_HIP((launch_fc_as<T, kFcReluMask>(st, fa, 512, 1, 1, &used, pr.begin, pr.end)));
     }
     {   // conv3 weight gradient
         DenseM<T> al{}; WgradB<T, 64, 9, 9, 7, 7, 3, 1> bl{act2}; EpiGrad ep{c->grad + o.w3, 576, 1.f};
         al.p[0] = dz3; al.ld = 64;
         const ProfPair pr = prof_pair(c, K_CONV3_WGRAD);
-        DQN_HIP((launch_gemm<T, 64, 64, 32, 2>(st, al, bl, ep, 64, 576, B * 49, 1, pick_splits(9, 1, B * 49, 32, 512),
+        DQN_HIP((launch_gemm<T, 64, 64, 32, 2>(st, al, bl, ep, 64, 576, B * 49, 1, pick_splits(9, B * 49, 32, 64),
                                                 ws.partial, ws.partial_cap, pr.begin, pr.end)));
     }
     {   // conv3 data gradient through conv2's ReLU
-        DgradA<T, 64, 7, 7, 9, 9, 3, 1> al{dz3}; DgradB<T, 64, 64, 3, 1> bl{sh + o.w3};
-        EpiDgradMask<T, 9, 9, 64, 1> ep{dz2, act2};
-        const int M = B * 81, tiles = (M + 63) / 64;
+        ConvWsArgs<T, Conv3DgradGeo<T>> ca{};
+        ca.x[0] = dz3; ca.w[0] = bsh + kBshW3; ca.out[0] = dz2; ca.mask = act2;
+        ca.M = B * 81; ca.scale = 1.f;
         const ProfPair pr = prof_pair(c, K_CONV3_DGRAD);
-        DQN_HIP((launch_gemm<T, 64, 64, 32, 2>(st, al, bl, ep, M, 64, 576, 1, pick_splits(tiles, 1, 576, 32, 8),
-                                                ws.partial, ws.partial_cap, pr.begin, pr.end)));
+        DQN_HIP((launch_conv_ws<T, Conv3DgradGeo<T>, kEpiReluMask>(st, ca, 1, pr.begin, pr.end)));
     }
     {   // conv2 weight gradient
         DenseM<T> al{}; WgradB<T, 32, 20, 20, 9, 9, 4, 2> bl{act1}; EpiGrad ep{c->grad + o.w2, 512, 1.f};
         al.p[0] = dz2; al.ld = 64;
         const ProfPair pr = prof_pair(c, K_CONV2_WGRAD);
-        DQN_HIP((launch_gemm<T, 64, 64, 32, 2>(st, al, bl, ep, 64, 512, B * 81, 1, pick_splits(8, 1, B * 81, 32, 512),
+        DQN_HIP((launch_gemm<T, 64, 64, 32, 2>(st, al, bl, ep, 64, 512, B * 81, 1, pick_splits(8, B * 81, 32, 64),
                                                 ws.partial, ws.partial_cap, pr.begin, pr.end)));
     }
-    {   // conv2 data gradient through conv1's ReLU: four stride-parity classes
-        DgradA<T, 64, 9, 9, 20, 20, 4, 2> al{dz2}; DgradB<T, 32, 64, 4, 2> bl{sh + o.w2};
-        EpiDgradMask<T, 20, 20, 32, 2> ep{dz1, act1};
+    {   // conv2 data gradient through conv1's ReLU: one problem per stride-parity class
+        ConvWsArgs<T, Conv2DgradGeo<T>> ca{};
+        for (int g = 0; g < 4; ++g) {
+            ca.x[g] = dz2; ca.w[g] = bsh + kBshW2 + static_cast<size_t>(g) * 32 * 256; ca.out[g] = dz1;
+        }
+        ca.mask = act1; ca.M = B * 100; ca.scale = 1.f;
         const ProfPair pr = prof_pair(c, K_CONV2_DGRAD);
-        DQN_HIP((launch_gemm<T, 128, 32, 32, 4>(st, al, bl, ep, B * 100, 32, 256, 4, 1, ws.partial, ws.partial_cap, pr.begin, pr.end)));
+        DQN_HIP((launch_conv_ws<T, Conv2DgradGeo<T>, kEpiReluMask>(st, ca, 4, pr.begin, pr.end)));
     }
     {   // conv1 weight gradient (input scale 1/255 folded into the epilogue)
         DenseM<T> al{}; Conv1WgradB<T> bl{s}; EpiGrad ep{c->grad + o.w1, 256, 1.f / 255.f};
         al.p[0] = dz1; al.ld = 32;
         const ProfPair pr = prof_pair(c, K_CONV1_WGRAD);
-        DQN_HIP((launch_gemm<T, 32, 128, 32, 1>(st, al, bl, ep, 32, 256, B * 400, 1, pick_splits(2, 1, B * 400, 32, 512),
+        DQN_HIP((launch_gemm<T, 32, 128, 32, 1>(st, al, bl, ep, 32, 256, B * 400, 1, pick_splits(2, B * 400, 32, 128),
                                                  ws.partial, ws.partial_cap, pr.begin, pr.end)));
     }
     {
@@ -558,26 +309,33 @@ static int train_impl(dqn_ctx* c, const uint8_t* s, const int32_t* a, const floa
         args.dz[2] = dz3; args.out[2] = c->grad + o.b3; args.rows[2] = B * 49;  args.chans[2] = 64;
         args.dz[3] = dzh; args.out[3] = c->grad + o.bf1; args.rows[3] = B;      args.chans[3] = 512;
         args.first_block[0] = 0;
-        for (int l = 0; l < 4; ++l) args.first_block[l + 1] = args.first_block[l] + args.chans[l] / 8;
-        {
+        int pofs = 0;
+        for (int l = 0; l < 4; ++l) {
+            args.chunks[l] = (args.rows[l] + kBiasRows - 1) / kBiasRows;
+            args.first_block[l + 1] = args.first_block[l] + args.chunks[l] * (args.chans[l] / 8);
+            args.first_partial[l] = pofs;
+            pofs += args.chunks[l] * args.chans[l];
+        }
+        args.partial = c->bias_partial;
+        args.tickets = c->bias_tickets;
         const ProfPair pr = prof_pair(c, K_BIAS_GRAD);
         if (pr.begin) (void)hipEventRecord(pr.begin, st);
         hipLaunchKernelGGL((bias_grad_kernel<T>), dim3(args.first_block[4]), dim3(256), 0, st, args);
         if (pr.end) (void)hipEventRecord(pr.end, st);
         DQN_LAUNCH_CHECK();
     }
-    }
     {
-        const size_t n = o.total, threads = n / 4 + 4;
-        {
+        RmsArgs ra;
+        ra.theta = c->theta; ra.grad = c->grad; ra.v = c->v; ra.m = c->m;
+        ra.sh = SHADOW ? c->sh : nullptr; ra.bsh = c->bsh; ra.off = o;
+        ra.lr = c->cfg.lr; ra.alpha = c->cfg.rms_alpha; ra.eps = c->cfg.rms_eps; ra.centered = c->cfg.centered;
+        const size_t n_flat = o.total - static_cast<size_t>(512) * 3136;
+        ra.flat_blocks = static_cast<int>((n_flat / 4 + 4 + 255) / 256);
         const ProfPair pr = prof_pair(c, K_RMSPROP);
         if (pr.begin) (void)hipEventRecord(pr.begin, st);
-        hipLaunchKernelGGL((rmsprop_kernel<T, SHADOW>), dim3(static_cast<unsigned>((threads + 255) / 256)), dim3(256), 0,
-                           st, c->theta, c->grad, c->v, c->m, static_cast<T*>(c->sh), n, c->cfg.lr, c->cfg.rms_alpha,
-                           c->cfg.rms_eps, c->cfg.centered);
+        hipLaunchKernelGGL((rmsprop_kernel<T, SHADOW>), dim3(ra.flat_blocks + 16 * 49), dim3(256), 0, st, ra);
         if (pr.end) (void)hipEventRecord(pr.end, st);
         DQN_LAUNCH_CHECK();
-    }
     }
     return DQN_OK;
 }
@@ -674,6 +432,11 @@ int dqn_create(const dqn_config* cfg, void* act_stream, void* train_stream, dqn_
         if (rc != DQN_OK) return rc;
         rc = alloc_ws(c->act_ws, cfg->max_envs, 1, c->A, c->esize, false);
         if (rc != DQN_OK) return rc;
+        DQN_HIP(hipMalloc(&c->bsh, kBshTotal * c->esize));
+        DQN_HIP(hipMemset(c->bsh, 0, kBshTotal * c->esize));
+        DQN_HIP(hipMalloc((void**)&c->bias_partial, 65536 * sizeof(float)));
+        DQN_HIP(hipMalloc((void**)&c->bias_tickets, 4 * sizeof(unsigned int)));
+        DQN_HIP(hipMemset(c->bias_tickets, 0, 4 * sizeof(unsigned int)));
         DQN_HIP(hipMalloc(&c->dzh, B * 512 * c->esize));
         DQN_HIP(hipMalloc(&c->dz3, B * 3136 * c->esize));
         DQN_HIP(hipMalloc(&c->dz2, B * 5184 * c->esize));
@@ -710,6 +473,7 @@ int dqn_destroy(dqn_ctx* c)
     free_ws(c->train_ws); free_ws(c->act_ws);
     (void)hipFree(c->dzh); (void)hipFree(c->dz3); (void)hipFree(c->dz2); (void)hipFree(c->dz1);
     (void)hipFree(c->dqv); (void)hipFree(c->lossv); (void)hipFree(c->loss_keep);
+    (void)hipFree(c->bsh); (void)hipFree(c->bias_partial); (void)hipFree(c->bias_tickets);
     if (c->ev_train) (void)hipEventDestroy(c->ev_train);
     if (c->ev_act) (void)hipEventDestroy(c->ev_act);
     if (c->ev_sync) (void)hipEventDestroy(c->ev_sync);
@@ -731,10 +495,19 @@ int dqn_set_params(dqn_ctx* c, int which, const float* host_src, size_t n)
     permute_blob(c->off, host_src, dev.data(), true);
     float* dst = blob_of(c, which);
     DQN_HIP(hipMemcpy(dst, dev.data(), n * sizeof(float), hipMemcpyHostToDevice));
-    if (c->cfg.precision == DQN_PRECISION_BF16 && (which == DQN_PARAMS_ONLINE || which == DQN_PARAMS_TARGET)) {
-        bf16_t* sh = static_cast<bf16_t*>(which == DQN_PARAMS_ONLINE ? c->sh : c->sh_t);
-        hipLaunchKernelGGL((shadow_cast_kernel<bf16_t>), dim3(static_cast<unsigned>((n + 255) / 256)), dim3(256), 0,
-                           c->train_stream, dst, sh, n);
+    const unsigned blocks = static_cast<unsigned>((n + 255) / 256);
+    if (which == DQN_PARAMS_ONLINE) {
+        if (c->cfg.precision == DQN_PRECISION_BF16)
+            hipLaunchKernelGGL((build_copies_kernel<bf16_t, true>), dim3(blocks), dim3(256), 0, c->train_stream, dst,
+                               static_cast<bf16_t*>(c->sh), static_cast<bf16_t*>(c->bsh), c->off);
+        else
+            hipLaunchKernelGGL((build_copies_kernel<float, false>), dim3(blocks), dim3(256), 0, c->train_stream, dst,
+                               static_cast<float*>(nullptr), static_cast<float*>(c->bsh), c->off);
+        DQN_LAUNCH_CHECK();
+        DQN_HIP(hipStreamSynchronize(c->train_stream));
+    } else if (which == DQN_PARAMS_TARGET && c->cfg.precision == DQN_PRECISION_BF16) {
+        hipLaunchKernelGGL((build_copies_kernel<bf16_t, true>), dim3(blocks), dim3(256), 0, c->train_stream, dst,
+                           static_cast<bf16_t*>(c->sh_t), static_cast<bf16_t*>(nullptr), c->off);
         DQN_LAUNCH_CHECK();
         DQN_HIP(hipStreamSynchronize(c->train_stream));
     }
