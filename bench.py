@@ -6,7 +6,8 @@ W = 8 samplers, epsilon = 0.1).
 
 One "step" = 4 act steps (W states each: Q evaluation, epsilon-greedy, push of W experiences) on the
 act stream + one replay sample/gather and one train step on the train stream; every `sync_every`
-train steps the synchronisation point of Algorithm 1 (flush, theta^- <- theta).
+train steps the synchronisation point of Algorithm 1 (flush, theta^- <- theta).  As in the paper, a
+trainer thread drives the train stream while the sampler side drives the act stream.
 
 Prints ONE JSON line.  `--sweep` instead prints the batch/W sweep table (bf16 MFMA utilisation per
 kernel and gather bandwidth) as plain text.
@@ -126,6 +127,7 @@ class Workload:
         torch.cuda.synchronize()
         self.train_steps = 0
         self.act_steps = 0
+        self.prepare_raw()
 
     def _fill(self, per_lane, args):
         torch, P, synth = self.torch, self.P, self.synth
@@ -148,20 +150,78 @@ class Workload:
                 P.replay_flush(self.rb, 1)
         torch.cuda.synchronize()
 
-    def step(self):
-        """Enqueue one benchmark step (no host synchronisation)."""
-        P = self.P
-        if self.train_steps % self.sync_every == 0:
-            P.dqn_sync_target(self.ctx, self.rb, 0)
-        for _ in range(self.acts_per_train):
-            k = self.act_steps % self.pool
-            P.dqn_act(self.ctx, self.states[k], self.W, 0.1, self.act_steps, 1, self.actions, None)
-            if self.W == self.lanes:
-                P.replay_push_step(self.rb, self.new_frames[k], self.actions, self.rew[k], self.term[k])
+    def prepare_raw(self):
+        """Pre-marshalled arguments for the hot loops (pointers as plain ints)."""
+        lib = self.P.binding._lib
+        self._lib = lib
+        self._p_states = [self.states[k].data_ptr() for k in range(self.pool)]
+        self._p_frames = [self.new_frames[k].data_ptr() for k in range(self.pool)]
+        self._p_rew = [self.rew[k].data_ptr() for k in range(self.pool)]
+        self._p_term = [self.term[k].data_ptr() for k in range(self.pool)]
+        self._p_actions = self.actions.data_ptr()
+        self._p_train = (self.s.data_ptr(), self.s2.data_ptr(), self.a.data_ptr(), self.r.data_ptr(),
+                         self.d.data_ptr(), self.loss.data_ptr())
+
+    def _fail(self, what, rc):
+        raise RuntimeError("%s failed (%d): %s" % (what, rc, self.P.dqn_last_error()))
+
+    def sync_point(self):
+        """Algorithm 1: both workers are idle; flush the temporary buffers, theta^- <- theta."""
+        self.P.dqn_sync_target(self.ctx, self.rb, 0)
+
+    def act_part(self, n_train_steps):
+        """Sampler side of n train steps: acts_per_train act steps each (Q evaluation, epsilon-greedy, push)."""
+        lib, ctx, rb, W, pool = self._lib, self.ctx, self.rb, self.W, self.pool
+        push = self.W == self.lanes
+        pa = self._p_actions
+        for _ in range(n_train_steps * self.acts_per_train):
+            k = self.act_steps % pool
+            rc = lib.dqn_act(ctx, self._p_states[k], W, 0.1, self.act_steps, 1, pa, None)
+            if rc:
+                self._fail("dqn_act", rc)
+            if push:
+                rc = lib.replay_push_step(rb, self._p_frames[k], pa, self._p_rew[k], self._p_term[k])
+                if rc:
+                    self._fail("replay_push_step", rc)
             self.act_steps += 1
-        P.replay_sample_gather(self.rb, self.B, self.train_steps, None, self.s, self.s2, self.a, self.r, self.d, None)
-        P.dqn_train_step(self.ctx, self.s, self.a, self.r, self.s2, self.d, self.B, self.loss)
-        self.train_steps += 1
+
+    def train_part(self, n_train_steps):
+        """Trainer side: sample + gather + train step, n times."""
+        lib, ctx, rb, B = self._lib, self.ctx, self.rb, self.B
+        ps, ps2, pa, pr, pd, pl = self._p_train
+        for _ in range(n_train_steps):
+            rc = lib.replay_sample_gather(rb, B, self.train_steps, None, ps, ps2, pa, pr, pd, None)
+            if rc:
+                self._fail("replay_sample_gather", rc)
+            rc = lib.dqn_train_step(ctx, ps, pa, pr, ps2, pd, B, pl)
+            if rc:
+                self._fail("dqn_train_step", rc)
+            self.train_steps += 1
+
+    def run(self, steps):
+        """`steps` benchmark steps: the trainer thread and the sampler (this) thread run concurrently
+        between synchronisation points, as in Algorithm 1 (no host synchronisation with the GPU)."""
+        import threading
+        done = 0
+        while done < steps:
+            if self.train_steps % self.sync_every == 0:
+                self.sync_point()
+            n = min(steps - done, self.sync_every - self.train_steps % self.sync_every)
+            err = []
+
+            def trainer():
+                try:
+                    self.train_part(n)
+                except Exception as e:      # noqa: BLE001
+                    err.append(e)
+
+            t = threading.Thread(target=trainer)
+            t.start()
+            self.act_part(n)
+            t.join()
+            if err:
+                raise err[0]
+            done += n
 
     def close(self):
         self.torch.cuda.synchronize()
@@ -173,8 +233,7 @@ def time_steps(wl, steps):
     torch = wl.torch
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(steps):
-        wl.step()
+    wl.run(steps)
     torch.cuda.synchronize()
     return time.perf_counter() - t0
 
@@ -185,8 +244,7 @@ def kernel_breakdown(wl, steps_each):
     out = {}
     for kid in range(1, P.dqn_profile_kernel_count() + 1):
         P.dqn_profile_select(wl.ctx, kid)
-        for _ in range(steps_each):
-            wl.step()
+        wl.run(steps_each)
         ms, n = P.dqn_profile_read(wl.ctx)
         out[P.dqn_profile_kernel_name(kid)] = ms / max(n, 1)
     P.dqn_profile_select(wl.ctx, 0)

@@ -167,7 +167,7 @@ __global__ __launch_bounds__(WAVES * 64) void conv_ws_kernel(ConvWsArgs<T, Geo> 
     extern __shared__ __attribute__((aligned(32))) unsigned char ws_smem[];
     T* sW = reinterpret_cast<T*>(ws_smem);
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int g = blockIdx.y;
     {
         const T* wg = a.w[g];
@@ -221,6 +221,7 @@ __global__ __launch_bounds__(WAVES * 64) void conv_ws_kernel(ConvWsArgs<T, Geo> 
         for (int s = 0; s < PD; ++s)
 #pragma unroll
             for (int t = 0; t < TP; ++t) ring[s][t] = fetch(s, t);
+        __builtin_amdgcn_sched_barrier(0);   // keep the whole ring in flight
 #pragma unroll
         for (int ks = 0; ks < KSTEPS; ++ks) {
             V8 cur[TP];
@@ -229,6 +230,7 @@ __global__ __launch_bounds__(WAVES * 64) void conv_ws_kernel(ConvWsArgs<T, Geo> 
             if (ks + PD < KSTEPS) {
 #pragma unroll
                 for (int t = 0; t < TP; ++t) ring[ks % PD][t] = fetch(ks + PD, t);
+                __builtin_amdgcn_sched_barrier(0);   // refill issued before this k-step's MFMAs
             }
 #pragma unroll
             for (int n = 0; n < TN; ++n) {
@@ -267,6 +269,94 @@ __global__ __launch_bounds__(WAVES * 64) void conv_ws_kernel(ConvWsArgs<T, Geo> 
     }
 }
 
+// Small-problem variant (an act step over W environments, a batch-32 train step): one workgroup per
+// 32-pixel tile, the four wavefronts split K between them, both operands go straight from global
+// memory (L2) into MFMA operand registers -- with one tile per workgroup there is no weight reuse
+// that LDS staging could serve -- and the four partial accumulators meet in LDS, added in wavefront
+// order.  Short dependent chains instead of one wavefront walking all of K.
+template <typename T, class Geo, int EPI>
+__global__ __launch_bounds__(256) void conv_sk_kernel(ConvWsArgs<T, Geo> a)
+{
+    typedef typename Vec8<T>::type V8;
+    typedef typename Geo::In In;
+    constexpr int N = Geo::N, K = Geo::K, KSTEPS = Geo::KSTEPS, TN = N / 32;
+    constexpr int KQ = KSTEPS / 4;
+    static_assert(KSTEPS % 4 == 0, "k-steps must split over four wavefronts");
+    __shared__ float red[4][TN * 16][64];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int g = blockIdx.y, tile = blockIdx.x;
+    const int lane_px = lane & 31, kg = lane >> 5;
+    const int r = tile * 32 + lane_px;
+    const bool live = r < a.M;
+    RowInfo ri = Geo::row(g, live ? r : 0);
+    if (!live && Geo::kPredicated) ri.tapmask = 0u;
+    const In* xg = a.x[g];
+    const In* px = xg + ri.in_off + kg * Geo::kLaneStep;
+    const T* wl = a.w[g] + static_cast<size_t>(lane_px) * K + kg * 8;
+
+    V8 pf[KQ], wf[KQ][TN];
+#pragma unroll
+    for (int s = 0; s < KQ; ++s) {
+        const int ks = wave * KQ + s;          // runtime k-step: offsets via the constexpr tables below
+        int koff = 0, tap = 0;
+#pragma unroll
+        for (int w = 0; w < 4; ++w)
+            if (w == wave) { koff = Geo::koff(w * KQ + s); tap = Geo::tap(w * KQ + s); }
+        if constexpr (Geo::kPredicated) {
+            const bool ok = (ri.tapmask >> tap) & 1u;
+            const V8 v = FragLoad<T, In>::get(ok ? px + koff : xg);
+            pf[s] = ok ? v : vec8_zero<T>();
+        } else {
+            pf[s] = FragLoad<T, In>::get(px + koff);
+        }
+#pragma unroll
+        for (int n = 0; n < TN; ++n) wf[s][n] = *reinterpret_cast<const V8*>(wl + static_cast<size_t>(n) * 32 * K + ks * 16);
+    }
+    __builtin_amdgcn_sched_barrier(0);   // every operand load is issued before the first MFMA waits
+    f32x16 acc[TN];
+#pragma unroll
+    for (int n = 0; n < TN; ++n)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[n][v] = 0.f;
+#pragma unroll
+    for (int s = 0; s < KQ; ++s)
+#pragma unroll
+        for (int n = 0; n < TN; ++n) mma_32x32x16(acc[n], wf[s][n], pf[s]);
+
+#pragma unroll
+    for (int n = 0; n < TN; ++n)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) red[wave][n * 16 + v][lane] = acc[n][v];
+    __syncthreads();
+    if (!live) return;
+    // quad (n, q) = four consecutive channels; the TN*4 quads are dealt round-robin to the wavefronts
+    T* og = a.out[g];
+    for (int quad = wave; quad < TN * 4; quad += 4) {
+        const int n = quad / 4, q = quad % 4;
+        const int ch = n * 32 + 8 * q + 4 * kg;
+        float v[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int idx = n * 16 + 4 * q + e;
+            v[e] = ((red[0][idx][lane] + red[1][idx][lane]) + red[2][idx][lane]) + red[3][idx][lane];
+        }
+        if constexpr (EPI == kEpiBiasRelu) {
+            const float4 bv = *reinterpret_cast<const float4*>(a.bias[g] + ch);
+            v[0] = fmaxf(v[0] * a.scale + bv.x, 0.f);
+            v[1] = fmaxf(v[1] * a.scale + bv.y, 0.f);
+            v[2] = fmaxf(v[2] * a.scale + bv.z, 0.f);
+            v[3] = fmaxf(v[3] * a.scale + bv.w, 0.f);
+        } else {
+            float m[4];
+            load4<T>(a.mask + ri.out_off + ch, m);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v[e] = m[e] > 0.f ? v[e] : 0.f;
+        }
+        store4<T>(og + ri.out_off + ch, v[0], v[1], v[2], v[3]);
+    }
+}
+
 template <typename T, class Geo> constexpr size_t conv_ws_smem() { return static_cast<size_t>(Geo::N) * (Geo::K + 8) * sizeof(T); }
 
 // Launches the kernel over `groups` independent problems of M rows each.
@@ -279,7 +369,10 @@ inline hipError_t launch_conv_ws(hipStream_t st, const ConvWsArgs<T, Geo>& a, in
     const int max_blocks = 512 / (groups > 0 ? groups : 1);   // persistent grid: about two workgroups per CU
     hipError_t e = hipSuccess;
     if (ev_begin) (void)hipEventRecord(ev_begin, st);
-    if (a.M >= 256 * 64) {
+    const int tiles32 = (a.M + 31) / 32;
+    if (tiles32 * groups <= 1024) {
+        hipLaunchKernelGGL((conv_sk_kernel<T, Geo, EPI>), dim3(tiles32, groups), dim3(256), 0, st, a);
+    } else if (a.M >= 256 * 64) {
         constexpr int TP = 2;
         auto kern = conv_ws_kernel<T, Geo, EPI, TP, WAVES>;
         static bool attr_set = false;

@@ -35,7 +35,7 @@ __global__ __launch_bounds__(WAVES * 64) void fc_as_kernel(FcAsArgs<T> a)
     extern __shared__ __attribute__((aligned(32))) unsigned char as_smem[];
     T* sX = reinterpret_cast<T*>(as_smem);
     const int ldk = a.kc + 8;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int g = blockIdx.z / a.slices, slice = blockIdx.z % a.slices;
     const int m0 = blockIdx.y * (TB * 32);
     const int k0 = slice * a.kc;
@@ -72,6 +72,7 @@ __global__ __launch_bounds__(WAVES * 64) void fc_as_kernel(FcAsArgs<T> a)
 #pragma unroll
             for (int s = 0; s < 4; ++s) nxt[s] = *reinterpret_cast<const V8*>(wp + kk + 64 + s * 16);
         }
+        __builtin_amdgcn_sched_barrier(0);   // next chunk's weight fragments in flight before the MFMAs
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
 #pragma unroll

@@ -74,7 +74,7 @@ constexpr int kLdsPad = 8;  // elements of padding per LDS row
 template <typename T, class AL, class BL, class EP, int BM, int BN, int BK, int WGM>
 __global__ __launch_bounds__(kGemmThreads) void gemm_nt_kernel(AL al, BL bl, EP ep, int M, int N, int K,
                                                                int k_per_split, int n_tiles,
-                                                               float* __restrict__ partial)
+                                                               float* __restrict__ partial, int always_partial)
 {
     typedef typename Vec8<T>::type V8;
     constexpr int WGN = 4 / WGM;
@@ -178,7 +178,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_nt_kernel(AL al, BL bl, EP 
         }
     }
 
-    const bool to_partial = gridDim.y > 1;
+    const bool to_partial = gridDim.y > 1 || always_partial;
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -215,8 +215,10 @@ __global__ __launch_bounds__(256) void splitk_finalize_kernel(EP ep, const float
 template <typename T, int BM, int BN, int BK, int WGM, class AL, class BL, class EP>
 inline hipError_t launch_gemm(hipStream_t st, const AL& al, const BL& bl, const EP& ep, int M, int N, int K,
                               int groups, int want_splits, float* partial, size_t partial_capacity,
-                              hipEvent_t ev_begin = nullptr, hipEvent_t ev_end = nullptr)
+                              hipEvent_t ev_begin = nullptr, hipEvent_t ev_end = nullptr, int* splits_deferred = nullptr)
 {
+    // splits_deferred != nullptr: always write partial sums [split][M][N], skip the reduction pass and
+    // report the number of splits; the caller's consumer kernel adds them in split order.
     const int m_tiles = (M + BM - 1) / BM, n_tiles = (N + BN - 1) / BN;
     int splits = want_splits < 1 ? 1 : want_splits;
     int kps = ((K + splits - 1) / splits + BK - 1) / BK * BK;
@@ -226,13 +228,14 @@ inline hipError_t launch_gemm(hipStream_t st, const AL& al, const BL& bl, const 
         splits = (K + kps - 1) / kps;
     }
     if (splits == 1) kps = (K + BK - 1) / BK * BK;
+    if (splits_deferred) *splits_deferred = splits;
     if (ev_begin) (void)hipEventRecord(ev_begin, st);   // optional timing of the main kernel only
     hipLaunchKernelGGL((gemm_nt_kernel<T, AL, BL, EP, BM, BN, BK, WGM>), dim3(m_tiles * n_tiles, splits, groups),
-                       dim3(kGemmThreads), 0, st, al, bl, ep, M, N, K, kps, n_tiles, partial);
+                       dim3(kGemmThreads), 0, st, al, bl, ep, M, N, K, kps, n_tiles, partial, splits_deferred ? 1 : 0);
     hipError_t e = hipGetLastError();
     if (ev_end) (void)hipEventRecord(ev_end, st);
     if (e != hipSuccess) return e;
-    if (splits > 1) {
+    if (splits > 1 && !splits_deferred) {
         const size_t mn = static_cast<size_t>(M) * N;
         hipLaunchKernelGGL((splitk_finalize_kernel<EP>), dim3(static_cast<unsigned>((mn + 255) / 256), groups),
                            dim3(256), 0, st, ep, partial, splits, M, N);

@@ -45,139 +45,164 @@ __host__ __device__ inline size_t bsh_index_w3(int r)
     return kBshW3 + (static_cast<size_t>(c) * 9 + p * 3 + q) * 64 + oc;
 }
 
-// h[b][8l .. 8l+7] for lane l: sum of the fc1 partial slices in slice order, + bias, ReLU, rounded
-// to the operand type (so that forward and backward see the same h).
-template <typename T>
-__device__ inline typename Vec8<T>::type fc1_finish(const float* __restrict__ partial, int slices, size_t slice_stride,
-                                                    const float* __restrict__ bias, int lane)
-{
-    float acc[8];
-#pragma unroll
-    for (int e = 0; e < 8; ++e) acc[e] = 0.f;
-    const float* p = partial + lane * 8;
-    for (int s = 0; s < slices; ++s) {
-        const float4 lo = *reinterpret_cast<const float4*>(p + s * slice_stride);
-        const float4 hi = *reinterpret_cast<const float4*>(p + s * slice_stride + 4);
-        acc[0] += lo.x; acc[1] += lo.y; acc[2] += lo.z; acc[3] += lo.w;
-        acc[4] += hi.x; acc[5] += hi.y; acc[6] += hi.z; acc[7] += hi.w;
-    }
-    const float4 blo = *reinterpret_cast<const float4*>(bias + lane * 8);
-    const float4 bhi = *reinterpret_cast<const float4*>(bias + lane * 8 + 4);
-    const float bv[8] = {blo.x, blo.y, blo.z, blo.w, bhi.x, bhi.y, bhi.z, bhi.w};
-    typename Vec8<T>::type h;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) h[e] = from_float<T>(fmaxf(acc[e] + bv[e], 0.f));
-    return h;
-}
+// ---- network head, forward: finish fc1, fc2 on the matrix cores, then action selection (act step)
+// or TD target / error / loss (train step, Eq. 1) -------------------------------------------------
+//
+// A workgroup owns kHeadRows samples.  Per group (parameter set x input): (1) every thread finishes
+// 16 features of fc1 -- adds the k-slices in slice order, bias, ReLU, rounds to the operand type (so
+// forward and backward see the same h) -- into an LDS tile; (2) the four wavefronts each take a
+// quarter of K = 512 of the fc2 product as 32x32 MFMAs (A = W2 rows straight from global memory,
+// B = the h tile), partial accumulators meet in LDS and are added in wavefront order; (3) Q rows land
+// in LDS.  The tail runs one thread per sample.
+constexpr int kHeadRows = 8;
 
-// Q[a] = b2[a] + <h, W2[a]> for all a, one wavefront: lane l owns k = 8l .. 8l+7; butterfly sums
-// (fixed order).  Returns Q[a] in lane a (a < A) and -inf elsewhere.
-template <typename T>
-__device__ inline float fc2_row(const typename Vec8<T>::type& hv, const T* __restrict__ w2, const float* __restrict__ b2,
-                                int A, int lane)
+struct HeadArgs {
+    const float* partial;        // [groups][slices][rows][512]
+    int slices, rows, A, groups;
+    const float* b1[3];
+    const void* w2[3];           // T [A][512]
+    const float* b2[3];
+    // act step
+    float epsilon;
+    uint64_t seed, act_step;
+    int32_t* actions;
+    float* q_out;                // [rows][A] or null
+    // train step
+    int double_dqn;
+    const int32_t* act;
+    const float* rew;
+    const float* done;
+    float gamma, huber;
+    void* h_online;              // T [rows][512]
+    float* q_all;                // [groups][rows][A]
+    float* dqv;
+    float* lossv;
+};
+
+constexpr int kHeadAct = 0, kHeadTrain = 1;
+
+template <typename T, int MODE>
+__global__ __launch_bounds__(256) void head_fwd_kernel(HeadArgs a)
 {
     typedef typename Vec8<T>::type V8;
-    float mine = -INFINITY;
-    for (int a0 = 0; a0 < A; a0 += 6) {
-        V8 wv[6];
-#pragma unroll
-        for (int u = 0; u < 6; ++u) {
-            const int a = a0 + u < A ? a0 + u : A - 1;
-            wv[u] = *reinterpret_cast<const V8*>(w2 + static_cast<size_t>(a) * 512 + lane * 8);
-        }
-#pragma unroll
-        for (int u = 0; u < 6; ++u) {
-            float acc = 0.f;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) acc += to_float(hv[e]) * to_float(wv[u][e]);
-#pragma unroll
-            for (int off = 32; off >= 1; off >>= 1) acc += __shfl_xor(acc, off, 64);
-            if (a0 + u < A && lane == a0 + u) mine = acc + b2[a0 + u];
-        }
-    }
-    return mine;
-}
+    constexpr int LDH = 512 + 8;
+    __shared__ __attribute__((aligned(32))) T s_h[kHeadRows * LDH];
+    __shared__ float s_red[4][16][64];
+    __shared__ float s_q[3][kHeadRows][kMaxActions];
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int row0 = blockIdx.x * kHeadRows;
+    const size_t sstride = static_cast<size_t>(a.rows) * 512, gstride = sstride * a.slices;
 
-// argmax over the lanes of a wavefront, lowest lane on ties; result uniform across the wavefront.
-__device__ inline int wave_argmax_lowest(float v, int lane)
-{
-    int idx = lane;
+    for (int g = 0; g < a.groups; ++g) {
+        // (1) finish fc1: thread -> (sample r = tid / 32, features 16 * (tid % 32) .. + 15)
+        {
+            const int r = tid >> 5, f0 = (tid & 31) * 16;
+            const int row = row0 + r;
+            float acc[16];
 #pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) {
-        const float ov = __shfl_xor(v, off, 64);
-        const int oi = __shfl_xor(idx, off, 64);
-        if (ov > v || (ov == v && oi < idx)) { v = ov; idx = oi; }
+            for (int e = 0; e < 16; ++e) acc[e] = 0.f;
+            if (row < a.rows) {
+                const float* p = a.partial + g * gstride + static_cast<size_t>(row) * 512 + f0;
+                for (int s0 = 0; s0 < a.slices; s0 += 4) {
+                    float4 v[4][4];
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        const int s = s0 + u < a.slices ? s0 + u : a.slices - 1;
+#pragma unroll
+                        for (int c = 0; c < 4; ++c) v[u][c] = *reinterpret_cast<const float4*>(p + s * sstride + 4 * c);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                    for (int u = 0; u < 4; ++u)
+                        if (s0 + u < a.slices) {
+#pragma unroll
+                            for (int c = 0; c < 4; ++c) {
+                                acc[4 * c + 0] += v[u][c].x; acc[4 * c + 1] += v[u][c].y;
+                                acc[4 * c + 2] += v[u][c].z; acc[4 * c + 3] += v[u][c].w;
+                            }
+                        }
+                }
+                const float* bp = a.b1[g] + f0;
+#pragma unroll
+                for (int e = 0; e < 16; ++e) acc[e] = fmaxf(acc[e] + bp[e], 0.f);
+            }
+            V8 lo, hi;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) { lo[e] = from_float<T>(acc[e]); hi[e] = from_float<T>(acc[8 + e]); }
+            *reinterpret_cast<V8*>(&s_h[r * LDH + f0]) = lo;
+            *reinterpret_cast<V8*>(&s_h[r * LDH + f0 + 8]) = hi;
+            if (MODE == kHeadTrain && g == 0 && row < a.rows) {
+                T* hp = static_cast<T*>(a.h_online) + static_cast<size_t>(row) * 512 + f0;
+                *reinterpret_cast<V8*>(hp) = lo;
+                *reinterpret_cast<V8*>(hp + 8) = hi;
+            }
+        }
+        __syncthreads();
+        // (2) fc2: wavefront `wave` covers k = 128 * wave .. + 127
+        {
+            const int lr = lane & 31, kg = lane >> 5;
+            const int arow = lr < a.A ? lr : a.A - 1;
+            const T* wp = static_cast<const T*>(a.w2[g]) + static_cast<size_t>(arow) * 512 + wave * 128 + kg * 8;
+            V8 wf[8];
+#pragma unroll
+            for (int s = 0; s < 8; ++s) wf[s] = *reinterpret_cast<const V8*>(wp + s * 16);
+            __builtin_amdgcn_sched_barrier(0);
+            f32x16 acc;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+#pragma unroll
+            for (int s = 0; s < 8; ++s) {
+                V8 hf = vec8_zero<T>();
+                if (lr < kHeadRows) hf = *reinterpret_cast<const V8*>(&s_h[lr * LDH + wave * 128 + s * 16 + kg * 8]);
+                mma_32x32x16(acc, wf[s], hf);
+            }
+#pragma unroll
+            for (int v = 0; v < 16; ++v) s_red[wave][v][lane] = acc[v];
+        }
+        __syncthreads();
+        // (3) lanes 0..7 and 32..39 of the accumulator layout hold the live samples: action index
+        //     8*(v/4) + 4*(lane/32) + (v%4), sample lane % 32
+        if (tid < 64 && (tid & 31) < kHeadRows) {
+            const int r = tid & 31, kg = tid >> 5;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int act_i = 8 * (v >> 2) + 4 * kg + (v & 3);
+                if (act_i < a.A)
+                    s_q[g][r][act_i] = (((s_red[0][v][tid] + s_red[1][v][tid]) + s_red[2][v][tid]) + s_red[3][v][tid]) + a.b2[g][act_i];
+            }
+        }
+        __syncthreads();
     }
-    return idx;
-}
 
-// Act step tail: finish fc1, fc2, epsilon-greedy; one wavefront per environment.
-template <typename T>
-__global__ __launch_bounds__(256) void fc2_act_kernel(const float* __restrict__ partial, int slices, const float* __restrict__ b1,
-                                                      const T* __restrict__ w2, const float* __restrict__ b2, int W, int A,
-                                                      float epsilon, uint64_t seed, uint64_t act_step,
-                                                      int32_t* __restrict__ actions, float* __restrict__ q_out)
-{
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int j = blockIdx.x * 4 + wave;
-    if (j >= W) return;
-    const typename Vec8<T>::type hv =
-        fc1_finish<T>(partial + static_cast<size_t>(j) * 512, slices, static_cast<size_t>(W) * 512, b1, lane);
-    const float q = fc2_row<T>(hv, w2, b2, A, lane);
-    if (q_out && lane < A) q_out[static_cast<size_t>(j) * A + lane] = q;
-    const int greedy = wave_argmax_lowest(q, lane);
-    if (lane == 0) {
-        const Philox4 d = philox_draw(seed, kTagAct, act_step, static_cast<uint32_t>(j));
+    if (tid >= kHeadRows) return;
+    const int row = row0 + tid;
+    if (row >= a.rows) return;
+    auto argmax_lowest = [&](const float* q) {
+        int best = 0;
+        for (int k = 1; k < a.A; ++k)
+            if (q[k] > q[best]) best = k;
+        return best;
+    };
+    if (MODE == kHeadAct) {
+        const float* q = s_q[0][tid];
+        if (a.q_out)
+            for (int k = 0; k < a.A; ++k) a.q_out[static_cast<size_t>(row) * a.A + k] = q[k];
+        const Philox4 d = philox_draw(a.seed, kTagAct, a.act_step, static_cast<uint32_t>(row));
         const float u = static_cast<float>(d.x[0] >> 8) * 0x1p-24f;
-        int act = greedy;
-        if (u < epsilon) act = static_cast<int>((static_cast<uint64_t>(d.x[1]) * static_cast<uint32_t>(A)) >> 32);
-        actions[j] = act;
-    }
-}
-
-// Train step head, forward half: finish fc1 and run fc2 for Q(s,.;theta), Q(s',.;theta^-) [and
-// Q(s',.;theta)], then per sample the TD target, the error, its clipped gradient and its loss term.
-// partial: [groups][slices][B][512].  Stores h of the online pass on s for the backward half.
-template <typename T>
-__global__ __launch_bounds__(256) void fc2_td_kernel(
-    const float* __restrict__ partial, int slices, const float* __restrict__ b1_online, const float* __restrict__ b1_target,
-    const T* __restrict__ w2_online, const T* __restrict__ w2_target, const float* __restrict__ b2_online,
-    const float* __restrict__ b2_target, int B, int A, int double_dqn, const int32_t* __restrict__ act,
-    const float* __restrict__ rew, const float* __restrict__ done, float gamma, float huber, T* __restrict__ h_online,
-    float* __restrict__ q_all, float* __restrict__ dqv, float* __restrict__ lossv)
-{
-    typedef typename Vec8<T>::type V8;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int b = blockIdx.x * 4 + wave;
-    if (b >= B) return;
-    const size_t sstride = static_cast<size_t>(B) * 512, gstride = sstride * slices;
-    const V8 h0 = fc1_finish<T>(partial + static_cast<size_t>(b) * 512, slices, sstride, b1_online, lane);
-    *reinterpret_cast<V8*>(h_online + static_cast<size_t>(b) * 512 + lane * 8) = h0;
-    const V8 h1 = fc1_finish<T>(partial + gstride + static_cast<size_t>(b) * 512, slices, sstride, b1_target, lane);
-    const float q_on = fc2_row<T>(h0, w2_online, b2_online, A, lane);
-    const float q_nt = fc2_row<T>(h1, w2_target, b2_target, A, lane);
-    int astar;
-    if (double_dqn) {
-        const V8 h2 = fc1_finish<T>(partial + 2 * gstride + static_cast<size_t>(b) * 512, slices, sstride, b1_online, lane);
-        const float q_no = fc2_row<T>(h2, w2_online, b2_online, A, lane);
-        if (lane < A) q_all[(static_cast<size_t>(2) * B + b) * A + lane] = q_no;
-        astar = wave_argmax_lowest(q_no, lane);
+        int act = argmax_lowest(q);
+        if (u < a.epsilon) act = static_cast<int>((static_cast<uint64_t>(d.x[1]) * static_cast<uint32_t>(a.A)) >> 32);
+        a.actions[row] = act;
     } else {
-        astar = wave_argmax_lowest(q_nt, lane);
-    }
-    if (lane < A) {
-        q_all[static_cast<size_t>(b) * A + lane] = q_on;
-        q_all[(static_cast<size_t>(B) + b) * A + lane] = q_nt;
-    }
-    const float boot = __shfl(q_nt, astar, 64);
-    const float q_sa = __shfl(q_on, act[b], 64);
-    if (lane == 0) {
-        const float y = rew[b] + gamma * (1.f - done[b]) * boot;
-        const float delta = q_sa - y;
+        for (int g = 0; g < a.groups; ++g)
+            for (int k = 0; k < a.A; ++k) a.q_all[(static_cast<size_t>(g) * a.rows + row) * a.A + k] = s_q[g][tid][k];
+        const float* qt = s_q[1][tid];
+        const int astar = a.double_dqn ? argmax_lowest(s_q[2][tid]) : argmax_lowest(qt);
+        const float y = a.rew[row] + a.gamma * (1.f - a.done[row]) * qt[astar];
+        const float delta = s_q[0][tid][a.act[row]] - y;
         const float ad = fabsf(delta);
-        lossv[b] = ad <= huber ? 0.5f * delta * delta : huber * (ad - 0.5f * huber);
-        const float clipped = fminf(fmaxf(delta, -huber), huber);
-        dqv[b] = clipped / static_cast<float>(B);
+        a.lossv[row] = ad <= a.huber ? 0.5f * delta * delta : a.huber * (ad - 0.5f * a.huber);
+        const float clipped = fminf(fmaxf(delta, -a.huber), a.huber);
+        a.dqv[row] = clipped / static_cast<float>(a.rows);
     }
 }
 
@@ -241,31 +266,28 @@ __global__ __launch_bounds__(256) void td_head_bwd_kernel(
     }
 }
 
-// Bias gradients = column sums of the four dZ matrices ([rows][C], T).  A block sums up to
-// kBiasRows rows of eight channels; the block that finishes a layer last adds the per-block sums in
-// block order, so the result does not depend on scheduling.
+// Bias gradients = column sums of the four dZ matrices ([rows][C], T), first stage: a block sums up
+// to kBiasRows rows of eight channels into partial[layer][chunk][C].  The optimiser kernel adds the
+// chunks in order (second stage), so no atomics and no extra launch are needed.
 constexpr int kBiasRows = 1024;
 struct BiasGradArgs {
     const void* dz[4];
-    float* out[4];
     int rows[4];
     int chans[4];
     int chunks[4];
     int first_block[5];
     int first_partial[4];   // offsets into `partial` (floats)
     float* partial;
-    unsigned int* tickets;  // [4], zero between launches
 };
 template <typename T>
 __global__ __launch_bounds__(256) void bias_grad_kernel(BiasGradArgs args)
 {
     typedef typename Vec8<T>::type V8;
     __shared__ float red[256][9];
-    __shared__ bool is_last;
     int layer = 0;
     while (layer < 3 && static_cast<int>(blockIdx.x) >= args.first_block[layer + 1]) ++layer;
     const int local = blockIdx.x - args.first_block[layer];
-    const int C = args.chans[layer], rows = args.rows[layer], cgs = C / 8, chunks = args.chunks[layer];
+    const int C = args.chans[layer], rows = args.rows[layer], cgs = C / 8;
     const int cg = local % cgs, chunk = local / cgs;
     const T* dz = static_cast<const T*>(args.dz[layer]) + cg * 8;
     const int r_end = min(rows, (chunk + 1) * kBiasRows);
@@ -286,24 +308,8 @@ __global__ __launch_bounds__(256) void bias_grad_kernel(BiasGradArgs args)
             for (int e = 0; e < 8; ++e) red[threadIdx.x][e] += red[threadIdx.x + stride][e];
         __syncthreads();
     }
-    float* part = args.partial + args.first_partial[layer];
-    if (threadIdx.x < 8) part[chunk * C + cg * 8 + threadIdx.x] = red[0][threadIdx.x];
-    __threadfence();
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        const unsigned int t = atomicAdd(&args.tickets[layer], 1u);
-        is_last = (t == static_cast<unsigned int>(cgs * chunks - 1));
-    }
-    __syncthreads();
-    if (is_last) {
-        __threadfence();
-        for (int c = threadIdx.x; c < C; c += 256) {
-            float sum = 0.f;
-            for (int k = 0; k < chunks; ++k) sum += __hip_atomic_load(&part[k * C + c], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            args.out[layer][c] = sum;
-        }
-        if (threadIdx.x == 0) args.tickets[layer] = 0u;
-    }
+    if (threadIdx.x < 8)
+        args.partial[args.first_partial[layer] + chunk * C + cg * 8 + threadIdx.x] = red[0][threadIdx.x];
 }
 
 // ---- optimiser --------------------------------------------------------------------------------
@@ -318,8 +324,26 @@ struct RmsArgs {
     Offsets off;
     float lr, alpha, eps;
     int centered;
-    int flat_blocks; // blocks [0, flat_blocks) are elementwise, the rest are fc1.w tiles
+    int flat_blocks; // blocks [0, flat_blocks) are elementwise, then 16*49 fc1.w tiles, then the bias blocks
+    // second stage of the bias gradients (conv1..3, fc1): chunk sums written by bias_grad_kernel
+    const float* bias_partial;
+    int bias_chunks[4];
+    int bias_first[4];
+    // deferred split-K sums of the conv weight gradients: [splits][tensor] fp32 each
+    const float* wg_partial[3];
+    int wg_splits[3];
+    float wg_scale[3];
 };
+
+// Index of the hidden-layer bias vector that blob element e belongs to, or -1.
+__device__ inline int hidden_bias_layer(const Offsets& o, size_t e)
+{
+    if (e >= o.b1 && e < o.w2) return 0;
+    if (e >= o.b2 && e < o.w3) return 1;
+    if (e >= o.b3 && e < o.wf1) return 2;
+    if (e >= o.bf1 && e < o.wf2) return 3;
+    return -1;
+}
 
 __device__ inline void rms_update(const RmsArgs& a, float& th, float g, float& vv, float& mm)
 {
@@ -355,8 +379,29 @@ __global__ __launch_bounds__(256) void rmsprop_kernel(RmsArgs a)
         auto to_blob = [&](size_t f) { return f < a.off.wf1 ? f : f + static_cast<size_t>(512) * 3136; };
         if (i < n4) {
             const size_t e = to_blob(4 * i);
+            if (hidden_bias_layer(a.off, e) >= 0) return;   // bias vectors are 4-aligned: handled by the bias blocks
             float4 th = *reinterpret_cast<float4*>(a.theta + e);
-            const float4 g = *reinterpret_cast<const float4*>(a.grad + e);
+            float4 g;
+            int conv = -1;
+            size_t r = 0, tsize = 0;
+            if (e < a.off.b1) { conv = 0; r = e - a.off.w1; tsize = 32 * 256; }
+            else if (e >= a.off.w2 && e < a.off.b2) { conv = 1; r = e - a.off.w2; tsize = 64 * 512; }
+            else if (e >= a.off.w3 && e < a.off.b3) { conv = 2; r = e - a.off.w3; tsize = 64 * 576; }
+            if (conv >= 0) {
+                // conv weight gradient: add the split-K slices in order, keep the sum for readers of the gradient
+                const float* p = a.wg_partial[conv] + r;
+                float4 sum = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll 4
+                for (int s = 0; s < a.wg_splits[conv]; ++s) {
+                    const float4 v4 = *reinterpret_cast<const float4*>(p + s * tsize);
+                    sum.x += v4.x; sum.y += v4.y; sum.z += v4.z; sum.w += v4.w;
+                }
+                const float sc = a.wg_scale[conv];
+                g = make_float4(sum.x * sc, sum.y * sc, sum.z * sc, sum.w * sc);
+                *reinterpret_cast<float4*>(const_cast<float*>(a.grad) + e) = g;
+            } else {
+                g = *reinterpret_cast<const float4*>(a.grad + e);
+            }
             float4 vv = *reinterpret_cast<float4*>(a.v + e);
             float4 mm = *reinterpret_cast<float4*>(a.m + e);
             rms_update(a, th.x, g.x, vv.x, mm.x);
@@ -379,6 +424,29 @@ __global__ __launch_bounds__(256) void rmsprop_kernel(RmsArgs a)
             if (a.centered) a.m[e] = mm;
             publish<T, SHADOW>(a, e, th);
         }
+        return;
+    }
+    if (static_cast<int>(blockIdx.x) >= a.flat_blocks + 16 * 49) {
+        // hidden-layer biases: finish the gradient (chunk sums in order), then update
+        const int idx = (blockIdx.x - a.flat_blocks - 16 * 49) * 256 + tid;   // 0 .. 671
+        if (idx >= 32 + 64 + 64 + 512) return;
+        int layer, c;
+        size_t e;
+        if (idx < 32) { layer = 0; c = idx; e = a.off.b1 + c; }
+        else if (idx < 96) { layer = 1; c = idx - 32; e = a.off.b2 + c; }
+        else if (idx < 160) { layer = 2; c = idx - 96; e = a.off.b3 + c; }
+        else { layer = 3; c = idx - 160; e = a.off.bf1 + c; }
+        const int C = layer == 0 ? 32 : (layer == 3 ? 512 : 64);
+        const float* part = a.bias_partial + a.bias_first[layer] + c;
+        float g = 0.f;
+        for (int k = 0; k < a.bias_chunks[layer]; ++k) g += part[k * C];
+        const_cast<float*>(a.grad)[e] = g;
+        float th = a.theta[e], vv = a.v[e], mm = a.m[e];
+        rms_update(a, th, g, vv, mm);
+        a.theta[e] = th;
+        a.v[e] = vv;
+        if (a.centered) a.m[e] = mm;
+        if (SHADOW) static_cast<T*>(a.sh)[e] = from_float<T>(th);
         return;
     }
     // fc1.w tile: rows o0 .. o0+31, columns f0 .. f0+63

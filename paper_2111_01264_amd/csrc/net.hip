@@ -59,7 +59,7 @@ struct dqn_ctx {
     void *dzh = nullptr, *dz3 = nullptr, *dz2 = nullptr, *dz1 = nullptr;
     float *dqv = nullptr, *lossv = nullptr, *loss_keep = nullptr;
     float* bias_partial = nullptr;
-    unsigned int* bias_tickets = nullptr;
+    float* wg_partial = nullptr;
     hipEvent_t ev_train = nullptr, ev_act = nullptr, ev_sync = nullptr;
     bool act_reads_online = false;   // an act step with use_target = 0 is in flight
     int last_B = 0;
@@ -72,6 +72,10 @@ struct dqn_ctx {
 namespace dqn {
 
 constexpr int kMaxFc1Slices = 49;
+// deferred split-K scratch of the three conv weight gradients
+constexpr size_t kWgMaxSplits = 64;
+constexpr size_t kWgOff1 = 0, kWgOff2 = kWgMaxSplits * 32 * 256, kWgOff3 = kWgOff2 + kWgMaxSplits * 64 * 512;
+constexpr size_t kWgTotal = kWgOff3 + kWgMaxSplits * 64 * 576;
 
 static int alloc_ws(Workspace& ws, int cap, int groups, int A, size_t esize, bool training)
 {
@@ -123,7 +127,7 @@ static int fc1_slices(int n, int groups)
 {
     const int row_tiles = n > 32 ? (n + 63) / 64 : 1;
     const int blocks = 4 * row_tiles * groups;
-    int s = 256 / blocks;
+    int s = 64 / blocks;         // few slices: the head kernel re-reads every slice
     if (s < 7) s = 7;            // 3136 / 7 = 448 columns of X per workgroup fit in LDS
     if (s > kMaxFc1Slices) s = kMaxFc1Slices;
     return s;
@@ -203,9 +207,11 @@ static int act_impl(dqn_ctx* c, const uint8_t* states, int W, float epsilon, uin
     int slices = 0;
     const int rc = forward_to_fc1<T>(c, c->act_stream, c->act_ws, 1, x, shadow, master, W, false, &slices);
     if (rc != DQN_OK) return rc;
-    hipLaunchKernelGGL((fc2_act_kernel<T>), dim3((W + 3) / 4), dim3(256), 0, c->act_stream, c->act_ws.partial, slices,
-                       master[0] + c->off.bf1, static_cast<const T*>(shadow[0]) + c->off.wf2, master[0] + c->off.bf2, W,
-                       c->A, epsilon, c->cfg.seed, act_step, actions, q_out);
+    HeadArgs ha{};
+    ha.partial = c->act_ws.partial; ha.slices = slices; ha.rows = W; ha.A = c->A; ha.groups = 1;
+    ha.b1[0] = master[0] + c->off.bf1; ha.w2[0] = static_cast<const T*>(shadow[0]) + c->off.wf2; ha.b2[0] = master[0] + c->off.bf2;
+    ha.epsilon = epsilon; ha.seed = c->cfg.seed; ha.act_step = act_step; ha.actions = actions; ha.q_out = q_out;
+    hipLaunchKernelGGL((head_fwd_kernel<T, kHeadAct>), dim3((W + kHeadRows - 1) / kHeadRows), dim3(256), 0, c->act_stream, ha);
     DQN_LAUNCH_CHECK();
     return DQN_OK;
 }
@@ -233,12 +239,19 @@ static int train_impl(dqn_ctx* c, const uint8_t* s, const int32_t* a, const floa
     T* dzh = static_cast<T*>(c->dzh); T* dz3 = static_cast<T*>(c->dz3);
     T* dz2 = static_cast<T*>(c->dz2); T* dz1 = static_cast<T*>(c->dz1);
 
+    int wg_splits[3] = {1, 1, 1};
     {
         const ProfPair pr = prof_pair(c, K_FC2_TD);
         if (pr.begin) (void)hipEventRecord(pr.begin, st);
-        hipLaunchKernelGGL((fc2_td_kernel<T>), dim3((B + 3) / 4), dim3(256), 0, st, ws.partial, slices, c->theta + o.bf1,
-                           c->theta_t + o.bf1, sh + o.wf2, sh_t + o.wf2, c->theta + o.bf2, c->theta_t + o.bf2, B, c->A,
-                           c->cfg.double_dqn, a, r, done, c->cfg.gamma, c->cfg.huber_delta, h, ws.q, c->dqv, c->lossv);
+        HeadArgs ha{};
+        ha.partial = ws.partial; ha.slices = slices; ha.rows = B; ha.A = c->A; ha.groups = groups;
+        for (int g = 0; g < groups; ++g) {
+            ha.b1[g] = master[g] + o.bf1; ha.w2[g] = static_cast<const T*>(shadow[g]) + o.wf2; ha.b2[g] = master[g] + o.bf2;
+        }
+        ha.double_dqn = c->cfg.double_dqn; ha.act = a; ha.rew = r; ha.done = done;
+        ha.gamma = c->cfg.gamma; ha.huber = c->cfg.huber_delta;
+        ha.h_online = h; ha.q_all = ws.q; ha.dqv = c->dqv; ha.lossv = c->lossv;
+        hipLaunchKernelGGL((head_fwd_kernel<T, kHeadTrain>), dim3((B + kHeadRows - 1) / kHeadRows), dim3(256), 0, st, ha);
         if (pr.end) (void)hipEventRecord(pr.end, st);
         DQN_LAUNCH_CHECK();
     }
@@ -270,7 +283,7 @@ static int train_impl(dqn_ctx* c, const uint8_t* s, const int32_t* a, const floa
         al.p[0] = dz3; al.ld = 64;
         const ProfPair pr = prof_pair(c, K_CONV3_WGRAD);
         DQN_HIP((launch_gemm<T, 64, 64, 32, 2>(st, al, bl, ep, 64, 576, B * 49, 1, pick_splits(9, B * 49, 32, 64),
-                                                ws.partial, ws.partial_cap, pr.begin, pr.end)));
+                                                c->wg_partial + kWgOff3, kWgMaxSplits * 64 * 576, pr.begin, pr.end, &wg_splits[2])));
     }
     {   // conv3 data gradient through conv2's ReLU
         ConvWsArgs<T, Conv3DgradGeo<T>> ca{};
@@ -284,7 +297,7 @@ static int train_impl(dqn_ctx* c, const uint8_t* s, const int32_t* a, const floa
         al.p[0] = dz2; al.ld = 64;
         const ProfPair pr = prof_pair(c, K_CONV2_WGRAD);
         DQN_HIP((launch_gemm<T, 64, 64, 32, 2>(st, al, bl, ep, 64, 512, B * 81, 1, pick_splits(8, B * 81, 32, 64),
-                                                ws.partial, ws.partial_cap, pr.begin, pr.end)));
+                                                c->wg_partial + kWgOff2, kWgMaxSplits * 64 * 512, pr.begin, pr.end, &wg_splits[1])));
     }
     {   // conv2 data gradient through conv1's ReLU: one problem per stride-parity class
         ConvWsArgs<T, Conv2DgradGeo<T>> ca{};
@@ -296,18 +309,19 @@ static int train_impl(dqn_ctx* c, const uint8_t* s, const int32_t* a, const floa
         DQN_HIP((launch_conv_ws<T, Conv2DgradGeo<T>, kEpiReluMask>(st, ca, 4, pr.begin, pr.end)));
     }
     {   // conv1 weight gradient (input scale 1/255 folded into the epilogue)
-        DenseM<T> al{}; Conv1WgradB<T> bl{s}; EpiGrad ep{c->grad + o.w1, 256, 1.f / 255.f};
+        DenseM<T> al{}; Conv1WgradB<T> bl{s}; EpiGrad ep{c->grad + o.w1, 256, 1.f};
         al.p[0] = dz1; al.ld = 32;
         const ProfPair pr = prof_pair(c, K_CONV1_WGRAD);
-        DQN_HIP((launch_gemm<T, 32, 128, 32, 1>(st, al, bl, ep, 32, 256, B * 400, 1, pick_splits(2, B * 400, 32, 128),
-                                                 ws.partial, ws.partial_cap, pr.begin, pr.end)));
+        DQN_HIP((launch_gemm<T, 32, 128, 32, 1>(st, al, bl, ep, 32, 256, B * 400, 1, pick_splits(2, B * 400, 32, kWgMaxSplits),
+                                                 c->wg_partial + kWgOff1, kWgMaxSplits * 32 * 256, pr.begin, pr.end, &wg_splits[0])));
     }
+    int bias_chunks[4], bias_first[4];
     {
         BiasGradArgs args;
-        args.dz[0] = dz1; args.out[0] = c->grad + o.b1; args.rows[0] = B * 400; args.chans[0] = 32;
-        args.dz[1] = dz2; args.out[1] = c->grad + o.b2; args.rows[1] = B * 81;  args.chans[1] = 64;
-        args.dz[2] = dz3; args.out[2] = c->grad + o.b3; args.rows[2] = B * 49;  args.chans[2] = 64;
-        args.dz[3] = dzh; args.out[3] = c->grad + o.bf1; args.rows[3] = B;      args.chans[3] = 512;
+        args.dz[0] = dz1; args.rows[0] = B * 400; args.chans[0] = 32;
+        args.dz[1] = dz2; args.rows[1] = B * 81;  args.chans[1] = 64;
+        args.dz[2] = dz3; args.rows[2] = B * 49;  args.chans[2] = 64;
+        args.dz[3] = dzh; args.rows[3] = B;       args.chans[3] = 512;
         args.first_block[0] = 0;
         int pofs = 0;
         for (int l = 0; l < 4; ++l) {
@@ -317,7 +331,7 @@ static int train_impl(dqn_ctx* c, const uint8_t* s, const int32_t* a, const floa
             pofs += args.chunks[l] * args.chans[l];
         }
         args.partial = c->bias_partial;
-        args.tickets = c->bias_tickets;
+        for (int l = 0; l < 4; ++l) { bias_chunks[l] = args.chunks[l]; bias_first[l] = args.first_partial[l]; }
         const ProfPair pr = prof_pair(c, K_BIAS_GRAD);
         if (pr.begin) (void)hipEventRecord(pr.begin, st);
         hipLaunchKernelGGL((bias_grad_kernel<T>), dim3(args.first_block[4]), dim3(256), 0, st, args);
@@ -331,9 +345,15 @@ static int train_impl(dqn_ctx* c, const uint8_t* s, const int32_t* a, const floa
         ra.lr = c->cfg.lr; ra.alpha = c->cfg.rms_alpha; ra.eps = c->cfg.rms_eps; ra.centered = c->cfg.centered;
         const size_t n_flat = o.total - static_cast<size_t>(512) * 3136;
         ra.flat_blocks = static_cast<int>((n_flat / 4 + 4 + 255) / 256);
+        ra.wg_partial[0] = c->wg_partial + kWgOff1; ra.wg_partial[1] = c->wg_partial + kWgOff2;
+        ra.wg_partial[2] = c->wg_partial + kWgOff3;
+        for (int l = 0; l < 3; ++l) { ra.wg_splits[l] = wg_splits[l]; ra.wg_scale[l] = 1.f; }
+        ra.wg_scale[0] = 1.f / 255.f;   // conv1 reads raw bytes: the input scale is applied to its gradient here
+        ra.bias_partial = c->bias_partial;
+        for (int l = 0; l < 4; ++l) { ra.bias_chunks[l] = bias_chunks[l]; ra.bias_first[l] = bias_first[l]; }
         const ProfPair pr = prof_pair(c, K_RMSPROP);
         if (pr.begin) (void)hipEventRecord(pr.begin, st);
-        hipLaunchKernelGGL((rmsprop_kernel<T, SHADOW>), dim3(ra.flat_blocks + 16 * 49), dim3(256), 0, st, ra);
+        hipLaunchKernelGGL((rmsprop_kernel<T, SHADOW>), dim3(ra.flat_blocks + 16 * 49 + 3), dim3(256), 0, st, ra);
         if (pr.end) (void)hipEventRecord(pr.end, st);
         DQN_LAUNCH_CHECK();
     }
@@ -435,8 +455,7 @@ int dqn_create(const dqn_config* cfg, void* act_stream, void* train_stream, dqn_
         DQN_HIP(hipMalloc(&c->bsh, kBshTotal * c->esize));
         DQN_HIP(hipMemset(c->bsh, 0, kBshTotal * c->esize));
         DQN_HIP(hipMalloc((void**)&c->bias_partial, 65536 * sizeof(float)));
-        DQN_HIP(hipMalloc((void**)&c->bias_tickets, 4 * sizeof(unsigned int)));
-        DQN_HIP(hipMemset(c->bias_tickets, 0, 4 * sizeof(unsigned int)));
+        DQN_HIP(hipMalloc((void**)&c->wg_partial, kWgTotal * sizeof(float)));
         DQN_HIP(hipMalloc(&c->dzh, B * 512 * c->esize));
         DQN_HIP(hipMalloc(&c->dz3, B * 3136 * c->esize));
         DQN_HIP(hipMalloc(&c->dz2, B * 5184 * c->esize));
@@ -473,7 +492,7 @@ int dqn_destroy(dqn_ctx* c)
     free_ws(c->train_ws); free_ws(c->act_ws);
     (void)hipFree(c->dzh); (void)hipFree(c->dz3); (void)hipFree(c->dz2); (void)hipFree(c->dz1);
     (void)hipFree(c->dqv); (void)hipFree(c->lossv); (void)hipFree(c->loss_keep);
-    (void)hipFree(c->bsh); (void)hipFree(c->bias_partial); (void)hipFree(c->bias_tickets);
+    (void)hipFree(c->bsh); (void)hipFree(c->bias_partial); (void)hipFree(c->wg_partial);
     if (c->ev_train) (void)hipEventDestroy(c->ev_train);
     if (c->ev_act) (void)hipEventDestroy(c->ev_act);
     if (c->ev_sync) (void)hipEventDestroy(c->ev_sync);
