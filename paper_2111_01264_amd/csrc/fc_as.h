@@ -109,6 +109,73 @@ __global__ __launch_bounds__(WAVES * 64) void fc_as_kernel(FcAsArgs<T> a)
     }
 }
 
+// Small-batch variant (at most 32 rows of X): one workgroup per (32 output features, K slice), its
+// four wavefronts split the slice between them, both operands go straight from global memory into
+// MFMA registers and the partial accumulators meet in LDS, added in wavefront order.  Streaming the
+// 3.2 MB of fc1 weights within a few microseconds takes ~100 compute units pulling at once, hence
+// the K slices across workgroups; like the large-batch kernel it then writes fp32 slices
+// [group][slice][M][N] that the consumer adds in slice order.  (Finishing inside this kernel through
+// a last-workgroup ticket was tried and is several times slower: the device-scope fence it needs
+// writes back the L2 of the issuing XCD.)
+template <typename T> struct FcSkArgs {
+    const T* x[kMaxGroups];      // [M][ldx], M <= 32
+    const T* w[kMaxGroups];      // [N][ldw]
+    float* partial;              // kFcPartial: [group][slice][M][N] fp32
+    T* dz;                       // kFcReluMask: [M][N]
+    const T* mask;               // kFcReluMask: activation indexed like dz
+    int M, N, ldx, ldw;
+};
+
+template <typename T, int EPI, int KPW, int KSLICES>
+__global__ __launch_bounds__(256) void fc_sk_kernel(FcSkArgs<T> a)
+{
+    typedef typename Vec8<T>::type V8;
+    static_assert(EPI == kFcPartial || KSLICES == 1, "only partial sums can be split over workgroups");
+    __shared__ float red[4][16][64];
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int g = blockIdx.y, n0 = blockIdx.x * 32, slice = blockIdx.z;
+    const int lr = lane & 31, kg = lane >> 5;
+    const int n = n0 + lr;
+    const int k0 = (slice * 4 + wave) * (KPW * 16) + kg * 8;
+    const T* wp = a.w[g] + static_cast<size_t>(n < a.N ? n : 0) * a.ldw + k0;
+    const bool x_ok = lr < a.M;
+    const T* xp = a.x[g] + static_cast<size_t>(x_ok ? lr : 0) * a.ldx + k0;
+    V8 wf[KPW], xf[KPW];
+#pragma unroll
+    for (int s = 0; s < KPW; ++s) {
+        wf[s] = *reinterpret_cast<const V8*>(wp + s * 16);
+        xf[s] = *reinterpret_cast<const V8*>(xp + s * 16);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    f32x16 acc;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+#pragma unroll
+    for (int s = 0; s < KPW; ++s) mma_32x32x16(acc, wf[s], x_ok ? xf[s] : vec8_zero<T>());
+#pragma unroll
+    for (int v = 0; v < 16; ++v) red[wave][v][lane] = acc[v];
+    __syncthreads();
+    // thread t owns accumulator slots (v, l) = (4*(t/64) + e, t%64), e = 0..3: one quad of features
+    const int q = tid >> 6, l = tid & 63;
+    float v4[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+        v4[e] = ((red[0][4 * q + e][l] + red[1][4 * q + e][l]) + red[2][4 * q + e][l]) + red[3][4 * q + e][l];
+    const int sample = l & 31;
+    const int nn = n0 + 8 * q + 4 * (l >> 5);
+    if (sample >= a.M || nn >= a.N) return;
+    if constexpr (EPI == kFcPartial) {
+        float* dst = a.partial + ((static_cast<size_t>(g) * KSLICES + slice) * a.M + sample) * a.N + nn;
+        *reinterpret_cast<float4*>(dst) = make_float4(v4[0], v4[1], v4[2], v4[3]);
+    } else {
+        const size_t idx = static_cast<size_t>(sample) * a.N + nn;
+        float m[4];
+        load4<T>(a.mask + idx, m);
+        store4<T>(a.dz + idx, m[0] > 0.f ? v4[0] : 0.f, m[1] > 0.f ? v4[1] : 0.f, m[2] > 0.f ? v4[2] : 0.f,
+                  m[3] > 0.f ? v4[3] : 0.f);
+    }
+}
+
 template <typename T, int EPI>
 inline hipError_t launch_fc_as(hipStream_t st, FcAsArgs<T> a, int K, int groups, int want_slices, int* slices_used,
                                hipEvent_t ev_begin = nullptr, hipEvent_t ev_end = nullptr)

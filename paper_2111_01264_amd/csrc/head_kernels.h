@@ -48,13 +48,15 @@ __host__ __device__ inline size_t bsh_index_w3(int r)
 // ---- network head, forward: finish fc1, fc2 on the matrix cores, then action selection (act step)
 // or TD target / error / loss (train step, Eq. 1) -------------------------------------------------
 //
-// A workgroup owns kHeadRows samples.  Per group (parameter set x input): (1) every thread finishes
-// 16 features of fc1 -- adds the k-slices in slice order, bias, ReLU, rounds to the operand type (so
-// forward and backward see the same h) -- into an LDS tile; (2) the four wavefronts each take a
-// quarter of K = 512 of the fc2 product as 32x32 MFMAs (A = W2 rows straight from global memory,
-// B = the h tile), partial accumulators meet in LDS and are added in wavefront order; (3) Q rows land
-// in LDS.  The tail runs one thread per sample.
-constexpr int kHeadRows = 8;
+// fc1 arrives as k-slices of fp32 partial sums [groups][slices][rows][512].  A workgroup owns
+// kHeadRows samples (few rows per workgroup: the slice sums are plain loads, and what bounds them is
+// how many compute units pull at once).  (1) Thread t finishes four features of one row for every
+// group -- slices added in slice order, bias, ReLU, rounded to the operand type so that forward and
+// backward see the same h -- into an LDS tile; the fc2 weight fragments are requested before that,
+// so both latencies overlap.  (2) Per group the four wavefronts each take a quarter of K = 512 of
+// the fc2 product as 32x32 MFMAs (A = W2 rows, B = the h tile); the partial accumulators meet in LDS
+// and are added in wavefront order.  (3) One thread per sample runs the tail.
+constexpr int kHeadRows = 2;
 
 struct HeadArgs {
     const float* partial;        // [groups][slices][rows][512]
@@ -73,7 +75,7 @@ struct HeadArgs {
     const float* rew;
     const float* done;
     float gamma, huber;
-    void* h_online;              // T [rows][512]
+    void* h_online;              // T [rows][512]: h of group 0, kept for the backward pass
     float* q_all;                // [groups][rows][A]
     float* dqv;
     float* lossv;
@@ -85,94 +87,89 @@ template <typename T, int MODE>
 __global__ __launch_bounds__(256) void head_fwd_kernel(HeadArgs a)
 {
     typedef typename Vec8<T>::type V8;
+    constexpr int G = MODE == kHeadAct ? 1 : 3;
     constexpr int LDH = 512 + 8;
-    __shared__ __attribute__((aligned(32))) T s_h[kHeadRows * LDH];
+    __shared__ __attribute__((aligned(32))) T s_h[G][kHeadRows][LDH];
     __shared__ float s_red[4][16][64];
-    __shared__ float s_q[3][kHeadRows][kMaxActions];
+    __shared__ float s_q[G][kHeadRows][kMaxActions + 1];
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int row0 = blockIdx.x * kHeadRows;
-    const size_t sstride = static_cast<size_t>(a.rows) * 512, gstride = sstride * a.slices;
+    const int lr = lane & 31, kg = lane >> 5;
+    const int arow = lr < a.A ? lr : a.A - 1;
 
-    for (int g = 0; g < a.groups; ++g) {
-        // (1) finish fc1: thread -> (sample r = tid / 32, features 16 * (tid % 32) .. + 15)
-        {
-            const int r = tid >> 5, f0 = (tid & 31) * 16;
-            const int row = row0 + r;
-            float acc[16];
+    // fc2 weight fragments of every group: requested first, consumed last
+    V8 wf[G][8];
 #pragma unroll
-            for (int e = 0; e < 16; ++e) acc[e] = 0.f;
-            if (row < a.rows) {
-                const float* p = a.partial + g * gstride + static_cast<size_t>(row) * 512 + f0;
-                for (int s0 = 0; s0 < a.slices; s0 += 4) {
-                    float4 v[4][4];
-#pragma unroll
-                    for (int u = 0; u < 4; ++u) {
-                        const int s = s0 + u < a.slices ? s0 + u : a.slices - 1;
-#pragma unroll
-                        for (int c = 0; c < 4; ++c) v[u][c] = *reinterpret_cast<const float4*>(p + s * sstride + 4 * c);
-                    }
-                    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-                    for (int u = 0; u < 4; ++u)
-                        if (s0 + u < a.slices) {
-#pragma unroll
-                            for (int c = 0; c < 4; ++c) {
-                                acc[4 * c + 0] += v[u][c].x; acc[4 * c + 1] += v[u][c].y;
-                                acc[4 * c + 2] += v[u][c].z; acc[4 * c + 3] += v[u][c].w;
-                            }
-                        }
-                }
-                const float* bp = a.b1[g] + f0;
-#pragma unroll
-                for (int e = 0; e < 16; ++e) acc[e] = fmaxf(acc[e] + bp[e], 0.f);
-            }
-            V8 lo, hi;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) { lo[e] = from_float<T>(acc[e]); hi[e] = from_float<T>(acc[8 + e]); }
-            *reinterpret_cast<V8*>(&s_h[r * LDH + f0]) = lo;
-            *reinterpret_cast<V8*>(&s_h[r * LDH + f0 + 8]) = hi;
-            if (MODE == kHeadTrain && g == 0 && row < a.rows) {
-                T* hp = static_cast<T*>(a.h_online) + static_cast<size_t>(row) * 512 + f0;
-                *reinterpret_cast<V8*>(hp) = lo;
-                *reinterpret_cast<V8*>(hp + 8) = hi;
-            }
-        }
-        __syncthreads();
-        // (2) fc2: wavefront `wave` covers k = 128 * wave .. + 127
-        {
-            const int lr = lane & 31, kg = lane >> 5;
-            const int arow = lr < a.A ? lr : a.A - 1;
+    for (int g = 0; g < G; ++g)
+        if (g < a.groups) {
             const T* wp = static_cast<const T*>(a.w2[g]) + static_cast<size_t>(arow) * 512 + wave * 128 + kg * 8;
-            V8 wf[8];
 #pragma unroll
-            for (int s = 0; s < 8; ++s) wf[s] = *reinterpret_cast<const V8*>(wp + s * 16);
-            __builtin_amdgcn_sched_barrier(0);
+            for (int s = 0; s < 8; ++s) wf[g][s] = *reinterpret_cast<const V8*>(wp + s * 16);
+        }
+
+    // (1) finish fc1: thread -> (row r = tid / 128, features 4 * (tid % 128) .. + 3)
+    {
+        const int r = tid >> 7, f0 = (tid & 127) * 4;
+        const int row = row0 + r;
+        const size_t sstride = static_cast<size_t>(a.rows) * 512, gstride = sstride * a.slices;
+#pragma unroll
+        for (int g = 0; g < G; ++g)
+            if (g < a.groups) {
+                float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (row < a.rows) {
+                    const float* p = a.partial + g * gstride + static_cast<size_t>(row) * 512 + f0;
+                    for (int s0 = 0; s0 < a.slices; s0 += 7) {
+                        float4 v[7];
+#pragma unroll
+                        for (int u = 0; u < 7; ++u) {
+                            const int s = s0 + u < a.slices ? s0 + u : a.slices - 1;
+                            v[u] = *reinterpret_cast<const float4*>(p + s * sstride);
+                        }
+#pragma unroll
+                        for (int u = 0; u < 7; ++u)
+                            if (s0 + u < a.slices) { acc.x += v[u].x; acc.y += v[u].y; acc.z += v[u].z; acc.w += v[u].w; }
+                    }
+                    const float4 bv = *reinterpret_cast<const float4*>(a.b1[g] + f0);
+                    acc.x = fmaxf(acc.x + bv.x, 0.f); acc.y = fmaxf(acc.y + bv.y, 0.f);
+                    acc.z = fmaxf(acc.z + bv.z, 0.f); acc.w = fmaxf(acc.w + bv.w, 0.f);
+                }
+                store4<T>(&s_h[g][r][f0], acc.x, acc.y, acc.z, acc.w);
+                if (MODE == kHeadTrain && g == 0 && row < a.rows)
+                    store4<T>(static_cast<T*>(a.h_online) + static_cast<size_t>(row) * 512 + f0, acc.x, acc.y, acc.z, acc.w);
+            }
+    }
+    __syncthreads();
+    // (2) fc2 per group; (3) Q rows to LDS
+#pragma unroll
+    for (int g = 0; g < G; ++g)
+        if (g < a.groups) {
             f32x16 acc;
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[v] = 0.f;
 #pragma unroll
             for (int s = 0; s < 8; ++s) {
                 V8 hf = vec8_zero<T>();
-                if (lr < kHeadRows) hf = *reinterpret_cast<const V8*>(&s_h[lr * LDH + wave * 128 + s * 16 + kg * 8]);
-                mma_32x32x16(acc, wf[s], hf);
+                if (lr < kHeadRows) hf = *reinterpret_cast<const V8*>(&s_h[g][lr][wave * 128 + s * 16 + kg * 8]);
+                mma_32x32x16(acc, wf[g][s], hf);
             }
+            if (g > 0) __syncthreads();   // s_red is free again
 #pragma unroll
             for (int v = 0; v < 16; ++v) s_red[wave][v][lane] = acc[v];
-        }
-        __syncthreads();
-        // (3) lanes 0..7 and 32..39 of the accumulator layout hold the live samples: action index
-        //     8*(v/4) + 4*(lane/32) + (v%4), sample lane % 32
-        if (tid < 64 && (tid & 31) < kHeadRows) {
-            const int r = tid & 31, kg = tid >> 5;
+            __syncthreads();
+            // accumulator layout: sample lane % 32, action 8*(v/4) + 4*(lane/32) + (v%4); wavefront w sums quad w
+            if (lr < kHeadRows) {
+                const int q = wave;
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int act_i = 8 * (v >> 2) + 4 * kg + (v & 3);
-                if (act_i < a.A)
-                    s_q[g][r][act_i] = (((s_red[0][v][tid] + s_red[1][v][tid]) + s_red[2][v][tid]) + s_red[3][v][tid]) + a.b2[g][act_i];
+                for (int e = 0; e < 4; ++e) {
+                    const int act_i = 8 * q + 4 * kg + e;
+                    const int v = 4 * q + e;
+                    if (act_i < a.A)
+                        s_q[g][lr][act_i] =
+                            (((s_red[0][v][lane] + s_red[1][v][lane]) + s_red[2][v][lane]) + s_red[3][v][lane]) + a.b2[g][act_i];
+                }
             }
         }
-        __syncthreads();
-    }
+    __syncthreads();
 
     if (tid >= kHeadRows) return;
     const int row = row0 + tid;
@@ -183,7 +180,7 @@ __global__ __launch_bounds__(256) void head_fwd_kernel(HeadArgs a)
             if (q[k] > q[best]) best = k;
         return best;
     };
-    if (MODE == kHeadAct) {
+    if constexpr (MODE == kHeadAct) {
         const float* q = s_q[0][tid];
         if (a.q_out)
             for (int k = 0; k < a.A; ++k) a.q_out[static_cast<size_t>(row) * a.A + k] = q[k];

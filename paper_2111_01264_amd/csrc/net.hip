@@ -40,10 +40,11 @@ struct Workspace {
     void* act1 = nullptr;   // [G*cap][20][20][32]
     void* act2 = nullptr;   // [G*cap][9][9][64]
     void* act3 = nullptr;   // [G*cap][7][7][64]
-    void* h = nullptr;      // [cap][512]  (online pass on s only)
+    void* h = nullptr;      // [cap][512]: fc1 output of the online pass on s (kept for the backward pass)
     float* q = nullptr;     // [G*cap][A]
-    float* partial = nullptr;   // fc1 slices [G][slices][cap][512]; split-K scratch of the weight gradients
+    float* partial = nullptr;   // fc1 k-slices
     size_t partial_cap = 0;
+
 };
 
 struct dqn_ctx {
@@ -134,7 +135,7 @@ static int fc1_slices(int n, int groups)
 }
 
 // Forward pass of `groups` independent (input, parameter set) pairs with n samples each, up to the
-// fc1 partial slices.  Returns the number of slices through *slices_out.
+// fc1 k-slices; the number of slices comes back through *slices_out.
 template <typename T>
 static int forward_to_fc1(dqn_ctx* c, hipStream_t st, Workspace& ws, int groups, const uint8_t* const* x,
                           const void* const* shadow, const float* const* master, int n, bool timed, int* slices_out)
@@ -180,7 +181,22 @@ static int forward_to_fc1(dqn_ctx* c, hipStream_t st, Workspace& ws, int groups,
         const ProfPair pr = pp(K_CONV3_FWD);
         DQN_HIP((launch_conv_ws<T, Conv3Geo<T>, kEpiBiasRelu>(st, a, groups, pr.begin, pr.end)));
     }
-    {   // fc1: k-slices of fp32 partial sums, finished by the fc2 kernels
+    // fc1 as k-slices of fp32 partial sums [groups][slices][n][512]; the head kernel adds them
+    if (n <= 32) {
+        FcSkArgs<T> a{};
+        for (int g = 0; g < groups; ++g) {
+            a.x[g] = act3 + g * e_act3;
+            a.w[g] = static_cast<const T*>(shadow[g]) + o.wf1;
+        }
+        a.partial = ws.partial;
+        a.M = n; a.N = 512; a.ldx = 3136; a.ldw = 3136;
+        const ProfPair pr = pp(K_FC1_FWD);
+        if (pr.begin) (void)hipEventRecord(pr.begin, st);
+        hipLaunchKernelGGL((fc_sk_kernel<T, kFcPartial, 7, 7>), dim3(16, groups, 7), dim3(256), 0, st, a);
+        if (pr.end) (void)hipEventRecord(pr.end, st);
+        DQN_LAUNCH_CHECK();
+        *slices_out = 7;
+    } else {
         FcAsArgs<T> a{};
         for (int g = 0; g < groups; ++g) {
             a.x[g] = act3 + g * e_act3;
@@ -188,10 +204,9 @@ static int forward_to_fc1(dqn_ctx* c, hipStream_t st, Workspace& ws, int groups,
         }
         a.partial = ws.partial;
         a.M = n; a.N = 512; a.ldx = 3136; a.ldw = 3136;
-        const int slices = fc1_slices(n, groups);
         const ProfPair pr = pp(K_FC1_FWD);
         int used = 0;
-        DQN_HIP((launch_fc_as<T, kFcPartial>(st, a, 3136, groups, slices, &used, pr.begin, pr.end)));
+        DQN_HIP((launch_fc_as<T, kFcPartial>(st, a, 3136, groups, fc1_slices(n, groups), &used, pr.begin, pr.end)));
         *slices_out = used;
     }
     return DQN_OK;
@@ -269,7 +284,16 @@ static int train_impl(dqn_ctx* c, const uint8_t* s, const int32_t* a, const floa
         const ProfPair pr = prof_pair(c, K_FC1_WGRAD);
         DQN_HIP((launch_gemm<T, 64, 128, 32, 2>(st, al, bl, ep, 512, 3136, B, 1, 1, ws.partial, ws.partial_cap, pr.begin, pr.end)));
     }
-    {   // fc1 data gradient through conv3's ReLU: dz3[b][f] = [act3 > 0] sum_o dZ[b][o] W1[o][f]
+    if (B <= 32) {   // fc1 data gradient through conv3's ReLU: dz3[b][f] = [act3 > 0] sum_o dZ[b][o] W1[o][f]
+        FcSkArgs<T> fa{};
+        fa.x[0] = dzh; fa.w[0] = bsh + kBshWf1; fa.dz = dz3; fa.mask = act3;
+        fa.M = B; fa.N = 3136; fa.ldx = 512; fa.ldw = 512;
+        const ProfPair pr = prof_pair(c, K_FC1_DGRAD);
+        if (pr.begin) (void)hipEventRecord(pr.begin, st);
+        hipLaunchKernelGGL((fc_sk_kernel<T, kFcReluMask, 8, 1>), dim3(98, 1, 1), dim3(256), 0, st, fa);
+        if (pr.end) (void)hipEventRecord(pr.end, st);
+        DQN_LAUNCH_CHECK();
+    } else {
         FcAsArgs<T> fa{};
         fa.x[0] = dzh; fa.w[0] = bsh + kBshWf1;
         fa.dz = dz3; fa.mask = act3;
