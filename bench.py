@@ -41,8 +41,8 @@ def kernel_work(name, B, A, groups, precision):
         "conv2_fwd": (2.0 * G * B * 81 * 64 * 512, G * B * (12800 + 5184) * e),
         "conv3_fwd": (2.0 * G * B * 49 * 64 * 576, G * B * (5184 + 3136) * e),
         "fc1_fwd": (2.0 * G * B * 512 * 3136, G * (B * (3136 + 512) * e) + min(G, 2) * 512 * 3136 * e),
-        "fc2_td": (2.0 * G * B * A * 512, G * B * 512 * e),
-        "td_head_bwd": (2.0 * B * 512 * 2, B * 512 * e * 2 + A * 512 * 4),
+        "head_td": (2.0 * G * B * A * 512, G * B * 512 * e),
+        "(unused)": (1.0, 1.0),
         "fc1_wgrad": (2.0 * 512 * 3136 * B, 512 * 3136 * 4 + B * (3136 + 512) * e),
         "fc1_dgrad": (2.0 * B * 3136 * 512, 512 * 3136 * e + B * (3136 * 2 + 512) * e),
         "conv3_wgrad": (2.0 * 64 * 576 * B * 49, B * (5184 + 3136) * e + 64 * 576 * 4),
@@ -50,7 +50,7 @@ def kernel_work(name, B, A, groups, precision):
         "conv2_wgrad": (2.0 * 64 * 512 * B * 81, B * (12800 + 5184) * e + 64 * 512 * 4),
         "conv2_dgrad": (2.0 * B * 400 * 32 * 256, B * (5184 + 2 * 12800) * e),
         "conv1_wgrad": (2.0 * 32 * 256 * B * 400, B * (28224 + 12800 * e) + 32 * 256 * 4),
-        "bias_grad": (1.0 * B * (12800 + 5184 + 3136 + 512), B * (12800 + 5184 + 3136 + 512) * e),
+        "small_grads": (1.0 * B * (12800 + 5184 + 3136 + 512), B * (12800 + 5184 + 3136 + 512 + 512) * e),
         "rmsprop": (10.0 * n_par, n_par * (28 + (2 if precision == "bf16" else 0))),
     }
     return t[name]
@@ -61,7 +61,7 @@ def roofline_for(name, avg_ms, B, A, groups, precision):
     peak_f = PEAK["bf16" if precision == "bf16" else "f32"][0]
     ridge = peak_f * 1e12 / (PEAK["hbm"][0] * 1e9)
     sec = avg_ms * 1e-3
-    if flops / max(nbytes, 1) >= ridge * 0.25 and name not in ("rmsprop", "bias_grad", "td_head_bwd", "fc2_td"):
+    if flops / max(nbytes, 1) >= ridge * 0.25 and name not in ("rmsprop", "small_grads", "(unused)", "head_td"):
         ach = flops / sec / 1e12
         return {"kernel": name, "bound": "mfma", "achieved": ach, "peak": peak_f, "unit": "TFLOP/s",
                 "frac": ach / peak_f, "traffic": None, "avg_launch_us": avg_ms * 1e3}
@@ -243,6 +243,8 @@ def kernel_breakdown(wl, steps_each):
     P = wl.P
     out = {}
     for kid in range(1, P.dqn_profile_kernel_count() + 1):
+        if P.dqn_profile_kernel_name(kid).startswith("("):
+            continue
         P.dqn_profile_select(wl.ctx, kid)
         wl.run(steps_each)
         ms, n = P.dqn_profile_read(wl.ctx)

@@ -365,27 +365,16 @@ inline hipError_t launch_conv_ws(hipStream_t st, const ConvWsArgs<T, Geo>& a, in
                                  hipEvent_t ev_end = nullptr)
 {
     constexpr size_t smem = conv_ws_smem<T, Geo>();
-    constexpr int WAVES = 4;
+    // large problems: 16 wavefronts share one LDS copy of the weights, so that two workgroups per
+    // compute unit keep 32 wavefronts' worth of operand loads in flight
+    constexpr int WAVES = 16, TP = 1;
     const int max_blocks = 512 / (groups > 0 ? groups : 1);   // persistent grid: about two workgroups per CU
     hipError_t e = hipSuccess;
     if (ev_begin) (void)hipEventRecord(ev_begin, st);
     const int tiles32 = (a.M + 31) / 32;
     if (tiles32 * groups <= 1024) {
         hipLaunchKernelGGL((conv_sk_kernel<T, Geo, EPI>), dim3(tiles32, groups), dim3(256), 0, st, a);
-    } else if (a.M >= 256 * 64) {
-        constexpr int TP = 2;
-        auto kern = conv_ws_kernel<T, Geo, EPI, TP, WAVES>;
-        static bool attr_set = false;
-        if (!attr_set) {
-            e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, smem);
-            if (e != hipSuccess) return e;
-            attr_set = true;
-        }
-        int tiles = (a.M + WAVES * TP * 32 - 1) / (WAVES * TP * 32);
-        if (tiles > max_blocks) tiles = max_blocks;
-        hipLaunchKernelGGL(kern, dim3(tiles, groups), dim3(WAVES * 64), smem, st, a);
     } else {
-        constexpr int TP = 1;
         auto kern = conv_ws_kernel<T, Geo, EPI, TP, WAVES>;
         static bool attr_set = false;
         if (!attr_set) {

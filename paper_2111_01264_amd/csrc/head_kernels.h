@@ -76,6 +76,7 @@ struct HeadArgs {
     const float* done;
     float gamma, huber;
     void* h_online;              // T [rows][512]: h of group 0, kept for the backward pass
+    void* dzh;                   // T [rows][512]: dLoss/d(fc1 pre-activation) = dq_b W2[a_b][.] [h > 0]
     float* q_all;                // [groups][rows][A]
     float* dqv;
     float* lossv;
@@ -92,6 +93,9 @@ __global__ __launch_bounds__(256) void head_fwd_kernel(HeadArgs a)
     __shared__ __attribute__((aligned(32))) T s_h[G][kHeadRows][LDH];
     __shared__ float s_red[4][16][64];
     __shared__ float s_q[G][kHeadRows][kMaxActions + 1];
+    __shared__ float s_dq[kHeadRows];
+    __shared__ int s_act[kHeadRows];
+    float h0[4] = {0.f, 0.f, 0.f, 0.f};   // this thread's four features of h (online pass on s)
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int row0 = blockIdx.x * kHeadRows;
     const int lr = lane & 31, kg = lane >> 5;
@@ -134,8 +138,11 @@ __global__ __launch_bounds__(256) void head_fwd_kernel(HeadArgs a)
                     acc.z = fmaxf(acc.z + bv.z, 0.f); acc.w = fmaxf(acc.w + bv.w, 0.f);
                 }
                 store4<T>(&s_h[g][r][f0], acc.x, acc.y, acc.z, acc.w);
-                if (MODE == kHeadTrain && g == 0 && row < a.rows)
-                    store4<T>(static_cast<T*>(a.h_online) + static_cast<size_t>(row) * 512 + f0, acc.x, acc.y, acc.z, acc.w);
+                if (MODE == kHeadTrain && g == 0) {
+                    h0[0] = acc.x; h0[1] = acc.y; h0[2] = acc.z; h0[3] = acc.w;
+                    if (row < a.rows)
+                        store4<T>(static_cast<T*>(a.h_online) + static_cast<size_t>(row) * 512 + f0, acc.x, acc.y, acc.z, acc.w);
+                }
             }
     }
     __syncthreads();
@@ -171,9 +178,6 @@ __global__ __launch_bounds__(256) void head_fwd_kernel(HeadArgs a)
         }
     __syncthreads();
 
-    if (tid >= kHeadRows) return;
-    const int row = row0 + tid;
-    if (row >= a.rows) return;
     auto argmax_lowest = [&](const float* q) {
         int best = 0;
         for (int k = 1; k < a.A; ++k)
@@ -181,6 +185,8 @@ __global__ __launch_bounds__(256) void head_fwd_kernel(HeadArgs a)
         return best;
     };
     if constexpr (MODE == kHeadAct) {
+        const int row = row0 + tid;
+        if (tid >= kHeadRows || row >= a.rows) return;
         const float* q = s_q[0][tid];
         if (a.q_out)
             for (int k = 0; k < a.A; ++k) a.q_out[static_cast<size_t>(row) * a.A + k] = q[k];
@@ -190,82 +196,48 @@ __global__ __launch_bounds__(256) void head_fwd_kernel(HeadArgs a)
         if (u < a.epsilon) act = static_cast<int>((static_cast<uint64_t>(d.x[1]) * static_cast<uint32_t>(a.A)) >> 32);
         a.actions[row] = act;
     } else {
-        for (int g = 0; g < a.groups; ++g)
-            for (int k = 0; k < a.A; ++k) a.q_all[(static_cast<size_t>(g) * a.rows + row) * a.A + k] = s_q[g][tid][k];
-        const float* qt = s_q[1][tid];
-        const int astar = a.double_dqn ? argmax_lowest(s_q[2][tid]) : argmax_lowest(qt);
-        const float y = a.rew[row] + a.gamma * (1.f - a.done[row]) * qt[astar];
-        const float delta = s_q[0][tid][a.act[row]] - y;
-        const float ad = fabsf(delta);
-        a.lossv[row] = ad <= a.huber ? 0.5f * delta * delta : a.huber * (ad - 0.5f * a.huber);
-        const float clipped = fminf(fmaxf(delta, -a.huber), a.huber);
-        a.dqv[row] = clipped / static_cast<float>(a.rows);
-    }
-}
-
-// Train step head, backward half.  dQ has one non-zero per row (the taken action), so fc2's
-// backward is a gather: dZ_fc1[b][o] = dq_b * W2[a_b][o] * [h[b][o] > 0];
-// dW2[a][o] = sum_{b: a_b = a} dq_b h[b][o];  db2[a] = sum_{b: a_b = a} dq_b;  loss = mean_b loss_b.
-// Each block owns 64 columns o; thread (o, part) accumulates the samples b = part (mod 4) in
-// increasing order into its own LDS column, the four parts are then added in order.
-template <typename T>
-__global__ __launch_bounds__(256) void td_head_bwd_kernel(
-    const T* __restrict__ h, const T* __restrict__ w2, const int32_t* __restrict__ act,
-    const float* __restrict__ dqv, const float* __restrict__ lossv, int B, int A, T* __restrict__ dzh,
-    float* __restrict__ g_w2, float* __restrict__ g_b2, float* __restrict__ loss_out, float* __restrict__ loss_keep)
-{
-    __shared__ float s_dq[kMaxBatch];
-    __shared__ int s_a[kMaxBatch];
-    __shared__ float s_acc[kMaxActions][256];
-    const int tid = threadIdx.x;
-    for (int b = tid; b < B; b += 256) { s_dq[b] = dqv[b]; s_a[b] = act[b]; }
-    for (int a = 0; a < A; ++a) s_acc[a][tid] = 0.f;
-    __syncthreads();
-    const int o = blockIdx.x * 64 + (tid & 63);
-    const int part = tid >> 6;
-    for (int b0 = part; b0 < B; b0 += 16) {
-        float hv[4];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int b = b0 + 4 * u;
-            hv[u] = b < B ? to_float(h[static_cast<size_t>(b) * 512 + o]) : 0.f;
-        }
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int b = b0 + 4 * u;
-            if (b < B) {
-                const int a = s_a[b];
-                const float g = s_dq[b] * to_float(w2[static_cast<size_t>(a) * 512 + o]);
-                dzh[static_cast<size_t>(b) * 512 + o] = hv[u] > 0.f ? from_float<T>(g) : from_float<T>(0.f);
-                s_acc[a][tid] += s_dq[b] * hv[u];
+        if (tid < kHeadRows) {
+            const int row = row0 + tid;
+            float dq = 0.f;
+            int act_b = 0;
+            if (row < a.rows) {
+                for (int g = 0; g < a.groups; ++g)
+                    for (int k = 0; k < a.A; ++k) a.q_all[(static_cast<size_t>(g) * a.rows + row) * a.A + k] = s_q[g][tid][k];
+                const float* qt = s_q[1][tid];
+                const int astar = a.double_dqn ? argmax_lowest(s_q[2][tid]) : argmax_lowest(qt);
+                const float y = a.rew[row] + a.gamma * (1.f - a.done[row]) * qt[astar];
+                act_b = a.act[row];
+                const float delta = s_q[0][tid][act_b] - y;
+                const float ad = fabsf(delta);
+                a.lossv[row] = ad <= a.huber ? 0.5f * delta * delta : a.huber * (ad - 0.5f * a.huber);
+                dq = fminf(fmaxf(delta, -a.huber), a.huber) / static_cast<float>(a.rows);
+                a.dqv[row] = dq;
             }
+            s_dq[tid] = dq;
+            s_act[tid] = act_b;
         }
-    }
-    __syncthreads();
-    for (int a = part; a < A; a += 4) {
-        const int oo = tid & 63;
-        g_w2[static_cast<size_t>(a) * 512 + o] = ((s_acc[a][oo] + s_acc[a][64 + oo]) + s_acc[a][128 + oo]) + s_acc[a][192 + oo];
-    }
-    if (blockIdx.x == 0) {
-        for (int a = tid; a < A; a += 256) {
-            float acc = 0.f;
-            for (int b = 0; b < B; ++b)
-                if (s_a[b] == a) acc += s_dq[b];
-            g_b2[a] = acc;
-        }
-        if (tid == 0) {
-            float acc = 0.f;
-            for (int b = 0; b < B; ++b) acc += lossv[b];
-            acc /= static_cast<float>(B);
-            *loss_keep = acc;
-            if (loss_out) *loss_out = acc;
+        __syncthreads();
+        // fc2's data gradient through fc1's ReLU for this workgroup's rows: dQ has one non-zero per row
+        const int r = tid >> 7, f0 = (tid & 127) * 4;
+        const int row = row0 + r;
+        if (row < a.rows) {
+            float w[4];
+            load4<T>(static_cast<const T*>(a.w2[0]) + static_cast<size_t>(s_act[r]) * 512 + f0, w);
+            const float dq = s_dq[r];
+            store4<T>(static_cast<T*>(a.dzh) + static_cast<size_t>(row) * 512 + f0, h0[0] > 0.f ? dq * w[0] : 0.f,
+                      h0[1] > 0.f ? dq * w[1] : 0.f, h0[2] > 0.f ? dq * w[2] : 0.f, h0[3] > 0.f ? dq * w[3] : 0.f);
         }
     }
 }
 
-// Bias gradients = column sums of the four dZ matrices ([rows][C], T), first stage: a block sums up
-// to kBiasRows rows of eight channels into partial[layer][chunk][C].  The optimiser kernel adds the
-// chunks in order (second stage), so no atomics and no extra launch are needed.
+// Small reductions of the backward pass, one launch:
+//  * blocks [0, first_block[4]): bias gradients = column sums of the four dZ matrices ([rows][C], T),
+//    first stage: a block sums up to kBiasRows rows of eight channels into partial[layer][chunk][C];
+//    the optimiser kernel adds the chunks in order, so no atomics and no extra launch are needed;
+//  * the last 32 blocks: fc2's weight gradient.  dQ has one non-zero per row (the taken action):
+//    dW2[a][o] = sum_{b: a_b = a} dq_b h[b][o];  db2[a] = sum_{b: a_b = a} dq_b;  loss = mean_b loss_b.
+//    Each block owns 16 columns o; thread (o, part) accumulates the samples b = part (mod 16) in
+//    increasing order into its own LDS column, the sixteen parts are then added in order.
 constexpr int kBiasRows = 1024;
 struct BiasGradArgs {
     const void* dz[4];
@@ -275,12 +247,73 @@ struct BiasGradArgs {
     int first_block[5];
     int first_partial[4];   // offsets into `partial` (floats)
     float* partial;
+    // fc2 weight gradient
+    const void* h;          // T [B][512]
+    const int32_t* act;
+    const float* dqv;
+    const float* lossv;
+    int B, A;
+    float* g_w2;
+    float* g_b2;
+    float* loss_out;
+    float* loss_keep;
 };
 template <typename T>
 __global__ __launch_bounds__(256) void bias_grad_kernel(BiasGradArgs args)
 {
     typedef typename Vec8<T>::type V8;
     __shared__ float red[256][9];
+    __shared__ float s_dq[kMaxBatch];
+    __shared__ int s_a[kMaxBatch];
+    __shared__ float s_acc[kMaxActions][256];
+    const int tid = threadIdx.x;
+    if (static_cast<int>(blockIdx.x) >= args.first_block[4]) {
+        const int B = args.B, A = args.A;
+        const T* h = static_cast<const T*>(args.h);
+        for (int b = tid; b < B; b += 256) { s_dq[b] = args.dqv[b]; s_a[b] = args.act[b]; }
+        for (int a = 0; a < A; ++a) s_acc[a][tid] = 0.f;
+        __syncthreads();
+        // 16 columns per block; thread (o, part): samples b = part (mod 16) in increasing order
+        const int ob = blockIdx.x - args.first_block[4];
+        const int oo = tid & 15, part = tid >> 4;
+        const int o = ob * 16 + oo;
+        for (int b0 = part; b0 < B; b0 += 64) {
+            float hv[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int b = b0 + 16 * u;
+                hv[u] = b < B ? to_float(h[static_cast<size_t>(b) * 512 + o]) : 0.f;
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int b = b0 + 16 * u;
+                if (b < B) s_acc[s_a[b]][tid] += s_dq[b] * hv[u];
+            }
+        }
+        __syncthreads();
+        for (int a = part; a < A; a += 16) {
+            float sum = 0.f;
+#pragma unroll
+            for (int p = 0; p < 16; ++p) sum += s_acc[a][p * 16 + oo];
+            args.g_w2[static_cast<size_t>(a) * 512 + o] = sum;
+        }
+        if (ob == 0) {
+            for (int a = tid; a < A; a += 256) {
+                float acc = 0.f;
+                for (int b = 0; b < B; ++b)
+                    if (s_a[b] == a) acc += s_dq[b];
+                args.g_b2[a] = acc;
+            }
+            if (tid == 0) {
+                float acc = 0.f;
+                for (int b = 0; b < B; ++b) acc += args.lossv[b];
+                acc /= static_cast<float>(B);
+                *args.loss_keep = acc;
+                if (args.loss_out) *args.loss_out = acc;
+            }
+        }
+        return;
+    }
     int layer = 0;
     while (layer < 3 && static_cast<int>(blockIdx.x) >= args.first_block[layer + 1]) ++layer;
     const int local = blockIdx.x - args.first_block[layer];
@@ -291,22 +324,21 @@ __global__ __launch_bounds__(256) void bias_grad_kernel(BiasGradArgs args)
     float acc[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) acc[e] = 0.f;
-    for (int r = chunk * kBiasRows + threadIdx.x; r < r_end; r += 256) {
+    for (int r = chunk * kBiasRows + tid; r < r_end; r += 256) {
         const V8 v = *reinterpret_cast<const V8*>(dz + static_cast<size_t>(r) * C);
 #pragma unroll
         for (int e = 0; e < 8; ++e) acc[e] += to_float(v[e]);
     }
 #pragma unroll
-    for (int e = 0; e < 8; ++e) red[threadIdx.x][e] = acc[e];
+    for (int e = 0; e < 8; ++e) red[tid][e] = acc[e];
     __syncthreads();
     for (int stride = 128; stride >= 1; stride >>= 1) {
-        if (static_cast<int>(threadIdx.x) < stride)
+        if (tid < stride)
 #pragma unroll
-            for (int e = 0; e < 8; ++e) red[threadIdx.x][e] += red[threadIdx.x + stride][e];
+            for (int e = 0; e < 8; ++e) red[tid][e] += red[tid + stride][e];
         __syncthreads();
     }
-    if (threadIdx.x < 8)
-        args.partial[args.first_partial[layer] + chunk * C + cg * 8 + threadIdx.x] = red[0][threadIdx.x];
+    if (tid < 8) args.partial[args.first_partial[layer] + chunk * C + cg * 8 + tid] = red[0][tid];
 }
 
 // ---- optimiser --------------------------------------------------------------------------------

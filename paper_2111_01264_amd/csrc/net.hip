@@ -8,7 +8,10 @@
 #include <vector>
 
 #include "common.h"
+#include <type_traits>
+
 #include "fc_as.h"
+#include "gemm_tn_tr.h"
 #include "head_kernels.h"
 #include "layers.h"
 
@@ -20,8 +23,8 @@ enum KernelId {
     K_RMSPROP, K_COUNT
 };
 static const char* const kKernelNames[K_COUNT] = {
-    "none", "conv1_fwd", "conv2_fwd", "conv3_fwd", "fc1_fwd", "fc2_td", "td_head_bwd", "fc1_wgrad",
-    "fc1_dgrad", "conv3_wgrad", "conv3_dgrad", "conv2_wgrad", "conv2_dgrad", "conv1_wgrad", "bias_grad",
+    "none", "conv1_fwd", "conv2_fwd", "conv3_fwd", "fc1_fwd", "head_td", "(unused)", "fc1_wgrad",
+    "fc1_dgrad", "conv3_wgrad", "conv3_dgrad", "conv2_wgrad", "conv2_dgrad", "conv1_wgrad", "small_grads",
     "rmsprop"};
 constexpr size_t kProfPairs = 4096;
 
@@ -119,6 +122,17 @@ static int pick_splits(int tiles, int K, int BK, int max_splits)
     const int by_k = K / (2 * BK) > 0 ? K / (2 * BK) : 1;
     if (s > by_k) s = by_k;
     if (s > max_splits) s = max_splits;
+    return s < 1 ? 1 : s;
+}
+
+// Split-K factor of a conv weight gradient with K contraction rows and `n_blocks` column blocks:
+// about 128 workgroups in total, at least two 32-row k-tiles each, at most kWgMaxSplits slices.
+static int wgrad_splits(int K, int n_blocks)
+{
+    int s = 128 / n_blocks;
+    const int by_k = K / 64 > 0 ? K / 64 : 1;
+    if (s > by_k) s = by_k;
+    if (s > static_cast<int>(kWgMaxSplits)) s = static_cast<int>(kWgMaxSplits);
     return s < 1 ? 1 : s;
 }
 
@@ -265,16 +279,8 @@ static int train_impl(dqn_ctx* c, const uint8_t* s, const int32_t* a, const floa
         }
         ha.double_dqn = c->cfg.double_dqn; ha.act = a; ha.rew = r; ha.done = done;
         ha.gamma = c->cfg.gamma; ha.huber = c->cfg.huber_delta;
-        ha.h_online = h; ha.q_all = ws.q; ha.dqv = c->dqv; ha.lossv = c->lossv;
+        ha.h_online = h; ha.dzh = dzh; ha.q_all = ws.q; ha.dqv = c->dqv; ha.lossv = c->lossv;
         hipLaunchKernelGGL((head_fwd_kernel<T, kHeadTrain>), dim3((B + kHeadRows - 1) / kHeadRows), dim3(256), 0, st, ha);
-        if (pr.end) (void)hipEventRecord(pr.end, st);
-        DQN_LAUNCH_CHECK();
-    }
-    {
-        const ProfPair pr = prof_pair(c, K_TD_HEAD_BWD);
-        if (pr.begin) (void)hipEventRecord(pr.begin, st);
-        hipLaunchKernelGGL((td_head_bwd_kernel<T>), dim3(8), dim3(256), 0, st, h, sh + o.wf2, a, c->dqv, c->lossv, B, c->A,
-                           dzh, c->grad + o.wf2, c->grad + o.bf2, loss_out, c->loss_keep);
         if (pr.end) (void)hipEventRecord(pr.end, st);
         DQN_LAUNCH_CHECK();
     }
@@ -282,7 +288,10 @@ static int train_impl(dqn_ctx* c, const uint8_t* s, const int32_t* a, const floa
         DenseM<T> al{}; DenseM<T> bl{}; EpiGrad ep{c->grad + o.wf1, 3136, 1.f};
         al.p[0] = dzh; al.ld = 512; bl.p[0] = act3; bl.ld = 3136;
         const ProfPair pr = prof_pair(c, K_FC1_WGRAD);
-        DQN_HIP((launch_gemm<T, 64, 128, 32, 2>(st, al, bl, ep, 512, 3136, B, 1, 1, ws.partial, ws.partial_cap, pr.begin, pr.end)));
+        if constexpr (std::is_same<T, bf16_t>::value)
+            DQN_HIP((launch_gemm_tn_tr<64, 128>(st, al, bl, ep, 512, 3136, B, 1, nullptr, 0, pr.begin, pr.end, nullptr)));
+        else
+            DQN_HIP((launch_gemm<T, 64, 128, 32, 2>(st, al, bl, ep, 512, 3136, B, 1, 1, ws.partial, ws.partial_cap, pr.begin, pr.end)));
     }
     if (B <= 32) {   // fc1 data gradient through conv3's ReLU: dz3[b][f] = [act3 > 0] sum_o dZ[b][o] W1[o][f]
         FcSkArgs<T> fa{};
@@ -306,6 +315,10 @@ static int train_impl(dqn_ctx* c, const uint8_t* s, const int32_t* a, const floa
         DenseM<T> al{}; WgradB<T, 64, 9, 9, 7, 7, 3, 1> bl{act2}; EpiGrad ep{c->grad + o.w3, 576, 1.f};
         al.p[0] = dz3; al.ld = 64;
         const ProfPair pr = prof_pair(c, K_CONV3_WGRAD);
+        if constexpr (std::is_same<T, bf16_t>::value)
+            DQN_HIP((launch_gemm_tn_tr<64, 192>(st, al, bl, ep, 64, 576, B * 49, wgrad_splits(B * 49, 3), c->wg_partial + kWgOff3,
+                                                kWgMaxSplits * 64 * 576, pr.begin, pr.end, &wg_splits[2])));
+        else
         DQN_HIP((launch_gemm<T, 64, 64, 32, 2>(st, al, bl, ep, 64, 576, B * 49, 1, pick_splits(9, B * 49, 32, 64),
                                                 c->wg_partial + kWgOff3, kWgMaxSplits * 64 * 576, pr.begin, pr.end, &wg_splits[2])));
     }
@@ -320,6 +333,10 @@ static int train_impl(dqn_ctx* c, const uint8_t* s, const int32_t* a, const floa
         DenseM<T> al{}; WgradB<T, 32, 20, 20, 9, 9, 4, 2> bl{act1}; EpiGrad ep{c->grad + o.w2, 512, 1.f};
         al.p[0] = dz2; al.ld = 64;
         const ProfPair pr = prof_pair(c, K_CONV2_WGRAD);
+        if constexpr (std::is_same<T, bf16_t>::value)
+            DQN_HIP((launch_gemm_tn_tr<64, 256>(st, al, bl, ep, 64, 512, B * 81, wgrad_splits(B * 81, 2), c->wg_partial + kWgOff2,
+                                                kWgMaxSplits * 64 * 512, pr.begin, pr.end, &wg_splits[1])));
+        else
         DQN_HIP((launch_gemm<T, 64, 64, 32, 2>(st, al, bl, ep, 64, 512, B * 81, 1, pick_splits(8, B * 81, 32, 64),
                                                 c->wg_partial + kWgOff2, kWgMaxSplits * 64 * 512, pr.begin, pr.end, &wg_splits[1])));
     }
@@ -336,6 +353,10 @@ static int train_impl(dqn_ctx* c, const uint8_t* s, const int32_t* a, const floa
         DenseM<T> al{}; Conv1WgradB<T> bl{s}; EpiGrad ep{c->grad + o.w1, 256, 1.f};
         al.p[0] = dz1; al.ld = 32;
         const ProfPair pr = prof_pair(c, K_CONV1_WGRAD);
+        if constexpr (std::is_same<T, bf16_t>::value)
+            DQN_HIP((launch_gemm_tn_tr<32, 128>(st, al, bl, ep, 32, 256, B * 400, wgrad_splits(B * 400, 2), c->wg_partial + kWgOff1,
+                                                kWgMaxSplits * 32 * 256, pr.begin, pr.end, &wg_splits[0])));
+        else
         DQN_HIP((launch_gemm<T, 32, 128, 32, 1>(st, al, bl, ep, 32, 256, B * 400, 1, pick_splits(2, B * 400, 32, kWgMaxSplits),
                                                  c->wg_partial + kWgOff1, kWgMaxSplits * 32 * 256, pr.begin, pr.end, &wg_splits[0])));
     }
@@ -355,10 +376,12 @@ static int train_impl(dqn_ctx* c, const uint8_t* s, const int32_t* a, const floa
             pofs += args.chunks[l] * args.chans[l];
         }
         args.partial = c->bias_partial;
+        args.h = h; args.act = a; args.dqv = c->dqv; args.lossv = c->lossv; args.B = B; args.A = c->A;
+        args.g_w2 = c->grad + o.wf2; args.g_b2 = c->grad + o.bf2; args.loss_out = loss_out; args.loss_keep = c->loss_keep;
         for (int l = 0; l < 4; ++l) { bias_chunks[l] = args.chunks[l]; bias_first[l] = args.first_partial[l]; }
         const ProfPair pr = prof_pair(c, K_BIAS_GRAD);
         if (pr.begin) (void)hipEventRecord(pr.begin, st);
-        hipLaunchKernelGGL((bias_grad_kernel<T>), dim3(args.first_block[4]), dim3(256), 0, st, args);
+        hipLaunchKernelGGL((bias_grad_kernel<T>), dim3(args.first_block[4] + 32), dim3(256), 0, st, args);
         if (pr.end) (void)hipEventRecord(pr.end, st);
         DQN_LAUNCH_CHECK();
     }
