@@ -365,27 +365,29 @@ inline hipError_t launch_conv_ws(hipStream_t st, const ConvWsArgs<T, Geo>& a, in
                                  hipEvent_t ev_end = nullptr)
 {
     constexpr size_t smem = conv_ws_smem<T, Geo>();
-    // large problems: 16 wavefronts share one LDS copy of the weights, so that two workgroups per
-    // compute unit keep 32 wavefronts' worth of operand loads in flight
-    constexpr int WAVES = 16, TP = 1;
-    const int max_blocks = 512 / (groups > 0 ? groups : 1);   // persistent grid: about two workgroups per CU
+    // Large problems: the wavefronts of a workgroup share one LDS copy of the weights (two
+    // workgroups fit a compute unit).  More wavefronts per workgroup keep more operand loads in
+    // flight, but the grid must still cover the chip about twice.
+    const int max_blocks = 512 / (groups > 0 ? groups : 1);
     hipError_t e = hipSuccess;
     if (ev_begin) (void)hipEventRecord(ev_begin, st);
     const int tiles32 = (a.M + 31) / 32;
-    if (tiles32 * groups <= 1024) {
-        hipLaunchKernelGGL((conv_sk_kernel<T, Geo, EPI>), dim3(tiles32, groups), dim3(256), 0, st, a);
-    } else {
-        auto kern = conv_ws_kernel<T, Geo, EPI, TP, WAVES>;
-        static bool attr_set = false;
+    auto launch_ws = [&](auto kern, int waves) {
+        static bool attr_set = false;   // one flag per kernel instantiation (generic lambda)
         if (!attr_set) {
             e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, smem);
-            if (e != hipSuccess) return e;
+            if (e != hipSuccess) return;
             attr_set = true;
         }
-        int tiles = (a.M + WAVES * TP * 32 - 1) / (WAVES * TP * 32);
+        int tiles = (a.M + waves * 32 - 1) / (waves * 32);
         if (tiles > max_blocks) tiles = max_blocks;
-        hipLaunchKernelGGL(kern, dim3(tiles, groups), dim3(WAVES * 64), smem, st, a);
-    }
+        hipLaunchKernelGGL(kern, dim3(tiles, groups), dim3(waves * 64), smem, st, a);
+    };
+    if (tiles32 * groups <= 1024) hipLaunchKernelGGL((conv_sk_kernel<T, Geo, EPI>), dim3(tiles32, groups), dim3(256), 0, st, a);
+    else if (tiles32 * groups >= 16 * 512) launch_ws(conv_ws_kernel<T, Geo, EPI, 1, 16>, 16);
+    else if (tiles32 * groups >= 8 * 512) launch_ws(conv_ws_kernel<T, Geo, EPI, 1, 8>, 8);
+    else launch_ws(conv_ws_kernel<T, Geo, EPI, 1, 4>, 4);
+    if (e != hipSuccess) return e;
     e = hipGetLastError();
     if (ev_end) (void)hipEventRecord(ev_end, st);
     return e;

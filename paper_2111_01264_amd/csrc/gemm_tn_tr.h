@@ -36,7 +36,8 @@ __device__ inline bf16x8 tr_fragment(const bf16_t* p, int pitch4 /* elements bet
     return r;
 }
 
-template <class AL, class BL, class EP, int BM, int BN>
+// D = k-tiles of operand vectors in flight per thread (registers); LDS is double-buffered.
+template <class AL, class BL, class EP, int BM, int BN, int D>
 __global__ __launch_bounds__(256) void gemm_tn_tr_kernel(AL al, BL bl, EP ep, int M, int N, int K, int k_per_split,
                                                          float* __restrict__ partial, int always_partial)
 {
@@ -61,29 +62,30 @@ __global__ __launch_bounds__(256) void gemm_tn_tr_kernel(AL al, BL bl, EP ep, in
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-    bf16x8 ra[NA], rb[NB];
-    auto fetch = [&](int k0) {
+    static_assert(D % 2 == 0, "the LDS buffer index must be a compile-time function of the ring slot");
+    bf16x8 ra[D][NA], rb[D][NB];
+    auto fetch = [&](int slot, int k0) {
 #pragma unroll
         for (int i = 0; i < NA; ++i) {
             const int v = tid + i * 256;
-            if (VA % 256 == 0 || v < VA) ra[i] = al.load(0, m0 + (v % (BM / 8)) * 8, k0 + v / (BM / 8), M, k_end);
+            if (VA % 256 == 0 || v < VA) ra[slot][i] = al.load(0, m0 + (v % (BM / 8)) * 8, k0 + v / (BM / 8), M, k_end);
         }
 #pragma unroll
         for (int i = 0; i < NB; ++i) {
             const int v = tid + i * 256;
-            if (VB % 256 == 0 || v < VB) rb[i] = bl.load(0, n0 + (v % (BN / 8)) * 8, k0 + v / (BN / 8), N, k_end);
+            if (VB % 256 == 0 || v < VB) rb[slot][i] = bl.load(0, n0 + (v % (BN / 8)) * 8, k0 + v / (BN / 8), N, k_end);
         }
     };
-    auto stash = [&](int buf) {
+    auto stash = [&](int slot, int buf) {
 #pragma unroll
         for (int i = 0; i < NA; ++i) {
             const int v = tid + i * 256;
-            if (VA % 256 == 0 || v < VA) *reinterpret_cast<bf16x8*>(&sA[buf][(v / (BM / 8)) * LDA + (v % (BM / 8)) * 8]) = ra[i];
+            if (VA % 256 == 0 || v < VA) *reinterpret_cast<bf16x8*>(&sA[buf][(v / (BM / 8)) * LDA + (v % (BM / 8)) * 8]) = ra[slot][i];
         }
 #pragma unroll
         for (int i = 0; i < NB; ++i) {
             const int v = tid + i * 256;
-            if (VB % 256 == 0 || v < VB) *reinterpret_cast<bf16x8*>(&sB[buf][(v / (BN / 8)) * LDB + (v % (BN / 8)) * 8]) = rb[i];
+            if (VB % 256 == 0 || v < VB) *reinterpret_cast<bf16x8*>(&sB[buf][(v / (BN / 8)) * LDB + (v % (BN / 8)) * 8]) = rb[slot][i];
         }
     };
 
@@ -91,24 +93,33 @@ __global__ __launch_bounds__(256) void gemm_tn_tr_kernel(AL al, BL bl, EP ep, in
     const int frag_row = 8 * (G >> 1) + (s >> 2);      // + 16 * ks (+4 for the second read)
     const int frag_col = 16 * (G & 1) + 4 * (s & 3);   // + 32 * tile
 
-    if (k_begin < k_end) fetch(k_begin);
-    int buf = 0;
-    for (int k0 = k_begin; k0 < k_end; k0 += KT, buf ^= 1) {
-        stash(buf);
-        __syncthreads();     // also: every wavefront is done reading the other buffer
-        if (k0 + KT < k_end) fetch(k0 + KT);
+    // tiles beyond k_end load zeros (the loaders bound-check k), so the ring needs no tail logic
 #pragma unroll
-        for (int ks = 0; ks < KT / 16; ++ks) {
-            bf16x8 fa[MT];
+    for (int u = 0; u < D - 1; ++u) fetch(u, k_begin + u * KT);
+    for (int kb = k_begin; kb < k_end; kb += D * KT) {
 #pragma unroll
-            for (int i = 0; i < MT; ++i) fa[i] = tr_fragment(&sA[buf][(ks * 16 + frag_row) * LDA + i * 32 + frag_col], 4 * LDA);
+        for (int u = 0; u < D; ++u) {
+            const int k0 = kb + u * KT;
+            if (k0 < k_end) {                 // uniform across the workgroup
+                fetch((u + D - 1) % D, k0 + (D - 1) * KT);
+                const int buf = u & 1;
+                stash(u, buf);
+                __syncthreads();     // also: every wavefront is done reading the other buffer
 #pragma unroll
-            for (int j = 0; j < NTW; ++j) {
-                const int nt = wave + 4 * j;
-                if (NT % 4 == 0 || nt < NT) {
-                    const bf16x8 fb = tr_fragment(&sB[buf][(ks * 16 + frag_row) * LDB + nt * 32 + frag_col], 4 * LDB);
+                for (int ks = 0; ks < KT / 16; ++ks) {
+                    bf16x8 fa[MT];
 #pragma unroll
-                    for (int i = 0; i < MT; ++i) mma_32x32x16(acc[i][j], fa[i], fb);
+                    for (int i = 0; i < MT; ++i)
+                        fa[i] = tr_fragment(&sA[buf][(ks * 16 + frag_row) * LDA + i * 32 + frag_col], 4 * LDA);
+#pragma unroll
+                    for (int j = 0; j < NTW; ++j) {
+                        const int nt = wave + 4 * j;
+                        if (NT % 4 == 0 || nt < NT) {
+                            const bf16x8 fb = tr_fragment(&sB[buf][(ks * 16 + frag_row) * LDB + nt * 32 + frag_col], 4 * LDB);
+#pragma unroll
+                            for (int i = 0; i < MT; ++i) mma_32x32x16(acc[i][j], fa[i], fb);
+                        }
+                    }
                 }
             }
         }
@@ -135,7 +146,7 @@ __global__ __launch_bounds__(256) void gemm_tn_tr_kernel(AL al, BL bl, EP ep, in
 
 // want_splits is clamped so that the slices fit `partial_capacity` floats; with splits_deferred the
 // kernel always writes slices [split][M][N] and the caller's consumer adds them in order.
-template <int BM, int BN, class AL, class BL, class EP>
+template <int BM, int BN, int D, class AL, class BL, class EP>
 inline hipError_t launch_gemm_tn_tr(hipStream_t st, const AL& al, const BL& bl, const EP& ep, int M, int N, int K, int want_splits,
                                     float* partial, size_t partial_capacity, hipEvent_t ev_begin, hipEvent_t ev_end,
                                     int* splits_deferred)
@@ -150,7 +161,7 @@ inline hipError_t launch_gemm_tn_tr(hipStream_t st, const AL& al, const BL& bl, 
     }
     if (splits_deferred) *splits_deferred = splits;
     if (ev_begin) (void)hipEventRecord(ev_begin, st);
-    hipLaunchKernelGGL((gemm_tn_tr_kernel<AL, BL, EP, BM, BN>), dim3((N + BN - 1) / BN, splits, (M + BM - 1) / BM), dim3(256), 0, st, al, bl, ep, M, N,
+    hipLaunchKernelGGL((gemm_tn_tr_kernel<AL, BL, EP, BM, BN, D>), dim3((N + BN - 1) / BN, splits, (M + BM - 1) / BM), dim3(256), 0, st, al, bl, ep, M, N,
                        K, kps, partial, splits_deferred ? 1 : 0);
     const hipError_t e = hipGetLastError();
     if (ev_end) (void)hipEventRecord(ev_end, st);

@@ -270,7 +270,8 @@ __global__ __launch_bounds__(256) void bias_grad_kernel(BiasGradArgs args)
     if (static_cast<int>(blockIdx.x) >= args.first_block[4]) {
         const int B = args.B, A = args.A;
         const T* h = static_cast<const T*>(args.h);
-        for (int b = tid; b < B; b += 256) { s_dq[b] = args.dqv[b]; s_a[b] = args.act[b]; }
+        float* s_loss = &red[0][0];   // 256 * 9 floats: room for kMaxBatch loss terms
+        for (int b = tid; b < B; b += 256) { s_dq[b] = args.dqv[b]; s_a[b] = args.act[b]; s_loss[b] = args.lossv[b]; }
         for (int a = 0; a < A; ++a) s_acc[a][tid] = 0.f;
         __syncthreads();
         // 16 columns per block; thread (o, part): samples b = part (mod 16) in increasing order
@@ -306,7 +307,7 @@ __global__ __launch_bounds__(256) void bias_grad_kernel(BiasGradArgs args)
             }
             if (tid == 0) {
                 float acc = 0.f;
-                for (int b = 0; b < B; ++b) acc += args.lossv[b];
+                for (int b = 0; b < B; ++b) acc += s_loss[b];
                 acc /= static_cast<float>(B);
                 *args.loss_keep = acc;
                 if (args.loss_out) *args.loss_out = acc;
@@ -420,10 +421,15 @@ __global__ __launch_bounds__(256) void rmsprop_kernel(RmsArgs a)
                 // conv weight gradient: add the split-K slices in order, keep the sum for readers of the gradient
                 const float* p = a.wg_partial[conv] + r;
                 float4 sum = make_float4(0.f, 0.f, 0.f, 0.f);
-#pragma unroll 4
-                for (int s = 0; s < a.wg_splits[conv]; ++s) {
-                    const float4 v4 = *reinterpret_cast<const float4*>(p + s * tsize);
-                    sum.x += v4.x; sum.y += v4.y; sum.z += v4.z; sum.w += v4.w;
+                const int ns = a.wg_splits[conv];
+                for (int s0 = 0; s0 < ns; s0 += 8) {
+                    float4 v4[8];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) v4[u] = *reinterpret_cast<const float4*>(p + (s0 + u < ns ? s0 + u : ns - 1) * tsize);
+                    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                    for (int u = 0; u < 8; ++u)
+                        if (s0 + u < ns) { sum.x += v4[u].x; sum.y += v4[u].y; sum.z += v4[u].z; sum.w += v4[u].w; }
                 }
                 const float sc = a.wg_scale[conv];
                 g = make_float4(sum.x * sc, sum.y * sc, sum.z * sc, sum.w * sc);

@@ -77,8 +77,8 @@ namespace dqn {
 
 constexpr int kMaxFc1Slices = 49;
 // deferred split-K scratch of the three conv weight gradients
-constexpr size_t kWgMaxSplits = 64;
-constexpr size_t kWgOff1 = 0, kWgOff2 = kWgMaxSplits * 32 * 256, kWgOff3 = kWgOff2 + kWgMaxSplits * 64 * 512;
+constexpr size_t kWgMaxSplits = 32, kWgMaxSplits1 = 128;   // conv1's gradient is small: more slices are cheap
+constexpr size_t kWgOff1 = 0, kWgOff2 = kWgMaxSplits1 * 32 * 256, kWgOff3 = kWgOff2 + kWgMaxSplits * 64 * 512;
 constexpr size_t kWgTotal = kWgOff3 + kWgMaxSplits * 64 * 576;
 
 static int alloc_ws(Workspace& ws, int cap, int groups, int A, size_t esize, bool training)
@@ -126,13 +126,14 @@ static int pick_splits(int tiles, int K, int BK, int max_splits)
 }
 
 // Split-K factor of a conv weight gradient with K contraction rows and `n_blocks` column blocks:
-// about 128 workgroups in total, at least two 32-row k-tiles each, at most kWgMaxSplits slices.
-static int wgrad_splits(int K, int n_blocks)
+// up to 256 workgroups in total, at least two 32-row k-tiles each, at most max_splits slices (every
+// slice is a full copy of the gradient that the optimiser kernel has to read back).
+static int wgrad_splits(int K, int n_blocks, int max_splits)
 {
-    int s = 128 / n_blocks;
+    int s = 256 / n_blocks;
     const int by_k = K / 64 > 0 ? K / 64 : 1;
     if (s > by_k) s = by_k;
-    if (s > static_cast<int>(kWgMaxSplits)) s = static_cast<int>(kWgMaxSplits);
+    if (s > max_splits) s = max_splits;
     return s < 1 ? 1 : s;
 }
 
@@ -289,7 +290,7 @@ static int train_impl(dqn_ctx* c, const uint8_t* s, const int32_t* a, const floa
         al.p[0] = dzh; al.ld = 512; bl.p[0] = act3; bl.ld = 3136;
         const ProfPair pr = prof_pair(c, K_FC1_WGRAD);
         if constexpr (std::is_same<T, bf16_t>::value)
-            DQN_HIP((launch_gemm_tn_tr<64, 128>(st, al, bl, ep, 512, 3136, B, 1, nullptr, 0, pr.begin, pr.end, nullptr)));
+            DQN_HIP((launch_gemm_tn_tr<64, 128, 2>(st, al, bl, ep, 512, 3136, B, 1, nullptr, 0, pr.begin, pr.end, nullptr)));
         else
             DQN_HIP((launch_gemm<T, 64, 128, 32, 2>(st, al, bl, ep, 512, 3136, B, 1, 1, ws.partial, ws.partial_cap, pr.begin, pr.end)));
     }
@@ -316,7 +317,7 @@ static int train_impl(dqn_ctx* c, const uint8_t* s, const int32_t* a, const floa
         al.p[0] = dz3; al.ld = 64;
         const ProfPair pr = prof_pair(c, K_CONV3_WGRAD);
         if constexpr (std::is_same<T, bf16_t>::value)
-            DQN_HIP((launch_gemm_tn_tr<64, 192>(st, al, bl, ep, 64, 576, B * 49, wgrad_splits(B * 49, 3), c->wg_partial + kWgOff3,
+            DQN_HIP((launch_gemm_tn_tr<64, 192, 4>(st, al, bl, ep, 64, 576, B * 49, wgrad_splits(B * 49, 3, 32), c->wg_partial + kWgOff3,
                                                 kWgMaxSplits * 64 * 576, pr.begin, pr.end, &wg_splits[2])));
         else
         DQN_HIP((launch_gemm<T, 64, 64, 32, 2>(st, al, bl, ep, 64, 576, B * 49, 1, pick_splits(9, B * 49, 32, 64),
@@ -334,7 +335,7 @@ static int train_impl(dqn_ctx* c, const uint8_t* s, const int32_t* a, const floa
         al.p[0] = dz2; al.ld = 64;
         const ProfPair pr = prof_pair(c, K_CONV2_WGRAD);
         if constexpr (std::is_same<T, bf16_t>::value)
-            DQN_HIP((launch_gemm_tn_tr<64, 256>(st, al, bl, ep, 64, 512, B * 81, wgrad_splits(B * 81, 2), c->wg_partial + kWgOff2,
+            DQN_HIP((launch_gemm_tn_tr<64, 256, 4>(st, al, bl, ep, 64, 512, B * 81, wgrad_splits(B * 81, 2, 32), c->wg_partial + kWgOff2,
                                                 kWgMaxSplits * 64 * 512, pr.begin, pr.end, &wg_splits[1])));
         else
         DQN_HIP((launch_gemm<T, 64, 64, 32, 2>(st, al, bl, ep, 64, 512, B * 81, 1, pick_splits(8, B * 81, 32, 64),
@@ -354,8 +355,8 @@ static int train_impl(dqn_ctx* c, const uint8_t* s, const int32_t* a, const floa
         al.p[0] = dz1; al.ld = 32;
         const ProfPair pr = prof_pair(c, K_CONV1_WGRAD);
         if constexpr (std::is_same<T, bf16_t>::value)
-            DQN_HIP((launch_gemm_tn_tr<32, 128>(st, al, bl, ep, 32, 256, B * 400, wgrad_splits(B * 400, 2), c->wg_partial + kWgOff1,
-                                                kWgMaxSplits * 32 * 256, pr.begin, pr.end, &wg_splits[0])));
+            DQN_HIP((launch_gemm_tn_tr<32, 128, 4>(st, al, bl, ep, 32, 256, B * 400, wgrad_splits(B * 400, 2, 128), c->wg_partial + kWgOff1,
+                                                kWgMaxSplits1 * 32 * 256, pr.begin, pr.end, &wg_splits[0])));
         else
         DQN_HIP((launch_gemm<T, 32, 128, 32, 1>(st, al, bl, ep, 32, 256, B * 400, 1, pick_splits(2, B * 400, 32, kWgMaxSplits),
                                                  c->wg_partial + kWgOff1, kWgMaxSplits * 32 * 256, pr.begin, pr.end, &wg_splits[0])));
