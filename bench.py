@@ -53,6 +53,8 @@ def kernel_work(name, B, A, groups, precision):
         "small_grads": (1.0 * B * (12800 + 5184 + 3136 + 512), B * (12800 + 5184 + 3136 + 512 + 512) * e),
         "rmsprop": (10.0 * n_par, n_par * (28 + (2 if precision == "bf16" else 0))),
     }
+    parts = ("fc1_wgrad", "conv3_wgrad", "conv2_wgrad", "conv1_wgrad", "small_grads")
+    t["wgrad_all"] = (sum(t[k][0] for k in parts), sum(t[k][1] for k in parts))   # bf16: one fused launch
     return t[name]
 
 
@@ -248,7 +250,8 @@ def kernel_breakdown(wl, steps_each):
         P.dqn_profile_select(wl.ctx, kid)
         wl.run(steps_each)
         ms, n = P.dqn_profile_read(wl.ctx)
-        out[P.dqn_profile_kernel_name(kid)] = ms / max(n, 1)
+        if n > 0:
+            out[P.dqn_profile_kernel_name(kid)] = ms / n
     P.dqn_profile_select(wl.ctx, 0)
     return out
 

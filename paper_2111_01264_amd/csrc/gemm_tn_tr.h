@@ -13,8 +13,9 @@
 // one 32x32x16 operand fragment.
 //
 // Loaders are the row-contiguous functors of layers.h (load(g, row0, k) -> rows row0..row0+7 at k).
-// Grid: x = n-blocks, y = split-K slices, z = m-blocks.  A block covers BM rows (one or two 32-row
-// tiles) and BN columns; wavefront w owns the 32-column tiles w, w+4, ...
+// A workgroup covers BM rows (one or two 32-row tiles) and BN columns of one split-K slice;
+// wavefront w owns the 32-column tiles w, w+4, ...  The caller (the fused weight-gradient kernel)
+// maps its block index to (column block, slice, row block).
 #pragma once
 #include "gemm_mfma.h"
 
@@ -36,21 +37,27 @@ __device__ inline bf16x8 tr_fragment(const bf16_t* p, int pitch4 /* elements bet
     return r;
 }
 
-// D = k-tiles of operand vectors in flight per thread (registers); LDS is double-buffered.
+// Bytes of LDS one workgroup of gemm_tn_tr_block needs.
+template <int BM, int BN> constexpr size_t gemm_tn_tr_smem() { return static_cast<size_t>(2) * 32 * ((BM + 16) + (BN + 16)) * 2; }
+
+// One workgroup's share: column block bx, split-K slice `split`, row block bz.  D = k-tiles of operand
+// vectors in flight per thread (registers); LDS (smem, gemm_tn_tr_smem bytes, 16-byte aligned) is
+// double-buffered.  to_partial: write fp32 slices [split][M][N] instead of calling the epilogue.
 template <class AL, class BL, class EP, int BM, int BN, int D>
-__global__ __launch_bounds__(256) void gemm_tn_tr_kernel(AL al, BL bl, EP ep, int M, int N, int K, int k_per_split,
-                                                         float* __restrict__ partial, int always_partial)
+__device__ inline void gemm_tn_tr_block(const AL& al, const BL& bl, const EP& ep, int M, int N, int K, int k_per_split,
+                                        float* __restrict__ partial, bool to_partial, int bx, int split, int bz,
+                                        unsigned char* smem)
 {
     constexpr int KT = 32;
     constexpr int LDA = BM + 16, LDB = BN + 16;     // row pitch = 32 (mod 128) bytes: conflict-free transposing reads
     constexpr int MT = BM / 32, NT = BN / 32, NTW = (NT + 3) / 4;
     constexpr int VA = KT * BM / 8, VB = KT * BN / 8;
     constexpr int NA = (VA + 255) / 256, NB = (VB + 255) / 256;
-    __shared__ __attribute__((aligned(16))) bf16_t sA[2][KT * LDA];
-    __shared__ __attribute__((aligned(16))) bf16_t sB[2][KT * LDB];
+    bf16_t (*sA)[KT * LDA] = reinterpret_cast<bf16_t (*)[KT * LDA]>(smem);
+    bf16_t (*sB)[KT * LDB] = reinterpret_cast<bf16_t (*)[KT * LDB]>(smem + static_cast<size_t>(2) * KT * LDA * 2);
 
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int n0 = blockIdx.x * BN, split = blockIdx.y, m0 = blockIdx.z * BM;
+    const int n0 = bx * BN, m0 = bz * BM;
     const int k_begin = split * k_per_split;
     const int k_end = min(K, k_begin + k_per_split);
 
@@ -125,7 +132,6 @@ __global__ __launch_bounds__(256) void gemm_tn_tr_kernel(AL al, BL bl, EP ep, in
         }
     }
 
-    const bool to_partial = gridDim.y > 1 || always_partial;
 #pragma unroll
     for (int i = 0; i < MT; ++i)
 #pragma unroll
@@ -144,28 +150,20 @@ __global__ __launch_bounds__(256) void gemm_tn_tr_kernel(AL al, BL bl, EP ep, in
         }
 }
 
-// want_splits is clamped so that the slices fit `partial_capacity` floats; with splits_deferred the
-// kernel always writes slices [split][M][N] and the caller's consumer adds them in order.
-template <int BM, int BN, int D, class AL, class BL, class EP>
-inline hipError_t launch_gemm_tn_tr(hipStream_t st, const AL& al, const BL& bl, const EP& ep, int M, int N, int K, int want_splits,
-                                    float* partial, size_t partial_capacity, hipEvent_t ev_begin, hipEvent_t ev_end,
-                                    int* splits_deferred)
+// Split-K geometry: k rows per slice (a multiple of the 32-row k-tile) and the resulting slice count,
+// clamped so that the slices fit `capacity` floats.
+inline void tn_tr_splits(int K, int want_splits, size_t mn, size_t capacity, int* kps_out, int* splits_out)
 {
     constexpr int KT = 32;
     int splits = want_splits < 1 ? 1 : want_splits;
     int kps = ((K + splits - 1) / splits + KT - 1) / KT * KT;
     splits = (K + kps - 1) / kps;
-    while (splits > 1 && static_cast<size_t>(splits) * M * N > partial_capacity) {
+    while (splits > 1 && static_cast<size_t>(splits) * mn > capacity) {
         kps += KT;
         splits = (K + kps - 1) / kps;
     }
-    if (splits_deferred) *splits_deferred = splits;
-    if (ev_begin) (void)hipEventRecord(ev_begin, st);
-    hipLaunchKernelGGL((gemm_tn_tr_kernel<AL, BL, EP, BM, BN, D>), dim3((N + BN - 1) / BN, splits, (M + BM - 1) / BM), dim3(256), 0, st, al, bl, ep, M, N,
-                       K, kps, partial, splits_deferred ? 1 : 0);
-    const hipError_t e = hipGetLastError();
-    if (ev_end) (void)hipEventRecord(ev_end, st);
-    return e;
+    *kps_out = kps;
+    *splits_out = splits;
 }
 
 }  // namespace dqn

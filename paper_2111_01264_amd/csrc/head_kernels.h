@@ -234,7 +234,7 @@ __global__ __launch_bounds__(256) void head_fwd_kernel(HeadArgs a)
 //  * blocks [0, first_block[4]): bias gradients = column sums of the four dZ matrices ([rows][C], T),
 //    first stage: a block sums up to kBiasRows rows of eight channels into partial[layer][chunk][C];
 //    the optimiser kernel adds the chunks in order, so no atomics and no extra launch are needed;
-//  * the last 32 blocks: fc2's weight gradient.  dQ has one non-zero per row (the taken action):
+//  * the last 33 blocks: fc2's weight gradient (32 blocks of 16 columns) and its bias gradient + loss.  dQ has one non-zero per row (the taken action):
 //    dW2[a][o] = sum_{b: a_b = a} dq_b h[b][o];  db2[a] = sum_{b: a_b = a} dq_b;  loss = mean_b loss_b.
 //    Each block owns 16 columns o; thread (o, part) accumulates the samples b = part (mod 16) in
 //    increasing order into its own LDS column, the sixteen parts are then added in order.
@@ -258,32 +258,39 @@ struct BiasGradArgs {
     float* loss_out;
     float* loss_keep;
 };
+constexpr size_t kSmallGradsSmem = (256 * 9 + kMaxBatch) * sizeof(float) + kMaxBatch * sizeof(int) + kMaxActions * 256 * sizeof(float);
+constexpr int kSmallGradsExtraBlocks = 33;   // fc2 weight gradient (32) + fc2 bias gradient / loss (1)
+
+// One workgroup of the small reductions; `block` counts from the first bias block, smem holds
+// kSmallGradsSmem bytes.
 template <typename T>
-__global__ __launch_bounds__(256) void bias_grad_kernel(BiasGradArgs args)
+__device__ inline void small_grads_block(const BiasGradArgs& args, int block, unsigned char* smem)
 {
     typedef typename Vec8<T>::type V8;
-    __shared__ float red[256][9];
-    __shared__ float s_dq[kMaxBatch];
-    __shared__ int s_a[kMaxBatch];
-    __shared__ float s_acc[kMaxActions][256];
+    float (*red)[9] = reinterpret_cast<float (*)[9]>(smem);
+    float* s_dq = reinterpret_cast<float*>(smem) + 256 * 9;
+    int* s_a = reinterpret_cast<int*>(s_dq + kMaxBatch);
+    float (*s_acc)[256] = reinterpret_cast<float (*)[256]>(s_a + kMaxBatch);
     const int tid = threadIdx.x;
-    if (static_cast<int>(blockIdx.x) >= args.first_block[4]) {
+    if (block >= args.first_block[4]) {
         const int B = args.B, A = args.A;
         const T* h = static_cast<const T*>(args.h);
         float* s_loss = &red[0][0];   // 256 * 9 floats: room for kMaxBatch loss terms
         for (int b = tid; b < B; b += 256) { s_dq[b] = args.dqv[b]; s_a[b] = args.act[b]; s_loss[b] = args.lossv[b]; }
         for (int a = 0; a < A; ++a) s_acc[a][tid] = 0.f;
         __syncthreads();
-        // 16 columns per block; thread (o, part): samples b = part (mod 16) in increasing order
-        const int ob = blockIdx.x - args.first_block[4];
+        // 16 columns per block; thread (o, part): samples b = part (mod 16) in increasing order.
+        // Block 32 is the bias "column" (h = 1) and also owns the batch-mean loss.
+        const int ob = block - args.first_block[4];
         const int oo = tid & 15, part = tid >> 4;
+        const bool bias_block = ob == 32;
         const int o = ob * 16 + oo;
         for (int b0 = part; b0 < B; b0 += 64) {
             float hv[4];
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
                 const int b = b0 + 16 * u;
-                hv[u] = b < B ? to_float(h[static_cast<size_t>(b) * 512 + o]) : 0.f;
+                hv[u] = b < B ? (bias_block ? 1.f : to_float(h[static_cast<size_t>(b) * 512 + o])) : 0.f;
             }
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
@@ -296,28 +303,32 @@ __global__ __launch_bounds__(256) void bias_grad_kernel(BiasGradArgs args)
             float sum = 0.f;
 #pragma unroll
             for (int p = 0; p < 16; ++p) sum += s_acc[a][p * 16 + oo];
-            args.g_w2[static_cast<size_t>(a) * 512 + o] = sum;
+            if (!bias_block) args.g_w2[static_cast<size_t>(a) * 512 + o] = sum;
+            else if (oo == 0) args.g_b2[a] = sum;
         }
-        if (ob == 0) {
-            for (int a = tid; a < A; a += 256) {
-                float acc = 0.f;
-                for (int b = 0; b < B; ++b)
-                    if (s_a[b] == a) acc += s_dq[b];
-                args.g_b2[a] = acc;
+        if (bias_block) {
+            // loss = (1/B) sum_b loss_b: thread t adds b = t, t+256, .. then a fixed binary tree
+            __syncthreads();
+            float acc = 0.f;
+            for (int b = tid; b < B; b += 256) acc += s_loss[b];
+            __syncthreads();
+            s_loss[tid] = acc;
+            __syncthreads();
+            for (int stride = 128; stride >= 1; stride >>= 1) {
+                if (tid < stride) s_loss[tid] += s_loss[tid + stride];
+                __syncthreads();
             }
             if (tid == 0) {
-                float acc = 0.f;
-                for (int b = 0; b < B; ++b) acc += s_loss[b];
-                acc /= static_cast<float>(B);
-                *args.loss_keep = acc;
-                if (args.loss_out) *args.loss_out = acc;
+                const float mean = s_loss[0] / static_cast<float>(B);
+                *args.loss_keep = mean;
+                if (args.loss_out) *args.loss_out = mean;
             }
         }
         return;
     }
     int layer = 0;
-    while (layer < 3 && static_cast<int>(blockIdx.x) >= args.first_block[layer + 1]) ++layer;
-    const int local = blockIdx.x - args.first_block[layer];
+    while (layer < 3 && block >= args.first_block[layer + 1]) ++layer;
+    const int local = block - args.first_block[layer];
     const int C = args.chans[layer], rows = args.rows[layer], cgs = C / 8;
     const int cg = local % cgs, chunk = local / cgs;
     const T* dz = static_cast<const T*>(args.dz[layer]) + cg * 8;
@@ -340,6 +351,13 @@ __global__ __launch_bounds__(256) void bias_grad_kernel(BiasGradArgs args)
         __syncthreads();
     }
     if (tid < 8) args.partial[args.first_partial[layer] + chunk * C + cg * 8 + tid] = red[0][tid];
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void bias_grad_kernel(BiasGradArgs args)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char sg_smem[];
+    small_grads_block<T>(args, static_cast<int>(blockIdx.x), sg_smem);
 }
 
 // ---- optimiser --------------------------------------------------------------------------------

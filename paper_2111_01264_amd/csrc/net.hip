@@ -11,7 +11,7 @@
 #include <type_traits>
 
 #include "fc_as.h"
-#include "gemm_tn_tr.h"
+#include "wgrad_all.h"
 #include "head_kernels.h"
 #include "layers.h"
 
@@ -20,12 +20,12 @@ namespace dqn {
 enum KernelId {
     K_NONE = 0, K_CONV1_FWD, K_CONV2_FWD, K_CONV3_FWD, K_FC1_FWD, K_FC2_TD, K_TD_HEAD_BWD, K_FC1_WGRAD,
     K_FC1_DGRAD, K_CONV3_WGRAD, K_CONV3_DGRAD, K_CONV2_WGRAD, K_CONV2_DGRAD, K_CONV1_WGRAD, K_BIAS_GRAD,
-    K_RMSPROP, K_COUNT
+    K_RMSPROP, K_WGRAD_ALL, K_COUNT
 };
 static const char* const kKernelNames[K_COUNT] = {
     "none", "conv1_fwd", "conv2_fwd", "conv3_fwd", "fc1_fwd", "head_td", "(unused)", "fc1_wgrad",
     "fc1_dgrad", "conv3_wgrad", "conv3_dgrad", "conv2_wgrad", "conv2_dgrad", "conv1_wgrad", "small_grads",
-    "rmsprop"};
+    "rmsprop", "wgrad_all"};
 constexpr size_t kProfPairs = 4096;
 
 // Layer geometries (Section 5: the Nature-DQN network).
@@ -285,15 +285,7 @@ static int train_impl(dqn_ctx* c, const uint8_t* s, const int32_t* a, const floa
         if (pr.end) (void)hipEventRecord(pr.end, st);
         DQN_LAUNCH_CHECK();
     }
-    {   // fc1 weight gradient: dW[o][f] = sum_b dZ[b][o] act3[b][f]
-        DenseM<T> al{}; DenseM<T> bl{}; EpiGrad ep{c->grad + o.wf1, 3136, 1.f};
-        al.p[0] = dzh; al.ld = 512; bl.p[0] = act3; bl.ld = 3136;
-        const ProfPair pr = prof_pair(c, K_FC1_WGRAD);
-        if constexpr (std::is_same<T, bf16_t>::value)
-            DQN_HIP((launch_gemm_tn_tr<64, 128, 2>(st, al, bl, ep, 512, 3136, B, 1, nullptr, 0, pr.begin, pr.end, nullptr)));
-        else
-            DQN_HIP((launch_gemm<T, 64, 128, 32, 2>(st, al, bl, ep, 512, 3136, B, 1, 1, ws.partial, ws.partial_cap, pr.begin, pr.end)));
-    }
+    // ---- data-gradient chain: fc1 -> conv3 -> conv2 ------------------------------------------------
     if (B <= 32) {   // fc1 data gradient through conv3's ReLU: dz3[b][f] = [act3 > 0] sum_o dZ[b][o] W1[o][f]
         FcSkArgs<T> fa{};
         fa.x[0] = dzh; fa.w[0] = bsh + kBshWf1; fa.dz = dz3; fa.mask = act3;
@@ -312,34 +304,12 @@ static int train_impl(dqn_ctx* c, const uint8_t* s, const int32_t* a, const floa
         int used = 0;
         DQN_HIP((launch_fc_as<T, kFcReluMask>(st, fa, 512, 1, 1, &used, pr.begin, pr.end)));
     }
-    {   // conv3 weight gradient
-        DenseM<T> al{}; WgradB<T, 64, 9, 9, 7, 7, 3, 1> bl{act2}; EpiGrad ep{c->grad + o.w3, 576, 1.f};
-        al.p[0] = dz3; al.ld = 64;
-        const ProfPair pr = prof_pair(c, K_CONV3_WGRAD);
-        if constexpr (std::is_same<T, bf16_t>::value)
-            DQN_HIP((launch_gemm_tn_tr<64, 192, 4>(st, al, bl, ep, 64, 576, B * 49, wgrad_splits(B * 49, 3, 32), c->wg_partial + kWgOff3,
-                                                kWgMaxSplits * 64 * 576, pr.begin, pr.end, &wg_splits[2])));
-        else
-        DQN_HIP((launch_gemm<T, 64, 64, 32, 2>(st, al, bl, ep, 64, 576, B * 49, 1, pick_splits(9, B * 49, 32, 64),
-                                                c->wg_partial + kWgOff3, kWgMaxSplits * 64 * 576, pr.begin, pr.end, &wg_splits[2])));
-    }
     {   // conv3 data gradient through conv2's ReLU
         ConvWsArgs<T, Conv3DgradGeo<T>> ca{};
         ca.x[0] = dz3; ca.w[0] = bsh + kBshW3; ca.out[0] = dz2; ca.mask = act2;
         ca.M = B * 81; ca.scale = 1.f;
         const ProfPair pr = prof_pair(c, K_CONV3_DGRAD);
         DQN_HIP((launch_conv_ws<T, Conv3DgradGeo<T>, kEpiReluMask>(st, ca, 1, pr.begin, pr.end)));
-    }
-    {   // conv2 weight gradient
-        DenseM<T> al{}; WgradB<T, 32, 20, 20, 9, 9, 4, 2> bl{act1}; EpiGrad ep{c->grad + o.w2, 512, 1.f};
-        al.p[0] = dz2; al.ld = 64;
-        const ProfPair pr = prof_pair(c, K_CONV2_WGRAD);
-        if constexpr (std::is_same<T, bf16_t>::value)
-            DQN_HIP((launch_gemm_tn_tr<64, 256, 4>(st, al, bl, ep, 64, 512, B * 81, wgrad_splits(B * 81, 2, 32), c->wg_partial + kWgOff2,
-                                                kWgMaxSplits * 64 * 512, pr.begin, pr.end, &wg_splits[1])));
-        else
-        DQN_HIP((launch_gemm<T, 64, 64, 32, 2>(st, al, bl, ep, 64, 512, B * 81, 1, pick_splits(8, B * 81, 32, 64),
-                                                c->wg_partial + kWgOff2, kWgMaxSplits * 64 * 512, pr.begin, pr.end, &wg_splits[1])));
     }
     {   // conv2 data gradient through conv1's ReLU: one problem per stride-parity class
         ConvWsArgs<T, Conv2DgradGeo<T>> ca{};
@@ -350,39 +320,86 @@ static int train_impl(dqn_ctx* c, const uint8_t* s, const int32_t* a, const floa
         const ProfPair pr = prof_pair(c, K_CONV2_DGRAD);
         DQN_HIP((launch_conv_ws<T, Conv2DgradGeo<T>, kEpiReluMask>(st, ca, 4, pr.begin, pr.end)));
     }
-    {   // conv1 weight gradient (input scale 1/255 folded into the epilogue)
-        DenseM<T> al{}; Conv1WgradB<T> bl{s}; EpiGrad ep{c->grad + o.w1, 256, 1.f};
-        al.p[0] = dz1; al.ld = 32;
-        const ProfPair pr = prof_pair(c, K_CONV1_WGRAD);
-        if constexpr (std::is_same<T, bf16_t>::value)
-            DQN_HIP((launch_gemm_tn_tr<32, 128, 4>(st, al, bl, ep, 32, 256, B * 400, wgrad_splits(B * 400, 2, 128), c->wg_partial + kWgOff1,
-                                                kWgMaxSplits1 * 32 * 256, pr.begin, pr.end, &wg_splits[0])));
-        else
-        DQN_HIP((launch_gemm<T, 32, 128, 32, 1>(st, al, bl, ep, 32, 256, B * 400, 1, pick_splits(2, B * 400, 32, kWgMaxSplits),
-                                                 c->wg_partial + kWgOff1, kWgMaxSplits * 32 * 256, pr.begin, pr.end, &wg_splits[0])));
-    }
+
+    // ---- weight gradients and small reductions ------------------------------------------------------
     int bias_chunks[4], bias_first[4];
+    BiasGradArgs bg;
+    bg.dz[0] = dz1; bg.rows[0] = B * 400; bg.chans[0] = 32;
+    bg.dz[1] = dz2; bg.rows[1] = B * 81;  bg.chans[1] = 64;
+    bg.dz[2] = dz3; bg.rows[2] = B * 49;  bg.chans[2] = 64;
+    bg.dz[3] = dzh; bg.rows[3] = B;       bg.chans[3] = 512;
+    bg.first_block[0] = 0;
     {
-        BiasGradArgs args;
-        args.dz[0] = dz1; args.rows[0] = B * 400; args.chans[0] = 32;
-        args.dz[1] = dz2; args.rows[1] = B * 81;  args.chans[1] = 64;
-        args.dz[2] = dz3; args.rows[2] = B * 49;  args.chans[2] = 64;
-        args.dz[3] = dzh; args.rows[3] = B;       args.chans[3] = 512;
-        args.first_block[0] = 0;
         int pofs = 0;
         for (int l = 0; l < 4; ++l) {
-            args.chunks[l] = (args.rows[l] + kBiasRows - 1) / kBiasRows;
-            args.first_block[l + 1] = args.first_block[l] + args.chunks[l] * (args.chans[l] / 8);
-            args.first_partial[l] = pofs;
-            pofs += args.chunks[l] * args.chans[l];
+            bg.chunks[l] = (bg.rows[l] + kBiasRows - 1) / kBiasRows;
+            bg.first_block[l + 1] = bg.first_block[l] + bg.chunks[l] * (bg.chans[l] / 8);
+            bg.first_partial[l] = pofs;
+            pofs += bg.chunks[l] * bg.chans[l];
+            bias_chunks[l] = bg.chunks[l];
+            bias_first[l] = bg.first_partial[l];
         }
-        args.partial = c->bias_partial;
-        args.h = h; args.act = a; args.dqv = c->dqv; args.lossv = c->lossv; args.B = B; args.A = c->A;
-        args.g_w2 = c->grad + o.wf2; args.g_b2 = c->grad + o.bf2; args.loss_out = loss_out; args.loss_keep = c->loss_keep;
-        for (int l = 0; l < 4; ++l) { bias_chunks[l] = args.chunks[l]; bias_first[l] = args.first_partial[l]; }
+    }
+    bg.partial = c->bias_partial;
+    bg.h = h; bg.act = a; bg.dqv = c->dqv; bg.lossv = c->lossv; bg.B = B; bg.A = c->A;
+    bg.g_w2 = c->grad + o.wf2; bg.g_b2 = c->grad + o.bf2; bg.loss_out = loss_out; bg.loss_keep = c->loss_keep;
+    const int small_blocks = bg.first_block[4] + kSmallGradsExtraBlocks;
+
+    if constexpr (std::is_same<T, bf16_t>::value) {
+        // one launch: conv1/conv2/conv3/fc1 weight gradients (transposing LDS reads) + the small reductions
+        WgradAllArgs wa{};
+        wa.a1.p[0] = dz1; wa.a1.ld = 32; wa.b1.x = s; wa.K1 = B * 400; wa.p1 = c->wg_partial + kWgOff1;
+        wa.a2.p[0] = dz2; wa.a2.ld = 64; wa.b2.x = act1; wa.K2 = B * 81; wa.p2 = c->wg_partial + kWgOff2;
+        wa.a3.p[0] = dz3; wa.a3.ld = 64; wa.b3.x = act2; wa.K3 = B * 49; wa.p3 = c->wg_partial + kWgOff3;
+        tn_tr_splits(wa.K1, wgrad_splits(wa.K1, 2, 128), 32 * 256, kWgMaxSplits1 * 32 * 256, &wa.kps1, &wa.splits1);
+        tn_tr_splits(wa.K2, wgrad_splits(wa.K2, 2, 32), 64 * 512, kWgMaxSplits * 64 * 512, &wa.kps2, &wa.splits2);
+        tn_tr_splits(wa.K3, wgrad_splits(wa.K3, 3, 32), 64 * 576, kWgMaxSplits * 64 * 576, &wa.kps3, &wa.splits3);
+        wg_splits[0] = wa.splits1; wg_splits[1] = wa.splits2; wg_splits[2] = wa.splits3;
+        wa.af.p[0] = dzh; wa.af.ld = 512; wa.bf.p[0] = act3; wa.bf.ld = 3136; wa.Kf = B;
+        wa.epf = EpiGrad{c->grad + o.wf1, 3136, 1.f};
+        wa.small = bg;
+        wa.first[0] = 0;
+        wa.first[1] = wa.first[0] + 2 * wa.splits1;
+        wa.first[2] = wa.first[1] + 2 * wa.splits2;
+        wa.first[3] = wa.first[2] + 3 * wa.splits3;
+        wa.first[4] = wa.first[3] + 25 * 8;
+        wa.first[5] = wa.first[4] + small_blocks;
+        const ProfPair pr = prof_pair(c, K_WGRAD_ALL);
+        if (pr.begin) (void)hipEventRecord(pr.begin, st);
+        hipLaunchKernelGGL(wgrad_all_kernel, dim3(wa.first[5]), dim3(256), kWgradAllSmem, st, wa);
+        if (pr.end) (void)hipEventRecord(pr.end, st);
+        DQN_LAUNCH_CHECK();
+    } else {
+        {   // fc1 weight gradient: dW[o][f] = sum_b dZ[b][o] act3[b][f]
+            DenseM<T> al{}; DenseM<T> bl{}; EpiGrad ep{c->grad + o.wf1, 3136, 1.f};
+            al.p[0] = dzh; al.ld = 512; bl.p[0] = act3; bl.ld = 3136;
+            const ProfPair pr = prof_pair(c, K_FC1_WGRAD);
+            DQN_HIP((launch_gemm<T, 64, 128, 32, 2>(st, al, bl, ep, 512, 3136, B, 1, 1, ws.partial, ws.partial_cap, pr.begin, pr.end)));
+        }
+        {   // conv3 weight gradient
+            DenseM<T> al{}; WgradB<T, 64, 9, 9, 7, 7, 3, 1> bl{act2}; EpiGrad ep{c->grad + o.w3, 576, 1.f};
+            al.p[0] = dz3; al.ld = 64;
+            const ProfPair pr = prof_pair(c, K_CONV3_WGRAD);
+            DQN_HIP((launch_gemm<T, 64, 64, 32, 2>(st, al, bl, ep, 64, 576, B * 49, 1, pick_splits(9, B * 49, 32, kWgMaxSplits),
+                                                    c->wg_partial + kWgOff3, kWgMaxSplits * 64 * 576, pr.begin, pr.end, &wg_splits[2])));
+        }
+        {   // conv2 weight gradient
+            DenseM<T> al{}; WgradB<T, 32, 20, 20, 9, 9, 4, 2> bl{act1}; EpiGrad ep{c->grad + o.w2, 512, 1.f};
+            al.p[0] = dz2; al.ld = 64;
+            const ProfPair pr = prof_pair(c, K_CONV2_WGRAD);
+            DQN_HIP((launch_gemm<T, 64, 64, 32, 2>(st, al, bl, ep, 64, 512, B * 81, 1, pick_splits(8, B * 81, 32, kWgMaxSplits),
+                                                    c->wg_partial + kWgOff2, kWgMaxSplits * 64 * 512, pr.begin, pr.end, &wg_splits[1])));
+        }
+        {   // conv1 weight gradient (the input scale 1/255 is applied by the optimiser kernel)
+            DenseM<T> al{}; Conv1WgradB<T> bl{s}; EpiGrad ep{c->grad + o.w1, 256, 1.f};
+            al.p[0] = dz1; al.ld = 32;
+            const ProfPair pr = prof_pair(c, K_CONV1_WGRAD);
+            DQN_HIP((launch_gemm<T, 32, 128, 32, 1>(st, al, bl, ep, 32, 256, B * 400, 1, pick_splits(2, B * 400, 32, kWgMaxSplits),
+                                                     c->wg_partial + kWgOff1, kWgMaxSplits * 32 * 256, pr.begin, pr.end, &wg_splits[0])));
+        }
         const ProfPair pr = prof_pair(c, K_BIAS_GRAD);
         if (pr.begin) (void)hipEventRecord(pr.begin, st);
-        hipLaunchKernelGGL((bias_grad_kernel<T>), dim3(args.first_block[4] + 32), dim3(256), 0, st, args);
+        hipLaunchKernelGGL((bias_grad_kernel<T>), dim3(small_blocks), dim3(256), kSmallGradsSmem, st, bg);
         if (pr.end) (void)hipEventRecord(pr.end, st);
         DQN_LAUNCH_CHECK();
     }
