@@ -54,6 +54,7 @@ def kernel_work(name, B, A, groups, precision):
         "rmsprop": (10.0 * n_par, n_par * (28 + (2 if precision == "bf16" else 0))),
     }
     parts = ("fc1_wgrad", "conv3_wgrad", "conv2_wgrad", "conv1_wgrad", "small_grads")
+    t["conv_tower"] = (sum(t[k][0] for k in ("conv1_fwd", "conv2_fwd", "conv3_fwd")), G * B * (28224 + 3136 * e) + B * (12800 + 5184) * e)
     t["wgrad_all"] = (sum(t[k][0] for k in parts), sum(t[k][1] for k in parts))   # bf16: one fused launch
     return t[name]
 

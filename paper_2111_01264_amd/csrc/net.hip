@@ -10,6 +10,7 @@
 #include "common.h"
 #include <type_traits>
 
+#include "conv_tower.h"
 #include "fc_as.h"
 #include "wgrad_all.h"
 #include "head_kernels.h"
@@ -23,7 +24,7 @@ enum KernelId {
     K_RMSPROP, K_WGRAD_ALL, K_COUNT
 };
 static const char* const kKernelNames[K_COUNT] = {
-    "none", "conv1_fwd", "conv2_fwd", "conv3_fwd", "fc1_fwd", "head_td", "(unused)", "fc1_wgrad",
+    "none", "conv_tower", "(conv2_fwd)", "(conv3_fwd)", "fc1_fwd", "head_td", "(unused)", "fc1_wgrad",
     "fc1_dgrad", "conv3_wgrad", "conv3_dgrad", "conv2_wgrad", "conv2_dgrad", "conv1_wgrad", "small_grads",
     "rmsprop", "wgrad_all"};
 constexpr size_t kProfPairs = 4096;
@@ -157,44 +158,30 @@ static int forward_to_fc1(dqn_ctx* c, hipStream_t st, Workspace& ws, int groups,
 {
     const Offsets& o = c->off;
     auto pp = [&](int id) { return timed ? prof_pair(c, id) : ProfPair(); };
-    const size_t e_act1 = static_cast<size_t>(n) * 12800, e_act2 = static_cast<size_t>(n) * 5184;
     const size_t e_act3 = static_cast<size_t>(n) * 3136;
     T* act1 = static_cast<T*>(ws.act1); T* act2 = static_cast<T*>(ws.act2); T* act3 = static_cast<T*>(ws.act3);
-    {   // conv1 on the uint8 state, 1/255 folded into the epilogue
-        ConvWsArgs<T, Conv1Geo<T>> a{};
+    {   // conv1 -> conv2 -> conv3 fused, one workgroup per sample; only group 0 of a train step keeps act1 / act2
+        TowerArgs<T> a{};
         for (int g = 0; g < groups; ++g) {
             a.x[g] = x[g];
-            a.w[g] = static_cast<const T*>(shadow[g]) + o.w1;
-            a.bias[g] = master[g] + o.b1;
-            a.out[g] = act1 + g * e_act1;
+            a.w1[g] = static_cast<const T*>(shadow[g]) + o.w1; a.b1[g] = master[g] + o.b1;
+            a.w2[g] = static_cast<const T*>(shadow[g]) + o.w2; a.b2[g] = master[g] + o.b2;
+            a.w3[g] = static_cast<const T*>(shadow[g]) + o.w3; a.b3[g] = master[g] + o.b3;
+            a.act1[g] = (timed && g == 0) ? act1 : nullptr;
+            a.act2[g] = (timed && g == 0) ? act2 : nullptr;
+            a.act3[g] = act3 + g * e_act3;
         }
-        a.M = n * 400; a.scale = 1.f / 255.f;
+        constexpr size_t smem = conv_tower_smem<T>();
+        static bool attr_set = false;
+        if (!attr_set) {
+            DQN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(conv_tower_kernel<T>), hipFuncAttributeMaxDynamicSharedMemorySize, smem));
+            attr_set = true;
+        }
         const ProfPair pr = pp(K_CONV1_FWD);
-        DQN_HIP((launch_conv_ws<T, Conv1Geo<T>, kEpiBiasRelu>(st, a, groups, pr.begin, pr.end)));
-    }
-    {
-        ConvWsArgs<T, Conv2Geo<T>> a{};
-        for (int g = 0; g < groups; ++g) {
-            a.x[g] = act1 + g * e_act1;
-            a.w[g] = static_cast<const T*>(shadow[g]) + o.w2;
-            a.bias[g] = master[g] + o.b2;
-            a.out[g] = act2 + g * e_act2;
-        }
-        a.M = n * 81; a.scale = 1.f;
-        const ProfPair pr = pp(K_CONV2_FWD);
-        DQN_HIP((launch_conv_ws<T, Conv2Geo<T>, kEpiBiasRelu>(st, a, groups, pr.begin, pr.end)));
-    }
-    {
-        ConvWsArgs<T, Conv3Geo<T>> a{};
-        for (int g = 0; g < groups; ++g) {
-            a.x[g] = act2 + g * e_act2;
-            a.w[g] = static_cast<const T*>(shadow[g]) + o.w3;
-            a.bias[g] = master[g] + o.b3;
-            a.out[g] = act3 + g * e_act3;
-        }
-        a.M = n * 49; a.scale = 1.f;
-        const ProfPair pr = pp(K_CONV3_FWD);
-        DQN_HIP((launch_conv_ws<T, Conv3Geo<T>, kEpiBiasRelu>(st, a, groups, pr.begin, pr.end)));
+        if (pr.begin) (void)hipEventRecord(pr.begin, st);
+        hipLaunchKernelGGL((conv_tower_kernel<T>), dim3(n, groups), dim3(512), smem, st, a);
+        if (pr.end) (void)hipEventRecord(pr.end, st);
+        DQN_LAUNCH_CHECK();
     }
     // fc1 as k-slices of fp32 partial sums [groups][slices][n][512]; the head kernel adds them
     if (n <= 32) {

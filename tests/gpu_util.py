@@ -15,8 +15,19 @@ def make_cfg(A, max_batch=32, max_envs=8, precision=P.DQN_PRECISION_FP32, double
     return c
 
 
+_KEEP = []
+
+
 def dev(a):
-    return torch.as_tensor(np.ascontiguousarray(a)).cuda()
+    """Host array -> device tensor that stays alive until the next synchronisation: the library's
+    streams are not torch's current stream, so a temporary must not go back to torch's caching
+    allocator (and be overwritten by the next upload) while a kernel may still read it."""
+    t = torch.as_tensor(np.ascontiguousarray(a)).cuda()
+    if len(_KEEP) > 512:
+        torch.cuda.synchronize()
+        _KEEP.clear()
+    _KEEP.append(t)
+    return t
 
 
 def rel_err(got, ref):

@@ -180,14 +180,18 @@ def run_flow(concurrent, iters, precision=P.DQN_PRECISION_FP32, check_oracle=Fal
         acts = torch.empty(W, dtype=torch.int32, device="cuda")
         q = torch.empty((W, A), dtype=torch.float32, device="cuda")
         act_step = 0
+        keep = []          # device inputs stay alive until the streams have consumed them
         for it in range(iters):
             for k in range(4):
                 states = synth.act_states(seed, act_step, W)
                 new_frames = states[:, 3].copy()                   # the frame each sampler just produced
                 ids = (np.arange(W, dtype=np.uint64) + np.uint64(1 << 30) + np.uint64(act_step * W))
                 _, rew, term = synth.transitions(seed, ids, A, 0.05, 0.05, 0.02)
-                P.dqn_act(ctx, dev(states), W, 0.1, act_step, 1, acts, q)
-                P.replay_push_step(rb, dev(new_frames), acts, dev(rew), dev(term))
+                d_states, d_frames, d_rew, d_term = dev(states), dev(new_frames), dev(rew), dev(term)
+                keep.append((d_states, d_frames, d_rew, d_term))
+                torch.cuda.current_stream().synchronize()      # uploads done before the act stream reads them
+                P.dqn_act(ctx, d_states, W, 0.1, act_step, 1, acts, q)
+                P.replay_push_step(rb, d_frames, acts, d_rew, d_term)
                 if check_oracle:
                     torch.cuda.synchronize()
                     want_a, want_q = orc.act(states, 0.1, act_step, use_target=True)

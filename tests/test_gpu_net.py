@@ -25,7 +25,9 @@ def gpu_act(ctx, states, eps, step, use_target, A):
     W = states.shape[0]
     acts = torch.empty(W, dtype=torch.int32, device="cuda")
     q = torch.empty((W, A), dtype=torch.float32, device="cuda")
-    P.dqn_act(ctx, dev(states), W, eps, step, use_target, acts, q)
+    d_states = dev(states)
+    torch.cuda.synchronize()
+    P.dqn_act(ctx, d_states, W, eps, step, use_target, acts, q)
     torch.cuda.synchronize()
     return acts.cpu().numpy(), q.cpu().numpy()
 
