@@ -2,6 +2,7 @@
 // (Eq. 1), fc2 backward, bias gradients, centered RMSProp (Appendix B) with the refresh of the
 // operand copies, and the target copy (theta^- <- theta).
 #pragma once
+#include "conv_tower.h"
 #include "conv_ws.h"
 #include "philox.h"
 
@@ -43,6 +44,23 @@ __host__ __device__ inline size_t bsh_index_w3(int r)
 {
     const int c = r % 64, q = (r / 64) % 3, p = (r / 192) % 3, oc = r / 576;
     return kBshW3 + (static_cast<size_t>(c) * 9 + p * 3 + q) * 64 + oc;
+}
+
+// Where blob element e lives in the 16-bit forward copy: identical, except that the conv weights are
+// kept in the fragment order of the fused conv kernel.  conv1's weights are stored there as fp16 (that
+// kernel runs conv1 on the f16 matrix instruction), everything else as bf16: shadow_store converts.
+__host__ __device__ inline size_t shadow_index(const Offsets& off, size_t e)
+{
+    if (e >= off.w1 && e < off.b1) { const int r = static_cast<int>(e - off.w1); return off.w1 + tower_frag_index(r / 256, r % 256, 256); }
+    if (e >= off.w2 && e < off.b2) { const int r = static_cast<int>(e - off.w2); return off.w2 + tower_frag_index(r / 512, r % 512, 512); }
+    if (e >= off.w3 && e < off.b3) { const int r = static_cast<int>(e - off.w3); return off.w3 + tower_frag_index(r / 576, r % 576, 576); }
+    return e;
+}
+
+template <typename T> __device__ inline void shadow_store(T* sh, const Offsets& off, size_t e, float v)
+{
+    if (e >= off.w1 && e < off.b1) reinterpret_cast<_Float16*>(sh)[shadow_index(off, e)] = static_cast<_Float16>(v);
+    else sh[shadow_index(off, e)] = from_float<T>(v);
 }
 
 // ---- network head, forward: finish fc1, fc2 on the matrix cores, then action selection (act step)
@@ -407,7 +425,7 @@ __device__ inline void rms_update(const RmsArgs& a, float& th, float g, float& v
 template <typename T, bool SHADOW>
 __device__ inline void publish(const RmsArgs& a, size_t e, float th)
 {
-    if (SHADOW) static_cast<T*>(a.sh)[e] = from_float<T>(th);
+    if (SHADOW) shadow_store<T>(static_cast<T*>(a.sh), a.off, e, th);
     if (e >= a.off.w2 && e < a.off.b2) static_cast<T*>(a.bsh)[bsh_index_w2(static_cast<int>(e - a.off.w2))] = from_float<T>(th);
     else if (e >= a.off.w3 && e < a.off.b3) static_cast<T*>(a.bsh)[bsh_index_w3(static_cast<int>(e - a.off.w3))] = from_float<T>(th);
 }
@@ -544,7 +562,7 @@ __global__ __launch_bounds__(256) void build_copies_kernel(const float* __restri
     const size_t e = blockIdx.x * static_cast<size_t>(blockDim.x) + threadIdx.x;
     if (e >= off.total) return;
     const T val = from_float<T>(theta[e]);
-    if (SHADOW) sh[e] = val;
+    if (SHADOW) shadow_store<T>(sh, off, e, theta[e]);
     if (bsh) {
         if (e >= off.w2 && e < off.b2) bsh[bsh_index_w2(static_cast<int>(e - off.w2))] = val;
         else if (e >= off.w3 && e < off.b3) bsh[bsh_index_w3(static_cast<int>(e - off.w3))] = val;

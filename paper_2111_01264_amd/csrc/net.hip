@@ -68,6 +68,7 @@ struct dqn_ctx {
     hipEvent_t ev_train = nullptr, ev_act = nullptr, ev_sync = nullptr;
     bool act_reads_online = false;   // an act step with use_target = 0 is in flight
     int last_B = 0;
+    int num_cus = 256;
     // per-kernel timing (dqn_profile_*)
     int prof_id = 0;
     std::vector<hipEvent_t> prof_events;   // pairs
@@ -160,28 +161,67 @@ static int forward_to_fc1(dqn_ctx* c, hipStream_t st, Workspace& ws, int groups,
     auto pp = [&](int id) { return timed ? prof_pair(c, id) : ProfPair(); };
     const size_t e_act3 = static_cast<size_t>(n) * 3136;
     T* act1 = static_cast<T*>(ws.act1); T* act2 = static_cast<T*>(ws.act2); T* act3 = static_cast<T*>(ws.act3);
-    {   // conv1 -> conv2 -> conv3 fused, one workgroup per sample; only group 0 of a train step keeps act1 / act2
-        TowerArgs<T> a{};
+    if constexpr (std::is_same<T, bf16_t>::value) {
+        // conv1 -> conv2 -> conv3 fused; only group 0 of a train step keeps act1 / act2 (the backward pass reads them)
+        TowerArgs a{};
         for (int g = 0; g < groups; ++g) {
             a.x[g] = x[g];
-            a.w1[g] = static_cast<const T*>(shadow[g]) + o.w1; a.b1[g] = master[g] + o.b1;
+            a.w1[g] = reinterpret_cast<const _Float16*>(static_cast<const T*>(shadow[g]) + o.w1); a.b1[g] = master[g] + o.b1;
             a.w2[g] = static_cast<const T*>(shadow[g]) + o.w2; a.b2[g] = master[g] + o.b2;
             a.w3[g] = static_cast<const T*>(shadow[g]) + o.w3; a.b3[g] = master[g] + o.b3;
             a.act1[g] = (timed && g == 0) ? act1 : nullptr;
             a.act2[g] = (timed && g == 0) ? act2 : nullptr;
             a.act3[g] = act3 + g * e_act3;
         }
-        constexpr size_t smem = conv_tower_smem<T>();
+        a.n = n; a.groups = groups;
         static bool attr_set = false;
         if (!attr_set) {
-            DQN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(conv_tower_kernel<T>), hipFuncAttributeMaxDynamicSharedMemorySize, smem));
+            DQN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(conv_tower_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, kTowerSmem));
             attr_set = true;
         }
+        const int total = n * groups;
         const ProfPair pr = pp(K_CONV1_FWD);
         if (pr.begin) (void)hipEventRecord(pr.begin, st);
-        hipLaunchKernelGGL((conv_tower_kernel<T>), dim3(n, groups), dim3(512), smem, st, a);
+        hipLaunchKernelGGL(conv_tower_kernel, dim3(total < c->num_cus ? total : c->num_cus), dim3(kTowerThreads), kTowerSmem, st, a);
         if (pr.end) (void)hipEventRecord(pr.end, st);
         DQN_LAUNCH_CHECK();
+    } else {
+        // fp32 mode: layer by layer; the event pair brackets all three launches
+        const size_t e_act1 = static_cast<size_t>(n) * 12800, e_act2 = static_cast<size_t>(n) * 5184;
+        const ProfPair pr = pp(K_CONV1_FWD);
+        {   // conv1 on the uint8 state, 1/255 folded into the epilogue
+            ConvWsArgs<T, Conv1Geo<T>> a{};
+            for (int g = 0; g < groups; ++g) {
+                a.x[g] = x[g];
+                a.w[g] = static_cast<const T*>(shadow[g]) + o.w1;
+                a.bias[g] = master[g] + o.b1;
+                a.out[g] = act1 + g * e_act1;
+            }
+            a.M = n * 400; a.scale = 1.f / 255.f;
+            DQN_HIP((launch_conv_ws<T, Conv1Geo<T>, kEpiBiasRelu>(st, a, groups, pr.begin, nullptr)));
+        }
+        {
+            ConvWsArgs<T, Conv2Geo<T>> a{};
+            for (int g = 0; g < groups; ++g) {
+                a.x[g] = act1 + g * e_act1;
+                a.w[g] = static_cast<const T*>(shadow[g]) + o.w2;
+                a.bias[g] = master[g] + o.b2;
+                a.out[g] = act2 + g * e_act2;
+            }
+            a.M = n * 81; a.scale = 1.f;
+            DQN_HIP((launch_conv_ws<T, Conv2Geo<T>, kEpiBiasRelu>(st, a, groups)));
+        }
+        {
+            ConvWsArgs<T, Conv3Geo<T>> a{};
+            for (int g = 0; g < groups; ++g) {
+                a.x[g] = act2 + g * e_act2;
+                a.w[g] = static_cast<const T*>(shadow[g]) + o.w3;
+                a.bias[g] = master[g] + o.b3;
+                a.out[g] = act3 + g * e_act3;
+            }
+            a.M = n * 49; a.scale = 1.f;
+            DQN_HIP((launch_conv_ws<T, Conv3Geo<T>, kEpiBiasRelu>(st, a, groups, nullptr, pr.end)));
+        }
     }
     // fc1 as k-slices of fp32 partial sums [groups][slices][n][512]; the head kernel adds them
     if (n <= 32) {
@@ -486,6 +526,10 @@ int dqn_create(const dqn_config* cfg, void* act_stream, void* train_stream, dqn_
     c->train_stream = static_cast<hipStream_t>(train_stream);
     const size_t n = c->off.total, B = cfg->max_batch;
     auto body = [&]() -> int {
+        int dev = 0;
+        DQN_HIP(hipGetDevice(&dev));
+        DQN_HIP(hipDeviceGetAttribute(&c->num_cus, hipDeviceAttributeMultiprocessorCount, dev));
+        if (c->num_cus < 1) c->num_cus = 1;
         float** blobs[5] = {&c->theta, &c->theta_t, &c->v, &c->m, &c->grad};
         for (auto p : blobs) {
             DQN_HIP(hipMalloc((void**)p, (n + 8) * sizeof(float)));
