@@ -179,10 +179,11 @@ static int forward_to_fc1(dqn_ctx* c, hipStream_t st, Workspace& ws, int groups,
             DQN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(conv_tower_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, kTowerSmem));
             attr_set = true;
         }
-        const int total = n * groups;
+        const int total = n * groups, grid = total < c->num_cus ? total : c->num_cus;
+        a.per = (total + grid - 1) / grid;
         const ProfPair pr = pp(K_CONV1_FWD);
         if (pr.begin) (void)hipEventRecord(pr.begin, st);
-        hipLaunchKernelGGL(conv_tower_kernel, dim3(total < c->num_cus ? total : c->num_cus), dim3(kTowerThreads), kTowerSmem, st, a);
+        hipLaunchKernelGGL(conv_tower_kernel, dim3(grid), dim3(kTowerThreads), kTowerSmem, st, a);
         if (pr.end) (void)hipEventRecord(pr.end, st);
         DQN_LAUNCH_CHECK();
     } else {
