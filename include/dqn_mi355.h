@@ -198,7 +198,9 @@ int synth_transitions(int32_t* actions, float* rewards, uint8_t* terminals, int6
 
 /* ---- per-kernel timing (measurement support) ------------------------------------------------- */
 
-/* Number of distinct kernels a train step launches, and their names (id 1 .. count). */
+/* Number of distinct kernels a train step launches, and their names (id 1 .. count).  The last id,
+ * "event_pair", is not a kernel: selecting it brackets nothing, so that its average is what the two
+ * event records of a bracket cost by themselves (subtract it from a kernel's bracketed time). */
 int dqn_profile_kernel_count(void);
 const char* dqn_profile_kernel_name(int kernel_id);
 

@@ -21,12 +21,12 @@ namespace dqn {
 enum KernelId {
     K_NONE = 0, K_CONV1_FWD, K_CONV2_FWD, K_CONV3_FWD, K_FC1_FWD, K_FC2_TD, K_TD_HEAD_BWD, K_FC1_WGRAD,
     K_FC1_DGRAD, K_CONV3_WGRAD, K_CONV3_DGRAD, K_CONV2_WGRAD, K_CONV2_DGRAD, K_CONV1_WGRAD, K_BIAS_GRAD,
-    K_RMSPROP, K_WGRAD_ALL, K_COUNT
+    K_RMSPROP, K_WGRAD_ALL, K_EVENT_PAIR, K_COUNT
 };
 static const char* const kKernelNames[K_COUNT] = {
     "none", "conv_tower", "(conv2_fwd)", "(conv3_fwd)", "fc1_fwd", "head_td", "(unused)", "fc1_wgrad",
     "fc1_dgrad", "conv3_wgrad", "conv3_dgrad", "conv2_wgrad", "conv2_dgrad", "conv1_wgrad", "small_grads",
-    "rmsprop", "wgrad_all"};
+    "rmsprop", "wgrad_all", "event_pair"};
 constexpr size_t kProfPairs = 4096;
 
 // Layer geometries (Section 5: the Nature-DQN network).
@@ -285,6 +285,10 @@ static int train_impl(dqn_ctx* c, const uint8_t* s, const int32_t* a, const floa
     const uint8_t* x[3] = {s, s2, s2};
     const void* shadow[3] = {c->sh, c->sh_t, c->sh};
     const float* master[3] = {c->theta, c->theta_t, c->theta};
+    {   // "event_pair": an empty bracket, i.e. what a pair of event records costs by itself on this stream
+        const ProfPair pr = prof_pair(c, K_EVENT_PAIR);
+        if (pr.begin) { (void)hipEventRecord(pr.begin, st); (void)hipEventRecord(pr.end, st); }
+    }
     int slices = 0;
     int rc = forward_to_fc1<T>(c, st, ws, groups, x, shadow, master, B, true, &slices);
     if (rc != DQN_OK) return rc;
