@@ -257,6 +257,8 @@ __global__ __launch_bounds__(256) void head_fwd_kernel(HeadArgs a)
 //    Each block owns 16 columns o; thread (o, part) accumulates the samples b = part (mod 16) in
 //    increasing order into its own LDS column, the sixteen parts are then added in order.
 constexpr int kBiasRows = 1024;
+constexpr int kRmsBiasLanes = 8;                                    // lanes per channel in the optimiser's bias blocks
+constexpr int kRmsBiasBlocks = (672 * kRmsBiasLanes + 255) / 256;  // 32 + 64 + 64 + 512 hidden-layer bias channels
 struct BiasGradArgs {
     const void* dz[4];
     int rows[4];
@@ -498,19 +500,27 @@ __global__ __launch_bounds__(256) void rmsprop_kernel(RmsArgs a)
         return;
     }
     if (static_cast<int>(blockIdx.x) >= a.flat_blocks + 16 * 49) {
-        // hidden-layer biases: finish the gradient (chunk sums in order), then update
-        const int idx = (blockIdx.x - a.flat_blocks - 16 * 49) * 256 + tid;   // 0 .. 671
-        if (idx >= 32 + 64 + 64 + 512) return;
-        int layer, c;
-        size_t e;
-        if (idx < 32) { layer = 0; c = idx; e = a.off.b1 + c; }
-        else if (idx < 96) { layer = 1; c = idx - 32; e = a.off.b2 + c; }
-        else if (idx < 160) { layer = 2; c = idx - 96; e = a.off.b3 + c; }
-        else { layer = 3; c = idx - 160; e = a.off.bf1 + c; }
+        // hidden-layer biases: finish the gradient, then update.  Eight adjacent lanes share a channel: lane j
+        // adds chunks j, j + 8, ... in order, then the eight sums meet in a fixed tree -- a large batch has
+        // hundreds of chunks and one lane walking them alone was the tail of this kernel.
+        const int idx = (blockIdx.x - a.flat_blocks - 16 * 49) * 256 + tid;
+        const int ch = idx / kRmsBiasLanes, j = idx % kRmsBiasLanes;
+        const bool live = ch < 32 + 64 + 64 + 512;
+        int layer = 3, c = 0;
+        size_t e = 0;
+        if (ch < 32) { layer = 0; c = ch; e = a.off.b1 + c; }
+        else if (ch < 96) { layer = 1; c = ch - 32; e = a.off.b2 + c; }
+        else if (ch < 160) { layer = 2; c = ch - 96; e = a.off.b3 + c; }
+        else if (live) { layer = 3; c = ch - 160; e = a.off.bf1 + c; }
         const int C = layer == 0 ? 32 : (layer == 3 ? 512 : 64);
         const float* part = a.bias_partial + a.bias_first[layer] + c;
         float g = 0.f;
-        for (int k = 0; k < a.bias_chunks[layer]; ++k) g += part[k * C];
+        if (live)
+            for (int k = j; k < a.bias_chunks[layer]; k += kRmsBiasLanes) g += part[k * C];
+        g += __shfl_down(g, 4, kRmsBiasLanes);
+        g += __shfl_down(g, 2, kRmsBiasLanes);
+        g += __shfl_down(g, 1, kRmsBiasLanes);
+        if (!live || j != 0) return;
         const_cast<float*>(a.grad)[e] = g;
         float th = a.theta[e], vv = a.v[e], mm = a.m[e];
         rms_update(a, th, g, vv, mm);
