@@ -42,6 +42,18 @@ template <typename T> __device__ inline typename Vec8<T>::type vec8_zero()
     return z;
 }
 
+// v if keep, else all-zero bits -- as a bitwise AND, not a select: the compiler turns "select(cond, loaded
+// value, 0)" back into a branch around the load, and a load that may be skipped spoils its count of loads in flight.
+template <typename T> __device__ inline typename Vec8<T>::type vec8_keep(const typename Vec8<T>::type& v, bool keep)
+{
+    typedef uint32_t words_t __attribute__((ext_vector_type(sizeof(typename Vec8<T>::type) / 4)));
+    words_t w = __builtin_bit_cast(words_t, v);
+    const uint32_t m = keep ? 0xFFFFFFFFu : 0u;
+#pragma unroll
+    for (int i = 0; i < static_cast<int>(sizeof(w) / 4); ++i) w[i] &= m;
+    return __builtin_bit_cast(typename Vec8<T>::type, w);
+}
+
 template <typename T> __device__ inline T from_float(float x) { return static_cast<T>(x); }
 template <typename T> __device__ inline float to_float(T x) { return static_cast<float>(x); }
 

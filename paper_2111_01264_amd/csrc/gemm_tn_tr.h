@@ -71,28 +71,33 @@ __device__ inline void gemm_tn_tr_block(const AL& al, const BL& bl, const EP& ep
 
     static_assert(D % 2 == 0, "the LDS buffer index must be a compile-time function of the ring slot");
     bf16x8 ra[D][NA], rb[D][NB];
+    // Vector v of a k-tile = (k row v % KT, eight columns v / KT): a thread's vectors share their k row, so the
+    // loader's decomposition of k (sample, pixel row, pixel column -- divisions) is computed once per thread and
+    // k-tile.  Every thread issues every load (surplus threads repeat the last vector; only `stash` is
+    // predicated): the number of loads in flight is then the same for all wavefronts and known to the compiler,
+    // which can wait for one ring slot instead of for everything outstanding.
     auto fetch = [&](int slot, int k0) {
 #pragma unroll
         for (int i = 0; i < NA; ++i) {
-            const int v = tid + i * 256;
-            if (VA % 256 == 0 || v < VA) ra[slot][i] = al.load(0, m0 + (v % (BM / 8)) * 8, k0 + v / (BM / 8), M, k_end);
+            const int v = VA % 256 == 0 ? tid + i * 256 : min(tid + i * 256, VA - 1);
+            ra[slot][i] = al.load(0, m0 + (v / KT) * 8, k0 + v % KT, M, k_end);
         }
 #pragma unroll
         for (int i = 0; i < NB; ++i) {
-            const int v = tid + i * 256;
-            if (VB % 256 == 0 || v < VB) rb[slot][i] = bl.load(0, n0 + (v % (BN / 8)) * 8, k0 + v / (BN / 8), N, k_end);
+            const int v = VB % 256 == 0 ? tid + i * 256 : min(tid + i * 256, VB - 1);
+            rb[slot][i] = bl.load(0, n0 + (v / KT) * 8, k0 + v % KT, N, k_end);
         }
     };
     auto stash = [&](int slot, int buf) {
 #pragma unroll
         for (int i = 0; i < NA; ++i) {
             const int v = tid + i * 256;
-            if (VA % 256 == 0 || v < VA) *reinterpret_cast<bf16x8*>(&sA[buf][(v / (BM / 8)) * LDA + (v % (BM / 8)) * 8]) = ra[slot][i];
+            if (VA % 256 == 0 || v < VA) *reinterpret_cast<bf16x8*>(&sA[buf][(v % KT) * LDA + (v / KT) * 8]) = ra[slot][i];
         }
 #pragma unroll
         for (int i = 0; i < NB; ++i) {
             const int v = tid + i * 256;
-            if (VB % 256 == 0 || v < VB) *reinterpret_cast<bf16x8*>(&sB[buf][(v / (BN / 8)) * LDB + (v % (BN / 8)) * 8]) = rb[slot][i];
+            if (VB % 256 == 0 || v < VB) *reinterpret_cast<bf16x8*>(&sB[buf][(v % KT) * LDB + (v / KT) * 8]) = rb[slot][i];
         }
     };
 
@@ -107,8 +112,8 @@ __device__ inline void gemm_tn_tr_block(const AL& al, const BL& bl, const EP& ep
 #pragma unroll
         for (int u = 0; u < D; ++u) {
             const int k0 = kb + u * KT;
+            fetch((u + D - 1) % D, k0 + (D - 1) * KT);   // unconditional: see fetch
             if (k0 < k_end) {                 // uniform across the workgroup
-                fetch((u + D - 1) % D, k0 + (D - 1) * KT);
                 const int buf = u & 1;
                 stash(u, buf);
                 __syncthreads();     // also: every wavefront is done reading the other buffer

@@ -250,7 +250,7 @@ __global__ __launch_bounds__(256) void head_fwd_kernel(HeadArgs a)
 
 // Small reductions of the backward pass, one launch:
 //  * blocks [0, first_block[4]): bias gradients = column sums of the four dZ matrices ([rows][C], T),
-//    first stage: a block sums up to kBiasRows rows of eight channels into partial[layer][chunk][C];
+//    first stage: a block sums up to kBiasRows rows (all channels) into partial[layer][chunk][C];
 //    the optimiser kernel adds the chunks in order, so no atomics and no extra launch are needed;
 //  * the last 33 blocks: fc2's weight gradient (32 blocks of 16 columns) and its bias gradient + loss.  dQ has one non-zero per row (the taken action):
 //    dW2[a][o] = sum_{b: a_b = a} dq_b h[b][o];  db2[a] = sum_{b: a_b = a} dq_b;  loss = mean_b loss_b.
@@ -346,31 +346,44 @@ __device__ inline void small_grads_block(const BiasGradArgs& args, int block, un
         }
         return;
     }
+    // column sums of one chunk of rows, all channels: thread -> (16-byte vector of the row, row mod RP), so a
+    // pass of the workgroup reads RP whole rows, fully coalesced; the RP partial rows meet in LDS in row order
     int layer = 0;
     while (layer < 3 && block >= args.first_block[layer + 1]) ++layer;
-    const int local = block - args.first_block[layer];
-    const int C = args.chans[layer], rows = args.rows[layer], cgs = C / 8;
-    const int cg = local % cgs, chunk = local / cgs;
-    const T* dz = static_cast<const T*>(args.dz[layer]) + cg * 8;
+    const int chunk = block - args.first_block[layer];
+    const int C = args.chans[layer], rows = args.rows[layer], VR = C / 8, RP = 256 / VR;
+    const int vec = tid % VR, rsub = tid / VR;
+    const T* dz = static_cast<const T*>(args.dz[layer]) + vec * 8;
     const int r_end = min(rows, (chunk + 1) * kBiasRows);
     float acc[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) acc[e] = 0.f;
-    for (int r = chunk * kBiasRows + tid; r < r_end; r += 256) {
-        const V8 v = *reinterpret_cast<const V8*>(dz + static_cast<size_t>(r) * C);
+    // four rows in flight per thread (clamped address, masked value: no load is ever skipped)
+    for (int r = chunk * kBiasRows + rsub; r < r_end; r += 4 * RP) {
+        V8 v[4];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) acc[e] += to_float(v[e]);
+        for (int u = 0; u < 4; ++u) {
+            const int rr = r + u * RP;
+            v[u] = vec8_keep<T>(*reinterpret_cast<const V8*>(dz + static_cast<size_t>(rr < r_end ? rr : r_end - 1) * C), rr < r_end);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[e] += to_float(v[u][e]);
     }
 #pragma unroll
     for (int e = 0; e < 8; ++e) red[tid][e] = acc[e];
     __syncthreads();
-    for (int stride = 128; stride >= 1; stride >>= 1) {
-        if (tid < stride)
-#pragma unroll
-            for (int e = 0; e < 8; ++e) red[tid][e] += red[tid + stride][e];
-        __syncthreads();
+    // RP partial rows per channel, added in row order; four lanes per channel take every fourth partial
+    // and meet in a fixed tree (RP is 64, 32 or 4)
+    for (int i = tid; i < 4 * C; i += 256) {
+        const int c = i >> 2, j = i & 3;
+        float sum = 0.f;
+        for (int q = j; q < RP; q += 4) sum += red[q * VR + (c >> 3)][c & 7];
+        sum += __shfl_down(sum, 2, 4);
+        sum += __shfl_down(sum, 1, 4);
+        if (j == 0) args.partial[args.first_partial[layer] + chunk * C + c] = sum;
     }
-    if (tid < 8) args.partial[args.first_partial[layer] + chunk * C + cg * 8 + tid] = red[0][tid];
 }
 
 template <typename T>

@@ -62,10 +62,14 @@ template <typename T> struct DenseM {
     static constexpr bool kAlongK = false;
     const T* p[kMaxGroups];
     int ld;
+    // Branch-free (the address is clamped, the value selected): a load that may be skipped makes the
+    // compiler wait for *all* outstanding loads wherever it needs one of them, which defeats a prefetch ring.
     __device__ typename Vec8<T>::type load(int g, int row0, int k, int rows, int k_end) const
     {
-        if (row0 >= rows || k >= k_end) return vec8_zero<T>();
-        return *reinterpret_cast<const typename Vec8<T>::type*>(p[g] + static_cast<size_t>(k) * ld + row0);
+        const bool ok = row0 < rows && k < k_end;
+        const int kc = k < k_end ? k : k_end - 1, rc = row0 < rows ? row0 : 0;
+        const typename Vec8<T>::type v = *reinterpret_cast<const typename Vec8<T>::type*>(p[g] + static_cast<size_t>(kc) * ld + rc);
+        return vec8_keep<T>(v, ok);
     }
 };
 
@@ -110,13 +114,15 @@ template <typename T, int CIN, int COUT, int KS, int S> struct DgradB {
 template <typename T, int CIN, int HIN, int WIN, int HOUT, int WOUT, int KS, int S> struct WgradB {
     static constexpr bool kAlongK = false;
     const T* x;
-    __device__ typename Vec8<T>::type load(int, int row0, int k, int rows, int k_end) const
+    __device__ typename Vec8<T>::type load(int, int row0, int k, int rows, int k_end) const   // branch-free, see DenseM
     {
-        if (row0 >= rows || k >= k_end) return vec8_zero<T>();
-        const int c0 = row0 % CIN, pq = row0 / CIN, q = pq % KS, p = pq / KS;
-        const int b = k / (HOUT * WOUT), ij = k % (HOUT * WOUT), i = ij / WOUT, j = ij % WOUT;
-        return *reinterpret_cast<const typename Vec8<T>::type*>(
+        const bool ok = row0 < rows && k < k_end;
+        const int kc = k < k_end ? k : k_end - 1, rc = row0 < rows ? row0 : 0;
+        const int c0 = rc % CIN, pq = rc / CIN, q = pq % KS, p = pq / KS;
+        const int b = kc / (HOUT * WOUT), ij = kc % (HOUT * WOUT), i = ij / WOUT, j = ij % WOUT;
+        const typename Vec8<T>::type v = *reinterpret_cast<const typename Vec8<T>::type*>(
             x + (static_cast<size_t>(b * HIN + i * S + p) * WIN + j * S + q) * CIN + c0);
+        return vec8_keep<T>(v, ok);
     }
 };
 
@@ -124,14 +130,17 @@ template <typename T, int CIN, int HIN, int WIN, int HOUT, int WOUT, int KS, int
 template <typename T> struct Conv1WgradB {
     static constexpr bool kAlongK = false;
     const uint8_t* x;
-    __device__ typename Vec8<T>::type load(int, int row0, int k, int rows, int k_end) const
+    __device__ typename Vec8<T>::type load(int, int row0, int k, int rows, int k_end) const   // branch-free, see DenseM
     {
-        if (row0 >= rows || k >= k_end) return vec8_zero<T>();
-        const int c = row0 >> 6, p = (row0 >> 3) & 7;
-        const int b = k / 400, ij = k % 400, i = ij / 20, j = ij % 20;
+        const bool ok = row0 < rows && k < k_end;
+        const int kc = k < k_end ? k : k_end - 1, rc = row0 < rows ? row0 : 0;
+        const int c = rc >> 6, p = (rc >> 3) & 7;
+        const int b = kc / 400, ij = kc % 400, i = ij / 20, j = ij % 20;
         const uint32_t* ptr = reinterpret_cast<const uint32_t*>(
             x + (static_cast<size_t>(b * 4 + c) * 84 + 4 * i + p) * 84 + 4 * j);
-        return vec8_from_u8<T>(ptr[0], ptr[1]);
+        const uint32_t lo = ptr[0], hi = ptr[1];
+        const uint32_t m = ok ? 0xFFFFFFFFu : 0u;   // byte 0 converts to 0.0
+        return vec8_from_u8<T>(lo & m, hi & m);
     }
 };
 

@@ -365,7 +365,7 @@ static int train_impl(dqn_ctx* c, const uint8_t* s, const int32_t* a, const floa
         int pofs = 0;
         for (int l = 0; l < 4; ++l) {
             bg.chunks[l] = (bg.rows[l] + kBiasRows - 1) / kBiasRows;
-            bg.first_block[l + 1] = bg.first_block[l] + bg.chunks[l] * (bg.chans[l] / 8);
+            bg.first_block[l + 1] = bg.first_block[l] + bg.chunks[l];
             bg.first_partial[l] = pofs;
             pofs += bg.chunks[l] * bg.chans[l];
             bias_chunks[l] = bg.chunks[l];
