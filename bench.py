@@ -310,7 +310,7 @@ def main():
     ap.add_argument("--sweep", action="store_true", help="print the batch/W roofline sweep instead of the JSON line")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py measures one MI355X: this build has no multi-GPU path, run with --gpus 1", file=sys.stderr)
+        print("bench.py measures one MI355X: this library runs on one GPU, run with --gpus 1", file=sys.stderr)
         return 2
 
     if args.sweep:

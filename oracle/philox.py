@@ -2,7 +2,7 @@
 as easy as 1, 2, 3", SC'11), written from its published definition.  TEST INFRASTRUCTURE ONLY.
 
 The paper names no generator for its epsilon-greedy draws (Section 2.1) or for "sampled randomly
-from D"; this build's reading fixes one counter-based generator that the oracle and the GPU
+from D"; the reading taken here fixes one counter-based generator that the oracle and the GPU
 library each implement on their own:
 
     key     = (seed & 0xFFFFFFFF, seed >> 32)

@@ -5,7 +5,7 @@ Follows Section 2.1 (experiences (s_t, a_t, r_t, s_{t+1}) buffered in D and "sam
 and Section 3 (experiences collected while training runs are held in temporary buffers and moved
 into D only at the synchronisation point, so D is constant during training; Algorithm 1's
 "flush all sampler threads' temporary buffers" step).  The paper does not say how a state is
-assembled from stored frames; this build's reading:
+assembled from stored frames; the reading taken here:
 
   * D holds single 84x84 uint8 frames o_t with (a_t, r_t, d_t); d_t = 1 iff the episode ended
     after a_t.  D is split into L lanes (one per sampler); lane l owns M = N/L slots and is a ring
