@@ -196,43 +196,58 @@ __global__ __launch_bounds__(256) void head_fwd_kernel(HeadArgs a)
         }
     __syncthreads();
 
-    auto argmax_lowest = [&](const float* q) {
-        int best = 0;
-        for (int k = 1; k < a.A; ++k)
-            if (q[k] > q[best]) best = k;
+    // Tail: wavefront 0, 32 lanes per row (kHeadRows = 2), lane k owns action k.  argmax with the lowest index
+    // among equal values (the tie rule of the greedy policy, Section 2.1), as a butterfly over the 32 lanes.
+    static_assert(kHeadRows == 2 && kMaxActions <= 32, "tail layout: one wavefront, 32 lanes per row");
+    auto argmax_lowest = [&](float v, int k) {   // every lane of the row returns the winner
+        int best = k;
+#pragma unroll
+        for (int m = 16; m >= 1; m >>= 1) {
+            const float ov = __shfl_xor(v, m, 32);
+            const int ob = __shfl_xor(best, m, 32);
+            if (ov > v || (ov == v && ob < best)) { v = ov; best = ob; }
+        }
         return best;
     };
+    const int trow = lane >> 5, tk = lane & 31;    // tail row / action of this lane (wavefront 0 only)
+    const float kNegInf = -__builtin_huge_valf();
     if constexpr (MODE == kHeadAct) {
-        const int row = row0 + tid;
-        if (tid >= kHeadRows || row >= a.rows) return;
-        const float* q = s_q[0][tid];
-        if (a.q_out)
-            for (int k = 0; k < a.A; ++k) a.q_out[static_cast<size_t>(row) * a.A + k] = q[k];
-        const Philox4 d = philox_draw(a.seed, kTagAct, a.act_step, static_cast<uint32_t>(row));
-        const float u = static_cast<float>(d.x[0] >> 8) * 0x1p-24f;
-        int act = argmax_lowest(q);
-        if (u < a.epsilon) act = static_cast<int>((static_cast<uint64_t>(d.x[1]) * static_cast<uint32_t>(a.A)) >> 32);
-        a.actions[row] = act;
+        if (wave != 0) return;
+        const int row = row0 + trow;
+        const float qv = tk < a.A ? s_q[0][trow][tk] : kNegInf;
+        int act = argmax_lowest(qv, tk);
+        if (row >= a.rows) return;
+        if (a.q_out && tk < a.A) a.q_out[static_cast<size_t>(row) * a.A + tk] = qv;
+        if (tk == 0) {
+            const Philox4 d = philox_draw(a.seed, kTagAct, a.act_step, static_cast<uint32_t>(row));
+            const float u = static_cast<float>(d.x[0] >> 8) * 0x1p-24f;
+            if (u < a.epsilon) act = static_cast<int>((static_cast<uint64_t>(d.x[1]) * static_cast<uint32_t>(a.A)) >> 32);
+            a.actions[row] = act;
+        }
     } else {
-        if (tid < kHeadRows) {
-            const int row = row0 + tid;
-            float dq = 0.f;
-            int act_b = 0;
-            if (row < a.rows) {
-                for (int g = 0; g < a.groups; ++g)
-                    for (int k = 0; k < a.A; ++k) a.q_all[(static_cast<size_t>(g) * a.rows + row) * a.A + k] = s_q[g][tid][k];
-                const float* qt = s_q[1][tid];
-                const int astar = a.double_dqn ? argmax_lowest(s_q[2][tid]) : argmax_lowest(qt);
-                const float y = a.rew[row] + a.gamma * (1.f - a.done[row]) * qt[astar];
-                act_b = a.act[row];
-                const float delta = s_q[0][tid][act_b] - y;
-                const float ad = fabsf(delta);
-                a.lossv[row] = ad <= a.huber ? 0.5f * delta * delta : a.huber * (ad - 0.5f * a.huber);
-                dq = fminf(fmaxf(delta, -a.huber), a.huber) / static_cast<float>(a.rows);
-                a.dqv[row] = dq;
+        if (wave == 0) {
+            const int row = row0 + trow;
+            const bool live = row < a.rows;
+            const float qt = tk < a.A ? s_q[1][trow][tk] : kNegInf;
+            const float qsel = a.double_dqn ? (tk < a.A ? s_q[2][trow][tk] : kNegInf) : qt;
+            const int astar = argmax_lowest(qsel, tk);
+            if (live && tk < a.A)
+                for (int g = 0; g < a.groups; ++g) a.q_all[(static_cast<size_t>(g) * a.rows + row) * a.A + tk] = s_q[g][trow][tk];
+            if (tk == 0) {
+                float dq = 0.f;
+                int act_b = 0;
+                if (live) {
+                    const float y = a.rew[row] + a.gamma * (1.f - a.done[row]) * s_q[1][trow][astar];
+                    act_b = a.act[row];
+                    const float delta = s_q[0][trow][act_b] - y;
+                    const float ad = fabsf(delta);
+                    a.lossv[row] = ad <= a.huber ? 0.5f * delta * delta : a.huber * (ad - 0.5f * a.huber);
+                    dq = fminf(fmaxf(delta, -a.huber), a.huber) / static_cast<float>(a.rows);
+                    a.dqv[row] = dq;
+                }
+                s_dq[trow] = dq;
+                s_act[trow] = act_b;
             }
-            s_dq[tid] = dq;
-            s_act[tid] = act_b;
         }
         __syncthreads();
         // fc2's data gradient through fc1's ReLU for this workgroup's rows: dQ has one non-zero per row
