@@ -59,6 +59,27 @@ def kernel_work(name, B, A, groups, precision):
     return t[name]
 
 
+# HBM traffic per launch measured with rocprofv3 (FETCH_SIZE and WRITE_SIZE in separate runs, scaled by what the
+# same counters read for the target copy of known size): {(kernel, batch, precision): (bytes, source file, sha1 of
+# that file when the counters were taken)}.  Reported only while the kernel's source still hashes to that value.
+TRAFFIC = {
+}
+
+
+def measured_traffic(name, B, precision):
+    import hashlib
+    ent = TRAFFIC.get((name, B, precision))
+    if not ent:
+        return None
+    nbytes, src, sha = ent
+    try:
+        with open(os.path.join(ROOT, src), "rb") as f:
+            cur = hashlib.sha1(f.read()).hexdigest()
+    except OSError:
+        return None
+    return nbytes if cur == sha else None
+
+
 def roofline_for(name, avg_ms, B, A, groups, precision):
     flops, nbytes = kernel_work(name, B, A, groups, precision)
     peak_f = PEAK["bf16" if precision == "bf16" else "f32"][0]
@@ -201,12 +222,22 @@ class Workload:
                 self._fail("dqn_train_step", rc)
             self.train_steps += 1
 
-    def run(self, steps):
+    def run(self, steps, part="both"):
         """`steps` benchmark steps: the trainer thread and the sampler (this) thread run concurrently
-        between synchronisation points, as in Algorithm 1 (no host synchronisation with the GPU)."""
+        between synchronisation points, as in Algorithm 1 (no host synchronisation with the GPU).
+        part = "train" / "act" runs only that side (same sync schedule), for the alone-vs-overlapped figures."""
         import threading
         done = 0
         while done < steps:
+            if part != "both":
+                self.sync_point()
+                n = min(steps - done, self.sync_every)
+                if part == "train":
+                    self.train_part(n)
+                else:
+                    self.act_part(n)
+                done += n
+                continue
             if self.train_steps % self.sync_every == 0:
                 self.sync_point()
             n = min(steps - done, self.sync_every - self.train_steps % self.sync_every)
@@ -232,11 +263,11 @@ class Workload:
         self.P.dqn_destroy(self.ctx)
 
 
-def time_steps(wl, steps):
+def time_steps(wl, steps, part="both"):
     torch = wl.torch
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    wl.run(steps)
+    wl.run(steps, part)
     torch.cuda.synchronize()
     return time.perf_counter() - t0
 
@@ -331,9 +362,14 @@ def main():
     wl.P.dqn_profile_select(wl.ctx, 0)
     # an event bracket also spans the two event records themselves: an empty bracket measures that share
     roof = roofline_for(dominant, max(ms / max(n, 1) - pair_ms, 1e-6), args.batch, args.actions, groups, args.precision)
+    roof["traffic"] = measured_traffic(dominant, args.batch, args.precision)
     roof["timed_launches"] = n
     roof["bracket_us"] = ms / max(n, 1) * 1e3
     roof["empty_bracket_us"] = pair_ms * 1e3
+    # each side alone (what the overlap hides): short runs outside the timed region
+    alone_steps = max(min(args.steps // 5, 2000), 1)
+    train_alone = alone_steps / time_steps(wl, alone_steps, "train")
+    act_alone = (alone_steps * args.acts_per_train * args.envs / time_steps(wl, alone_steps, "act")) if args.acts_per_train else 0.0
     wl.close()
 
     out = {
@@ -341,6 +377,8 @@ def main():
         "value": args.steps / elapsed,
         "unit": "train steps/s",
         "act_states_per_sec": args.steps * args.acts_per_train * args.envs / elapsed,
+        "alone": {"train_steps_per_sec": train_alone, "act_states_per_sec": act_alone,
+                  "note": "each side run by itself over %d steps; `value` is with both overlapped" % alone_steps},
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": 1e3 * elapsed / args.steps,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
