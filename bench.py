@@ -63,6 +63,8 @@ def kernel_work(name, B, A, groups, precision):
 # same counters read for the target copy of known size): {(kernel, batch, precision): (bytes, source file, sha1 of
 # that file when the counters were taken)}.  Reported only while the kernel's source still hashes to that value.
 TRAFFIC = {
+    ("rmsprop", 32, "bf16"): (64.65e6, "paper_2111_01264_amd/csrc/head_kernels.h", "6b7ae4a43013544605212a5a9fb975849f73f52c"),
+    ("rmsprop", 256, "bf16"): (68.18e6, "paper_2111_01264_amd/csrc/head_kernels.h", "6b7ae4a43013544605212a5a9fb975849f73f52c"),
 }
 
 
