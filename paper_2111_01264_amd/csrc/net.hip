@@ -391,11 +391,11 @@ static int train_impl(dqn_ctx* c, const uint8_t* s, const int32_t* a, const floa
         wa.epf = EpiGrad{c->grad + o.wf1, 3136, 1.f};
         wa.small = bg;
         wa.first[0] = 0;
-        wa.first[1] = wa.first[0] + 2 * wa.splits1;
-        wa.first[2] = wa.first[1] + 2 * wa.splits2;
-        wa.first[3] = wa.first[2] + 3 * wa.splits3;
+        wa.first[1] = wa.first[0] + small_blocks;
+        wa.first[2] = wa.first[1] + 3 * wa.splits3;
+        wa.first[3] = wa.first[2] + 2 * wa.splits2;
         wa.first[4] = wa.first[3] + 25 * 8;
-        wa.first[5] = wa.first[4] + small_blocks;
+        wa.first[5] = wa.first[4] + 2 * wa.splits1;
         const ProfPair pr = prof_pair(c, K_WGRAD_ALL);
         if (pr.begin) (void)hipEventRecord(pr.begin, st);
         hipLaunchKernelGGL(wgrad_all_kernel, dim3(wa.first[5]), dim3(256), kWgradAllSmem, st, wa);

@@ -2,7 +2,7 @@
 // tensors exist, and the four weight-gradient GEMMs (conv1, conv2, conv3, fc1) and the small
 // reductions (bias gradients, fc2 gradient, loss) are independent of each other; at batch 32 each is
 // a few microseconds of work behind a launch that costs about as much on the host.  The grid is the
-// concatenation of their workgroups, heaviest first.
+// concatenation of their workgroups.
 #pragma once
 #include "gemm_tn_tr.h"
 #include "head_kernels.h"
@@ -18,7 +18,7 @@ struct WgradAllArgs {
     // fc1: dW[o][f] = sum_b dZ[b][o] * act3[b][f], written straight into the gradient blob
     DenseM<bf16_t> af, bf; EpiGrad epf; int Kf;
     BiasGradArgs small;
-    int first[6];   // first block of: conv1, conv2, conv3, fc1, small reductions, end
+    int first[6];   // first block of: small reductions, conv3, conv2, fc1, conv1, end
 };
 
 constexpr int kWg1BN = 128, kWg2BN = 256, kWg3BN = 192, kWgfBN = 128;   // column blocks: 2, 2, 3, 25 per slice
@@ -28,26 +28,28 @@ constexpr size_t kWgradAllSmem =
 __global__ __launch_bounds__(256) void wgrad_all_kernel(WgradAllArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char wg_smem[];
+    // grid order: small reductions, conv3, conv2, fc1, conv1 -- longest workgroups first; the grid exceeds what is
+    // resident at once, and the workgroups that start late should be the short ones (conv1's)
     const int blk = blockIdx.x;
     const EpiGrad none{nullptr, 0, 1.f};
     if (blk < a.first[1]) {
-        const int i = blk - a.first[0];
-        gemm_tn_tr_block<DenseM<bf16_t>, Conv1WgradB<bf16_t>, EpiGrad, 32, kWg1BN, 4>(
-            a.a1, a.b1, none, 32, 256, a.K1, a.kps1, a.p1, true, i % 2, i / 2, 0, wg_smem);
+        small_grads_block<bf16_t>(a.small, blk - a.first[0], wg_smem);
     } else if (blk < a.first[2]) {
         const int i = blk - a.first[1];
-        gemm_tn_tr_block<DenseM<bf16_t>, WgradB<bf16_t, 32, 20, 20, 9, 9, 4, 2>, EpiGrad, 64, kWg2BN, 4>(
-            a.a2, a.b2, none, 64, 512, a.K2, a.kps2, a.p2, true, i % 2, i / 2, 0, wg_smem);
-    } else if (blk < a.first[3]) {
-        const int i = blk - a.first[2];
         gemm_tn_tr_block<DenseM<bf16_t>, WgradB<bf16_t, 64, 9, 9, 7, 7, 3, 1>, EpiGrad, 64, kWg3BN, 4>(
             a.a3, a.b3, none, 64, 576, a.K3, a.kps3, a.p3, true, i % 3, i / 3, 0, wg_smem);
+    } else if (blk < a.first[3]) {
+        const int i = blk - a.first[2];
+        gemm_tn_tr_block<DenseM<bf16_t>, WgradB<bf16_t, 32, 20, 20, 9, 9, 4, 2>, EpiGrad, 64, kWg2BN, 4>(
+            a.a2, a.b2, none, 64, 512, a.K2, a.kps2, a.p2, true, i % 2, i / 2, 0, wg_smem);
     } else if (blk < a.first[4]) {
         const int i = blk - a.first[3];
         gemm_tn_tr_block<DenseM<bf16_t>, DenseM<bf16_t>, EpiGrad, 64, kWgfBN, 2>(
             a.af, a.bf, a.epf, 512, 3136, a.Kf, (a.Kf + 31) / 32 * 32, nullptr, false, i % 25, 0, i / 25, wg_smem);
     } else {
-        small_grads_block<bf16_t>(a.small, blk - a.first[4], wg_smem);
+        const int i = blk - a.first[4];
+        gemm_tn_tr_block<DenseM<bf16_t>, Conv1WgradB<bf16_t>, EpiGrad, 32, kWg1BN, 4>(
+            a.a1, a.b1, none, 32, 256, a.K1, a.kps1, a.p1, true, i % 2, i / 2, 0, wg_smem);
     }
 }
 
