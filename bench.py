@@ -109,6 +109,7 @@ class Workload:
         self.seed = args.seed
         self.precision = args.precision
         self.acts_per_train = args.acts_per_train
+        self.fused_push = not args.separate_push
         self.sync_every = args.sync_every
         self.double = int(args.double_dqn)
         torch.cuda.set_device(0)
@@ -196,20 +197,34 @@ class Workload:
         self.P.dqn_sync_target(self.ctx, self.rb, 0)
 
     def act_part(self, n_train_steps):
-        """Sampler side of n train steps: acts_per_train act steps each (Q evaluation, epsilon-greedy, push)."""
+        """Sampler side of n train steps: acts_per_train act steps each (Q evaluation, epsilon-greedy, push of the
+        experiences the step produced).  From the second step on, the push of step t-1 and the Q evaluation of
+        step t are one call (dqn_act_push_step); the last push of the part is issued by itself."""
         lib, ctx, rb, W, pool = self._lib, self.ctx, self.rb, self.W, self.pool
         push = self.W == self.lanes
         pa = self._p_actions
+        pending = -1
         for _ in range(n_train_steps * self.acts_per_train):
             k = self.act_steps % pool
-            rc = lib.dqn_act(ctx, self._p_states[k], W, 0.1, self.act_steps, 1, pa, None)
-            if rc:
-                self._fail("dqn_act", rc)
-            if push:
-                rc = lib.replay_push_step(rb, self._p_frames[k], pa, self._p_rew[k], self._p_term[k])
+            if push and pending >= 0 and self.fused_push:
+                rc = lib.dqn_act_push_step(ctx, rb, self._p_frames[pending], pa, self._p_rew[pending], self._p_term[pending],
+                                           self._p_states[k], W, 0.1, self.act_steps, 1, pa, None)
                 if rc:
-                    self._fail("replay_push_step", rc)
+                    self._fail("dqn_act_push_step", rc)
+            else:
+                rc = lib.dqn_act(ctx, self._p_states[k], W, 0.1, self.act_steps, 1, pa, None)
+                if rc:
+                    self._fail("dqn_act", rc)
+                if push and not self.fused_push:
+                    rc = lib.replay_push_step(rb, self._p_frames[k], pa, self._p_rew[k], self._p_term[k])
+                    if rc:
+                        self._fail("replay_push_step", rc)
+            pending = k
             self.act_steps += 1
+        if push and self.fused_push and pending >= 0:
+            rc = lib.replay_push_step(rb, self._p_frames[pending], pa, self._p_rew[pending], self._p_term[pending])
+            if rc:
+                self._fail("replay_push_step", rc)
 
     def train_part(self, n_train_steps):
         """Trainer side: sample + gather + train step, n times."""
@@ -340,6 +355,8 @@ def main():
     ap.add_argument("--seed", type=int, default=211101264 + 2)
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--separate-push", action="store_true",
+                    help="replay_push_step and dqn_act as two calls per act step instead of dqn_act_push_step")
     ap.add_argument("--sweep", action="store_true", help="print the batch/W roofline sweep instead of the JSON line")
     args = ap.parse_args()
     if args.gpus != 1:

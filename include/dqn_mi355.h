@@ -156,6 +156,20 @@ int replay_push(replay* rb, int32_t lane, const uint8_t* frames, const int32_t* 
 int replay_push_step(replay* rb, const uint8_t* frames, const int32_t* actions, const float* rewards,
                      const uint8_t* terminals);
 
+/* One synchronized step of the samplers as a single launch sequence (Section 4: one device
+ * transaction per step for all W environments): exactly replay_push_step(rb, push_frames, push_actions,
+ * push_rewards, push_terminals) -- the experiences the previous step produced -- followed by
+ * dqn_act(ctx, states, W, epsilon, act_step, use_target, actions, q_out) on the states that step led
+ * to; in the reduced-precision mode the append rides in the first kernel of the act step instead of
+ * costing a dependent launch of its own.  push_actions may be the `actions` buffer of the previous
+ * call (it is read before this call's actions are written).  The replay memory's push stream must be
+ * the context's act stream.  Arguments, results and errors as for the two calls; DQN_EINVAL also if
+ * the streams differ. */
+int dqn_act_push_step(dqn_ctx* ctx, replay* rb, const uint8_t* push_frames, const int32_t* push_actions,
+                      const float* push_rewards, const uint8_t* push_terminals, const uint8_t* states,
+                      int32_t W, float epsilon, uint64_t act_step, int32_t use_target, int32_t* actions,
+                      float* q_out);
+
 /* Moves every lane's buffered experiences into D in push order, overwriting the oldest. */
 int replay_flush(replay* rb, int32_t blocking);
 

@@ -56,6 +56,9 @@ EXPORTS = {
     "replay_push": (C.c_int, [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                               C.c_int32]),
     "replay_push_step": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
+    "dqn_act_push_step": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                    C.c_void_p, C.c_int32, C.c_float, C.c_uint64, C.c_int32, C.c_void_p,
+                                    C.c_void_p]),
     "replay_flush": (C.c_int, [C.c_void_p, C.c_int32]),
     "replay_num_valid": (C.c_int64, [C.c_void_p]),
     "replay_sample_gather": (C.c_int, [C.c_void_p, C.c_int32, C.c_uint64, C.c_void_p, C.c_void_p,
@@ -171,6 +174,13 @@ def replay_push(rb, lane, frames, actions, rewards, terminals, n):
 
 def replay_push_step(rb, frames, actions, rewards, terminals):
     _check(_lib.replay_push_step(rb, _ptr(frames), _ptr(actions), _ptr(rewards), _ptr(terminals)))
+
+
+def dqn_act_push_step(ctx, rb, push_frames, push_actions, push_rewards, push_terminals, states, W, epsilon,
+                      act_step, use_target, actions, q_out=None):
+    _check(_lib.dqn_act_push_step(ctx, rb, _ptr(push_frames), _ptr(push_actions), _ptr(push_rewards),
+                                  _ptr(push_terminals), _ptr(states), W, epsilon, act_step, use_target,
+                                  _ptr(actions), _ptr(q_out)))
 
 
 def replay_flush(rb, blocking):

@@ -107,6 +107,8 @@ struct TowerArgs {
     bf16_t* act3[kMaxGroups];   // [n][49][64]
     int n, groups;
     int per;                    // items per workgroup = ceil(n * groups / grid size), computed by the host
+    int tower_blocks;           // workgroups [0, tower_blocks) run the tower, the next push.L ones the append below
+    PushStepPlan push;          // optional (L = 0: none): one experience per lane into the temporary buffers
 };
 
 constexpr int kTowerP1 = 40, kTowerP2 = kTowerP2_;   // LDS pixel pitch (elements) of conv1 / conv2 outputs
@@ -131,6 +133,12 @@ __global__ __launch_bounds__(kTowerThreads) void conv_tower_kernel(TowerArgs a)
     float* sB2 = sB1 + 32;
     float* sB3 = sB2 + 64;
 
+    if (static_cast<int>(blockIdx.x) >= a.tower_blocks) {
+        // An act step's launch sequence also carries the append of the previous step's experiences (Section 3:
+        // temporary buffers): independent byte copies that would otherwise cost a dependent launch of their own.
+        push_step_block(a.push, static_cast<int>(blockIdx.x) - a.tower_blocks);
+        return;
+    }
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lp = lane & 31, kg = lane >> 5;
     const int nt = wave >> 2, kq = wave & 3;

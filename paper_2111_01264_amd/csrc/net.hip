@@ -155,7 +155,8 @@ static int fc1_slices(int n, int groups)
 // fc1 k-slices; the number of slices comes back through *slices_out.
 template <typename T>
 static int forward_to_fc1(dqn_ctx* c, hipStream_t st, Workspace& ws, int groups, const uint8_t* const* x,
-                          const void* const* shadow, const float* const* master, int n, bool timed, int* slices_out)
+                          const void* const* shadow, const float* const* master, int n, bool timed, int* slices_out,
+                          const PushStepPlan* push = nullptr)
 {
     const Offsets& o = c->off;
     auto pp = [&](int id) { return timed ? prof_pair(c, id) : ProfPair(); };
@@ -181,9 +182,12 @@ static int forward_to_fc1(dqn_ctx* c, hipStream_t st, Workspace& ws, int groups,
         }
         const int total = n * groups, grid = total < c->num_cus ? total : c->num_cus;
         a.per = (total + grid - 1) / grid;
+        a.tower_blocks = grid;
+        a.push.L = 0;
+        if (push) a.push = *push;
         const ProfPair pr = pp(K_CONV1_FWD);
         if (pr.begin) (void)hipEventRecord(pr.begin, st);
-        hipLaunchKernelGGL(conv_tower_kernel, dim3(grid), dim3(kTowerThreads), kTowerSmem, st, a);
+        hipLaunchKernelGGL(conv_tower_kernel, dim3(grid + a.push.L), dim3(kTowerThreads), kTowerSmem, st, a);
         if (pr.end) (void)hipEventRecord(pr.end, st);
         DQN_LAUNCH_CHECK();
     } else {
@@ -257,13 +261,13 @@ static int forward_to_fc1(dqn_ctx* c, hipStream_t st, Workspace& ws, int groups,
 
 template <typename T>
 static int act_impl(dqn_ctx* c, const uint8_t* states, int W, float epsilon, uint64_t act_step, int use_target,
-                    int32_t* actions, float* q_out)
+                    int32_t* actions, float* q_out, const PushStepPlan* push = nullptr)
 {
     const uint8_t* x[1] = {states};
     const void* shadow[1] = {use_target ? c->sh_t : c->sh};
     const float* master[1] = {use_target ? c->theta_t : c->theta};
     int slices = 0;
-    const int rc = forward_to_fc1<T>(c, c->act_stream, c->act_ws, 1, x, shadow, master, W, false, &slices);
+    const int rc = forward_to_fc1<T>(c, c->act_stream, c->act_ws, 1, x, shadow, master, W, false, &slices, push);
     if (rc != DQN_OK) return rc;
     HeadArgs ha{};
     ha.partial = c->act_ws.partial; ha.slices = slices; ha.rows = W; ha.A = c->A; ha.groups = 1;
@@ -664,6 +668,36 @@ int dqn_act(dqn_ctx* c, const uint8_t* states, int32_t W, float epsilon, uint64_
                        ? act_impl<bf16_t>(c, states, W, epsilon, act_step, use_target, actions, q_out)
                        : act_impl<float>(c, states, W, epsilon, act_step, use_target, actions, q_out);
     if (rc != DQN_OK) return rc;
+    if (!use_target) {
+        DQN_HIP(hipEventRecord(c->ev_act, c->act_stream));
+        c->act_reads_online = true;
+    }
+    return DQN_OK;
+}
+
+int dqn_act_push_step(dqn_ctx* c, replay* rb, const uint8_t* push_frames, const int32_t* push_actions,
+                      const float* push_rewards, const uint8_t* push_terminals, const uint8_t* states, int32_t W,
+                      float epsilon, uint64_t act_step, int32_t use_target, int32_t* actions, float* q_out)
+{
+    if (!c || !rb) return fail(DQN_EINVAL, "dqn_act_push_step: ctx or rb is null");
+    if (replay_push_stream(rb) != c->act_stream)
+        return fail(DQN_EINVAL, "dqn_act_push_step: the replay memory's push stream is not the context's act stream");
+    if (c->cfg.precision != DQN_PRECISION_BF16) {
+        // fp32 mode has no fused launch to ride in: the two calls, in order
+        const int rc = replay_push_step(rb, push_frames, push_actions, push_rewards, push_terminals);
+        return rc != DQN_OK ? rc : dqn_act(c, states, W, epsilon, act_step, use_target, actions, q_out);
+    }
+    if (W < 1 || W > c->cfg.max_envs) return fail(DQN_EINVAL, "dqn_act_push_step: W = %d outside 1..%d", W, c->cfg.max_envs);
+    if (!states || !actions) return fail(DQN_EINVAL, "dqn_act_push_step: null pointer");
+    if (!aligned16(states)) return fail(DQN_EINVAL, "dqn_act_push_step: states not 16-byte aligned");
+    if (!(epsilon >= 0.f && epsilon <= 1.f)) return fail(DQN_EINVAL, "dqn_act_push_step: epsilon outside [0,1]");
+    PushStepPlan plan;
+    int rc = replay_plan_push_step(rb, push_frames, push_actions, push_rewards, push_terminals, &plan);
+    if (rc != DQN_OK) return rc;
+    if (!use_target) DQN_HIP(hipStreamWaitEvent(c->act_stream, c->ev_train, 0));
+    rc = act_impl<bf16_t>(c, states, W, epsilon, act_step, use_target, actions, q_out, &plan);
+    if (rc != DQN_OK) return rc;
+    replay_commit_push_step(rb);
     if (!use_target) {
         DQN_HIP(hipEventRecord(c->ev_act, c->act_stream));
         c->act_reads_online = true;

@@ -9,8 +9,6 @@
 
 namespace dqn {
 
-constexpr int kMaxLanes = 64;
-
 struct LaneTable {
     int32_t head[kMaxLanes];   // next write position inside the lane
     int32_t count[kMaxLanes];  // visible frames in the lane
@@ -42,21 +40,6 @@ struct replay {
 
 namespace dqn {
 
-// A frame is 7056 = 110.25 x 64 bytes, so frames in a [n][84][84] array start at every 16-byte phase of a
-// 64-byte line.  A 16-byte store whose group of four lanes straddles a line boundary reaches memory as two
-// partial writes (measured: 1.75x the written bytes on average); shifting the vector index by the
-// destination's phase makes every group of four lanes cover exactly one line.
-__device__ inline int line_phase(const void* p) { return static_cast<int>((reinterpret_cast<uintptr_t>(p) >> 4) & 3); }
-
-__device__ inline void copy_frame(uint8_t* __restrict__ dst, const uint8_t* __restrict__ src)
-{
-    const uint4* s = reinterpret_cast<const uint4*>(src);
-    uint4* d = reinterpret_cast<uint4*>(dst);
-    const int ph = line_phase(dst);
-    for (int v = static_cast<int>(threadIdx.x) - ph; v < kFrameVec16; v += blockDim.x)
-        if (v >= 0) d[v] = s[v];
-}
-
 // Temporary buffer append: frame i of the call goes to staging slot first + i of its lane.
 __global__ __launch_bounds__(256) void push_kernel(
     const uint8_t* __restrict__ frames, const int32_t* __restrict__ actions,
@@ -74,21 +57,7 @@ __global__ __launch_bounds__(256) void push_kernel(
 }
 
 // One experience per lane: row l of the call goes to staging slot l * S + staged[l].
-__global__ __launch_bounds__(256) void push_step_kernel(
-    const uint8_t* __restrict__ frames, const int32_t* __restrict__ actions,
-    const float* __restrict__ rewards, const uint8_t* __restrict__ terminals,
-    uint8_t* __restrict__ st_frames, int32_t* __restrict__ st_actions, float* __restrict__ st_rewards,
-    uint8_t* __restrict__ st_terminals, LaneTable staged, int64_t S)
-{
-    const int64_t l = blockIdx.x;
-    const int64_t dst = l * S + staged.count[l];
-    copy_frame(st_frames + dst * kFrameBytes, frames + l * kFrameBytes);
-    if (threadIdx.x == 0) {
-        st_actions[dst] = actions[l];
-        st_rewards[dst] = rewards[l];
-        st_terminals[dst] = terminals[l];
-    }
-}
+__global__ __launch_bounds__(256) void push_step_kernel(PushStepPlan plan) { push_step_block(plan, blockIdx.x); }
 
 // Flush: staged experience number blockIdx.x (lanes concatenated) moves to its ring slot.
 __global__ __launch_bounds__(256) void flush_kernel(
@@ -334,20 +303,12 @@ int replay_push(replay* rb, int32_t lane, const uint8_t* frames, const int32_t* 
 int replay_push_step(replay* rb, const uint8_t* frames, const int32_t* actions, const float* rewards,
                      const uint8_t* terminals)
 {
-    if (!rb) return fail(DQN_EINVAL, "replay_push_step: rb is null");
-    if (!frames || !actions || !rewards || !terminals) return fail(DQN_EINVAL, "replay_push_step: null pointer");
-    if (!aligned16(frames)) return fail(DQN_EINVAL, "replay_push_step: frames not 16-byte aligned");
-    LaneTable staged;
-    for (int l = 0; l < rb->L; ++l) {
-        if (rb->staged[l] + 1 > rb->S)
-            return fail(DQN_ESTATE, "replay_push_step: lane %d buffer is full (%lld experiences); flush first", l,
-                        (long long)rb->S);
-        staged.count[l] = (int32_t)rb->staged[l];
-    }
-    hipLaunchKernelGGL(push_step_kernel, dim3(rb->L), dim3(256), 0, rb->push_stream, frames, actions, rewards,
-                       terminals, rb->st_frames, rb->st_actions, rb->st_rewards, rb->st_terminals, staged, rb->S);
+    PushStepPlan plan;
+    const int rc = replay_plan_push_step(rb, frames, actions, rewards, terminals, &plan);
+    if (rc != DQN_OK) return rc;
+    hipLaunchKernelGGL(push_step_kernel, dim3(rb->L), dim3(256), 0, rb->push_stream, plan);
     DQN_LAUNCH_CHECK();
-    for (int l = 0; l < rb->L; ++l) rb->staged[l] += 1;
+    replay_commit_push_step(rb);
     return DQN_OK;
 }
 
@@ -380,6 +341,30 @@ static int flush_enqueue(replay* rb)
 }  // extern "C"
 
 namespace dqn {
+int replay_plan_push_step(replay* rb, const uint8_t* frames, const int32_t* actions, const float* rewards,
+                          const uint8_t* terminals, PushStepPlan* plan)
+{
+    if (!rb) return fail(DQN_EINVAL, "replay_push_step: rb is null");
+    if (!frames || !actions || !rewards || !terminals) return fail(DQN_EINVAL, "replay_push_step: null pointer");
+    if (!aligned16(frames)) return fail(DQN_EINVAL, "replay_push_step: frames not 16-byte aligned");
+    for (int l = 0; l < rb->L; ++l) {
+        if (rb->staged[l] + 1 > rb->S)
+            return fail(DQN_ESTATE, "replay_push_step: lane %d buffer is full (%lld experiences); flush first", l,
+                        (long long)rb->S);
+        plan->slot[l] = (int32_t)rb->staged[l];
+    }
+    plan->frames = frames; plan->actions = actions; plan->rewards = rewards; plan->terminals = terminals;
+    plan->st_frames = rb->st_frames; plan->st_actions = rb->st_actions; plan->st_rewards = rb->st_rewards;
+    plan->st_terminals = rb->st_terminals;
+    plan->S = rb->S; plan->L = rb->L;
+    return DQN_OK;
+}
+
+void replay_commit_push_step(replay* rb)
+{
+    for (int l = 0; l < rb->L; ++l) rb->staged[l] += 1;
+}
+
 // Used by dqn_sync_target as well: orders push_stream -> flush (sample_stream) -> push_stream.
 int replay_flush_ordered(replay* rb)
 {

@@ -239,3 +239,67 @@ def test_two_streams_equal_one_stream_bitwise(precision):
     assert np.array_equal(th1, th2) and np.array_equal(tt1, tt2)
     th3, _ = run_flow(concurrent=True, iters=9, precision=precision)
     assert np.array_equal(th2, th3)           # and run-to-run reproducible
+
+
+@pytest.mark.parametrize("precision", [P.DQN_PRECISION_BF16, P.DQN_PRECISION_FP32], ids=["bf16", "fp32"])
+def test_act_push_step_equals_the_two_calls(precision):
+    """dqn_act_push_step(previous experiences, new states) == replay_push_step + dqn_act, bit for bit:
+    same actions and Q at every step, same replay contents after the flush.  The previous step's
+    `actions` buffer is passed as push_actions (read before it is overwritten)."""
+    seed, A, W, steps = 2111012661, 6, 8, 7
+    N = 8 * 64
+    cfg = make_cfg(A, max_batch=32, max_envs=W, precision=precision, seed=seed)
+    theta = synth.init_params(seed, A)
+    results = []
+    for fused in (False, True):
+        st = torch.cuda.Stream()
+        ctx = P.dqn_create(cfg, st, st)
+        rb = P.replay_create(N, W, 16, seed, st, st)
+        try:
+            P.dqn_set_params(ctx, P.DQN_PARAMS_ONLINE, theta)
+            P.dqn_set_params(ctx, P.DQN_PARAMS_TARGET, theta)
+            acts = torch.empty(W, dtype=torch.int32, device="cuda")
+            q = torch.empty((W, A), dtype=torch.float32, device="cuda")
+            log = []
+            prev = None
+            for t in range(steps):
+                states = synth.act_states(seed, t, W)
+                ids = np.arange(W, dtype=np.uint64) + np.uint64(1 << 30) + np.uint64(t * W)
+                _, rew, term = synth.transitions(seed, ids, A, 0.3, 0.3, 0.1)
+                cur = (dev(states), dev(states[:, 3].copy()), dev(rew), dev(term))
+                torch.cuda.synchronize()
+                if not fused:
+                    P.dqn_act(ctx, cur[0], W, 0.25, t, 1, acts, q)
+                    P.replay_push_step(rb, cur[1], acts, cur[2], cur[3])
+                elif prev is None:
+                    P.dqn_act(ctx, cur[0], W, 0.25, t, 1, acts, q)
+                else:
+                    P.dqn_act_push_step(ctx, rb, prev[1], acts, prev[2], prev[3], cur[0], W, 0.25, t, 1, acts, q)
+                torch.cuda.synchronize()
+                log.append((acts.cpu().numpy().copy(), q.cpu().numpy().copy()))
+                prev = cur
+            if fused:
+                P.replay_push_step(rb, prev[1], acts, prev[2], prev[3])
+            P.replay_flush(rb, 1)
+            assert P.replay_num_valid(rb) == W * (steps - 4)
+            B = 16
+            idx = torch.as_tensor(np.array([lane * (N // W) + 3 + (k % (steps - 4)) for k, lane in
+                                            enumerate(list(range(W)) * 2)], dtype=np.int64)).cuda()
+            s = torch.empty((B, 4, 84, 84), dtype=torch.uint8, device="cuda")
+            s2 = torch.empty_like(s)
+            a = torch.empty(B, dtype=torch.int32, device="cuda")
+            r = torch.empty(B, dtype=torch.float32, device="cuda")
+            d = torch.empty(B, dtype=torch.float32, device="cuda")
+            P.replay_sample_gather(rb, B, 0, idx, s, s2, a, r, d, None)
+            torch.cuda.synchronize()
+            results.append((log, [x.cpu().numpy().copy() for x in (s, s2, a, r, d)]))
+        finally:
+            torch.cuda.synchronize()
+            P.replay_destroy(rb)
+            P.dqn_destroy(ctx)
+    (log_a, rep_a), (log_b, rep_b) = results
+    for (aa, qa), (ab, qb) in zip(log_a, log_b):
+        assert np.array_equal(aa, ab) and np.array_equal(qa, qb)
+    for xa, xb in zip(rep_a, rep_b):
+        assert np.array_equal(xa, xb)
+    assert rep_a[2].min() >= 0            # real transitions, not the invalid-index marker
