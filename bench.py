@@ -55,6 +55,7 @@ def kernel_work(name, B, A, groups, precision):
     }
     parts = ("fc1_wgrad", "conv3_wgrad", "conv2_wgrad", "conv1_wgrad", "small_grads")
     t["conv_tower"] = (sum(t[k][0] for k in ("conv1_fwd", "conv2_fwd", "conv3_fwd")), G * B * (28224 + 3136 * e) + B * (12800 + 5184) * e)
+    t["conv_tower_bwd"] = (t["conv3_dgrad"][0] + t["conv2_dgrad"][0], B * (3136 + 2 * 5184 + 2 * 12800) * e)   # dz2 stays in LDS
     t["wgrad_all"] = (sum(t[k][0] for k in parts), sum(t[k][1] for k in parts))   # bf16: one fused launch
     return t[name]
 

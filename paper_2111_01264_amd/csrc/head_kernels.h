@@ -30,20 +30,23 @@ inline Offsets make_offsets(int A)
 // Backward operand copies ("transposed shadows"), one buffer of T:
 //   conv2: [4 parity classes][32 c][(p2, q2, o) = 256]   conv3: [64 c][(p, q, o) = 576]
 //   fc1:   [3136 f][512 o]
+// In reduced precision the two conv matrices are kept in MFMA fragment order (tower_frag_index over
+// [c][k]), the order the fused data-gradient kernel loads them in; fp32 keeps them row-major.
 constexpr size_t kBshW2 = 0, kBshW3 = 4 * 32 * 256, kBshWf1 = kBshW3 + 64 * 576;
 constexpr size_t kBshTotal = kBshWf1 + static_cast<size_t>(3136) * 512;
 
 // Where element r of conv2.w ([o][p][q][c]) / conv3.w lives in the backward copy.
-__host__ __device__ inline size_t bsh_index_w2(int r)
+template <typename T> __host__ __device__ inline size_t bsh_index_w2(int r)
 {
     const int c = r % 32, q = (r / 32) % 4, p = (r / 128) % 4, oc = r / 512;
-    const int cls = (p % 2) * 2 + (q % 2);
-    return kBshW2 + ((static_cast<size_t>(cls) * 32 + c) * 4 + (p / 2) * 2 + (q / 2)) * 64 + oc;
+    const int cls = (p % 2) * 2 + (q % 2), k = ((p / 2) * 2 + (q / 2)) * 64 + oc;
+    return kBshW2 + static_cast<size_t>(cls) * 32 * 256 + (sizeof(T) == 2 ? tower_frag_index(c, k, 256) : static_cast<size_t>(c) * 256 + k);
 }
-__host__ __device__ inline size_t bsh_index_w3(int r)
+template <typename T> __host__ __device__ inline size_t bsh_index_w3(int r)
 {
     const int c = r % 64, q = (r / 64) % 3, p = (r / 192) % 3, oc = r / 576;
-    return kBshW3 + (static_cast<size_t>(c) * 9 + p * 3 + q) * 64 + oc;
+    const int k = (p * 3 + q) * 64 + oc;
+    return kBshW3 + (sizeof(T) == 2 ? tower_frag_index(c, k, 576) : static_cast<size_t>(c) * 576 + k);
 }
 
 // Where blob element e lives in the 16-bit forward copy: identical, except that the conv weights are
@@ -456,8 +459,8 @@ template <typename T, bool SHADOW>
 __device__ inline void publish(const RmsArgs& a, size_t e, float th)
 {
     if (SHADOW) shadow_store<T>(static_cast<T*>(a.sh), a.off, e, th);
-    if (e >= a.off.w2 && e < a.off.b2) static_cast<T*>(a.bsh)[bsh_index_w2(static_cast<int>(e - a.off.w2))] = from_float<T>(th);
-    else if (e >= a.off.w3 && e < a.off.b3) static_cast<T*>(a.bsh)[bsh_index_w3(static_cast<int>(e - a.off.w3))] = from_float<T>(th);
+    if (e >= a.off.w2 && e < a.off.b2) static_cast<T*>(a.bsh)[bsh_index_w2<T>(static_cast<int>(e - a.off.w2))] = from_float<T>(th);
+    else if (e >= a.off.w3 && e < a.off.b3) static_cast<T*>(a.bsh)[bsh_index_w3<T>(static_cast<int>(e - a.off.w3))] = from_float<T>(th);
 }
 
 // Centered RMSProp (Appendix B) fused with the refresh of the operand copies.  Elementwise blocks
@@ -602,8 +605,8 @@ __global__ __launch_bounds__(256) void build_copies_kernel(const float* __restri
     const T val = from_float<T>(theta[e]);
     if (SHADOW) shadow_store<T>(sh, off, e, theta[e]);
     if (bsh) {
-        if (e >= off.w2 && e < off.b2) bsh[bsh_index_w2(static_cast<int>(e - off.w2))] = val;
-        else if (e >= off.w3 && e < off.b3) bsh[bsh_index_w3(static_cast<int>(e - off.w3))] = val;
+        if (e >= off.w2 && e < off.b2) bsh[bsh_index_w2<T>(static_cast<int>(e - off.w2))] = val;
+        else if (e >= off.w3 && e < off.b3) bsh[bsh_index_w3<T>(static_cast<int>(e - off.w3))] = val;
         else if (e >= off.wf1 && e < off.bf1) {
             const size_t r = e - off.wf1;
             bsh[kBshWf1 + (r % 3136) * 512 + r / 3136] = val;

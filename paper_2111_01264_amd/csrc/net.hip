@@ -11,6 +11,7 @@
 #include <type_traits>
 
 #include "conv_tower.h"
+#include "conv_tower_bwd.h"
 #include "fc_as.h"
 #include "wgrad_all.h"
 #include "head_kernels.h"
@@ -21,12 +22,12 @@ namespace dqn {
 enum KernelId {
     K_NONE = 0, K_CONV1_FWD, K_CONV2_FWD, K_CONV3_FWD, K_FC1_FWD, K_FC2_TD, K_TD_HEAD_BWD, K_FC1_WGRAD,
     K_FC1_DGRAD, K_CONV3_WGRAD, K_CONV3_DGRAD, K_CONV2_WGRAD, K_CONV2_DGRAD, K_CONV1_WGRAD, K_BIAS_GRAD,
-    K_RMSPROP, K_WGRAD_ALL, K_EVENT_PAIR, K_COUNT
+    K_RMSPROP, K_WGRAD_ALL, K_EVENT_PAIR, K_TOWER_BWD, K_COUNT
 };
 static const char* const kKernelNames[K_COUNT] = {
     "none", "conv_tower", "(conv2_fwd)", "(conv3_fwd)", "fc1_fwd", "head_td", "(unused)", "fc1_wgrad",
     "fc1_dgrad", "conv3_wgrad", "conv3_dgrad", "conv2_wgrad", "conv2_dgrad", "conv1_wgrad", "small_grads",
-    "rmsprop", "wgrad_all", "event_pair"};
+    "rmsprop", "wgrad_all", "event_pair", "conv_tower_bwd"};
 constexpr size_t kProfPairs = 4096;
 
 // Layer geometries (Section 5: the Nature-DQN network).
@@ -340,21 +341,40 @@ static int train_impl(dqn_ctx* c, const uint8_t* s, const int32_t* a, const floa
         int used = 0;
         DQN_HIP((launch_fc_as<T, kFcReluMask>(st, fa, 512, 1, 1, &used, pr.begin, pr.end)));
     }
-    {   // conv3 data gradient through conv2's ReLU
-        ConvWsArgs<T, Conv3DgradGeo<T>> ca{};
-        ca.x[0] = dz3; ca.w[0] = bsh + kBshW3; ca.out[0] = dz2; ca.mask = act2;
-        ca.M = B * 81; ca.scale = 1.f;
-        const ProfPair pr = prof_pair(c, K_CONV3_DGRAD);
-        DQN_HIP((launch_conv_ws<T, Conv3DgradGeo<T>, kEpiReluMask>(st, ca, 1, pr.begin, pr.end)));
-    }
-    {   // conv2 data gradient through conv1's ReLU: one problem per stride-parity class
-        ConvWsArgs<T, Conv2DgradGeo<T>> ca{};
-        for (int g = 0; g < 4; ++g) {
-            ca.x[g] = dz2; ca.w[g] = bsh + kBshW2 + static_cast<size_t>(g) * 32 * 256; ca.out[g] = dz1;
+    if constexpr (std::is_same<T, bf16_t>::value) {
+        // conv3 and conv2 data gradients in one persistent launch, dz2 handed over in LDS
+        TowerBwdArgs ta{};
+        ta.dz3 = dz3; ta.act2 = act2; ta.act1 = act1; ta.w3d = bsh + kBshW3; ta.w2d = bsh + kBshW2;
+        ta.dz2 = dz2; ta.dz1 = dz1; ta.n = B;
+        static bool attr_set = false;
+        if (!attr_set) {
+            DQN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(conv_tower_bwd_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, kTowerBwdSmem));
+            attr_set = true;
         }
-        ca.mask = act1; ca.M = B * 100; ca.scale = 1.f;
-        const ProfPair pr = prof_pair(c, K_CONV2_DGRAD);
-        DQN_HIP((launch_conv_ws<T, Conv2DgradGeo<T>, kEpiReluMask>(st, ca, 4, pr.begin, pr.end)));
+        const int grid = B < c->num_cus ? B : c->num_cus;
+        ta.per = (B + grid - 1) / grid;
+        const ProfPair pr = prof_pair(c, K_TOWER_BWD);
+        if (pr.begin) (void)hipEventRecord(pr.begin, st);
+        hipLaunchKernelGGL(conv_tower_bwd_kernel, dim3(grid), dim3(kTowerThreads), kTowerBwdSmem, st, ta);
+        if (pr.end) (void)hipEventRecord(pr.end, st);
+        DQN_LAUNCH_CHECK();
+    } else {
+        {   // conv3 data gradient through conv2's ReLU
+            ConvWsArgs<T, Conv3DgradGeo<T>> ca{};
+            ca.x[0] = dz3; ca.w[0] = bsh + kBshW3; ca.out[0] = dz2; ca.mask = act2;
+            ca.M = B * 81; ca.scale = 1.f;
+            const ProfPair pr = prof_pair(c, K_CONV3_DGRAD);
+            DQN_HIP((launch_conv_ws<T, Conv3DgradGeo<T>, kEpiReluMask>(st, ca, 1, pr.begin, pr.end)));
+        }
+        {   // conv2 data gradient through conv1's ReLU: one problem per stride-parity class
+            ConvWsArgs<T, Conv2DgradGeo<T>> ca{};
+            for (int g = 0; g < 4; ++g) {
+                ca.x[g] = dz2; ca.w[g] = bsh + kBshW2 + static_cast<size_t>(g) * 32 * 256; ca.out[g] = dz1;
+            }
+            ca.mask = act1; ca.M = B * 100; ca.scale = 1.f;
+            const ProfPair pr = prof_pair(c, K_CONV2_DGRAD);
+            DQN_HIP((launch_conv_ws<T, Conv2DgradGeo<T>, kEpiReluMask>(st, ca, 4, pr.begin, pr.end)));
+        }
     }
 
     // ---- weight gradients and small reductions ------------------------------------------------------
