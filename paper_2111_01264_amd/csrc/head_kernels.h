@@ -115,14 +115,29 @@ __global__ __launch_bounds__(256) void head_fwd_kernel(HeadArgs a)
     __shared__ float s_red[4][16][64];
     __shared__ float s_q[G][kHeadRows][kMaxActions + 1];
     __shared__ float s_dq[kHeadRows];
-    __shared__ int s_act[kHeadRows];
     float h0[4] = {0.f, 0.f, 0.f, 0.f};   // this thread's four features of h (online pass on s)
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int row0 = blockIdx.x * kHeadRows;
     const int lr = lane & 31, kg = lane >> 5;
     const int arow = lr < a.A ? lr : a.A - 1;
 
-    // fc2 weight fragments of every group: requested first, consumed last
+    // Every global operand is requested here, before anything waits: a cold round trip to memory costs
+    // over a microsecond, and the stages below would otherwise pay one each (fc2's bias, the transition's
+    // reward / terminal flag / action, the taken action's row of W2).
+    const int hr = tid >> 7, hf0 = (tid & 127) * 4;                 // stage (1) and the dzh epilogue: row, features
+    const int hrow = row0 + hr < a.rows ? row0 + hr : a.rows - 1;
+    const int trow_ = lane >> 5;                                      // tail: row of this lane
+    const int trow_c = row0 + trow_ < a.rows ? row0 + trow_ : a.rows - 1;
+    int act_taken = 0, act_tail = 0;
+    float rew_tail = 0.f, done_tail = 0.f;
+    if constexpr (MODE == kHeadTrain) {
+        act_taken = a.act[hrow];
+        act_tail = a.act[trow_c];
+        rew_tail = a.rew[trow_c];
+        done_tail = a.done[trow_c];
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    // fc2 weight fragments of every group: consumed last
     V8 wf[G][8];
 #pragma unroll
     for (int g = 0; g < G; ++g)
@@ -132,9 +147,25 @@ __global__ __launch_bounds__(256) void head_fwd_kernel(HeadArgs a)
             for (int s = 0; s < 8; ++s) wf[g][s] = *reinterpret_cast<const V8*>(wp + s * 16);
         }
 
+    float4 b1v[G];
+    float b2v[G][4];
+#pragma unroll
+    for (int g = 0; g < G; ++g)
+        if (g < a.groups) {
+            b1v[g] = *reinterpret_cast<const float4*>(a.b1[g] + hf0);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int act_i = 8 * wave + 4 * kg + e;
+                b2v[g][e] = a.b2[g][act_i < a.A ? act_i : a.A - 1];
+            }
+        }
+    float w2row[4] = {0.f, 0.f, 0.f, 0.f};
+    if constexpr (MODE == kHeadTrain) load4<T>(static_cast<const T*>(a.w2[0]) + static_cast<size_t>(act_taken) * 512 + hf0, w2row);
+    __builtin_amdgcn_sched_barrier(0);
+
     // (1) finish fc1: thread -> (row r = tid / 128, features 4 * (tid % 128) .. + 3)
     {
-        const int r = tid >> 7, f0 = (tid & 127) * 4;
+        const int r = hr, f0 = hf0;
         const int row = row0 + r;
         const size_t sstride = static_cast<size_t>(a.rows) * 512, gstride = sstride * a.slices;
 #pragma unroll
@@ -154,7 +185,7 @@ __global__ __launch_bounds__(256) void head_fwd_kernel(HeadArgs a)
                         for (int u = 0; u < 7; ++u)
                             if (s0 + u < a.slices) { acc.x += v[u].x; acc.y += v[u].y; acc.z += v[u].z; acc.w += v[u].w; }
                     }
-                    const float4 bv = *reinterpret_cast<const float4*>(a.b1[g] + f0);
+                    const float4 bv = b1v[g];
                     acc.x = fmaxf(acc.x + bv.x, 0.f); acc.y = fmaxf(acc.y + bv.y, 0.f);
                     acc.z = fmaxf(acc.z + bv.z, 0.f); acc.w = fmaxf(acc.w + bv.w, 0.f);
                 }
@@ -193,7 +224,7 @@ __global__ __launch_bounds__(256) void head_fwd_kernel(HeadArgs a)
                     const int v = 4 * q + e;
                     if (act_i < a.A)
                         s_q[g][lr][act_i] =
-                            (((s_red[0][v][lane] + s_red[1][v][lane]) + s_red[2][v][lane]) + s_red[3][v][lane]) + a.b2[g][act_i];
+                            (((s_red[0][v][lane] + s_red[1][v][lane]) + s_red[2][v][lane]) + s_red[3][v][lane]) + b2v[g][e];
                 }
             }
         }
@@ -240,8 +271,8 @@ __global__ __launch_bounds__(256) void head_fwd_kernel(HeadArgs a)
                 float dq = 0.f;
                 int act_b = 0;
                 if (live) {
-                    const float y = a.rew[row] + a.gamma * (1.f - a.done[row]) * s_q[1][trow][astar];
-                    act_b = a.act[row];
+                    const float y = rew_tail + a.gamma * (1.f - done_tail) * s_q[1][trow][astar];
+                    act_b = act_tail;
                     const float delta = s_q[0][trow][act_b] - y;
                     const float ad = fabsf(delta);
                     a.lossv[row] = ad <= a.huber ? 0.5f * delta * delta : a.huber * (ad - 0.5f * a.huber);
@@ -249,7 +280,6 @@ __global__ __launch_bounds__(256) void head_fwd_kernel(HeadArgs a)
                     a.dqv[row] = dq;
                 }
                 s_dq[trow] = dq;
-                s_act[trow] = act_b;
             }
         }
         __syncthreads();
@@ -257,8 +287,7 @@ __global__ __launch_bounds__(256) void head_fwd_kernel(HeadArgs a)
         const int r = tid >> 7, f0 = (tid & 127) * 4;
         const int row = row0 + r;
         if (row < a.rows) {
-            float w[4];
-            load4<T>(static_cast<const T*>(a.w2[0]) + static_cast<size_t>(s_act[r]) * 512 + f0, w);
+            const float* w = w2row;
             const float dq = s_dq[r];
             store4<T>(static_cast<T*>(a.dzh) + static_cast<size_t>(row) * 512 + f0, h0[0] > 0.f ? dq * w[0] : 0.f,
                       h0[1] > 0.f ? dq * w[1] : 0.f, h0[2] > 0.f ? dq * w[2] : 0.f, h0[3] > 0.f ? dq * w[3] : 0.f);
