@@ -304,6 +304,9 @@ __global__ __launch_bounds__(256) void head_fwd_kernel(HeadArgs a)
 //    Each block owns 16 columns o; thread (o, part) accumulates the samples b = part (mod 16) in
 //    increasing order into its own LDS column, the sixteen parts are then added in order.
 constexpr int kBiasRows = 1024;
+constexpr int kRmsConvLanes = 8;                                    // lanes per float4 of a conv weight in the optimiser's conv blocks
+constexpr int kRmsConvQuads = (32 * 256 + 64 * 512 + 64 * 576) / 4;
+constexpr int kRmsConvBlocks = (kRmsConvQuads * kRmsConvLanes + 255) / 256;
 constexpr int kRmsBiasLanes = 8;                                    // lanes per channel in the optimiser's bias blocks
 constexpr int kRmsBiasBlocks = (672 * kRmsBiasLanes + 255) / 256;  // 32 + 64 + 64 + 512 hidden-layer bias channels
 struct BiasGradArgs {
@@ -452,7 +455,7 @@ struct RmsArgs {
     Offsets off;
     float lr, alpha, eps;
     int centered;
-    int flat_blocks; // blocks [0, flat_blocks) are elementwise, then 16*49 fc1.w tiles, then the bias blocks
+    int flat_blocks; // after the kRmsConvBlocks conv-weight blocks: [0, flat_blocks) elementwise, then 16*49 fc1.w tiles, then the bias blocks
     // second stage of the bias gradients (conv1..3, fc1): chunk sums written by bias_grad_kernel
     const float* bias_partial;
     int bias_chunks[4];
@@ -492,49 +495,83 @@ __device__ inline void publish(const RmsArgs& a, size_t e, float th)
     else if (e >= a.off.w3 && e < a.off.b3) static_cast<T*>(a.bsh)[bsh_index_w3<T>(static_cast<int>(e - a.off.w3))] = from_float<T>(th);
 }
 
-// Centered RMSProp (Appendix B) fused with the refresh of the operand copies.  Elementwise blocks
-// cover everything but fc1.w; fc1.w is walked in 32 x 64 tiles so that its transposed copy
+// Centered RMSProp (Appendix B) fused with the refresh of the operand copies.  The conv weights come first
+// (their gradient is finished here from split-K slices), elementwise blocks cover the rest except fc1.w and the
+// hidden-layer biases; fc1.w is walked in 32 x 64 tiles so that its transposed copy
 // ([f][o], the operand of fc1's data gradient) is written in full 64/128-byte rows via LDS.
 template <typename T, bool SHADOW>
 __global__ __launch_bounds__(256) void rmsprop_kernel(RmsArgs a)
 {
     __shared__ T tile[64][32 + 8];
     const int tid = threadIdx.x;
-    if (static_cast<int>(blockIdx.x) < a.flat_blocks) {
+    if (static_cast<int>(blockIdx.x) < kRmsConvBlocks) {
+        // Conv weights: their gradient arrives as split-K slices (up to 128 of them at small batches).  Eight adjacent
+        // lanes share four weights: lane j requests slices j, j + 8, ... (eight per round trip) and adds them in that order, the
+        // eight sums meet in a fixed tree, lane 0 updates.  (One lane walking all slices, eight loads at a time, was a
+        // chain of dependent round trips that outlasted the streaming of every other parameter.)
+        const int idx = blockIdx.x * 256 + tid;
+        const int q = idx / kRmsConvLanes, j = idx % kRmsConvLanes;
+        if (q >= kRmsConvQuads) return;   // whole lane groups leave together
+        int conv = 2;
+        size_t r = static_cast<size_t>(q - (32 * 256 + 64 * 512) / 4) * 4, tsize = 64 * 576, e = a.off.w3 + r;
+        if (q < 32 * 256 / 4) { conv = 0; r = static_cast<size_t>(q) * 4; tsize = 32 * 256; e = a.off.w1 + r; }
+        else if (q < (32 * 256 + 64 * 512) / 4) { conv = 1; r = static_cast<size_t>(q - 32 * 256 / 4) * 4; tsize = 64 * 512; e = a.off.w2 + r; }
+        const float* p = a.wg_partial[conv] + r;
+        const int ns = a.wg_splits[conv];
+        float4 th = make_float4(0.f, 0.f, 0.f, 0.f), vv = th, mm = th;
+        if (j == 0) {
+            th = *reinterpret_cast<float4*>(a.theta + e);
+            vv = *reinterpret_cast<float4*>(a.v + e);
+            mm = *reinterpret_cast<float4*>(a.m + e);
+        }
+        constexpr int kPerLane = 8;       // slices per lane and round trip: one trip up to 64 slices, two up to 128
+        float4 sum = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int s0 = j; s0 < ns; s0 += kPerLane * kRmsConvLanes) {
+            float4 v4[kPerLane];
+#pragma unroll
+            for (int u = 0; u < kPerLane; ++u) {
+                const int sl = s0 + u * kRmsConvLanes;
+                v4[u] = *reinterpret_cast<const float4*>(p + static_cast<size_t>(sl < ns ? sl : ns - 1) * tsize);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int u = 0; u < kPerLane; ++u)
+                if (s0 + u * kRmsConvLanes < ns) { sum.x += v4[u].x; sum.y += v4[u].y; sum.z += v4[u].z; sum.w += v4[u].w; }
+        }
+#pragma unroll
+        for (int d = kRmsConvLanes / 2; d >= 1; d >>= 1) {
+            sum.x += __shfl_down(sum.x, d, kRmsConvLanes); sum.y += __shfl_down(sum.y, d, kRmsConvLanes);
+            sum.z += __shfl_down(sum.z, d, kRmsConvLanes); sum.w += __shfl_down(sum.w, d, kRmsConvLanes);
+        }
+        if (j != 0) return;
+        const float sc = a.wg_scale[conv];
+        const float4 g = make_float4(sum.x * sc, sum.y * sc, sum.z * sc, sum.w * sc);
+        *reinterpret_cast<float4*>(const_cast<float*>(a.grad) + e) = g;   // kept for readers of the gradient
+        rms_update(a, th.x, g.x, vv.x, mm.x);
+        rms_update(a, th.y, g.y, vv.y, mm.y);
+        rms_update(a, th.z, g.z, vv.z, mm.z);
+        rms_update(a, th.w, g.w, vv.w, mm.w);
+        *reinterpret_cast<float4*>(a.theta + e) = th;
+        *reinterpret_cast<float4*>(a.v + e) = vv;
+        if (a.centered) *reinterpret_cast<float4*>(a.m + e) = mm;
+        publish<T, SHADOW>(a, e, th.x);
+        publish<T, SHADOW>(a, e + 1, th.y);
+        publish<T, SHADOW>(a, e + 2, th.z);
+        publish<T, SHADOW>(a, e + 3, th.w);
+        return;
+    }
+    const int block = static_cast<int>(blockIdx.x) - kRmsConvBlocks;
+    if (block < a.flat_blocks) {
         const size_t n_flat = a.off.total - static_cast<size_t>(512) * 3136;
         const size_t n4 = n_flat / 4;
-        const size_t i = blockIdx.x * static_cast<size_t>(256) + tid;
+        const size_t i = block * static_cast<size_t>(256) + tid;
         auto to_blob = [&](size_t f) { return f < a.off.wf1 ? f : f + static_cast<size_t>(512) * 3136; };
         if (i < n4) {
             const size_t e = to_blob(4 * i);
             if (hidden_bias_layer(a.off, e) >= 0) return;   // bias vectors are 4-aligned: handled by the bias blocks
+            if (e < a.off.b1 || (e >= a.off.w2 && e < a.off.b2) || (e >= a.off.w3 && e < a.off.b3)) return;   // conv weights: the blocks above
             float4 th = *reinterpret_cast<float4*>(a.theta + e);
-            float4 g;
-            int conv = -1;
-            size_t r = 0, tsize = 0;
-            if (e < a.off.b1) { conv = 0; r = e - a.off.w1; tsize = 32 * 256; }
-            else if (e >= a.off.w2 && e < a.off.b2) { conv = 1; r = e - a.off.w2; tsize = 64 * 512; }
-            else if (e >= a.off.w3 && e < a.off.b3) { conv = 2; r = e - a.off.w3; tsize = 64 * 576; }
-            if (conv >= 0) {
-                // conv weight gradient: add the split-K slices in order, keep the sum for readers of the gradient
-                const float* p = a.wg_partial[conv] + r;
-                float4 sum = make_float4(0.f, 0.f, 0.f, 0.f);
-                const int ns = a.wg_splits[conv];
-                for (int s0 = 0; s0 < ns; s0 += 8) {
-                    float4 v4[8];
-#pragma unroll
-                    for (int u = 0; u < 8; ++u) v4[u] = *reinterpret_cast<const float4*>(p + (s0 + u < ns ? s0 + u : ns - 1) * tsize);
-                    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-                    for (int u = 0; u < 8; ++u)
-                        if (s0 + u < ns) { sum.x += v4[u].x; sum.y += v4[u].y; sum.z += v4[u].z; sum.w += v4[u].w; }
-                }
-                const float sc = a.wg_scale[conv];
-                g = make_float4(sum.x * sc, sum.y * sc, sum.z * sc, sum.w * sc);
-                *reinterpret_cast<float4*>(const_cast<float*>(a.grad) + e) = g;
-            } else {
-                g = *reinterpret_cast<const float4*>(a.grad + e);
-            }
+            const float4 g = *reinterpret_cast<const float4*>(a.grad + e);
             float4 vv = *reinterpret_cast<float4*>(a.v + e);
             float4 mm = *reinterpret_cast<float4*>(a.m + e);
             rms_update(a, th.x, g.x, vv.x, mm.x);
@@ -559,11 +596,11 @@ __global__ __launch_bounds__(256) void rmsprop_kernel(RmsArgs a)
         }
         return;
     }
-    if (static_cast<int>(blockIdx.x) >= a.flat_blocks + 16 * 49) {
+    if (block >= a.flat_blocks + 16 * 49) {
         // hidden-layer biases: finish the gradient, then update.  Eight adjacent lanes share a channel: lane j
         // adds chunks j, j + 8, ... in order, then the eight sums meet in a fixed tree -- a large batch has
         // hundreds of chunks and one lane walking them alone was the tail of this kernel.
-        const int idx = (blockIdx.x - a.flat_blocks - 16 * 49) * 256 + tid;
+        const int idx = (block - a.flat_blocks - 16 * 49) * 256 + tid;
         const int ch = idx / kRmsBiasLanes, j = idx % kRmsBiasLanes;
         const bool live = ch < 32 + 64 + 64 + 512;
         int layer = 3, c = 0;
@@ -591,7 +628,7 @@ __global__ __launch_bounds__(256) void rmsprop_kernel(RmsArgs a)
         return;
     }
     // fc1.w tile: rows o0 .. o0+31, columns f0 .. f0+63
-    const int t = blockIdx.x - a.flat_blocks;
+    const int t = block - a.flat_blocks;
     const int o0 = (t / 49) * 32, f0 = (t % 49) * 64;
 #pragma unroll
     for (int u = 0; u < 2; ++u) {

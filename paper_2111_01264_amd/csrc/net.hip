@@ -474,7 +474,7 @@ static int train_impl(dqn_ctx* c, const uint8_t* s, const int32_t* a, const floa
         for (int l = 0; l < 4; ++l) { ra.bias_chunks[l] = bias_chunks[l]; ra.bias_first[l] = bias_first[l]; }
         const ProfPair pr = prof_pair(c, K_RMSPROP);
         if (pr.begin) (void)hipEventRecord(pr.begin, st);
-        hipLaunchKernelGGL((rmsprop_kernel<T, SHADOW>), dim3(ra.flat_blocks + 16 * 49 + kRmsBiasBlocks), dim3(256), 0, st, ra);
+        hipLaunchKernelGGL((rmsprop_kernel<T, SHADOW>), dim3(kRmsConvBlocks + ra.flat_blocks + 16 * 49 + kRmsBiasBlocks), dim3(256), 0, st, ra);
         if (pr.end) (void)hipEventRecord(pr.end, st);
         DQN_LAUNCH_CHECK();
     }
