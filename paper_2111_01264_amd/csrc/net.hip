@@ -4,6 +4,7 @@
 #include <math.h>
 #include <string.h>
 
+#include <atomic>
 #include <new>
 #include <vector>
 
@@ -67,6 +68,7 @@ struct dqn_ctx {
     float* bias_partial = nullptr;
     float* wg_partial = nullptr;
     hipEvent_t ev_train = nullptr, ev_act = nullptr, ev_sync = nullptr;
+    std::atomic<bool> train_unrecorded{false};   // a train step has been enqueued since ev_train was last recorded
     bool act_reads_online = false;   // an act step with use_target = 0 is in flight
     int last_B = 0;
     int num_cus = 256;
@@ -258,6 +260,18 @@ static int forward_to_fc1(dqn_ctx* c, hipStream_t st, Workspace& ws, int groups,
         *slices_out = used;
     }
     return DQN_OK;
+}
+
+// act_stream waits for every train step enqueued so far.  The event is recorded here, by the reader, and not
+// after every train step: an event record costs the train stream several microseconds per step, and with the
+// target parameters (Concurrent Training, Section 3) nobody ever waits for it.
+static hipError_t wait_for_train(dqn_ctx* c)
+{
+    if (c->train_unrecorded.exchange(false, std::memory_order_acq_rel)) {
+        const hipError_t e = hipEventRecord(c->ev_train, c->train_stream);
+        if (e != hipSuccess) return e;
+    }
+    return hipStreamWaitEvent(c->act_stream, c->ev_train, 0);
 }
 
 template <typename T>
@@ -682,7 +696,7 @@ int dqn_act(dqn_ctx* c, const uint8_t* states, int32_t W, float epsilon, uint64_
     if (!(epsilon >= 0.f && epsilon <= 1.f)) return fail(DQN_EINVAL, "dqn_act: epsilon outside [0,1]");
     if (!use_target) {
         // standard DQN: the policy needs the parameters the last update produced (Section 3)
-        DQN_HIP(hipStreamWaitEvent(c->act_stream, c->ev_train, 0));
+        DQN_HIP(wait_for_train(c));
     }
     const int rc = c->cfg.precision == DQN_PRECISION_BF16
                        ? act_impl<bf16_t>(c, states, W, epsilon, act_step, use_target, actions, q_out)
@@ -714,7 +728,7 @@ int dqn_act_push_step(dqn_ctx* c, replay* rb, const uint8_t* push_frames, const 
     PushStepPlan plan;
     int rc = replay_plan_push_step(rb, push_frames, push_actions, push_rewards, push_terminals, &plan);
     if (rc != DQN_OK) return rc;
-    if (!use_target) DQN_HIP(hipStreamWaitEvent(c->act_stream, c->ev_train, 0));
+    if (!use_target) DQN_HIP(wait_for_train(c));
     rc = act_impl<bf16_t>(c, states, W, epsilon, act_step, use_target, actions, q_out, &plan);
     if (rc != DQN_OK) return rc;
     replay_commit_push_step(rb);
@@ -741,7 +755,7 @@ int dqn_train_step(dqn_ctx* c, const uint8_t* s, const int32_t* a, const float* 
     if (c->cfg.precision == DQN_PRECISION_BF16) rc = train_impl<bf16_t, true>(c, s, a, r, s2, done, B, loss_out);
     else rc = train_impl<float, false>(c, s, a, r, s2, done, B, loss_out);
     if (rc != DQN_OK) return rc;
-    DQN_HIP(hipEventRecord(c->ev_train, c->train_stream));
+    c->train_unrecorded.store(true, std::memory_order_release);   // the event is recorded by the first reader, if any
     c->last_B = B;
     return DQN_OK;
 }
