@@ -355,17 +355,19 @@ __device__ inline void small_grads_block(const BiasGradArgs& args, int block, un
         const int oo = tid & 15, part = tid >> 4;
         const bool bias_block = ob == 32;
         const int o = ob * 16 + oo;
-        for (int b0 = part; b0 < B; b0 += 64) {
-            float hv[4];
+        // sixteen samples in flight per thread (clamped address: no load is ever skipped)
+        const size_t oc = bias_block ? 0 : o;
+        for (int b0 = part; b0 < B; b0 += 256) {
+            T hv[16];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
+            for (int u = 0; u < 16; ++u) {
                 const int b = b0 + 16 * u;
-                hv[u] = b < B ? (bias_block ? 1.f : to_float(h[static_cast<size_t>(b) * 512 + o])) : 0.f;
+                hv[u] = h[static_cast<size_t>(b < B ? b : B - 1) * 512 + oc];
             }
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
+            for (int u = 0; u < 16; ++u) {
                 const int b = b0 + 16 * u;
-                if (b < B) s_acc[s_a[b]][tid] += s_dq[b] * hv[u];
+                if (b < B) s_acc[s_a[b]][tid] += s_dq[b] * (bias_block ? 1.f : to_float(hv[u]));
             }
         }
         __syncthreads();
@@ -408,16 +410,16 @@ __device__ inline void small_grads_block(const BiasGradArgs& args, int block, un
     float acc[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) acc[e] = 0.f;
-    // four rows in flight per thread (clamped address, masked value: no load is ever skipped)
-    for (int r = chunk * kBiasRows + rsub; r < r_end; r += 4 * RP) {
-        V8 v[4];
+    // sixteen rows in flight per thread (clamped address, masked value: no load is ever skipped)
+    for (int r = chunk * kBiasRows + rsub; r < r_end; r += 16 * RP) {
+        V8 v[16];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
+        for (int u = 0; u < 16; ++u) {
             const int rr = r + u * RP;
             v[u] = vec8_keep<T>(*reinterpret_cast<const V8*>(dz + static_cast<size_t>(rr < r_end ? rr : r_end - 1) * C), rr < r_end);
         }
 #pragma unroll
-        for (int u = 0; u < 4; ++u)
+        for (int u = 0; u < 16; ++u)
 #pragma unroll
             for (int e = 0; e < 8; ++e) acc[e] += to_float(v[u][e]);
     }

@@ -83,6 +83,7 @@ namespace dqn {
 constexpr int kMaxFc1Slices = 49;
 // deferred split-K scratch of the three conv weight gradients
 constexpr size_t kWgMaxSplits = 32, kWgMaxSplits1 = 128;   // conv1's gradient is small: more slices are cheap
+constexpr size_t kWgFp32Splits = 32;                       // fp32 mode (separate launches per layer)
 constexpr size_t kWgOff1 = 0, kWgOff2 = kWgMaxSplits1 * 32 * 256, kWgOff3 = kWgOff2 + kWgMaxSplits * 64 * 512;
 constexpr size_t kWgTotal = kWgOff3 + kWgMaxSplits * 64 * 576;
 
@@ -422,8 +423,8 @@ static int train_impl(dqn_ctx* c, const uint8_t* s, const int32_t* a, const floa
         wa.a2.p[0] = dz2; wa.a2.ld = 64; wa.b2.x = act1; wa.K2 = B * 81; wa.p2 = c->wg_partial + kWgOff2;
         wa.a3.p[0] = dz3; wa.a3.ld = 64; wa.b3.x = act2; wa.K3 = B * 49; wa.p3 = c->wg_partial + kWgOff3;
         tn_tr_splits(wa.K1, wgrad_splits(wa.K1, 2, 128), 32 * 256, kWgMaxSplits1 * 32 * 256, &wa.kps1, &wa.splits1);
-        tn_tr_splits(wa.K2, wgrad_splits(wa.K2, 2, 32), 64 * 512, kWgMaxSplits * 64 * 512, &wa.kps2, &wa.splits2);
-        tn_tr_splits(wa.K3, wgrad_splits(wa.K3, 3, 32), 64 * 576, kWgMaxSplits * 64 * 576, &wa.kps3, &wa.splits3);
+        tn_tr_splits(wa.K2, wgrad_splits(wa.K2, 2, static_cast<int>(kWgMaxSplits)), 64 * 512, kWgMaxSplits * 64 * 512, &wa.kps2, &wa.splits2);
+        tn_tr_splits(wa.K3, wgrad_splits(wa.K3, 3, static_cast<int>(kWgMaxSplits)), 64 * 576, kWgMaxSplits * 64 * 576, &wa.kps3, &wa.splits3);
         wg_splits[0] = wa.splits1; wg_splits[1] = wa.splits2; wg_splits[2] = wa.splits3;
         wa.af.p[0] = dzh; wa.af.ld = 512; wa.bf.p[0] = act3; wa.bf.ld = 3136; wa.Kf = B;
         wa.epf = EpiGrad{c->grad + o.wf1, 3136, 1.f};
@@ -450,21 +451,21 @@ static int train_impl(dqn_ctx* c, const uint8_t* s, const int32_t* a, const floa
             DenseM<T> al{}; WgradB<T, 64, 9, 9, 7, 7, 3, 1> bl{act2}; EpiGrad ep{c->grad + o.w3, 576, 1.f};
             al.p[0] = dz3; al.ld = 64;
             const ProfPair pr = prof_pair(c, K_CONV3_WGRAD);
-            DQN_HIP((launch_gemm<T, 64, 64, 32, 2>(st, al, bl, ep, 64, 576, B * 49, 1, pick_splits(9, B * 49, 32, kWgMaxSplits),
+            DQN_HIP((launch_gemm<T, 64, 64, 32, 2>(st, al, bl, ep, 64, 576, B * 49, 1, pick_splits(9, B * 49, 32, kWgFp32Splits),
                                                     c->wg_partial + kWgOff3, kWgMaxSplits * 64 * 576, pr.begin, pr.end, &wg_splits[2])));
         }
         {   // conv2 weight gradient
             DenseM<T> al{}; WgradB<T, 32, 20, 20, 9, 9, 4, 2> bl{act1}; EpiGrad ep{c->grad + o.w2, 512, 1.f};
             al.p[0] = dz2; al.ld = 64;
             const ProfPair pr = prof_pair(c, K_CONV2_WGRAD);
-            DQN_HIP((launch_gemm<T, 64, 64, 32, 2>(st, al, bl, ep, 64, 512, B * 81, 1, pick_splits(8, B * 81, 32, kWgMaxSplits),
+            DQN_HIP((launch_gemm<T, 64, 64, 32, 2>(st, al, bl, ep, 64, 512, B * 81, 1, pick_splits(8, B * 81, 32, kWgFp32Splits),
                                                     c->wg_partial + kWgOff2, kWgMaxSplits * 64 * 512, pr.begin, pr.end, &wg_splits[1])));
         }
         {   // conv1 weight gradient (the input scale 1/255 is applied by the optimiser kernel)
             DenseM<T> al{}; Conv1WgradB<T> bl{s}; EpiGrad ep{c->grad + o.w1, 256, 1.f};
             al.p[0] = dz1; al.ld = 32;
             const ProfPair pr = prof_pair(c, K_CONV1_WGRAD);
-            DQN_HIP((launch_gemm<T, 32, 128, 32, 1>(st, al, bl, ep, 32, 256, B * 400, 1, pick_splits(2, B * 400, 32, kWgMaxSplits),
+            DQN_HIP((launch_gemm<T, 32, 128, 32, 1>(st, al, bl, ep, 32, 256, B * 400, 1, pick_splits(2, B * 400, 32, kWgFp32Splits),
                                                      c->wg_partial + kWgOff1, kWgMaxSplits * 32 * 256, pr.begin, pr.end, &wg_splits[0])));
         }
         const ProfPair pr = prof_pair(c, K_BIAS_GRAD);
