@@ -179,3 +179,11 @@ def test_train_parity_bf16():
 def test_train_parity_bf16_double_dqn():
     run_train_parity(A=18, B=40, steps=2, precision=P.DQN_PRECISION_BF16, double_dqn=1, N=2000, lanes=8,
                      p_term=0.01, seed=8, check_params=False, p_reward=0.4)
+
+
+def test_train_parity_bf16_several_samples_per_workgroup():
+    # batch 300 > the number of compute units: the fused conv kernels (forward and data-gradient) walk more than
+    # one sample per persistent workgroup, with a ragged last range
+    run_train_parity(A=6, B=300, steps=1, precision=P.DQN_PRECISION_BF16, double_dqn=0, N=4000, lanes=8,
+                     p_term=0.01, seed=9, check_params=False, p_reward=0.4)
+
