@@ -61,11 +61,16 @@ def kernel_work(name, B, A, groups, precision):
 
 
 # HBM traffic per launch measured with rocprofv3 (FETCH_SIZE and WRITE_SIZE in separate runs, scaled by what the
-# same counters read for the target copy of known size): {(kernel, batch, precision): (bytes, source file, sha1 of
-# that file when the counters were taken)}.  Reported only while the kernel's source still hashes to that value.
+# same counters read for the target copy of known size; summaries under profiles/hbm_traffic_*.txt):
+# {(kernel, batch, precision): (bytes, source files of the kernel, sha1 over their concatenation when the counters
+# were taken)}.  Reported only while the kernel's sources still hash to that value.
+_C = "paper_2111_01264_amd/csrc/"
+_RMS_SRC = (_C + "head_kernels.h",)
+_WG_SRC = (_C + "wgrad_all.h", _C + "gemm_tn_tr.h", _C + "layers.h", _C + "head_kernels.h", _C + "gemm_mfma.h")
 TRAFFIC = {
-    ("rmsprop", 32, "bf16"): (64.65e6, "paper_2111_01264_amd/csrc/head_kernels.h", "6b7ae4a43013544605212a5a9fb975849f73f52c"),
-    ("rmsprop", 256, "bf16"): (68.18e6, "paper_2111_01264_amd/csrc/head_kernels.h", "6b7ae4a43013544605212a5a9fb975849f73f52c"),
+    ("rmsprop", 32, "bf16"): (64.46e6, _RMS_SRC, "a9bbaa84860722f6dea88f24ef4bfbd7aac80c82"),
+    ("rmsprop", 256, "bf16"): (67.98e6, _RMS_SRC, "a9bbaa84860722f6dea88f24ef4bfbd7aac80c82"),
+    ("wgrad_all", 256, "bf16"): (94.00e6, _WG_SRC, "089c9a1ebdb22b8bedc664e79cd90e57e0b5dafd"),
 }
 
 
@@ -74,13 +79,15 @@ def measured_traffic(name, B, precision):
     ent = TRAFFIC.get((name, B, precision))
     if not ent:
         return None
-    nbytes, src, sha = ent
+    nbytes, srcs, sha = ent
+    h = hashlib.sha1()
     try:
-        with open(os.path.join(ROOT, src), "rb") as f:
-            cur = hashlib.sha1(f.read()).hexdigest()
+        for src in srcs:
+            with open(os.path.join(ROOT, src), "rb") as f:
+                h.update(f.read())
     except OSError:
         return None
-    return nbytes if cur == sha else None
+    return nbytes if h.hexdigest() == sha else None
 
 
 def roofline_for(name, avg_ms, B, A, groups, precision):
