@@ -8,6 +8,10 @@
 // consecutive k per lane).  MFMA A = weights (row i = output feature), B = samples (column j = b),
 // so lane l ends up with sample (l % 32) and four consecutive features per register quad.
 //
+// 16-bit weights arrive in MFMA fragment order (tower_frag_index over [feature][k]): the operand of k-step ks of
+// feature tile nt is the contiguous 1 KB row (nt * K/16 + ks); row-major weights (fp32 mode) are read as 32 separate
+// 32-byte pieces per wavefront load, which is bound by the address unit (a full pass per cache line).
+//
 // K may be split over blockIdx.z: each slice then writes fp32 partial sums [slice][b][n], which the
 // consumer kernel adds in slice order while it loads them (no separate reduction pass).
 #pragma once
@@ -27,6 +31,13 @@ template <typename T> struct FcAsArgs {
 };
 
 constexpr int kFcPartial = 0, kFcReluMask = 1;
+
+// Pointer to this lane's 8 weights of k-step ks (16 k each) of the 32-feature tile nt; w is [N][K].
+template <typename T> __device__ inline const T* fc_weight_fragment(const T* w, int nt, int ks, int K, int lane)
+{
+    if constexpr (sizeof(T) == 2) return w + (static_cast<size_t>(nt * (K >> 4) + ks) * 64 + lane) * 8;
+    else return w + static_cast<size_t>(nt * 32 + (lane & 31)) * K + ks * 16 + (lane >> 5) * 8;
+}
 
 template <typename T, int EPI, int TB, int WAVES>
 __global__ __launch_bounds__(WAVES * 64) void fc_as_kernel(FcAsArgs<T> a)
@@ -55,7 +66,7 @@ __global__ __launch_bounds__(WAVES * 64) void fc_as_kernel(FcAsArgs<T> a)
     const int lane_r = lane & 31, kg = lane >> 5;
     const int n = (blockIdx.x * WAVES + wave) * 32 + lane_r;
     const bool n_ok = n < a.N;
-    const T* wp = a.w[g] + static_cast<size_t>(n_ok ? n : 0) * a.ldw + k0 + kg * 8;
+    const int ntile = n_ok ? blockIdx.x * WAVES + wave : 0, ks0 = k0 >> 4;   // N is a multiple of 32: tiles are whole
 
     f32x16 acc[TB];
 #pragma unroll
@@ -66,11 +77,11 @@ __global__ __launch_bounds__(WAVES * 64) void fc_as_kernel(FcAsArgs<T> a)
     // four k-steps (64 k) per iteration, the next iteration's weight fragments already in flight
     V8 cur[4], nxt[4];
 #pragma unroll
-    for (int s = 0; s < 4; ++s) cur[s] = *reinterpret_cast<const V8*>(wp + s * 16);
+    for (int s = 0; s < 4; ++s) cur[s] = *reinterpret_cast<const V8*>(fc_weight_fragment<T>(a.w[g], ntile, ks0 + s, a.ldw, lane));
     for (int kk = 0; kk < klen; kk += 64) {
         if (kk + 64 < klen) {
 #pragma unroll
-            for (int s = 0; s < 4; ++s) nxt[s] = *reinterpret_cast<const V8*>(wp + kk + 64 + s * 16);
+            for (int s = 0; s < 4; ++s) nxt[s] = *reinterpret_cast<const V8*>(fc_weight_fragment<T>(a.w[g], ntile, ks0 + (kk >> 4) + 4 + s, a.ldw, lane));
         }
         __builtin_amdgcn_sched_barrier(0);   // next chunk's weight fragments in flight before the MFMAs
 #pragma unroll
@@ -137,13 +148,13 @@ __global__ __launch_bounds__(256) void fc_sk_kernel(FcSkArgs<T> a)
     const int lr = lane & 31, kg = lane >> 5;
     const int n = n0 + lr;
     const int k0 = (slice * 4 + wave) * (KPW * 16) + kg * 8;
-    const T* wp = a.w[g] + static_cast<size_t>(n < a.N ? n : 0) * a.ldw + k0;
+    const int ntile = n < a.N ? blockIdx.x : 0, ks0 = (slice * 4 + wave) * KPW;   // N is a multiple of 32
     const bool x_ok = lr < a.M;
     const T* xp = a.x[g] + static_cast<size_t>(x_ok ? lr : 0) * a.ldx + k0;
     V8 wf[KPW], xf[KPW];
 #pragma unroll
     for (int s = 0; s < KPW; ++s) {
-        wf[s] = *reinterpret_cast<const V8*>(wp + s * 16);
+        wf[s] = *reinterpret_cast<const V8*>(fc_weight_fragment<T>(a.w[g], ntile, ks0 + s, a.ldw, lane));
         xf[s] = *reinterpret_cast<const V8*>(xp + s * 16);
     }
     __builtin_amdgcn_sched_barrier(0);

@@ -30,8 +30,9 @@ inline Offsets make_offsets(int A)
 // Backward operand copies ("transposed shadows"), one buffer of T:
 //   conv2: [4 parity classes][32 c][(p2, q2, o) = 256]   conv3: [64 c][(p, q, o) = 576]
 //   fc1:   [3136 f][512 o]
-// In reduced precision the two conv matrices are kept in MFMA fragment order (tower_frag_index over
-// [c][k]), the order the fused data-gradient kernel loads them in; fp32 keeps them row-major.
+// In reduced precision all three are kept in MFMA fragment order (tower_frag_index over [row][k]: conv per
+// (class,) [c][k], fc1 over [f][o]), the order their consumers load them in: one operand of a 32x32x16 MFMA is then
+// one contiguous 1 KB row instead of 32 separate cache lines; fp32 keeps them row-major.
 constexpr size_t kBshW2 = 0, kBshW3 = 4 * 32 * 256, kBshWf1 = kBshW3 + 64 * 576;
 constexpr size_t kBshTotal = kBshWf1 + static_cast<size_t>(3136) * 512;
 
@@ -49,14 +50,20 @@ template <typename T> __host__ __device__ inline size_t bsh_index_w3(int r)
     return kBshW3 + (sizeof(T) == 2 ? tower_frag_index(c, k, 576) : static_cast<size_t>(c) * 576 + k);
 }
 
-// Where blob element e lives in the 16-bit forward copy: identical, except that the conv weights are
-// kept in the fragment order of the fused conv kernel.  conv1's weights are stored there as fp16 (that
+template <typename T> __host__ __device__ inline size_t bsh_index_wf1(int o, int f)
+{
+    return kBshWf1 + (sizeof(T) == 2 ? tower_frag_index(f, o, 512) : static_cast<size_t>(f) * 512 + o);
+}
+
+// Where blob element e lives in the 16-bit forward copy: identical, except that the conv weights and fc1's are
+// kept in MFMA fragment order (of the fused conv kernel / the fc kernels).  conv1's weights are stored there as fp16 (that
 // kernel runs conv1 on the f16 matrix instruction), everything else as bf16: shadow_store converts.
 __host__ __device__ inline size_t shadow_index(const Offsets& off, size_t e)
 {
     if (e >= off.w1 && e < off.b1) { const int r = static_cast<int>(e - off.w1); return off.w1 + tower_frag_index(r / 256, r % 256, 256); }
     if (e >= off.w2 && e < off.b2) { const int r = static_cast<int>(e - off.w2); return off.w2 + tower_frag_index(r / 512, r % 512, 512); }
     if (e >= off.w3 && e < off.b3) { const int r = static_cast<int>(e - off.w3); return off.w3 + tower_frag_index(r / 576, r % 576, 576); }
+    if (e >= off.wf1 && e < off.bf1) { const int r = static_cast<int>(e - off.wf1); return off.wf1 + tower_frag_index(r / 3136, r % 3136, 3136); }
     return e;
 }
 
@@ -499,8 +506,8 @@ __device__ inline void publish(const RmsArgs& a, size_t e, float th)
 
 // Centered RMSProp (Appendix B) fused with the refresh of the operand copies.  The conv weights come first
 // (their gradient is finished here from split-K slices), elementwise blocks cover the rest except fc1.w and the
-// hidden-layer biases; fc1.w is walked in 32 x 64 tiles so that its transposed copy
-// ([f][o], the operand of fc1's data gradient) is written in full 64/128-byte rows via LDS.
+// hidden-layer biases; fc1.w is walked in 32 x 64 tiles whose two 16-bit copies (forward [o][f] and backward
+// [f][o], both in fragment order; fp32: the row-major [f][o] copy) are written in whole 512-byte pieces via LDS.
 template <typename T, bool SHADOW>
 __global__ __launch_bounds__(256) void rmsprop_kernel(RmsArgs a)
 {
@@ -648,15 +655,30 @@ __global__ __launch_bounds__(256) void rmsprop_kernel(RmsArgs a)
         *reinterpret_cast<float4*>(a.theta + e) = th;
         *reinterpret_cast<float4*>(a.v + e) = vv;
         if (a.centered) *reinterpret_cast<float4*>(a.m + e) = mm;
-        if (SHADOW) store4<T>(static_cast<T*>(a.sh) + e, th.x, th.y, th.z, th.w);
         tile[c4 + 0][r] = from_float<T>(th.x);
         tile[c4 + 1][r] = from_float<T>(th.y);
         tile[c4 + 2][r] = from_float<T>(th.z);
         tile[c4 + 3][r] = from_float<T>(th.w);
     }
     __syncthreads();
-    {
-        typedef typename Vec8<T>::type V8;
+    typedef typename Vec8<T>::type V8;
+    if constexpr (sizeof(T) == 2) {
+        // Both 16-bit copies of the tile in fragment order: a copy's eight (32 rows x 8 k) pieces are 512 contiguous
+        // bytes each, one piece per 32 threads.
+        const int piece = tid >> 5, rr = tid & 31;
+        {   // backward copy, rows = f (two 32-row tiles), k = o
+            const int ft = piece >> 2, k8 = (piece & 3) * 8;
+            const V8 val = *reinterpret_cast<const V8*>(&tile[ft * 32 + rr][k8]);
+            *reinterpret_cast<V8*>(static_cast<T*>(a.bsh) + bsh_index_wf1<T>(o0 + k8, f0 + ft * 32 + rr)) = val;
+        }
+        if (SHADOW) {   // forward copy, rows = o, k = f
+            const int k8 = piece * 8;
+            V8 val;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) val[j] = tile[k8 + j][rr];
+            *reinterpret_cast<V8*>(static_cast<T*>(a.sh) + a.off.wf1 + tower_frag_index(o0 + rr, f0 + k8, 3136)) = val;
+        }
+    } else {
         const int f = tid / 4, part = (tid % 4) * 8;
         const V8 val = *reinterpret_cast<const V8*>(&tile[f][part]);
         *reinterpret_cast<V8*>(static_cast<T*>(a.bsh) + kBshWf1 + static_cast<size_t>(f0 + f) * 512 + o0 + part) = val;
@@ -677,7 +699,7 @@ __global__ __launch_bounds__(256) void build_copies_kernel(const float* __restri
         else if (e >= off.w3 && e < off.b3) bsh[bsh_index_w3<T>(static_cast<int>(e - off.w3))] = val;
         else if (e >= off.wf1 && e < off.bf1) {
             const size_t r = e - off.wf1;
-            bsh[kBshWf1 + (r % 3136) * 512 + r / 3136] = val;
+            bsh[bsh_index_wf1<T>(static_cast<int>(r / 3136), static_cast<int>(r % 3136))] = val;
         }
     }
 }
