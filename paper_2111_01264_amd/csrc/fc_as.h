@@ -51,22 +51,45 @@ __global__ __launch_bounds__(WAVES * 64) void fc_as_kernel(FcAsArgs<T> a)
     const int m0 = blockIdx.y * (TB * 32);
     const int k0 = slice * a.kc;
     const int klen = min(a.kc, a.K - k0);
-    {
-        const T* xg = a.x[g];
-        const int vec_per_row = klen / 8;
-        for (int v = tid; v < TB * 32 * vec_per_row; v += WAVES * 64) {
-            const int r = v / vec_per_row, kc8 = v % vec_per_row;
-            V8 val = vec8_zero<T>();
-            if (m0 + r < a.M) val = *reinterpret_cast<const V8*>(xg + static_cast<size_t>(m0 + r) * a.ldx + k0 + kc8 * 8);
-            *reinterpret_cast<V8*>(&sX[r * ldk + kc8 * 8]) = val;
-        }
-    }
-    __syncthreads();
-
     const int lane_r = lane & 31, kg = lane >> 5;
     const int n = (blockIdx.x * WAVES + wave) * 32 + lane_r;
     const bool n_ok = n < a.N;
     const int ntile = n_ok ? blockIdx.x * WAVES + wave : 0, ks0 = k0 >> 4;   // N is a multiple of 32: tiles are whole
+
+    // The weight stream: a ring of D k-steps of fragments in flight per wavefront, requested before the slab of X
+    // is staged so that both latencies overlap.  Loads are never skipped (the k-step is clamped): the count of
+    // loads in flight stays known to the compiler, which then waits for one slot only.
+    constexpr int D = 8;
+    const int steps = klen >> 4;
+    auto wload = [&](int st) {
+        return *reinterpret_cast<const V8*>(fc_weight_fragment<T>(a.w[g], ntile, ks0 + (st < steps ? st : steps - 1), a.ldw, lane));
+    };
+    V8 ring[D];
+#pragma unroll
+    for (int u = 0; u < D; ++u) ring[u] = wload(u);
+    __builtin_amdgcn_sched_barrier(0);
+    {
+        // the slab of X: eight 16-byte vectors in flight per thread (clamped address, masked value), then their LDS stores --
+        // one vector per trip of a plain loop would be a chain of dependent memory round trips
+        const T* xg = a.x[g];
+        const int vec_per_row = klen / 8, total = TB * 32 * vec_per_row;
+        for (int v0 = tid; v0 < total; v0 += 8 * WAVES * 64) {
+            V8 val[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int v = v0 + u * WAVES * 64 < total ? v0 + u * WAVES * 64 : total - 1;
+                const int r = v / vec_per_row, kc8 = v % vec_per_row;
+                const int row = m0 + r < a.M ? m0 + r : a.M - 1;
+                val[u] = vec8_keep<T>(*reinterpret_cast<const V8*>(xg + static_cast<size_t>(row) * a.ldx + k0 + kc8 * 8), m0 + r < a.M);
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int v = v0 + u * WAVES * 64;
+                if (v < total) *reinterpret_cast<V8*>(&sX[(v / vec_per_row) * ldk + (v % vec_per_row) * 8]) = val[u];
+            }
+        }
+    }
+    __syncthreads();
 
     f32x16 acc[TB];
 #pragma unroll
@@ -74,26 +97,26 @@ __global__ __launch_bounds__(WAVES * 64) void fc_as_kernel(FcAsArgs<T> a)
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[t][v] = 0.f;
 
-    // four k-steps (64 k) per iteration, the next iteration's weight fragments already in flight
-    V8 cur[4], nxt[4];
+    // steps is a multiple of 4 (k per slice is a multiple of 64): whole chunks of D = 8 steps, then possibly four more
+    const T* xrow[TB];
 #pragma unroll
-    for (int s = 0; s < 4; ++s) cur[s] = *reinterpret_cast<const V8*>(fc_weight_fragment<T>(a.w[g], ntile, ks0 + s, a.ldw, lane));
-    for (int kk = 0; kk < klen; kk += 64) {
-        if (kk + 64 < klen) {
+    for (int t = 0; t < TB; ++t) xrow[t] = &sX[(t * 32 + lane_r) * ldk + kg * 8];
+    int base = 0;
+    for (; base + D <= steps; base += D) {
 #pragma unroll
-            for (int s = 0; s < 4; ++s) nxt[s] = *reinterpret_cast<const V8*>(fc_weight_fragment<T>(a.w[g], ntile, ks0 + (kk >> 4) + 4 + s, a.ldw, lane));
+        for (int u = 0; u < D; ++u) {
+            const V8 w = ring[u];
+            ring[u] = wload(base + u + D);
+#pragma unroll
+            for (int t = 0; t < TB; ++t) mma_32x32x16(acc[t], w, *reinterpret_cast<const V8*>(xrow[t] + (base + u) * 16));
+            __builtin_amdgcn_sched_barrier(0);
         }
-        __builtin_amdgcn_sched_barrier(0);   // next chunk's weight fragments in flight before the MFMAs
+    }
+    if (base < steps) {
 #pragma unroll
-        for (int s = 0; s < 4; ++s) {
+        for (int u = 0; u < 4; ++u)
 #pragma unroll
-            for (int t = 0; t < TB; ++t) {
-                const V8 xf = *reinterpret_cast<const V8*>(&sX[(t * 32 + lane_r) * ldk + kk + s * 16 + kg * 8]);
-                mma_32x32x16(acc[t], cur[s], xf);
-            }
-        }
-#pragma unroll
-        for (int s = 0; s < 4; ++s) cur[s] = nxt[s];
+            for (int t = 0; t < TB; ++t) mma_32x32x16(acc[t], ring[u], *reinterpret_cast<const V8*>(xrow[t] + (base + u) * 16));
     }
 
     // lane: sample b = m0 + t*32 + lane_r; values: features 8*q + 4*kg + e of this wavefront's 32
@@ -202,18 +225,9 @@ inline hipError_t launch_fc_as(hipStream_t st, FcAsArgs<T> a, int K, int groups,
     const int n_blocks = (a.N + WAVES * 32 - 1) / (WAVES * 32);
     hipError_t e = hipSuccess;
     if (ev_begin) (void)hipEventRecord(ev_begin, st);
-    if (a.M > 32) {
-        constexpr int TB = 2;
-        const size_t smem = static_cast<size_t>(TB) * 32 * (kc + 8) * sizeof(T);
-        auto kern = fc_as_kernel<T, EPI, TB, WAVES>;
-        static size_t attr_smem = 0;
-        if (smem > attr_smem) {
-            e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, smem);
-            if (e != hipSuccess) return e;
-            attr_smem = smem;
-        }
-        hipLaunchKernelGGL(kern, dim3(n_blocks, (a.M + TB * 32 - 1) / (TB * 32), groups * slices), dim3(WAVES * 64), smem, st, a);
-    } else {
+    {
+        // One 32-row tile of X per workgroup: with two, the grid of a batch-256 step was 100-224 workgroups on 256 CUs,
+        // one per CU, and nothing overlapped a workgroup's staging, streaming and storing phases.
         constexpr int TB = 1;
         const size_t smem = static_cast<size_t>(TB) * 32 * (kc + 8) * sizeof(T);
         auto kern = fc_as_kernel<T, EPI, TB, WAVES>;
@@ -223,7 +237,7 @@ inline hipError_t launch_fc_as(hipStream_t st, FcAsArgs<T> a, int K, int groups,
             if (e != hipSuccess) return e;
             attr_smem = smem;
         }
-        hipLaunchKernelGGL(kern, dim3(n_blocks, 1, groups * slices), dim3(WAVES * 64), smem, st, a);
+        hipLaunchKernelGGL(kern, dim3(n_blocks, (a.M + TB * 32 - 1) / (TB * 32), groups * slices), dim3(WAVES * 64), smem, st, a);
     }
     e = hipGetLastError();
     if (ev_end) (void)hipEventRecord(ev_end, st);

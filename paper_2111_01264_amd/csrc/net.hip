@@ -147,7 +147,7 @@ static int wgrad_splits(int K, int n_blocks, int max_splits)
 // the consumer's slice sum stays small.
 static int fc1_slices(int n, int groups)
 {
-    const int row_tiles = n > 32 ? (n + 63) / 64 : 1;
+    const int row_tiles = (n + 31) / 32;
     const int blocks = 4 * row_tiles * groups;
     int s = 64 / blocks;         // few slices: the head kernel re-reads every slice
     if (s < 7) s = 7;            // 3136 / 7 = 448 columns of X per workgroup fit in LDS
