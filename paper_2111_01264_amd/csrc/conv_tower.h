@@ -90,9 +90,7 @@ template <int KQ> __device__ inline float4 tower_finish(const float4* x, const f
     return r;
 }
 
-// Offset (elements) of conv3's k-step ks inside a pixel's 3x3x64 window of the LDS copy of conv2's output.
 constexpr int kTowerP2_ = 72;
-constexpr int tower_conv3_offset(int ks) { return (((ks >> 2) / 3) * 9 + (ks >> 2) % 3) * kTowerP2_ + (ks & 3) * 16; }
 
 struct TowerArgs {
     const uint8_t* x[kMaxGroups];      // [n][4][84][84], 16-byte aligned
@@ -116,7 +114,7 @@ constexpr int kTowerXBytes = 4 * 84 * 84;             // 28,224 = 1764 x 16
 constexpr int kTowerThreads = 512;                    // the index arithmetic below assumes exactly this block size
 constexpr int kTowerXchgBytes = 2 * 3 * 4 * 3 * 64 * 16;   // row exchange, [nt][tile][finisher][slot][lane] float4
 // LDS: exchange block (its head doubles as the state buffer), conv1 weights, act1, act2, biases
-constexpr size_t kTowerSmem = kTowerXchgBytes + 32 * 256 * 2 + 400 * kTowerP1 * 2 + 81 * kTowerP2 * 2 + 160 * 4;
+constexpr size_t kTowerSmem = kTowerXchgBytes + 32 * 256 * 2 + 400 * kTowerP1 * 2 + 81 * kTowerP2 * 2 + kTowerThreads * 4;   // biases: 160 floats used, one slot per thread
 static_assert(kTowerXBytes <= kTowerXchgBytes, "the state buffer overlays the exchange block");
 
 __global__ __launch_bounds__(kTowerThreads) void conv_tower_kernel(TowerArgs a)
@@ -156,37 +154,55 @@ __global__ __launch_bounds__(kTowerThreads) void conv_tower_kernel(TowerArgs a)
         xv0 = xs_[tid]; xv1 = xs_[tid + 512]; xv2 = xs_[tid + 1024]; xv3 = xs_[last_vec];                      \
     }
 
-    // conv3 k-steps of this wavefront's quarter: offsets inside a pixel's window (wavefront-uniform)
-    int off3[9];
-#pragma unroll
-    for (int k = 0; k < 9; ++k)
-        off3[k] = kq == 0 ? tower_conv3_offset(k) : kq == 1 ? tower_conv3_offset(9 + k) : kq == 2 ? tower_conv3_offset(18 + k) : tower_conv3_offset(27 + k);
-
     V8 wf2[8], wf3[9];
     uint4 xv0, xv1, xv2, xv3;
     int g = 0, b = first;   // item = (group, sample); no run-time division (groups <= 4)
     while (b >= a.n) { b -= a.n; ++g; }
-    DQN_TOWER_FETCH_STATE(g, b)
+    DQN_TOWER_FETCH_STATE(g, b)   // first thing on the way: everything below it is address arithmetic
+
+    // conv3 k-steps of this wavefront's quarter: offsets inside a pixel's window (wavefront-uniform, plain scalar
+    // arithmetic -- written as a choice between per-quarter constants it compiled to a chain of ~30 branches in
+    // front of the first load)
+    int off3[9];
+#pragma unroll
+    for (int k = 0; k < 9; ++k) {
+        const int ks = 9 * kq + k, tap = ks >> 2, p = (tap * 11) >> 5 /* tap / 3 for tap <= 8 */, q = tap - 3 * p;
+        off3[k] = (p * 9 + q) * kTowerP2_ + (ks & 3) * 16;
+    }
+
     int cur_g = -1;
     for (int it = first; it < last; ++it, ++b) {
         if (b == a.n) { b = 0; ++g; }
-        if (g != cur_g) {   // first item, or the range crosses into the next group: (re)load the weights
-            cur_g = g;      // (every wavefront has passed the barrier that ends the previous item)
+        // First item, or the range crosses into the next group: (re)load the weights (every wavefront has passed the
+        // barrier that ends the previous item).  What conv1 needs -- its own 16 KB of weights and the state -- is requested
+        // and parked in LDS first; the 139 KB of conv2/conv3 fragments are requested after that and arrive while conv1 runs
+        // (requested first, they stood in front of conv1's operands in the memory pipeline: a CU draws ~64 B/clk).
+        const bool new_group = g != cur_g;
+        if (new_group) {
+            cur_g = g;
+            const f16x8 w1a = *reinterpret_cast<const f16x8*>(a.w1[g] + tid * 8);
+            const f16x8 w1b = *reinterpret_cast<const f16x8*>(a.w1[g] + (tid + 512) * 8);
+            // biases: every thread loads one (address chosen without a branch, clamped) and stores it to a slot of its own --
+            // behind a condition the compiler sinks the load to the store, a dependent round trip of its own
+            const int bt = tid < 160 ? tid : 159;
+            const float* bp = bt < 32 ? a.b1[g] + bt : (bt < 96 ? a.b2[g] + (bt - 32) : a.b3[g] + (bt - 96));
+            const float bias = *bp;
+            *reinterpret_cast<f16x8*>(sW1 + tid * 8) = w1a;
+            *reinterpret_cast<f16x8*>(sW1 + (tid + 512) * 8) = w1b;
+            sB1[tid] = bias;
+        }
+        {
+            uint4* d = reinterpret_cast<uint4*>(sX);
+            d[tid] = xv0; d[tid + 512] = xv1; d[tid + 1024] = xv2; d[last_vec] = xv3;   // clamped lanes rewrite the last vector with itself
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        if (new_group) {
             const T* p2 = a.w2[g] + (static_cast<size_t>(nt * 32 + kq * 8) * 64 + lane) * 8;
 #pragma unroll
             for (int k = 0; k < 8; ++k) wf2[k] = *reinterpret_cast<const V8*>(p2 + k * 512);
             const T* p3 = a.w3[g] + (static_cast<size_t>(nt * 36 + kq * 9) * 64 + lane) * 8;
 #pragma unroll
             for (int k = 0; k < 9; ++k) wf3[k] = *reinterpret_cast<const V8*>(p3 + k * 512);
-            const f16x8 w1a = *reinterpret_cast<const f16x8*>(a.w1[g] + tid * 8);
-            const f16x8 w1b = *reinterpret_cast<const f16x8*>(a.w1[g] + (tid + 512) * 8);
-            *reinterpret_cast<f16x8*>(sW1 + tid * 8) = w1a;
-            *reinterpret_cast<f16x8*>(sW1 + (tid + 512) * 8) = w1b;
-            if (tid < 160) sB1[tid] = tid < 32 ? a.b1[g][tid] : (tid < 96 ? a.b2[g][tid - 32] : a.b3[g][tid - 96]);
-        }
-        {
-            uint4* d = reinterpret_cast<uint4*>(sX);
-            d[tid] = xv0; d[tid + 512] = xv1; d[tid + 1024] = xv2; d[last_vec] = xv3;   // clamped lanes rewrite the last vector with itself
         }
         if (it + 1 < last) {   // the next item's state: in flight while this item computes
             if (b + 1 < a.n) DQN_TOWER_FETCH_STATE(g, b + 1) else DQN_TOWER_FETCH_STATE(g + 1, 0)

@@ -101,11 +101,11 @@ __global__ __launch_bounds__(kTowerThreads) void conv_tower_bwd_kernel(TowerBwdA
     }
     // conv3 stage, k-step 9 * kq + k: tap (p, q) = (ks / 4 / 3, ks / 4 % 3), channels 16 * (ks % 4) + 8 * kg .. + 7 of
     // dz3 at (y - p, x - q): element offset relative to the pixel's own position in the padded image
-    int off3[9];
+    int off3[9];   // plain scalar arithmetic: a choice between per-quarter constants compiles to a chain of branches
 #pragma unroll
     for (int k = 0; k < 9; ++k) {
-        auto off = [](int ks) { return -((((ks >> 2) / 3) * 11 + (ks >> 2) % 3) * kTbPitch) + (ks & 3) * 16; };
-        off3[k] = kq == 0 ? off(k) : kq == 1 ? off(9 + k) : kq == 2 ? off(18 + k) : off(27 + k);
+        const int ks = 9 * kq + k, tap = ks >> 2, p = (tap * 11) >> 5 /* tap / 3 for tap <= 8 */, q = tap - 3 * p;
+        off3[k] = -((p * 11 + q) * kTbPitch) + (ks & 3) * 16;
     }
 
     // a sample's dz3: 49 pixels x 128 bytes = 392 vectors, one per thread, fetched one sample ahead
