@@ -143,6 +143,7 @@ __global__ __launch_bounds__(256) void head_fwd_kernel(HeadArgs a)
         rew_tail = a.rew[trow_c];
         done_tail = a.done[trow_c];
     }
+    Philox4 draw{};   // act step: the exploration draw of this lane's row
     __builtin_amdgcn_sched_barrier(0);
     // fc2 weight fragments of every group: consumed last
     V8 wf[G][8];
@@ -187,6 +188,12 @@ __global__ __launch_bounds__(256) void head_fwd_kernel(HeadArgs a)
                         for (int u = 0; u < 7; ++u) {
                             const int s = s0 + u < a.slices ? s0 + u : a.slices - 1;
                             v[u] = *reinterpret_cast<const float4*>(p + s * sstride);
+                        }
+                        if constexpr (MODE == kHeadAct) {
+                            // depends on nothing that is loaded: computed under the latency of the requests above, not in the tail
+                            __builtin_amdgcn_sched_barrier(0);
+                            if (s0 == 0) draw = philox_draw(a.seed, kTagAct, a.act_step, static_cast<uint32_t>(row0 + trow_));
+                            __builtin_amdgcn_sched_barrier(0);
                         }
 #pragma unroll
                         for (int u = 0; u < 7; ++u)
@@ -260,7 +267,7 @@ __global__ __launch_bounds__(256) void head_fwd_kernel(HeadArgs a)
         if (row >= a.rows) return;
         if (a.q_out && tk < a.A) a.q_out[static_cast<size_t>(row) * a.A + tk] = qv;
         if (tk == 0) {
-            const Philox4 d = philox_draw(a.seed, kTagAct, a.act_step, static_cast<uint32_t>(row));
+            const Philox4 d = draw;
             const float u = static_cast<float>(d.x[0] >> 8) * 0x1p-24f;
             if (u < a.epsilon) act = static_cast<int>((static_cast<uint64_t>(d.x[1]) * static_cast<uint32_t>(a.A)) >> 32);
             a.actions[row] = act;
