@@ -144,6 +144,8 @@ __global__ __launch_bounds__(256) void head_fwd_kernel(HeadArgs a)
         done_tail = a.done[trow_c];
     }
     Philox4 draw{};   // act step: the exploration draw of this lane's row
+    float b2_tail = 0.f;   // act step: fc2 bias of this lane's action (the tail reads the Q value straight from the partials)
+    if constexpr (MODE == kHeadAct) b2_tail = a.b2[0][(lane & 31) < a.A ? (lane & 31) : a.A - 1];
     __builtin_amdgcn_sched_barrier(0);
     // fc2 weight fragments of every group: consumed last
     V8 wf[G][8];
@@ -230,7 +232,7 @@ __global__ __launch_bounds__(256) void head_fwd_kernel(HeadArgs a)
             for (int v = 0; v < 16; ++v) s_red[wave][v][lane] = acc[v];
             __syncthreads();
             // accumulator layout: sample lane % 32, action 8*(v/4) + 4*(lane/32) + (v%4); wavefront w sums quad w
-            if (lr < kHeadRows) {
+            if (MODE == kHeadTrain && lr < kHeadRows) {
                 const int q = wave;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
@@ -242,7 +244,7 @@ __global__ __launch_bounds__(256) void head_fwd_kernel(HeadArgs a)
                 }
             }
         }
-    __syncthreads();
+    if constexpr (MODE == kHeadTrain) __syncthreads();
 
     // Tail: wavefront 0, 32 lanes per row (kHeadRows = 2), lane k owns action k.  argmax with the lowest index
     // among equal values (the tie rule of the greedy policy, Section 2.1), as a butterfly over the 32 lanes.
@@ -262,7 +264,10 @@ __global__ __launch_bounds__(256) void head_fwd_kernel(HeadArgs a)
     if constexpr (MODE == kHeadAct) {
         if (wave != 0) return;
         const int row = row0 + trow;
-        const float qv = tk < a.A ? s_q[0][trow][tk] : kNegInf;
+        // Q(row, action tk): the four k-quarter partials of accumulator slot (sample trow, action tk), in wavefront order
+        const int tkc = tk < a.A ? tk : a.A - 1;
+        const int v = 4 * (tkc >> 3) + (tkc & 3), src = ((tkc >> 2) & 1) * 32 + trow;
+        const float qv = tk < a.A ? (((s_red[0][v][src] + s_red[1][v][src]) + s_red[2][v][src]) + s_red[3][v][src]) + b2_tail : kNegInf;
         int act = argmax_lowest(qv, tk);
         if (row >= a.rows) return;
         if (a.q_out && tk < a.A) a.q_out[static_cast<size_t>(row) * a.A + tk] = qv;
