@@ -118,6 +118,7 @@ class Workload:
         self.precision = args.precision
         self.acts_per_train = args.acts_per_train
         self.fused_push = not args.separate_push
+        self.fused_gather = not args.separate_gather
         self.sync_every = args.sync_every
         self.double = int(args.double_dqn)
         torch.cuda.set_device(0)
@@ -238,6 +239,15 @@ class Workload:
         """Trainer side: sample + gather + train step, n times."""
         lib, ctx, rb, B = self._lib, self.ctx, self.rb, self.B
         ps, ps2, pa, pr, pd, pl = self._p_train
+        if self.fused_gather:
+            # one call per step; the gather of the next minibatch rides in this step's launches (not for the last
+            # step of the part: a synchronisation point may follow, and the replay memory changes there)
+            for i in range(n_train_steps):
+                rc = lib.dqn_train_step_sampled(ctx, rb, B, self.train_steps, 1 if i + 1 < n_train_steps else 0, pl)
+                if rc:
+                    self._fail("dqn_train_step_sampled", rc)
+                self.train_steps += 1
+            return
         for _ in range(n_train_steps):
             rc = lib.replay_sample_gather(rb, B, self.train_steps, None, ps, ps2, pa, pr, pd, None)
             if rc:
@@ -365,6 +375,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--separate-push", action="store_true",
                     help="replay_push_step and dqn_act as two calls per act step instead of dqn_act_push_step")
+    ap.add_argument("--separate-gather", action="store_true",
+                    help="replay_sample_gather and dqn_train_step as two calls instead of dqn_train_step_sampled")
     ap.add_argument("--sweep", action="store_true", help="print the batch/W roofline sweep instead of the JSON line")
     args = ap.parse_args()
     if args.gpus != 1:

@@ -193,6 +193,17 @@ int replay_sample_gather(replay* rb, int32_t B, uint64_t sample_step, const int6
                          uint8_t* s, uint8_t* s2, int32_t* a, float* r, float* done,
                          int64_t* idx_out);
 
+/* replay_sample_gather(rb, B, sample_step, NULL, ...) into buffers owned by ctx, followed by dqn_train_step on
+ * them -- with the gather taken out of the chain of dependent launches: if prefetch_next != 0, workgroups
+ * riding in one of this step's kernels already gather the minibatch of sample_step + 1 into the other of two
+ * buffer sets (the replay memory is constant between synchronisation points, Section 3 / Algorithm 1), and
+ * the next call, if it asks for exactly that minibatch (same rb, B, sample_step + 1, and no replay_flush /
+ * dqn_sync_target in between), finds it there.  Any other call gathers first, as the two separate calls
+ * would: results are identical to theirs in every case.  The replay's sample_stream must be ctx's
+ * train_stream.  Errors: those of the two calls. */
+int dqn_train_step_sampled(dqn_ctx* ctx, replay* rb, int32_t B, uint64_t sample_step,
+                           int32_t prefetch_next, float* loss_out);
+
 /* ---- seeded synthetic inputs (benchmark support; stands in for emulator output) ----------- */
 
 /* Frame i of the call gets id = id0 + i * id_step and is written to dst[i] ([n,84,84] uint8):

@@ -49,6 +49,7 @@ EXPORTS = {
     "dqn_train_step": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                  C.c_void_p, C.c_int32, C.c_void_p]),
     "dqn_get_train_q": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
+    "dqn_train_step_sampled": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_uint64, C.c_int32, C.c_void_p]),
     "dqn_sync_target": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32]),
     "replay_create": (C.c_int, [C.c_int64, C.c_int32, C.c_int64, C.c_uint64, C.c_void_p, C.c_void_p,
                                 C.POINTER(C.c_void_p)]),
@@ -142,6 +143,10 @@ def dqn_act(ctx, states, W, epsilon, act_step, use_target, actions, q_out=None):
 
 def dqn_train_step(ctx, s, a, r, s2, done, B, loss_out=None):
     _check(_lib.dqn_train_step(ctx, _ptr(s), _ptr(a), _ptr(r), _ptr(s2), _ptr(done), B, _ptr(loss_out)))
+
+
+def dqn_train_step_sampled(ctx, rb, B, sample_step, prefetch_next, loss_out=None):
+    _check(_lib.dqn_train_step_sampled(ctx, rb, B, sample_step, 1 if prefetch_next else 0, _ptr(loss_out)))
 
 
 def dqn_get_train_q(ctx, B, A, double_dqn=False):

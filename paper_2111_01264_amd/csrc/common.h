@@ -6,6 +6,7 @@
 #include <stdio.h>
 
 #include "../../include/dqn_mi355.h"
+#include "philox.h"
 
 namespace dqn {
 
@@ -83,6 +84,109 @@ __device__ inline void push_step_block(const PushStepPlan& p, int lane)
         p.st_terminals[dst] = p.terminals[lane];
     }
 }
+
+struct LaneTable {
+    int32_t head[kMaxLanes];   // next write position inside the lane
+    int32_t count[kMaxLanes];  // visible frames in the lane
+};
+
+// One replay_sample_gather call as data for a kernel (for a caller that folds the gather into a launch of its own).
+struct GatherPlan {
+    const uint8_t* frames; const int32_t* actions; const float* rewards; const uint8_t* terminals;   // the ring
+    LaneTable tab;
+    int32_t L; int64_t M, V;
+    uint64_t seed, sample_step;
+    const int64_t* idx_in;
+    uint8_t* s; uint8_t* s2; int32_t* a; float* r; float* done; int64_t* idx_out;
+    int32_t B;                  // 0 = nothing to gather
+};
+
+// Workgroup (frame f of the five-frame window ages j-3 .. j+1, sample b), 256 threads.  The frame is read once and
+// written into s (position f, f <= 3) and s2 (position f-1, f >= 1), each zeroed if a terminal flag lies between
+// the frame and the newest frame of that stack (Section 2.1: states are stacks of the four latest frames).
+__device__ inline void gather_block(const GatherPlan& p, int f, int b)
+{
+    const uint8_t* __restrict__ frames = p.frames; const int32_t* __restrict__ actions = p.actions;
+    const float* __restrict__ rewards = p.rewards; const uint8_t* __restrict__ terminals = p.terminals;
+    const LaneTable& tab = p.tab;
+    const int32_t L = p.L; const int64_t M = p.M, V = p.V; const uint64_t seed = p.seed, sample_step = p.sample_step;
+    const int64_t* __restrict__ idx_in = p.idx_in; uint8_t* __restrict__ s = p.s; uint8_t* __restrict__ s2 = p.s2;
+    int32_t* __restrict__ a = p.a; float* __restrict__ r = p.r; float* __restrict__ done = p.done; int64_t* __restrict__ idx_out = p.idx_out;
+    int64_t idx;
+    if (idx_in) {
+        idx = idx_in[b];
+    } else {
+        const Philox4 d = philox_draw(seed, kTagSample, sample_step, static_cast<uint32_t>(b));
+        const uint64_t u = (static_cast<uint64_t>(d.x[1]) << 32) | d.x[0];
+        int64_t k = static_cast<int64_t>(__umul64hi(u, static_cast<uint64_t>(V)));
+        int lane = 0;
+        for (;;) {
+            const int64_t v = tab.count[lane] > 4 ? tab.count[lane] - 4 : 0;
+            if (k < v || lane == L - 1) break;
+            k -= v;
+            ++lane;
+        }
+        idx = lane * M + 3 + k;
+    }
+    bool ok = idx >= 0 && idx < static_cast<int64_t>(L) * M;
+    int lane = 0;
+    int64_t j = 0;
+    if (ok) {
+        lane = static_cast<int>(idx / M);
+        j = idx % M;
+        ok = j >= 3 && j <= static_cast<int64_t>(tab.count[lane]) - 2;
+    }
+    uint4* ds = (f <= 3) ? reinterpret_cast<uint4*>(s + (static_cast<int64_t>(b) * 4 + f) * kFrameBytes) : nullptr;
+    uint4* ds2 = (f >= 1) ? reinterpret_cast<uint4*>(s2 + (static_cast<int64_t>(b) * 4 + f - 1) * kFrameBytes) : nullptr;
+    const int ph = ds ? line_phase(ds) : 0, ph2 = ds2 ? line_phase(ds2) : 0;   // see copy_frame
+    if (!ok) {
+        const uint4 z = make_uint4(0, 0, 0, 0);
+        for (int v = threadIdx.x; v < kFrameVec16 + 3; v += blockDim.x) {
+            if (ds && v - ph >= 0 && v - ph < kFrameVec16) ds[v - ph] = z;
+            if (ds2 && v - ph2 >= 0 && v - ph2 < kFrameVec16) ds2[v - ph2] = z;
+        }
+        if (f == 0 && threadIdx.x == 0) {
+            a[b] = -1; r[b] = 0.f; done[b] = 0.f;
+            if (idx_out) idx_out[b] = idx;
+        }
+        return;
+    }
+    const int64_t base = static_cast<int64_t>(tab.head[lane]) - tab.count[lane] + M;  // >= 0
+    const int64_t lane0 = lane * M;
+    // terminal flags of ages j-3 .. j
+    uint32_t t[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) t[u] = terminals[lane0 + (base + j - 3 + u) % M];
+    uint32_t any_s = 0, any_s2 = 0;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        if (u >= f && u <= 2) any_s |= t[u];
+        if (u >= f) any_s2 |= t[u];
+    }
+    const int64_t slot = lane0 + (base + j - 3 + f) % M;
+    const uint4* src = reinterpret_cast<const uint4*>(frames + slot * kFrameBytes);
+    const uint4 z = make_uint4(0, 0, 0, 0);
+    // each destination with its own phase shift; the second read of the frame comes from cache
+    for (int v = threadIdx.x; v < kFrameVec16 + 3; v += blockDim.x) {
+        const int v1 = v - ph, v2 = v - ph2;
+        if (ds && v1 >= 0 && v1 < kFrameVec16) ds[v1] = any_s ? z : src[v1];
+        if (ds2 && v2 >= 0 && v2 < kFrameVec16) ds2[v2] = any_s2 ? z : src[v2];
+    }
+    if (f == 0 && threadIdx.x == 0) {
+        const int64_t tslot = lane0 + (base + j) % M;
+        a[b] = actions[tslot];
+        r[b] = rewards[tslot];
+        done[b] = t[3] ? 1.f : 0.f;
+        if (idx_out) idx_out[b] = idx;
+    }
+}
+
+// Validates a replay_sample_gather call and fills `plan` without enqueuing anything.
+int replay_plan_sample_gather(replay* rb, int32_t B, uint64_t sample_step, const int64_t* idx_in, uint8_t* s, uint8_t* s2,
+                              int32_t* a, float* r, float* done, int64_t* idx_out, GatherPlan* plan);
+// Changes with every flush (and differs between replay memories): two gathers of the same sample step read the same
+// minibatch iff their epochs are equal.
+uint64_t replay_epoch(const replay* rb);
 
 // Validates a replay_push_step call and fills `plan` without enqueuing anything; replay_commit_push_step then
 // records that the experiences have been appended (call it once the kernel carrying the plan is enqueued).

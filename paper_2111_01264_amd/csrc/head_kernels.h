@@ -2,6 +2,7 @@
 // (Eq. 1), fc2 backward, bias gradients, centered RMSProp (Appendix B) with the refresh of the
 // operand copies, and the target copy (theta^- <- theta).
 #pragma once
+#include "common.h"
 #include "conv_tower.h"
 #include "conv_ws.h"
 #include "philox.h"
@@ -89,6 +90,7 @@ constexpr int kHeadRows = 2;
 struct HeadArgs {
     const float* partial;        // [groups][slices][rows][512]
     int slices, rows, A, groups;
+    int head_blocks;             // workgroups of the head proper (the first ones of the grid)
     const float* b1[3];
     const void* w2[3];           // T [A][512]
     const float* b2[3];
@@ -108,6 +110,10 @@ struct HeadArgs {
     float* q_all;                // [groups][rows][A]
     float* dqv;
     float* lossv;
+    // Train step: workgroups [head_blocks, head_blocks + 5 * gather.B) gather the NEXT minibatch from the replay memory
+    // (D is constant between synchronisation points, Section 3): independent byte copies that would otherwise cost a
+    // dependent launch of their own in front of every train step.  (Last in the struct: the act step never reads it.)
+    GatherPlan gather;
 };
 
 constexpr int kHeadAct = 0, kHeadTrain = 1;
@@ -122,6 +128,13 @@ __global__ __launch_bounds__(256) void head_fwd_kernel(HeadArgs a)
     __shared__ float s_red[4][16][64];
     __shared__ float s_q[G][kHeadRows][kMaxActions + 1];
     __shared__ float s_dq[kHeadRows];
+    if constexpr (MODE == kHeadTrain) {
+        if (static_cast<int>(blockIdx.x) >= a.head_blocks) {
+            const int i = static_cast<int>(blockIdx.x) - a.head_blocks;
+            gather_block(a.gather, i % 5, i / 5);
+            return;
+        }
+    }
     float h0[4] = {0.f, 0.f, 0.f, 0.f};   // this thread's four features of h (online pass on s)
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int row0 = blockIdx.x * kHeadRows;

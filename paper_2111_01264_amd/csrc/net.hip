@@ -70,6 +70,16 @@ struct dqn_ctx {
     hipEvent_t ev_train = nullptr, ev_act = nullptr, ev_sync = nullptr;
     std::atomic<bool> train_unrecorded{false};   // a train step has been enqueued since ev_train was last recorded
     bool act_reads_online = false;   // an act step with use_target = 0 is in flight
+    // dqn_train_step_sampled: two sets of minibatch buffers; `pre_*` describes the minibatch gathered ahead, if any
+    uint8_t* mb_s[2] = {nullptr, nullptr};
+    uint8_t* mb_s2[2] = {nullptr, nullptr};
+    int32_t* mb_a[2] = {nullptr, nullptr};
+    float* mb_r[2] = {nullptr, nullptr};
+    float* mb_d[2] = {nullptr, nullptr};
+    bool pre_valid = false;
+    const replay* pre_rb = nullptr;
+    int pre_B = 0, pre_buf = 0;
+    uint64_t pre_step = 0, pre_epoch = 0;
     int last_B = 0;
     int num_cus = 256;
     // per-kernel timing (dqn_profile_*)
@@ -289,14 +299,16 @@ static int act_impl(dqn_ctx* c, const uint8_t* states, int W, float epsilon, uin
     ha.partial = c->act_ws.partial; ha.slices = slices; ha.rows = W; ha.A = c->A; ha.groups = 1;
     ha.b1[0] = master[0] + c->off.bf1; ha.w2[0] = static_cast<const T*>(shadow[0]) + c->off.wf2; ha.b2[0] = master[0] + c->off.bf2;
     ha.epsilon = epsilon; ha.seed = c->cfg.seed; ha.act_step = act_step; ha.actions = actions; ha.q_out = q_out;
-    hipLaunchKernelGGL((head_fwd_kernel<T, kHeadAct>), dim3((W + kHeadRows - 1) / kHeadRows), dim3(256), 0, c->act_stream, ha);
+    ha.head_blocks = (W + kHeadRows - 1) / kHeadRows;
+    ha.gather.B = 0;
+    hipLaunchKernelGGL((head_fwd_kernel<T, kHeadAct>), dim3(ha.head_blocks), dim3(256), 0, c->act_stream, ha);
     DQN_LAUNCH_CHECK();
     return DQN_OK;
 }
 
 template <typename T, bool SHADOW>
 static int train_impl(dqn_ctx* c, const uint8_t* s, const int32_t* a, const float* r, const uint8_t* s2,
-                      const float* done, int B, float* loss_out)
+                      const float* done, int B, float* loss_out, const GatherPlan* ride = nullptr)
 {
     const Offsets& o = c->off;
     hipStream_t st = c->train_stream;
@@ -333,7 +345,10 @@ static int train_impl(dqn_ctx* c, const uint8_t* s, const int32_t* a, const floa
         ha.double_dqn = c->cfg.double_dqn; ha.act = a; ha.rew = r; ha.done = done;
         ha.gamma = c->cfg.gamma; ha.huber = c->cfg.huber_delta;
         ha.h_online = h; ha.dzh = dzh; ha.q_all = ws.q; ha.dqv = c->dqv; ha.lossv = c->lossv;
-        hipLaunchKernelGGL((head_fwd_kernel<T, kHeadTrain>), dim3((B + kHeadRows - 1) / kHeadRows), dim3(256), 0, st, ha);
+        ha.head_blocks = (B + kHeadRows - 1) / kHeadRows;
+        ha.gather.B = 0;
+        if (ride) ha.gather = *ride;
+        hipLaunchKernelGGL((head_fwd_kernel<T, kHeadTrain>), dim3(ha.head_blocks + 5 * ha.gather.B), dim3(256), 0, st, ha);
         if (pr.end) (void)hipEventRecord(pr.end, st);
         DQN_LAUNCH_CHECK();
     }
@@ -603,6 +618,13 @@ int dqn_create(const dqn_config* cfg, void* act_stream, void* train_stream, dqn_
         DQN_HIP(hipMalloc((void**)&c->dqv, B * sizeof(float)));
         DQN_HIP(hipMalloc((void**)&c->lossv, B * sizeof(float)));
         DQN_HIP(hipMalloc((void**)&c->loss_keep, sizeof(float)));
+        for (int i = 0; i < 2; ++i) {
+            DQN_HIP(hipMalloc((void**)&c->mb_s[i], B * kStateBytes));
+            DQN_HIP(hipMalloc((void**)&c->mb_s2[i], B * kStateBytes));
+            DQN_HIP(hipMalloc((void**)&c->mb_a[i], B * sizeof(int32_t)));
+            DQN_HIP(hipMalloc((void**)&c->mb_r[i], B * sizeof(float)));
+            DQN_HIP(hipMalloc((void**)&c->mb_d[i], B * sizeof(float)));
+        }
         DQN_HIP(hipEventCreateWithFlags(&c->ev_train, hipEventDisableTiming));
         DQN_HIP(hipEventCreateWithFlags(&c->ev_act, hipEventDisableTiming));
         DQN_HIP(hipEventCreateWithFlags(&c->ev_sync, hipEventDisableTiming));
@@ -633,6 +655,9 @@ int dqn_destroy(dqn_ctx* c)
     (void)hipFree(c->dzh); (void)hipFree(c->dz3); (void)hipFree(c->dz2); (void)hipFree(c->dz1);
     (void)hipFree(c->dqv); (void)hipFree(c->lossv); (void)hipFree(c->loss_keep);
     (void)hipFree(c->bsh); (void)hipFree(c->bias_partial); (void)hipFree(c->wg_partial);
+    for (int i = 0; i < 2; ++i) {
+        (void)hipFree(c->mb_s[i]); (void)hipFree(c->mb_s2[i]); (void)hipFree(c->mb_a[i]); (void)hipFree(c->mb_r[i]); (void)hipFree(c->mb_d[i]);
+    }
     if (c->ev_train) (void)hipEventDestroy(c->ev_train);
     if (c->ev_act) (void)hipEventDestroy(c->ev_act);
     if (c->ev_sync) (void)hipEventDestroy(c->ev_sync);
@@ -758,6 +783,48 @@ int dqn_train_step(dqn_ctx* c, const uint8_t* s, const int32_t* a, const float* 
     if (rc != DQN_OK) return rc;
     c->train_unrecorded.store(true, std::memory_order_release);   // the event is recorded by the first reader, if any
     c->last_B = B;
+    return DQN_OK;
+}
+
+int dqn_train_step_sampled(dqn_ctx* c, replay* rb, int32_t B, uint64_t sample_step, int32_t prefetch_next, float* loss_out)
+{
+    if (!c || !rb) return fail(DQN_EINVAL, "dqn_train_step_sampled: null handle");
+    if (B < 1 || B > c->cfg.max_batch) return fail(DQN_EINVAL, "dqn_train_step_sampled: B = %d outside 1..%d", B, c->cfg.max_batch);
+    if (replay_sample_stream(rb) != c->train_stream)
+        return fail(DQN_EINVAL, "dqn_train_step_sampled: the replay's sample stream must be the train stream");
+    int buf = 0;
+    if (c->pre_valid && c->pre_rb == rb && c->pre_B == B && c->pre_step == sample_step && c->pre_epoch == replay_epoch(rb)) {
+        buf = c->pre_buf;   // gathered inside the previous call's launches, and no flush since
+    } else {
+        const int rc = replay_sample_gather(rb, B, sample_step, nullptr, c->mb_s[0], c->mb_s2[0], c->mb_a[0], c->mb_r[0], c->mb_d[0], nullptr);
+        if (rc != DQN_OK) return rc;
+    }
+    c->pre_valid = false;
+    GatherPlan plan;
+    const GatherPlan* ride = nullptr;
+    if (prefetch_next) {
+        const int nb = buf ^ 1;
+        const int rc = replay_plan_sample_gather(rb, B, sample_step + 1, nullptr, c->mb_s[nb], c->mb_s2[nb], c->mb_a[nb], c->mb_r[nb],
+                                                 c->mb_d[nb], nullptr, &plan);
+        if (rc != DQN_OK) return rc;
+        ride = &plan;
+    }
+    if (c->act_reads_online) {
+        DQN_HIP(hipStreamWaitEvent(c->train_stream, c->ev_act, 0));
+        c->act_reads_online = false;
+    }
+    int rc;
+    if (c->cfg.precision == DQN_PRECISION_BF16)
+        rc = train_impl<bf16_t, true>(c, c->mb_s[buf], c->mb_a[buf], c->mb_r[buf], c->mb_s2[buf], c->mb_d[buf], B, loss_out, ride);
+    else
+        rc = train_impl<float, false>(c, c->mb_s[buf], c->mb_a[buf], c->mb_r[buf], c->mb_s2[buf], c->mb_d[buf], B, loss_out, ride);
+    if (rc != DQN_OK) return rc;
+    c->train_unrecorded.store(true, std::memory_order_release);
+    c->last_B = B;
+    if (ride) {
+        c->pre_valid = true; c->pre_rb = rb; c->pre_B = B; c->pre_step = sample_step + 1; c->pre_epoch = replay_epoch(rb);
+        c->pre_buf = buf ^ 1;
+    }
     return DQN_OK;
 }
 

@@ -2,17 +2,12 @@
 // merged at the synchronisation point (Section 3), uniform sampling (Section 2.1) and the fused
 // sample + frame-stack gather with terminal masking.  All of it is byte/index work bound by HBM
 // bandwidth: frames move as 16-byte vectors (7056 = 441 * 16), one frame per workgroup.
+#include <atomic>
 #include <new>
 
 #include "common.h"
-#include "philox.h"
 
 namespace dqn {
-
-struct LaneTable {
-    int32_t head[kMaxLanes];   // next write position inside the lane
-    int32_t count[kMaxLanes];  // visible frames in the lane
-};
 
 struct FlushTable {
     int32_t head[kMaxLanes];
@@ -36,6 +31,7 @@ struct replay {
     uint8_t* st_terminals;
     int64_t head[dqn::kMaxLanes], count[dqn::kMaxLanes], staged[dqn::kMaxLanes];
     hipEvent_t ev_push, ev_flush;
+    uint64_t epoch;   // (creation serial << 32) + flushes so far
 };
 
 namespace dqn {
@@ -80,87 +76,8 @@ __global__ __launch_bounds__(256) void flush_kernel(
     }
 }
 
-// One workgroup per (sample b, frame f of the five-frame window ages j-3 .. j+1).  The frame is
-// read once and written into s (position f, f <= 3) and s2 (position f-1, f >= 1), each zeroed
-// if a terminal flag lies between the frame and the newest frame of that stack.
-__global__ __launch_bounds__(256) void sample_gather_kernel(
-    const uint8_t* __restrict__ frames, const int32_t* __restrict__ actions,
-    const float* __restrict__ rewards, const uint8_t* __restrict__ terminals, LaneTable tab,
-    int32_t L, int64_t M, int64_t V, uint64_t seed, uint64_t sample_step,
-    const int64_t* __restrict__ idx_in, uint8_t* __restrict__ s, uint8_t* __restrict__ s2,
-    int32_t* __restrict__ a, float* __restrict__ r, float* __restrict__ done,
-    int64_t* __restrict__ idx_out)
-{
-    const int f = blockIdx.x;
-    const int b = blockIdx.y;
-    int64_t idx;
-    if (idx_in) {
-        idx = idx_in[b];
-    } else {
-        const Philox4 d = philox_draw(seed, kTagSample, sample_step, static_cast<uint32_t>(b));
-        const uint64_t u = (static_cast<uint64_t>(d.x[1]) << 32) | d.x[0];
-        int64_t k = static_cast<int64_t>(__umul64hi(u, static_cast<uint64_t>(V)));
-        int lane = 0;
-        for (;;) {
-            const int64_t v = tab.count[lane] > 4 ? tab.count[lane] - 4 : 0;
-            if (k < v || lane == L - 1) break;
-            k -= v;
-            ++lane;
-        }
-        idx = lane * M + 3 + k;
-    }
-    bool ok = idx >= 0 && idx < static_cast<int64_t>(L) * M;
-    int lane = 0;
-    int64_t j = 0;
-    if (ok) {
-        lane = static_cast<int>(idx / M);
-        j = idx % M;
-        ok = j >= 3 && j <= static_cast<int64_t>(tab.count[lane]) - 2;
-    }
-    uint4* ds = (f <= 3) ? reinterpret_cast<uint4*>(s + (static_cast<int64_t>(b) * 4 + f) * kFrameBytes) : nullptr;
-    uint4* ds2 = (f >= 1) ? reinterpret_cast<uint4*>(s2 + (static_cast<int64_t>(b) * 4 + f - 1) * kFrameBytes) : nullptr;
-    const int ph = ds ? line_phase(ds) : 0, ph2 = ds2 ? line_phase(ds2) : 0;   // see copy_frame
-    if (!ok) {
-        const uint4 z = make_uint4(0, 0, 0, 0);
-        for (int v = threadIdx.x; v < kFrameVec16 + 3; v += blockDim.x) {
-            if (ds && v - ph >= 0 && v - ph < kFrameVec16) ds[v - ph] = z;
-            if (ds2 && v - ph2 >= 0 && v - ph2 < kFrameVec16) ds2[v - ph2] = z;
-        }
-        if (f == 0 && threadIdx.x == 0) {
-            a[b] = -1; r[b] = 0.f; done[b] = 0.f;
-            if (idx_out) idx_out[b] = idx;
-        }
-        return;
-    }
-    const int64_t base = static_cast<int64_t>(tab.head[lane]) - tab.count[lane] + M;  // >= 0
-    const int64_t lane0 = lane * M;
-    // terminal flags of ages j-3 .. j
-    uint32_t t[4];
-#pragma unroll
-    for (int u = 0; u < 4; ++u) t[u] = terminals[lane0 + (base + j - 3 + u) % M];
-    uint32_t any_s = 0, any_s2 = 0;
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-        if (u >= f && u <= 2) any_s |= t[u];
-        if (u >= f) any_s2 |= t[u];
-    }
-    const int64_t slot = lane0 + (base + j - 3 + f) % M;
-    const uint4* src = reinterpret_cast<const uint4*>(frames + slot * kFrameBytes);
-    const uint4 z = make_uint4(0, 0, 0, 0);
-    // each destination with its own phase shift; the second read of the frame comes from cache
-    for (int v = threadIdx.x; v < kFrameVec16 + 3; v += blockDim.x) {
-        const int v1 = v - ph, v2 = v - ph2;
-        if (ds && v1 >= 0 && v1 < kFrameVec16) ds[v1] = any_s ? z : src[v1];
-        if (ds2 && v2 >= 0 && v2 < kFrameVec16) ds2[v2] = any_s2 ? z : src[v2];
-    }
-    if (f == 0 && threadIdx.x == 0) {
-        const int64_t tslot = lane0 + (base + j) % M;
-        a[b] = actions[tslot];
-        r[b] = rewards[tslot];
-        done[b] = t[3] ? 1.f : 0.f;
-        if (idx_out) idx_out[b] = idx;
-    }
-}
+// One workgroup per (sample b, frame f of the five-frame window): see gather_block.
+__global__ __launch_bounds__(256) void sample_gather_kernel(GatherPlan plan) { gather_block(plan, blockIdx.x, blockIdx.y); }
 
 // ---- seeded synthetic inputs ------------------------------------------------------------------
 __host__ __device__ inline uint64_t mix64(uint64_t z)
@@ -242,6 +159,10 @@ int replay_create(int64_t capacity_frames, int32_t lanes, int64_t staging_per_la
     replay* rb = new (std::nothrow) replay();
     if (!rb) return fail(DQN_ENOMEM, "replay_create: host allocation failed");
     rb->N = capacity_frames; rb->M = M; rb->S = staging_per_lane; rb->L = lanes; rb->seed = seed;
+    {   // epochs of different replay memories never coincide (a new one may reuse the address of a destroyed one)
+        static std::atomic<uint64_t> serial{1};
+        rb->epoch = serial.fetch_add(1) << 32;
+    }
     rb->push_stream = static_cast<hipStream_t>(push_stream);
     rb->sample_stream = static_cast<hipStream_t>(sample_stream);
     const int64_t SN = staging_per_lane * lanes;
@@ -335,6 +256,7 @@ static int flush_enqueue(replay* rb)
         rb->count[l] = rb->count[l] + rb->staged[l] > rb->M ? rb->M : rb->count[l] + rb->staged[l];
         rb->staged[l] = 0;
     }
+    ++rb->epoch;
     return DQN_OK;
 }
 
@@ -377,6 +299,25 @@ int replay_flush_ordered(replay* rb)
     return DQN_OK;
 }
 
+int replay_plan_sample_gather(replay* rb, int32_t B, uint64_t sample_step, const int64_t* idx_in, uint8_t* s, uint8_t* s2,
+                              int32_t* a, float* r, float* done, int64_t* idx_out, GatherPlan* plan)
+{
+    if (!rb) return fail(DQN_EINVAL, "replay_sample_gather: rb is null");
+    if (B < 1 || B > 65535) return fail(DQN_EINVAL, "replay_sample_gather: B = %d outside 1..65535", B);
+    if (!s || !s2 || !a || !r || !done) return fail(DQN_EINVAL, "replay_sample_gather: null output pointer");
+    if (!aligned16(s) || !aligned16(s2)) return fail(DQN_EINVAL, "replay_sample_gather: s/s2 not 16-byte aligned");
+    const int64_t V = replay_num_valid(rb);
+    if (V <= 0) return fail(DQN_ESTATE, "replay_sample_gather: replay memory holds no complete transition");
+    plan->frames = rb->frames; plan->actions = rb->actions; plan->rewards = rb->rewards; plan->terminals = rb->terminals;
+    for (int l = 0; l < rb->L; ++l) { plan->tab.head[l] = (int32_t)rb->head[l]; plan->tab.count[l] = (int32_t)rb->count[l]; }
+    plan->L = rb->L; plan->M = rb->M; plan->V = V; plan->seed = rb->seed; plan->sample_step = sample_step;
+    plan->idx_in = idx_in; plan->s = s; plan->s2 = s2; plan->a = a; plan->r = r; plan->done = done; plan->idx_out = idx_out;
+    plan->B = B;
+    return DQN_OK;
+}
+
+uint64_t replay_epoch(const replay* rb) { return rb->epoch; }
+
 hipStream_t replay_sample_stream(replay* rb) { return rb->sample_stream; }
 hipStream_t replay_push_stream(replay* rb) { return rb->push_stream; }
 }  // namespace dqn
@@ -403,17 +344,10 @@ int64_t replay_num_valid(const replay* rb)
 int replay_sample_gather(replay* rb, int32_t B, uint64_t sample_step, const int64_t* idx_in,
                          uint8_t* s, uint8_t* s2, int32_t* a, float* r, float* done, int64_t* idx_out)
 {
-    if (!rb) return fail(DQN_EINVAL, "replay_sample_gather: rb is null");
-    if (B < 1 || B > 65535) return fail(DQN_EINVAL, "replay_sample_gather: B = %d outside 1..65535", B);
-    if (!s || !s2 || !a || !r || !done) return fail(DQN_EINVAL, "replay_sample_gather: null output pointer");
-    if (!aligned16(s) || !aligned16(s2)) return fail(DQN_EINVAL, "replay_sample_gather: s/s2 not 16-byte aligned");
-    const int64_t V = replay_num_valid(rb);
-    if (V <= 0) return fail(DQN_ESTATE, "replay_sample_gather: replay memory holds no complete transition");
-    LaneTable tab;
-    for (int l = 0; l < rb->L; ++l) { tab.head[l] = (int32_t)rb->head[l]; tab.count[l] = (int32_t)rb->count[l]; }
-    hipLaunchKernelGGL(sample_gather_kernel, dim3(5, B), dim3(256), 0, rb->sample_stream, rb->frames,
-                       rb->actions, rb->rewards, rb->terminals, tab, rb->L, rb->M, V, rb->seed, sample_step,
-                       idx_in, s, s2, a, r, done, idx_out);
+    GatherPlan plan;
+    const int rc = replay_plan_sample_gather(rb, B, sample_step, idx_in, s, s2, a, r, done, idx_out, &plan);
+    if (rc != DQN_OK) return rc;
+    hipLaunchKernelGGL(sample_gather_kernel, dim3(5, B), dim3(256), 0, rb->sample_stream, plan);
     DQN_LAUNCH_CHECK();
     return DQN_OK;
 }

@@ -303,3 +303,59 @@ def test_act_push_step_equals_the_two_calls(precision):
     for xa, xb in zip(rep_a, rep_b):
         assert np.array_equal(xa, xb)
     assert rep_a[2].min() >= 0            # real transitions, not the invalid-index marker
+
+
+@pytest.mark.parametrize("precision", [P.DQN_PRECISION_BF16, P.DQN_PRECISION_FP32], ids=["bf16", "fp32"])
+def test_train_step_sampled_equals_the_two_calls(precision):
+    """dqn_train_step_sampled == replay_sample_gather + dqn_train_step, bit for bit (parameters and loss after every
+    step), also when the minibatch gathered ahead goes stale (a flush in between) or is not the one asked for next."""
+    seed, A, B, lanes, per_lane = 2111012662, 6, 24, 4, 300
+    N = lanes * 1024
+    cfg = make_cfg(A, max_batch=32, max_envs=8, precision=precision, seed=seed)
+    theta = synth.init_params(seed, A)
+    sample_steps = [0, 1, 2, 3, 5, 6, 7]      # after 3 comes 5: the minibatch of 4 was gathered ahead and is dropped
+    flush_before = {2, 6}                     # new experiences become visible before these positions
+    results = []
+    for fused in (False, True):
+        st = torch.cuda.Stream()
+        ctx = P.dqn_create(cfg, st, st)
+        rb = P.replay_create(N, lanes, 320, seed, st, st)
+        try:
+            P.dqn_set_params(ctx, P.DQN_PARAMS_ONLINE, theta)
+            P.dqn_set_params(ctx, P.DQN_PARAMS_TARGET, theta)
+            device_fill(rb, seed, lanes, per_lane, A, st, 0.3, 0.02, chunk=per_lane)
+            s = torch.empty((B, 4, 84, 84), dtype=torch.uint8, device="cuda")
+            s2 = torch.empty_like(s)
+            a = torch.empty(B, dtype=torch.int32, device="cuda")
+            r = torch.empty(B, dtype=torch.float32, device="cuda")
+            d = torch.empty(B, dtype=torch.float32, device="cuda")
+            loss = torch.zeros(1, dtype=torch.float32, device="cuda")
+            extra = torch.empty((40, 84, 84), dtype=torch.uint8, device="cuda")
+            ea = torch.empty(40, dtype=torch.int32, device="cuda")
+            er = torch.empty(40, dtype=torch.float32, device="cuda")
+            et = torch.empty(40, dtype=torch.uint8, device="cuda")
+            tn, tp, tt = synth.thresholds(0.3, 0.3, 0.02)
+            log = []
+            for pos, step in enumerate(sample_steps):
+                if pos in flush_before:
+                    for lane in range(lanes):
+                        P.synth_frames(extra, 40, (1 << 20) + pos * 1000 + lane, lanes, seed, synth.STREAM_REPLAY, synth.PIX_T,
+                                       synth.BACKGROUND, st)
+                        P.synth_transitions(ea, er, et, 40, (1 << 20) + pos * 1000 + lane, lanes, seed, A, tn, tp, tt, st)
+                        P.replay_push(rb, lane, extra, ea, er, et, 40)
+                    P.dqn_sync_target(ctx, rb, 1)
+                if fused:
+                    P.dqn_train_step_sampled(ctx, rb, B, step, True, loss)
+                else:
+                    P.replay_sample_gather(rb, B, step, None, s, s2, a, r, d, None)
+                    P.dqn_train_step(ctx, s, a, r, s2, d, B, loss)
+                torch.cuda.synchronize()
+                log.append((float(loss.item()), P.dqn_get_params(ctx, P.DQN_PARAMS_ONLINE).copy()))
+            results.append(log)
+        finally:
+            P.replay_destroy(rb)
+            P.dqn_destroy(ctx)
+    for pos, ((l0, t0), (l1, t1)) in enumerate(zip(*results)):
+        assert l0 == l1, ("loss", pos, l0, l1)
+        assert np.array_equal(t0, t1), ("theta", pos)
+    assert not np.array_equal(results[0][0][1], results[0][-1][1])   # the steps did change the parameters
