@@ -93,19 +93,21 @@ template <int KQ> __device__ inline float4 tower_finish(const float4* x, const f
 constexpr int kTowerP2_ = 72;
 
 struct TowerArgs {
-    const uint8_t* x[kMaxGroups];      // [n][4][84][84], 16-byte aligned
-    const _Float16* w1[kMaxGroups];    // fragment order, fp16
-    const bf16_t* w2[kMaxGroups];      // fragment order, bf16
-    const bf16_t* w3[kMaxGroups];
-    const float* b1[kMaxGroups];
-    const float* b2[kMaxGroups];
-    const float* b3[kMaxGroups];
-    bf16_t* act1[kMaxGroups];   // [n][400][32] or null
-    bf16_t* act2[kMaxGroups];   // [n][81][64] or null
-    bf16_t* act3[kMaxGroups];   // [n][49][64]
+    // what a workgroup needs first sits in the first 64 bytes: kernel arguments are fetched by cache line, and every
+    // further line touched on the way to the first load of the state is a dependent miss of its own
     int n, groups;
     int per;                    // items per workgroup = ceil(n * groups / grid size), computed by the host
     int tower_blocks;           // workgroups [0, tower_blocks) run the tower, the next push.L ones the append below
+    const uint8_t* x[kMaxGroups];      // [n][4][84][84], 16-byte aligned
+    const _Float16* w1[kMaxGroups];    // fragment order, fp16
+    const float* b1[kMaxGroups];
+    const float* b2[kMaxGroups];
+    const float* b3[kMaxGroups];
+    const bf16_t* w2[kMaxGroups];      // fragment order, bf16
+    const bf16_t* w3[kMaxGroups];
+    bf16_t* act1[kMaxGroups];   // [n][400][32] or null
+    bf16_t* act2[kMaxGroups];   // [n][81][64] or null
+    bf16_t* act3[kMaxGroups];   // [n][49][64]
     PushStepPlan push;          // optional (L = 0: none): one experience per lane into the temporary buffers
 };
 
