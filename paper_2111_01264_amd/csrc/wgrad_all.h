@@ -32,17 +32,20 @@ __global__ __launch_bounds__(256) void wgrad_all_kernel(WgradAllArgs a)
     // resident at once, and the workgroups that start late should be the short ones (conv1's)
     const int blk = blockIdx.x;
     const EpiGrad none{nullptr, 0, 1.f};
-    if (blk < a.first[1]) {
+    // the four boundaries in one scalar load (read one by one, each is a load-wait-branch step of its own)
+    const int f1 = a.first[1], f2 = a.first[2], f3 = a.first[3], f4 = a.first[4];
+    asm volatile("" :: "s"(f1), "s"(f2), "s"(f3), "s"(f4));
+    if (blk < f1) {
         small_grads_block<bf16_t>(a.small, blk - a.first[0], wg_smem);
-    } else if (blk < a.first[2]) {
+    } else if (blk < f2) {
         const int i = blk - a.first[1];
         gemm_tn_tr_block<DenseM<bf16_t>, WgradB<bf16_t, 64, 9, 9, 7, 7, 3, 1>, EpiGrad, 64, kWg3BN, 4>(
             a.a3, a.b3, none, 64, 576, a.K3, a.kps3, a.p3, true, i % 3, i / 3, 0, wg_smem);
-    } else if (blk < a.first[3]) {
+    } else if (blk < f3) {
         const int i = blk - a.first[2];
         gemm_tn_tr_block<DenseM<bf16_t>, WgradB<bf16_t, 32, 20, 20, 9, 9, 4, 2>, EpiGrad, 64, kWg2BN, 4>(
             a.a2, a.b2, none, 64, 512, a.K2, a.kps2, a.p2, true, i % 2, i / 2, 0, wg_smem);
-    } else if (blk < a.first[4]) {
+    } else if (blk < f4) {
         const int i = blk - a.first[3];
         gemm_tn_tr_block<DenseM<bf16_t>, DenseM<bf16_t>, EpiGrad, 64, kWgfBN, 2>(
             a.af, a.bf, a.epf, 512, 3136, a.Kf, (a.Kf + 31) / 32 * 32, nullptr, false, i % 25, 0, i / 25, wg_smem);
