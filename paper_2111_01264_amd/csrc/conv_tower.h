@@ -197,8 +197,9 @@ __global__ __launch_bounds__(kTowerThreads) void conv_tower_kernel(TowerArgs a)
             uint4* d = reinterpret_cast<uint4*>(sX);
             d[tid] = xv0; d[tid + 512] = xv1; d[tid + 1024] = xv2; d[last_vec] = xv3;   // clamped lanes rewrite the last vector with itself
         }
-        // conv2/conv3 fragments of a new group: requested one per k-step inside conv1's MFMA stream (17 KB per wavefront --
-        // requested in one go they hold every wavefront ~0.5 us in front of the barrier below, just being issued)
+        // conv2/conv3 fragments of a new group: requested a few k-steps apart inside conv1's (conv2's weights) and conv2's
+        // (conv3's weights) MFMA streams (17 KB per wavefront -- requested in one go they hold every wavefront ~0.5 us in
+        // front of the barrier below, just being issued)
         const T* p2 = a.w2[g] + (static_cast<size_t>(nt * 32 + kq * 8) * 64 + lane) * 8;
         const T* p3 = a.w3[g] + (static_cast<size_t>(nt * 36 + kq * 9) * 64 + lane) * 8;
         if (it + 1 < last) {   // the next item's state: in flight while this item computes
@@ -249,13 +250,9 @@ __global__ __launch_bounds__(kTowerThreads) void conv_tower_kernel(TowerArgs a)
 #pragma unroll
                     for (int t = 0; t < NT; ++t)
                         acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(w, bytes_as_f16_subnormals(cur[t].x, cur[t].y), acc[t], 0, 0, 0);
-                    if (new_group) {
-                        if (k < 8) wf2[k] = *reinterpret_cast<const V8*>(p2 + k * 512);
-                        else wf3[k - 8] = *reinterpret_cast<const V8*>(p3 + (k - 8) * 512);
-                    }
+                    if (new_group && (k & 1)) wf2[k >> 1] = *reinterpret_cast<const V8*>(p2 + (k >> 1) * 512);   // conv2's: every other k-step
                     __builtin_amdgcn_sched_barrier(0);
                 }
-                if (new_group) wf3[8] = *reinterpret_cast<const V8*>(p3 + 8 * 512);
                 // output stage: scale, bias, ReLU -> LDS (+ global); rows 8q + 4kg .. + 3 are channels of this lane's pixel
 #pragma unroll
                 for (int t = 0; t < NT; ++t) {
@@ -304,6 +301,7 @@ __global__ __launch_bounds__(kTowerThreads) void conv_tower_kernel(TowerArgs a)
                     const V8 cur = ring[step % D];
                     if (step + D < 24) ring[step % D] = fetch(step + D);
                     mma_32x32x16(acc[step / 8], wf2[step % 8], cur);
+                    if (new_group && step >= 4 && step < 22 && (step & 1) == 0) wf3[(step - 4) >> 1] = *reinterpret_cast<const V8*>(p3 + ((step - 4) >> 1) * 512);   // conv3's
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
