@@ -182,47 +182,60 @@ __global__ __launch_bounds__(256) void head_fwd_kernel(HeadArgs a)
                 b2v[g][e] = a.b2[g][act_i < a.A ? act_i : a.A - 1];
             }
         }
-    float w2row[4] = {0.f, 0.f, 0.f, 0.f};
-    if constexpr (MODE == kHeadTrain) load4<T>(static_cast<const T*>(a.w2[0]) + static_cast<size_t>(act_taken) * 512 + hf0, w2row);
+    float4 w2row = make_float4(0.f, 0.f, 0.f, 0.f);   // train step: the taken action's row of W2 at this thread's features
     __builtin_amdgcn_sched_barrier(0);
 
-    // (1) finish fc1: thread -> (row r = tid / 128, features 4 * (tid % 128) .. + 3)
+    // (1) finish fc1: thread -> (row r = tid / 128, features 4 * (tid % 128) .. + 3).  The slices of ALL groups are
+    // requested before any is added (group by group, each group's sum waited for its own round trip), from a clamped
+    // row (no load is ever skipped); what depends on an earlier load (the taken action's row of W2) or on nothing
+    // (the exploration draw) follows the requests and is covered by their latency.
     {
         const int r = hr, f0 = hf0;
         const int row = row0 + r;
         const size_t sstride = static_cast<size_t>(a.rows) * 512, gstride = sstride * a.slices;
+        const float* p0 = a.partial + static_cast<size_t>(hrow) * 512 + f0;
+        float4 acc[G];
+#pragma unroll
+        for (int g = 0; g < G; ++g) acc[g] = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int s0 = 0; s0 < a.slices; s0 += 7) {
+            float4 v[G][7];
+#pragma unroll
+            for (int g = 0; g < G; ++g)
+                if (g < a.groups) {
+#pragma unroll
+                    for (int u = 0; u < 7; ++u) {
+                        const int sl = s0 + u < a.slices ? s0 + u : a.slices - 1;
+                        v[g][u] = *reinterpret_cast<const float4*>(p0 + g * gstride + sl * sstride);
+                    }
+                }
+            __builtin_amdgcn_sched_barrier(0);
+            if (s0 == 0) {
+                if constexpr (MODE == kHeadTrain) {
+                    float w[4];
+                    load4<T>(static_cast<const T*>(a.w2[0]) + static_cast<size_t>(act_taken) * 512 + hf0, w);
+                    w2row = make_float4(w[0], w[1], w[2], w[3]);
+                } else draw = philox_draw(a.seed, kTagAct, a.act_step, static_cast<uint32_t>(row0 + trow_));
+            }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int g = 0; g < G; ++g)
+                if (g < a.groups) {
+#pragma unroll
+                    for (int u = 0; u < 7; ++u)
+                        if (s0 + u < a.slices) { acc[g].x += v[g][u].x; acc[g].y += v[g][u].y; acc[g].z += v[g][u].z; acc[g].w += v[g][u].w; }
+                }
+        }
 #pragma unroll
         for (int g = 0; g < G; ++g)
             if (g < a.groups) {
-                float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (row < a.rows) {
-                    const float* p = a.partial + g * gstride + static_cast<size_t>(row) * 512 + f0;
-                    for (int s0 = 0; s0 < a.slices; s0 += 7) {
-                        float4 v[7];
-#pragma unroll
-                        for (int u = 0; u < 7; ++u) {
-                            const int s = s0 + u < a.slices ? s0 + u : a.slices - 1;
-                            v[u] = *reinterpret_cast<const float4*>(p + s * sstride);
-                        }
-                        if constexpr (MODE == kHeadAct) {
-                            // depends on nothing that is loaded: computed under the latency of the requests above, not in the tail
-                            __builtin_amdgcn_sched_barrier(0);
-                            if (s0 == 0) draw = philox_draw(a.seed, kTagAct, a.act_step, static_cast<uint32_t>(row0 + trow_));
-                            __builtin_amdgcn_sched_barrier(0);
-                        }
-#pragma unroll
-                        for (int u = 0; u < 7; ++u)
-                            if (s0 + u < a.slices) { acc.x += v[u].x; acc.y += v[u].y; acc.z += v[u].z; acc.w += v[u].w; }
-                    }
-                    const float4 bv = b1v[g];
-                    acc.x = fmaxf(acc.x + bv.x, 0.f); acc.y = fmaxf(acc.y + bv.y, 0.f);
-                    acc.z = fmaxf(acc.z + bv.z, 0.f); acc.w = fmaxf(acc.w + bv.w, 0.f);
-                }
-                store4<T>(&s_h[g][r][f0], acc.x, acc.y, acc.z, acc.w);
+                const float4 bv = b1v[g];
+                const float4 hv = make_float4(fmaxf(acc[g].x + bv.x, 0.f), fmaxf(acc[g].y + bv.y, 0.f), fmaxf(acc[g].z + bv.z, 0.f),
+                                              fmaxf(acc[g].w + bv.w, 0.f));
+                store4<T>(&s_h[g][r][f0], hv.x, hv.y, hv.z, hv.w);   // a row past the batch repeats the last one; nobody reads its Q
                 if (MODE == kHeadTrain && g == 0) {
-                    h0[0] = acc.x; h0[1] = acc.y; h0[2] = acc.z; h0[3] = acc.w;
+                    h0[0] = hv.x; h0[1] = hv.y; h0[2] = hv.z; h0[3] = hv.w;
                     if (row < a.rows)
-                        store4<T>(static_cast<T*>(a.h_online) + static_cast<size_t>(row) * 512 + f0, acc.x, acc.y, acc.z, acc.w);
+                        store4<T>(static_cast<T*>(a.h_online) + static_cast<size_t>(row) * 512 + f0, hv.x, hv.y, hv.z, hv.w);
                 }
             }
     }
@@ -319,7 +332,7 @@ __global__ __launch_bounds__(256) void head_fwd_kernel(HeadArgs a)
         const int r = tid >> 7, f0 = (tid & 127) * 4;
         const int row = row0 + r;
         if (row < a.rows) {
-            const float* w = w2row;
+            const float w[4] = {w2row.x, w2row.y, w2row.z, w2row.w};
             const float dq = s_dq[r];
             store4<T>(static_cast<T*>(a.dzh) + static_cast<size_t>(row) * 512 + f0, h0[0] > 0.f ? dq * w[0] : 0.f,
                       h0[1] > 0.f ? dq * w[1] : 0.f, h0[2] > 0.f ? dq * w[2] : 0.f, h0[3] > 0.f ? dq * w[3] : 0.f);
