@@ -125,8 +125,7 @@ __global__ __launch_bounds__(256) void head_fwd_kernel(HeadArgs a)
     constexpr int G = MODE == kHeadAct ? 1 : 3;
     constexpr int LDH = 512 + 8;
     __shared__ __attribute__((aligned(32))) T s_h[G][kHeadRows][LDH];
-    __shared__ float s_red[4][16][64];
-    __shared__ float s_q[G][kHeadRows][kMaxActions + 1];
+    __shared__ float s_red[G][4][16][64];   // fc2 partial accumulators: [group][k-quarter wavefront][slot][lane]
     __shared__ float s_dq[kHeadRows];
     if constexpr (MODE == kHeadTrain) {
         if (static_cast<int>(blockIdx.x) >= a.head_blocks) {
@@ -157,8 +156,9 @@ __global__ __launch_bounds__(256) void head_fwd_kernel(HeadArgs a)
         done_tail = a.done[trow_c];
     }
     Philox4 draw{};   // act step: the exploration draw of this lane's row
-    float b2_tail = 0.f;   // act step: fc2 bias of this lane's action (the tail reads the Q value straight from the partials)
-    if constexpr (MODE == kHeadAct) b2_tail = a.b2[0][(lane & 31) < a.A ? (lane & 31) : a.A - 1];
+    float b2_tail[G];   // fc2 bias of this lane's action in the tail (which reads its Q values straight from the partials)
+#pragma unroll
+    for (int g = 0; g < G; ++g) b2_tail[g] = a.b2[g < a.groups ? g : 0][(lane & 31) < a.A ? (lane & 31) : a.A - 1];   // never skipped
     __builtin_amdgcn_sched_barrier(0);
     // fc2 weight fragments of every group: consumed last
     V8 wf[G][8];
@@ -171,17 +171,9 @@ __global__ __launch_bounds__(256) void head_fwd_kernel(HeadArgs a)
         }
 
     float4 b1v[G];
-    float b2v[G][4];
 #pragma unroll
     for (int g = 0; g < G; ++g)
-        if (g < a.groups) {
-            b1v[g] = *reinterpret_cast<const float4*>(a.b1[g] + hf0);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const int act_i = 8 * wave + 4 * kg + e;
-                b2v[g][e] = a.b2[g][act_i < a.A ? act_i : a.A - 1];
-            }
-        }
+        if (g < a.groups) b1v[g] = *reinterpret_cast<const float4*>(a.b1[g] + hf0);
     float4 w2row = make_float4(0.f, 0.f, 0.f, 0.f);   // train step: the taken action's row of W2 at this thread's features
     __builtin_amdgcn_sched_barrier(0);
 
@@ -240,7 +232,7 @@ __global__ __launch_bounds__(256) void head_fwd_kernel(HeadArgs a)
             }
     }
     __syncthreads();
-    // (2) fc2 per group; (3) Q rows to LDS
+    // (2) fc2 per group: every wavefront's k-quarter of the accumulator goes to LDS, one barrier for all groups
 #pragma unroll
     for (int g = 0; g < G; ++g)
         if (g < a.groups) {
@@ -253,24 +245,10 @@ __global__ __launch_bounds__(256) void head_fwd_kernel(HeadArgs a)
                 if (lr < kHeadRows) hf = *reinterpret_cast<const V8*>(&s_h[g][lr][wave * 128 + s * 16 + kg * 8]);
                 mma_32x32x16(acc, wf[g][s], hf);
             }
-            if (g > 0) __syncthreads();   // s_red is free again
 #pragma unroll
-            for (int v = 0; v < 16; ++v) s_red[wave][v][lane] = acc[v];
-            __syncthreads();
-            // accumulator layout: sample lane % 32, action 8*(v/4) + 4*(lane/32) + (v%4); wavefront w sums quad w
-            if (MODE == kHeadTrain && lr < kHeadRows) {
-                const int q = wave;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const int act_i = 8 * q + 4 * kg + e;
-                    const int v = 4 * q + e;
-                    if (act_i < a.A)
-                        s_q[g][lr][act_i] =
-                            (((s_red[0][v][lane] + s_red[1][v][lane]) + s_red[2][v][lane]) + s_red[3][v][lane]) + b2v[g][e];
-                }
-            }
+            for (int v = 0; v < 16; ++v) s_red[g][wave][v][lane] = acc[v];
         }
-    if constexpr (MODE == kHeadTrain) __syncthreads();
+    __syncthreads();
 
     // Tail: wavefront 0, 32 lanes per row (kHeadRows = 2), lane k owns action k.  argmax with the lowest index
     // among equal values (the tie rule of the greedy policy, Section 2.1), as a butterfly over the 32 lanes.
@@ -287,13 +265,17 @@ __global__ __launch_bounds__(256) void head_fwd_kernel(HeadArgs a)
     };
     const int trow = lane >> 5, tk = lane & 31;    // tail row / action of this lane (wavefront 0 only)
     const float kNegInf = -__builtin_huge_valf();
+    // Q_g(row trow, action tk): accumulator layout is sample lane % 32, action 8*(v/4) + 4*(lane/32) + (v%4); the four
+    // k-quarter partials of that slot are added in wavefront order, then the bias
+    const int tkc = tk < a.A ? tk : a.A - 1;
+    const int qslot = 4 * (tkc >> 3) + (tkc & 3), qsrc = ((tkc >> 2) & 1) * 32 + trow;
+    auto q_of = [&](int g) {
+        return (((s_red[g][0][qslot][qsrc] + s_red[g][1][qslot][qsrc]) + s_red[g][2][qslot][qsrc]) + s_red[g][3][qslot][qsrc]) + b2_tail[g];
+    };
     if constexpr (MODE == kHeadAct) {
         if (wave != 0) return;
         const int row = row0 + trow;
-        // Q(row, action tk): the four k-quarter partials of accumulator slot (sample trow, action tk), in wavefront order
-        const int tkc = tk < a.A ? tk : a.A - 1;
-        const int v = 4 * (tkc >> 3) + (tkc & 3), src = ((tkc >> 2) & 1) * 32 + trow;
-        const float qv = tk < a.A ? (((s_red[0][v][src] + s_red[1][v][src]) + s_red[2][v][src]) + s_red[3][v][src]) + b2_tail : kNegInf;
+        const float qv = tk < a.A ? q_of(0) : kNegInf;
         int act = argmax_lowest(qv, tk);
         if (row >= a.rows) return;
         if (a.q_out && tk < a.A) a.q_out[static_cast<size_t>(row) * a.A + tk] = qv;
@@ -307,18 +289,25 @@ __global__ __launch_bounds__(256) void head_fwd_kernel(HeadArgs a)
         if (wave == 0) {
             const int row = row0 + trow;
             const bool live = row < a.rows;
-            const float qt = tk < a.A ? s_q[1][trow][tk] : kNegInf;
-            const float qsel = a.double_dqn ? (tk < a.A ? s_q[2][trow][tk] : kNegInf) : qt;
+            const float q0 = q_of(0), q1 = q_of(1);
+            const float q2 = a.groups > 2 ? q_of(G - 1) : 0.f;   // Double DQN: Q(s', .; theta) selects the action
+            const float qt = tk < a.A ? q1 : kNegInf;
+            const float qsel = a.double_dqn ? (tk < a.A ? q2 : kNegInf) : qt;
             const int astar = argmax_lowest(qsel, tk);
-            if (live && tk < a.A)
-                for (int g = 0; g < a.groups; ++g) a.q_all[(static_cast<size_t>(g) * a.rows + row) * a.A + tk] = s_q[g][trow][tk];
+            if (live && tk < a.A) {
+                a.q_all[(static_cast<size_t>(0) * a.rows + row) * a.A + tk] = q0;
+                a.q_all[(static_cast<size_t>(1) * a.rows + row) * a.A + tk] = q1;
+                if (a.groups > 2) a.q_all[(static_cast<size_t>(2) * a.rows + row) * a.A + tk] = q2;
+            }
+            // the two values the TD error needs sit in other lanes of this row: Q(s', a*; theta^-) and Q(s, a_b; theta)
+            const float q1_star = __shfl(q1, astar, 32), q0_taken = __shfl(q0, act_tail, 32);
             if (tk == 0) {
                 float dq = 0.f;
                 int act_b = 0;
                 if (live) {
-                    const float y = rew_tail + a.gamma * (1.f - done_tail) * s_q[1][trow][astar];
+                    const float y = rew_tail + a.gamma * (1.f - done_tail) * q1_star;
                     act_b = act_tail;
-                    const float delta = s_q[0][trow][act_b] - y;
+                    const float delta = q0_taken - y;
                     const float ad = fabsf(delta);
                     a.lossv[row] = ad <= a.huber ? 0.5f * delta * delta : a.huber * (ad - 0.5f * a.huber);
                     dq = fminf(fmaxf(delta, -a.huber), a.huber) / static_cast<float>(a.rows);
