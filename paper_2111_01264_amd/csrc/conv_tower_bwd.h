@@ -87,6 +87,12 @@ __global__ __launch_bounds__(kTowerThreads) void conv_tower_bwd_kernel(TowerBwdA
     const int first = blockIdx.x * a.per, last = min(a.n, first + a.per);
     if (first >= last) return;
 
+    // a sample's dz3: 49 pixels x 128 bytes = 392 vectors, one per thread, fetched one sample ahead.  The first sample's is
+    // requested before the weights: loads return in order, and behind 139 KB of fragments the staging below waited ~1 us
+    uint4 xv = make_uint4(0, 0, 0, 0);
+    if (tid < 392) xv = reinterpret_cast<const uint4*>(a.dz3 + static_cast<size_t>(first) * 3136)[tid];
+    __builtin_amdgcn_sched_barrier(0);
+
     // zero both images once: the borders are never written again
     for (int v = tid; v < 2 * kTbImg / 8; v += kTowerThreads) reinterpret_cast<uint4*>(sP3)[v] = make_uint4(0, 0, 0, 0);
 
@@ -108,11 +114,8 @@ __global__ __launch_bounds__(kTowerThreads) void conv_tower_bwd_kernel(TowerBwdA
         off3[k] = -((p * 11 + q) * kTbPitch) + (ks & 3) * 16;
     }
 
-    // a sample's dz3: 49 pixels x 128 bytes = 392 vectors, one per thread, fetched one sample ahead
-    uint4 xv = make_uint4(0, 0, 0, 0);
     const int my_px = tid >> 3, my_part = tid & 7;
     const int my_dst = (((my_px / 7) + 2) * 11 + (my_px % 7) + 2) * kTbPitch + my_part * 8;
-    if (tid < 392) xv = reinterpret_cast<const uint4*>(a.dz3 + static_cast<size_t>(first) * 3136)[tid];
     __syncthreads();   // the zero fill is complete
 
     for (int b = first; b < last; ++b) {
