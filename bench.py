@@ -68,9 +68,9 @@ _C = "paper_2111_01264_amd/csrc/"
 _RMS_SRC = (_C + "head_kernels.h",)
 _WG_SRC = (_C + "wgrad_all.h", _C + "gemm_tn_tr.h", _C + "layers.h", _C + "head_kernels.h", _C + "gemm_mfma.h")
 TRAFFIC = {
-    ("rmsprop", 32, "bf16"): (64.46e6, _RMS_SRC, "ef5e023bdfbe39bc5bd784181855ca48e83993b6"),
-    ("rmsprop", 256, "bf16"): (67.98e6, _RMS_SRC, "ef5e023bdfbe39bc5bd784181855ca48e83993b6"),
-    ("wgrad_all", 256, "bf16"): (94.05e6, _WG_SRC, "05dee8593cb12e8e1b0f50de39b30e1b60d43d2f"),
+    ("rmsprop", 32, "bf16"): (64.46e6, _RMS_SRC, "a5bd12e1bf91c84713a1613f1bd07926f3e2d214"),
+    ("rmsprop", 256, "bf16"): (67.98e6, _RMS_SRC, "a5bd12e1bf91c84713a1613f1bd07926f3e2d214"),
+    ("wgrad_all", 256, "bf16"): (94.05e6, _WG_SRC, "94f5fa2dd064004f544fcf5187f116f546cdf851"),
 }
 
 
