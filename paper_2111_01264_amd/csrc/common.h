@@ -165,12 +165,14 @@ __device__ inline void gather_block(const GatherPlan& p, int f, int b)
     }
     const int64_t slot = lane0 + (base + j - 3 + f) % M;
     const uint4* src = reinterpret_cast<const uint4*>(frames + slot * kFrameBytes);
-    const uint4 z = make_uint4(0, 0, 0, 0);
+    // a frame behind a terminal flag is zeroed with a mask (a choice between the loaded vector and a zero vector made the
+    // compiler keep the zero vector in scratch memory and load through a pointer)
+    const uint32_t keep_s = any_s ? 0u : 0xFFFFFFFFu, keep_s2 = any_s2 ? 0u : 0xFFFFFFFFu;
     // each destination with its own phase shift; the second read of the frame comes from cache
     for (int v = threadIdx.x; v < kFrameVec16 + 3; v += blockDim.x) {
         const int v1 = v - ph, v2 = v - ph2;
-        if (ds && v1 >= 0 && v1 < kFrameVec16) ds[v1] = any_s ? z : src[v1];
-        if (ds2 && v2 >= 0 && v2 < kFrameVec16) ds2[v2] = any_s2 ? z : src[v2];
+        if (ds && v1 >= 0 && v1 < kFrameVec16) { uint4 w = src[v1]; w.x &= keep_s; w.y &= keep_s; w.z &= keep_s; w.w &= keep_s; ds[v1] = w; }
+        if (ds2 && v2 >= 0 && v2 < kFrameVec16) { uint4 w = src[v2]; w.x &= keep_s2; w.y &= keep_s2; w.z &= keep_s2; w.w &= keep_s2; ds2[v2] = w; }
     }
     if (f == 0 && threadIdx.x == 0) {
         const int64_t tslot = lane0 + (base + j) % M;
