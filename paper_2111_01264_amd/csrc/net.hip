@@ -437,7 +437,7 @@ static int train_impl(dqn_ctx* c, const uint8_t* s, const int32_t* a, const floa
         wa.a1.p[0] = dz1; wa.a1.ld = 32; wa.b1.x = s; wa.K1 = B * 400; wa.p1 = c->wg_partial + kWgOff1;
         wa.a2.p[0] = dz2; wa.a2.ld = 64; wa.b2.x = act1; wa.K2 = B * 81; wa.p2 = c->wg_partial + kWgOff2;
         wa.a3.p[0] = dz3; wa.a3.ld = 64; wa.b3.x = act2; wa.K3 = B * 49; wa.p3 = c->wg_partial + kWgOff3;
-        tn_tr_splits(wa.K1, wgrad_splits(wa.K1, 2, 128), 32 * 256, kWgMaxSplits1 * 32 * 256, &wa.kps1, &wa.splits1);
+        tn_tr_splits(wa.K1, wgrad_splits(wa.K1, 2, wa.K1 <= 16384 ? 64 : static_cast<int>(kWgMaxSplits1))   /* small batch: the optimiser's reads of the slices weigh more than shorter workgroups here */, 32 * 256, kWgMaxSplits1 * 32 * 256, &wa.kps1, &wa.splits1);
         tn_tr_splits(wa.K2, wgrad_splits(wa.K2, 2, static_cast<int>(kWgMaxSplits)), 64 * 512, kWgMaxSplits * 64 * 512, &wa.kps2, &wa.splits2);
         tn_tr_splits(wa.K3, wgrad_splits(wa.K3, 3, static_cast<int>(kWgMaxSplits)), 64 * 576, kWgMaxSplits * 64 * 576, &wa.kps3, &wa.splits3);
         wg_splits[0] = wa.splits1; wg_splits[1] = wa.splits2; wg_splits[2] = wa.splits3;
