@@ -21,6 +21,14 @@ Transition `i` metadata:  w = word(seed, STREAM_META, i, 0);
     terminal bits tb = (w >> 24) & 0xFFFFFF  -> 1 if tb < T_term
     action bits  ab = (w >> 48) & 0xFFFF     -> (ab * A) >> 16
     with T_x = floor(p_x * 2**24).
+
+Synthetic environment (stands in for the Atari emulator, which is not available; Algorithm 1's "environment
+instance ... for each sampler thread").  Environment j of W emits the observation sequence o_0, o_1, ..:
+    o_n = frame(seed, STREAM_ENV, i) with i = n * W + j.
+At its n-th step it receives an action a and answers with (r, d) from w = word(seed, STREAM_ENV_META, i, 0):
+    good = (((w >> 48) & 0xFFFF) * A) >> 16;  r = reward bits of w as above if a == good, else 0;
+    d = terminal bits of w as above (independent of a).
+After d = 1 the next observation o_{n+1} opens a new episode.
 """
 from __future__ import annotations
 
@@ -42,6 +50,8 @@ PIX_T = math.ceil(0.05 * (1 << 24))  # 838861
 STREAM_REPLAY = 0   # replay-ring frames
 STREAM_META = 1     # reward / terminal / action of a stored transition
 STREAM_ACT = 2      # states handed to the act step
+STREAM_ENV = 3      # observations of the synthetic environments
+STREAM_ENV_META = 4 # their rewards / terminals / rewarded actions
 
 
 def _mix64(z: np.ndarray) -> np.ndarray:
@@ -113,6 +123,27 @@ def transitions(seed: int, ids, num_actions: int, p_neg=0.05, p_pos=0.05, p_term
     terminals = (tb < t_term).astype(np.uint8)
     actions = ((ab * num_actions) >> 16).astype(np.int32)
     return actions, rewards, terminals
+
+
+def env_frames(seed: int, num_envs: int, n: int) -> np.ndarray:
+    """[W, 84, 84] uint8: observation o_n of every synthetic environment."""
+    ids = np.uint64(n) * np.uint64(num_envs) + np.arange(num_envs, dtype=np.uint64)
+    return frames(seed, STREAM_ENV, ids)
+
+
+def env_outcomes(seed: int, num_envs: int, n: int, actions, num_actions: int, p_neg=0.05, p_pos=0.05, p_term=0.001):
+    """(rewards float32 [W], terminals uint8 [W]) of every synthetic environment's n-th step under `actions`."""
+    ids = np.uint64(n) * np.uint64(num_envs) + np.arange(num_envs, dtype=np.uint64)
+    t_neg, t_pos, t_term = thresholds(p_neg, p_pos, p_term)
+    w = words(seed, STREAM_ENV_META, ids, np.zeros(1, dtype=np.uint64))
+    rb = (w & np.uint64(0xFFFFFF)).astype(np.int64)
+    tb = ((w >> np.uint64(24)) & np.uint64(0xFFFFFF)).astype(np.int64)
+    good = ((((w >> np.uint64(48)) & np.uint64(0xFFFF)).astype(np.int64)) * num_actions) >> 16
+    r = np.zeros(num_envs, dtype=np.float32)
+    r[rb < t_neg] = -1.0
+    r[rb >= (1 << 24) - t_pos] = 1.0
+    r[np.asarray(actions, dtype=np.int64) != good] = 0.0
+    return r, (tb < t_term).astype(np.uint8)
 
 
 def act_states(seed: int, step: int, num_envs: int) -> np.ndarray:
