@@ -222,6 +222,74 @@ int synth_transitions(int32_t* actions, float* rewards, uint8_t* terminals, int6
                       uint64_t id0, uint64_t id_step, uint64_t seed, int32_t num_actions,
                       uint32_t t_neg, uint32_t t_pos, uint32_t t_term, void* stream);
 
+/* ---- Algorithm 1: the main loop around the calls above (Sections 3 and 4) ------------------- */
+
+/* The paper's host program: W sampler threads, one trainer thread and the main thread that
+ * synchronises them.  The samplers step W synthetic environments that live on the host like an emulator
+ * would (seeded stand-ins for it, defined below); everything else is the calls above.
+ *   every C timesteps   wait for trainer and samplers; append what is pending; flush the temporary
+ *                       buffers into D; theta^- <- theta (dqn_sync_target); hand the trainer thread
+ *                       C / F minibatches (dqn_train_step_sampled, sample_step = train steps so far);
+ *   every W timesteps   one dqn_act_push_step for all W states from theta^- at the given epsilon
+ *                       (act_step = act steps so far; the previous step's experiences ride along),
+ *                       one download of the W actions, each sampler thread steps its environment, one
+ *                       upload of the W new observations, rewards and terminal flags.
+ * Timesteps count single environment steps, so one act step advances t by W (Section 4); the
+ * synchronisation happens when t mod C == 0 with t counted from 0.
+ *
+ * Synthetic environment j (j < W), with word() the generator of synth_frames below and stream tags 3
+ * (observations) and 4 (outcomes): its n-th observation o_n is frame id n*W + j of stream 3 (pixel
+ * threshold 838861, background 40).  Its n-th step under action a returns, from w = word(id n*W + j, 0)
+ * of stream 4: reward = (-1 if (w & 0xFFFFFF) < t_reward_neg, +1 if (w & 0xFFFFFF) >= 2^24 -
+ * t_reward_pos, else 0) if a == (((w >> 48) & 0xFFFF) * A) >> 16, else 0; terminal = ((w >> 24) &
+ * 0xFFFFFF) < t_term.  The state handed to the network is the stack (o_{n-3}, .., o_n) with the
+ * observations from before the latest terminal step replaced by zeros (and zeros before o_0): the states
+ * acted from are the states replay_sample_gather later rebuilds.  Environment j writes lane j of D with
+ * the experience (o_n, a_n, r_n, terminal_n). */
+typedef struct {
+    int32_t W;             /* sampler threads = environments = replay lanes (Section 4)            */
+    int32_t C;             /* target update period in timesteps; multiple of W and of F (Table 5)  */
+    int32_t F;             /* timesteps per train step (Table 5: 4)                                */
+    int32_t B;             /* minibatch size (Table 5: 32)                                         */
+    float epsilon;         /* exploration rate of dqn_alg1_run                                     */
+    uint32_t t_reward_neg, t_reward_pos, t_term;   /* thresholds on 24-bit draws, see above        */
+    uint64_t env_seed;     /* seed of the synthetic environments                                   */
+} dqn_alg1_config;
+
+typedef struct dqn_alg1 dqn_alg1;
+
+/* ctx and rb stay owned by the caller and must outlive the handle; rb needs W lanes, its push stream
+ * must be ctx's act stream and its sample stream ctx's train stream, and staging_per_lane >= C / W
+ * (and >= the prepopulation's timesteps / W).  Allocates pinned host arrays and device buffers for W
+ * observations, stacks, actions, rewards and flags, and starts the W + 1 threads (idle until a call
+ * below).  While a call below runs, no other thread may use ctx or rb.  Errors: DQN_EINVAL, DQN_ENOMEM,
+ * DQN_EHIP. */
+int dqn_alg1_create(dqn_ctx* ctx, replay* rb, const dqn_alg1_config* host_cfg, dqn_alg1** host_out);
+/* Waits for the threads, frees the buffers; does not touch ctx or rb. */
+int dqn_alg1_destroy(dqn_alg1* h);
+
+/* Fills D with experiences collected at random: timesteps / W act steps at epsilon = 1 without training,
+ * then a blocking flush.  These steps advance the environments and the act-step counter but not t.
+ * timesteps must be a multiple of W. */
+int dqn_alg1_prepopulate(dqn_alg1* h, int64_t timesteps);
+
+/* Runs timesteps (a multiple of C) of the loop above, continuing from where the last call stopped.
+ * Returns when every launch has been enqueued and the trainer thread is idle; the experiences of the
+ * last block are still in the temporary buffers (one of them pending on the device), as they would be
+ * at that instant of the paper's loop.  An error inside the trainer thread is reported by the next
+ * synchronisation point or by this call's return. */
+int dqn_alg1_run(dqn_alg1* h, int64_t timesteps);
+
+/* Appends the pending experience and flushes the temporary buffers into D (blocking), so that D can be
+ * inspected; the next dqn_alg1_run starts with its own synchronisation point as usual. */
+int dqn_alg1_flush(dqn_alg1* h);
+
+/* Host-side counters (any pointer may be NULL): timesteps of dqn_alg1_run so far, act steps and train
+ * steps issued, sum of rewards and number of finished episodes over all environments (prepopulation
+ * included). */
+int dqn_alg1_stats(const dqn_alg1* h, int64_t* host_t, int64_t* host_act_steps, int64_t* host_train_steps,
+                   double* host_reward_sum, int64_t* host_episodes);
+
 /* ---- per-kernel timing (measurement support) ------------------------------------------------- */
 
 /* Number of distinct kernels a train step launches, and their names (id 1 .. count).  The last id,

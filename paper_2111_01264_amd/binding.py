@@ -23,6 +23,14 @@ DQN_PRECISION_FP32, DQN_PRECISION_BF16 = 0, 1
 DQN_PARAMS_ONLINE, DQN_PARAMS_TARGET, DQN_PARAMS_RMS_V, DQN_PARAMS_RMS_M, DQN_PARAMS_GRAD = range(5)
 
 
+class dqn_alg1_config(C.Structure):
+    _fields_ = [
+        ("W", C.c_int32), ("C", C.c_int32), ("F", C.c_int32), ("B", C.c_int32), ("epsilon", C.c_float),
+        ("t_reward_neg", C.c_uint32), ("t_reward_pos", C.c_uint32), ("t_term", C.c_uint32),
+        ("env_seed", C.c_uint64),
+    ]
+
+
 class DqnError(RuntimeError):
     def __init__(self, code, message):
         super().__init__("dqn_mi355 error %d: %s" % (code, message))
@@ -69,6 +77,13 @@ EXPORTS = {
     "synth_transitions": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_uint64,
                                     C.c_uint64, C.c_uint64, C.c_int32, C.c_uint32, C.c_uint32,
                                     C.c_uint32, C.c_void_p]),
+    "dqn_alg1_create": (C.c_int, [C.c_void_p, C.c_void_p, C.POINTER(dqn_alg1_config), C.POINTER(C.c_void_p)]),
+    "dqn_alg1_destroy": (C.c_int, [C.c_void_p]),
+    "dqn_alg1_prepopulate": (C.c_int, [C.c_void_p, C.c_int64]),
+    "dqn_alg1_run": (C.c_int, [C.c_void_p, C.c_int64]),
+    "dqn_alg1_flush": (C.c_int, [C.c_void_p]),
+    "dqn_alg1_stats": (C.c_int, [C.c_void_p, C.POINTER(C.c_int64), C.POINTER(C.c_int64), C.POINTER(C.c_int64),
+                                 C.POINTER(C.c_double), C.POINTER(C.c_int64)]),
     "dqn_profile_kernel_count": (C.c_int, []),
     "dqn_profile_kernel_name": (C.c_char_p, [C.c_int]),
     "dqn_profile_select": (C.c_int, [C.c_void_p, C.c_int]),
@@ -210,6 +225,35 @@ def synth_transitions(actions, rewards, terminals, n, id0, id_step, seed, num_ac
                       t_term, stream):
     _check(_lib.synth_transitions(_ptr(actions), _ptr(rewards), _ptr(terminals), n, id0, id_step, seed,
                                   num_actions, t_neg, t_pos, t_term, _stream(stream)))
+
+
+def dqn_alg1_create(ctx, rb, cfg: dqn_alg1_config):
+    out = C.c_void_p()
+    _check(_lib.dqn_alg1_create(ctx, rb, C.byref(cfg), C.byref(out)))
+    return out
+
+
+def dqn_alg1_destroy(h):
+    _check(_lib.dqn_alg1_destroy(h))
+
+
+def dqn_alg1_prepopulate(h, timesteps):
+    _check(_lib.dqn_alg1_prepopulate(h, timesteps))
+
+
+def dqn_alg1_run(h, timesteps):
+    _check(_lib.dqn_alg1_run(h, timesteps))
+
+
+def dqn_alg1_flush(h):
+    _check(_lib.dqn_alg1_flush(h))
+
+
+def dqn_alg1_stats(h):
+    t, na, nt, ep = C.c_int64(), C.c_int64(), C.c_int64(), C.c_int64()
+    rs = C.c_double()
+    _check(_lib.dqn_alg1_stats(h, C.byref(t), C.byref(na), C.byref(nt), C.byref(rs), C.byref(ep)))
+    return {"t": t.value, "act_steps": na.value, "train_steps": nt.value, "reward_sum": rs.value, "episodes": ep.value}
 
 
 def dqn_profile_kernel_count():

@@ -1,0 +1,406 @@
+// Algorithm 1 (DQN with Concurrent Training and Synchronized Execution, main thread) as a native host orchestrator:
+// W sampler threads and one trainer thread around the hot-path calls of this library.
+//
+//   * every C timesteps: wait for the trainer and the samplers, append what is pending, flush the temporary buffers
+//     into D, theta^- <- theta (dqn_sync_target), dispatch the trainer thread for C / F minibatches;
+//   * every W timesteps: wait for the samplers, evaluate Q(s^(j), .) for all W states in one minibatch (Section 4) --
+//     with the previous step's experiences riding in the same launches --, hand every sampler its action;
+//   * a sampler thread takes one step in its environment with that action.
+//
+// The environments are synthetic (a seeded frame generator stands in for the Atari emulator, see the header): they
+// live on the host, as an emulator would, one per sampler thread.  States, actions, rewards and terminal flags cross
+// the bus through pinned "shared arrays" (Section 4) -- per act step one batched upload (W new frames, W rewards, W
+// flags) and one download (W actions), whatever W is.  The frame stacks themselves stay on the device: a small kernel
+// shifts each stack and appends the new frame, clearing what belongs to a finished episode (the rule the replay
+// gather applies, so the states acted from are the states training later rebuilds).
+#include <atomic>
+#include <condition_variable>
+#include <mutex>
+#include <new>
+#include <thread>
+#include <vector>
+
+#include "common.h"
+
+namespace dqn {
+
+namespace {
+
+constexpr uint64_t kGammaEnv = 0x9E3779B97F4A7C15ull;
+inline uint64_t mix64_host(uint64_t z)
+{
+    z ^= z >> 30; z *= 0xBF58476D1CE4E5B9ull;
+    z ^= z >> 27; z *= 0x94D049BB133111EBull;
+    z ^= z >> 31;
+    return z;
+}
+constexpr uint32_t kStreamEnv = 3, kStreamEnvMeta = 4;   // stream tags of the synthetic environments
+constexpr uint32_t kPixThreshold = 838861;               // ceil(0.05 * 2^24)
+constexpr uint32_t kBackground = 40;
+
+// Observation `id` of the environment stream: the frame generator of the header, on the host.
+void env_frame_host(uint64_t stream_key, uint64_t id, uint8_t* dst)
+{
+    const uint64_t fkey = mix64_host(stream_key + id);
+    for (uint32_t g = 0; g < kFrameBytes / 2; ++g) {
+        const uint64_t w = mix64_host(fkey + kGammaEnv * (static_cast<uint64_t>(g) + 1));
+        const uint32_t lo = static_cast<uint32_t>(w), hi = static_cast<uint32_t>(w >> 32);
+        dst[2 * g] = static_cast<uint8_t>((lo >> 8) < kPixThreshold ? (lo & 0xFFu) : kBackground);
+        dst[2 * g + 1] = static_cast<uint8_t>((hi >> 8) < kPixThreshold ? (hi & 0xFFu) : kBackground);
+    }
+}
+
+// Shift every environment's frame stack by one and append its new observation; a stack whose previous step ended
+// an episode keeps only the new observation.  One workgroup per environment, thread -> 16-byte vector of a frame.
+__global__ __launch_bounds__(256) void env_advance_kernel(uint8_t* __restrict__ states, const uint8_t* __restrict__ new_frames,
+                                                          const uint8_t* __restrict__ terminals)
+{
+    const int j = blockIdx.x;
+    uint4* st = reinterpret_cast<uint4*>(states + static_cast<size_t>(j) * kStateBytes);
+    const uint4* nf = reinterpret_cast<const uint4*>(new_frames + static_cast<size_t>(j) * kFrameBytes);
+    const bool reset = terminals[j] != 0;
+    const uint4 z = make_uint4(0, 0, 0, 0);
+    for (int v = threadIdx.x; v < kFrameVec16; v += blockDim.x) {
+        const uint4 f1 = st[kFrameVec16 + v], f2 = st[2 * kFrameVec16 + v], f3 = st[3 * kFrameVec16 + v];
+        st[v] = reset ? z : f1;
+        st[kFrameVec16 + v] = reset ? z : f2;
+        st[2 * kFrameVec16 + v] = reset ? z : f3;
+        st[3 * kFrameVec16 + v] = nf[v];
+    }
+}
+
+}  // namespace
+}  // namespace dqn
+
+using namespace dqn;
+
+struct dqn_alg1 {
+    dqn_ctx* ctx = nullptr;
+    replay* rb = nullptr;
+    dqn_alg1_config cfg{};
+    int A = 0;
+    hipStream_t act_stream = nullptr;
+    uint64_t key_env = 0, key_meta = 0;
+    uint32_t t_neg = 0, t_pos = 0, t_term = 0;
+    // pinned host arrays shared between the main thread and the sampler threads
+    uint8_t* h_frames[2] = {nullptr, nullptr};   // [W][84*84]: observations o_n / o_{n+1}, alternating
+    int32_t* h_actions = nullptr;
+    float* h_rewards = nullptr;
+    uint8_t* h_terminals = nullptr;
+    // device side of the same
+    uint8_t* d_frames[2] = {nullptr, nullptr};
+    uint8_t* d_states = nullptr;                 // [W][4][84][84]
+    int32_t* d_actions = nullptr;
+    float* d_rewards = nullptr;
+    uint8_t* d_terminals = nullptr;
+    // progress
+    int64_t n = 0;            // steps every environment has taken
+    int cur = 0;              // d_frames[cur] holds o_n
+    bool started = false;     // o_0 generated, states initialised
+    bool pending = false;     // experience n-1 is complete on the device and not yet appended
+    int64_t t = 0, act_steps = 0, train_steps = 0, episodes = 0;
+    double reward_sum = 0.0;
+    // worker threads: tasks are handed out by generation number
+    std::mutex mu;
+    std::condition_variable cv_work, cv_done;
+    uint64_t sampler_gen = 0, trainer_gen = 0;
+    int sampler_task = 0;     // 0: observation o_0, 1: one environment step
+    int samplers_done = 0;
+    bool trainer_busy = false, stop = false;
+    int trainer_rc = DQN_OK;
+    char trainer_err[256] = {0};
+    int64_t trainer_first = 0;
+    int trainer_count = 0;
+    std::vector<std::thread> samplers;
+    std::thread trainer;
+};
+
+namespace {
+
+void sampler_main(dqn_alg1* h, int j)
+{
+    uint64_t seen = 0;
+    for (;;) {
+        int task;
+        int64_t n;
+        int nb;
+        {
+            std::unique_lock<std::mutex> lk(h->mu);
+            h->cv_work.wait(lk, [&] { return h->stop || h->sampler_gen != seen; });
+            if (h->stop) return;
+            seen = h->sampler_gen;
+            task = h->sampler_task; n = h->n; nb = h->cur ^ 1;
+        }
+        const int W = h->cfg.W;
+        if (task == 0) {
+            env_frame_host(h->key_env, static_cast<uint64_t>(j), h->h_frames[h->cur] + static_cast<size_t>(j) * kFrameBytes);
+        } else {
+            // one step of environment j with the action the main thread distributed: (r_n, d_n), then o_{n+1}
+            const uint64_t id = static_cast<uint64_t>(n) * W + j;
+            const uint64_t w = mix64_host(mix64_host(h->key_meta + id) + kGammaEnv);
+            const uint32_t rb = static_cast<uint32_t>(w & 0xFFFFFFu), tb = static_cast<uint32_t>((w >> 24) & 0xFFFFFFu);
+            const uint32_t ab = static_cast<uint32_t>((w >> 48) & 0xFFFFu);
+            const int good = static_cast<int>((ab * static_cast<uint32_t>(h->A)) >> 16);
+            float r = rb < h->t_neg ? -1.f : (rb >= (1u << 24) - h->t_pos ? 1.f : 0.f);
+            if (h->h_actions[j] != good) r = 0.f;
+            h->h_rewards[j] = r;
+            h->h_terminals[j] = tb < h->t_term ? 1 : 0;
+            env_frame_host(h->key_env, id + W, h->h_frames[nb] + static_cast<size_t>(j) * kFrameBytes);
+        }
+        {
+            std::lock_guard<std::mutex> lk(h->mu);
+            if (++h->samplers_done == W) h->cv_done.notify_all();
+        }
+    }
+}
+
+void trainer_main(dqn_alg1* h)
+{
+    uint64_t seen = 0;
+    for (;;) {
+        int64_t first;
+        int count;
+        {
+            std::unique_lock<std::mutex> lk(h->mu);
+            h->cv_work.wait(lk, [&] { return h->stop || h->trainer_gen != seen; });
+            if (h->stop) return;
+            seen = h->trainer_gen;
+            first = h->trainer_first; count = h->trainer_count;
+        }
+        int rc = DQN_OK;
+        for (int i = 0; i < count && rc == DQN_OK; ++i)
+            rc = dqn_train_step_sampled(h->ctx, h->rb, h->cfg.B, static_cast<uint64_t>(first + i), i + 1 < count, nullptr);
+        {
+            std::lock_guard<std::mutex> lk(h->mu);
+            h->trainer_rc = rc;
+            if (rc != DQN_OK) snprintf(h->trainer_err, sizeof(h->trainer_err), "%s", dqn_last_error());
+            h->trainer_busy = false;
+            h->cv_done.notify_all();
+        }
+    }
+}
+
+void run_samplers(dqn_alg1* h, int task)
+{
+    std::unique_lock<std::mutex> lk(h->mu);
+    h->sampler_task = task;
+    h->samplers_done = 0;
+    ++h->sampler_gen;
+    h->cv_work.notify_all();
+    h->cv_done.wait(lk, [&] { return h->samplers_done == h->cfg.W; });
+}
+
+int wait_trainer(dqn_alg1* h)
+{
+    std::unique_lock<std::mutex> lk(h->mu);
+    h->cv_done.wait(lk, [&] { return !h->trainer_busy; });
+    if (h->trainer_rc != DQN_OK) {
+        const int rc = h->trainer_rc;
+        h->trainer_rc = DQN_OK;
+        return fail(rc, "trainer thread: %s", h->trainer_err);
+    }
+    return DQN_OK;
+}
+
+// Uploads what the samplers just produced for step n (r_n, d_n, o_{n+1}) and advances the frame stacks.
+int upload_and_advance(dqn_alg1* h)
+{
+    const int W = h->cfg.W, nb = h->cur ^ 1;
+    DQN_HIP(hipMemcpyAsync(h->d_frames[nb], h->h_frames[nb], static_cast<size_t>(W) * kFrameBytes, hipMemcpyHostToDevice, h->act_stream));
+    DQN_HIP(hipMemcpyAsync(h->d_rewards, h->h_rewards, W * sizeof(float), hipMemcpyHostToDevice, h->act_stream));
+    DQN_HIP(hipMemcpyAsync(h->d_terminals, h->h_terminals, W, hipMemcpyHostToDevice, h->act_stream));
+    hipLaunchKernelGGL(env_advance_kernel, dim3(W), dim3(256), 0, h->act_stream, h->d_states, h->d_frames[nb], h->d_terminals);
+    DQN_LAUNCH_CHECK();
+    return DQN_OK;
+}
+
+int start_envs(dqn_alg1* h)
+{
+    const int W = h->cfg.W;
+    run_samplers(h, 0);   // o_0 of every environment into h_frames[cur]
+    for (int j = 0; j < W; ++j) h->h_terminals[j] = 1;   // "episode start": the stack keeps only the new observation
+    DQN_HIP(hipMemcpyAsync(h->d_frames[h->cur], h->h_frames[h->cur], static_cast<size_t>(W) * kFrameBytes, hipMemcpyHostToDevice, h->act_stream));
+    DQN_HIP(hipMemcpyAsync(h->d_terminals, h->h_terminals, W, hipMemcpyHostToDevice, h->act_stream));
+    hipLaunchKernelGGL(env_advance_kernel, dim3(W), dim3(256), 0, h->act_stream, h->d_states, h->d_frames[h->cur], h->d_terminals);
+    DQN_LAUNCH_CHECK();
+    DQN_HIP(hipStreamSynchronize(h->act_stream));   // h_terminals is reused by the samplers
+    h->started = true;
+    return DQN_OK;
+}
+
+// One act step: Q for all W states in one minibatch, actions to the samplers, one environment step each.
+int act_step(dqn_alg1* h, float epsilon)
+{
+    const int W = h->cfg.W;
+    int rc;
+    if (h->pending) {
+        // experience n-1 = (o_{n-1}, a_{n-1}, r_{n-1}, d_{n-1}) rides in this step's launches; a_{n-1} is read from the
+        // actions buffer before the same call overwrites it with a_n
+        rc = dqn_act_push_step(h->ctx, h->rb, h->d_frames[h->cur ^ 1], h->d_actions, h->d_rewards, h->d_terminals, h->d_states, W, epsilon,
+                               static_cast<uint64_t>(h->act_steps), 1, h->d_actions, nullptr);
+        h->pending = false;
+    } else {
+        rc = dqn_act(h->ctx, h->d_states, W, epsilon, static_cast<uint64_t>(h->act_steps), 1, h->d_actions, nullptr);
+    }
+    if (rc != DQN_OK) return rc;
+    DQN_HIP(hipMemcpyAsync(h->h_actions, h->d_actions, W * sizeof(int32_t), hipMemcpyDeviceToHost, h->act_stream));
+    DQN_HIP(hipStreamSynchronize(h->act_stream));
+    ++h->act_steps;
+    run_samplers(h, 1);
+    for (int j = 0; j < W; ++j) { h->reward_sum += h->h_rewards[j]; h->episodes += h->h_terminals[j]; }
+    rc = upload_and_advance(h);
+    if (rc != DQN_OK) return rc;
+    h->cur ^= 1;
+    ++h->n;
+    h->pending = true;
+    h->t += W;
+    return DQN_OK;
+}
+
+// Appends the pending experience by itself (in front of a flush).
+int append_pending(dqn_alg1* h)
+{
+    if (!h->pending) return DQN_OK;
+    const int rc = replay_push_step(h->rb, h->d_frames[h->cur ^ 1], h->d_actions, h->d_rewards, h->d_terminals);
+    if (rc != DQN_OK) return rc;
+    h->pending = false;
+    return DQN_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int dqn_alg1_create(dqn_ctx* ctx, replay* rb, const dqn_alg1_config* cfg, dqn_alg1** out)
+{
+    if (!ctx || !rb || !cfg || !out) return fail(DQN_EINVAL, "dqn_alg1_create: null pointer");
+    const int W = cfg->W;
+    if (W < 1 || W > dqn_ctx_max_envs(ctx) || W > kMaxLanes) return fail(DQN_EINVAL, "dqn_alg1_create: W = %d outside 1..%d", W, dqn_ctx_max_envs(ctx));
+    if (replay_lanes(rb) != W) return fail(DQN_EINVAL, "dqn_alg1_create: the replay memory needs one lane per sampler (%d lanes, W = %d)", replay_lanes(rb), W);
+    if (replay_push_stream(rb) != dqn_ctx_act_stream(ctx)) return fail(DQN_EINVAL, "dqn_alg1_create: the replay's push stream must be the act stream");
+    if (cfg->C < 1 || cfg->F < 1 || cfg->C % W != 0 || cfg->C % cfg->F != 0)
+        return fail(DQN_EINVAL, "dqn_alg1_create: C = %d must be a positive multiple of W = %d and of F = %d", cfg->C, W, cfg->F);
+    if (cfg->B < 1 || cfg->B > dqn_ctx_max_batch(ctx)) return fail(DQN_EINVAL, "dqn_alg1_create: B = %d outside 1..%d", cfg->B, dqn_ctx_max_batch(ctx));
+    if (!(cfg->epsilon >= 0.f && cfg->epsilon <= 1.f)) return fail(DQN_EINVAL, "dqn_alg1_create: epsilon outside [0,1]");
+    if (cfg->t_reward_neg > (1u << 24) || cfg->t_reward_pos > (1u << 24) || cfg->t_term > (1u << 24) ||
+        static_cast<uint64_t>(cfg->t_reward_neg) + cfg->t_reward_pos > (1u << 24))
+        return fail(DQN_EINVAL, "dqn_alg1_create: environment thresholds exceed 2^24");
+    dqn_alg1* h = new (std::nothrow) dqn_alg1();
+    if (!h) return fail(DQN_ENOMEM, "dqn_alg1_create: host allocation failed");
+    h->ctx = ctx; h->rb = rb; h->cfg = *cfg; h->A = dqn_ctx_num_actions(ctx); h->act_stream = dqn_ctx_act_stream(ctx);
+    h->key_env = mix64_host(cfg->env_seed + kGammaEnv * (kStreamEnv + 1ull));
+    h->key_meta = mix64_host(cfg->env_seed + kGammaEnv * (kStreamEnvMeta + 1ull));
+    h->t_neg = cfg->t_reward_neg; h->t_pos = cfg->t_reward_pos; h->t_term = cfg->t_term;
+    auto body = [&]() -> int {
+        const size_t fb = static_cast<size_t>(W) * kFrameBytes;
+        for (int i = 0; i < 2; ++i) {
+            DQN_HIP(hipHostMalloc(reinterpret_cast<void**>(&h->h_frames[i]), fb, hipHostMallocDefault));
+            DQN_HIP(hipMalloc(reinterpret_cast<void**>(&h->d_frames[i]), fb));
+        }
+        DQN_HIP(hipHostMalloc(reinterpret_cast<void**>(&h->h_actions), W * sizeof(int32_t), hipHostMallocDefault));
+        DQN_HIP(hipHostMalloc(reinterpret_cast<void**>(&h->h_rewards), W * sizeof(float), hipHostMallocDefault));
+        DQN_HIP(hipHostMalloc(reinterpret_cast<void**>(&h->h_terminals), W, hipHostMallocDefault));
+        DQN_HIP(hipMalloc(reinterpret_cast<void**>(&h->d_states), static_cast<size_t>(W) * kStateBytes));
+        DQN_HIP(hipMemset(h->d_states, 0, static_cast<size_t>(W) * kStateBytes));
+        DQN_HIP(hipMalloc(reinterpret_cast<void**>(&h->d_actions), W * sizeof(int32_t)));
+        DQN_HIP(hipMalloc(reinterpret_cast<void**>(&h->d_rewards), W * sizeof(float)));
+        DQN_HIP(hipMalloc(reinterpret_cast<void**>(&h->d_terminals), W));
+        DQN_HIP(hipDeviceSynchronize());
+        return DQN_OK;
+    };
+    const int rc = body();
+    if (rc != DQN_OK) {
+        char saved[512];
+        snprintf(saved, sizeof(saved), "%s", error_buffer());
+        dqn_alg1_destroy(h);
+        return fail(rc, "dqn_alg1_create: %s", saved);
+    }
+    for (int j = 0; j < W; ++j) h->samplers.emplace_back(sampler_main, h, j);
+    h->trainer = std::thread(trainer_main, h);
+    *out = h;
+    return DQN_OK;
+}
+
+int dqn_alg1_destroy(dqn_alg1* h)
+{
+    if (!h) return DQN_OK;
+    {
+        std::unique_lock<std::mutex> lk(h->mu);
+        h->cv_done.wait(lk, [&] { return !h->trainer_busy; });
+        h->stop = true;
+        h->cv_work.notify_all();
+    }
+    for (std::thread& t : h->samplers) t.join();
+    if (h->trainer.joinable()) h->trainer.join();
+    if (h->act_stream) (void)hipStreamSynchronize(h->act_stream);
+    for (int i = 0; i < 2; ++i) { (void)hipHostFree(h->h_frames[i]); (void)hipFree(h->d_frames[i]); }
+    (void)hipHostFree(h->h_actions); (void)hipHostFree(h->h_rewards); (void)hipHostFree(h->h_terminals);
+    (void)hipFree(h->d_states); (void)hipFree(h->d_actions); (void)hipFree(h->d_rewards); (void)hipFree(h->d_terminals);
+    delete h;
+    return DQN_OK;
+}
+
+int dqn_alg1_prepopulate(dqn_alg1* h, int64_t timesteps)
+{
+    if (!h) return fail(DQN_EINVAL, "dqn_alg1_prepopulate: handle is null");
+    if (timesteps < 0 || timesteps % h->cfg.W != 0) return fail(DQN_EINVAL, "dqn_alg1_prepopulate: timesteps must be a multiple of W");
+    int rc = wait_trainer(h);
+    if (rc != DQN_OK) return rc;
+    if (!h->started && (rc = start_envs(h)) != DQN_OK) return rc;
+    const int64_t t0 = h->t;
+    for (int64_t k = 0; k < timesteps / h->cfg.W; ++k)
+        if ((rc = act_step(h, 1.f)) != DQN_OK) return rc;
+    h->t = t0;   // prepopulation does not count as timesteps of the algorithm
+    if ((rc = append_pending(h)) != DQN_OK) return rc;
+    return replay_flush(h->rb, 1);
+}
+
+int dqn_alg1_run(dqn_alg1* h, int64_t timesteps)
+{
+    if (!h) return fail(DQN_EINVAL, "dqn_alg1_run: handle is null");
+    if (timesteps < 0 || timesteps % h->cfg.C != 0) return fail(DQN_EINVAL, "dqn_alg1_run: timesteps must be a multiple of C");
+    int rc;
+    if (!h->started && (rc = start_envs(h)) != DQN_OK) return rc;
+    const int W = h->cfg.W, C = h->cfg.C, F = h->cfg.F;
+    for (int64_t block = 0; block < timesteps / C; ++block) {
+        // t mod C == 0: the samplers are idle (they only run inside act_step); wait for the trainer, then synchronise
+        if ((rc = wait_trainer(h)) != DQN_OK) return rc;
+        if ((rc = append_pending(h)) != DQN_OK) return rc;
+        if ((rc = dqn_sync_target(h->ctx, h->rb, 0)) != DQN_OK) return rc;
+        {
+            std::lock_guard<std::mutex> lk(h->mu);
+            h->trainer_first = h->train_steps;
+            h->trainer_count = C / F;
+            h->trainer_busy = true;
+            ++h->trainer_gen;
+            h->cv_work.notify_all();
+        }
+        h->train_steps += C / F;
+        for (int k = 0; k < C / W; ++k)
+            if ((rc = act_step(h, h->cfg.epsilon)) != DQN_OK) return rc;
+    }
+    return wait_trainer(h);   // every launch of the last block has been issued when this returns
+}
+
+int dqn_alg1_flush(dqn_alg1* h)
+{
+    if (!h) return fail(DQN_EINVAL, "dqn_alg1_flush: handle is null");
+    int rc = wait_trainer(h);
+    if (rc != DQN_OK) return rc;
+    if ((rc = append_pending(h)) != DQN_OK) return rc;
+    return replay_flush(h->rb, 1);
+}
+
+int dqn_alg1_stats(const dqn_alg1* h, int64_t* host_t, int64_t* host_act_steps, int64_t* host_train_steps, double* host_reward_sum,
+                   int64_t* host_episodes)
+{
+    if (!h) return fail(DQN_EINVAL, "dqn_alg1_stats: handle is null");
+    if (host_t) *host_t = h->t;
+    if (host_act_steps) *host_act_steps = h->act_steps;
+    if (host_train_steps) *host_train_steps = h->train_steps;
+    if (host_reward_sum) *host_reward_sum = h->reward_sum;
+    if (host_episodes) *host_episodes = h->episodes;
+    return DQN_OK;
+}
+
+}  // extern "C"

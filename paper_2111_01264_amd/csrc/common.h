@@ -36,6 +36,12 @@ inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 int replay_flush_ordered(replay* rb);
 hipStream_t replay_sample_stream(replay* rb);
 hipStream_t replay_push_stream(replay* rb);
+int replay_lanes(const replay* rb);
+// Context internals needed by the Algorithm 1 orchestrator.
+hipStream_t dqn_ctx_act_stream(dqn_ctx* c);
+int dqn_ctx_num_actions(const dqn_ctx* c);
+int dqn_ctx_max_envs(const dqn_ctx* c);
+int dqn_ctx_max_batch(const dqn_ctx* c);
 
 constexpr int kFrameBytes = 84 * 84;          // 7056 = 441 * 16
 constexpr int kFrameVec16 = kFrameBytes / 16; // 441

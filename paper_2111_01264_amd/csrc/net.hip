@@ -555,6 +555,11 @@ static int sync_both(dqn_ctx* c)
     return DQN_OK;
 }
 
+hipStream_t dqn_ctx_act_stream(dqn_ctx* c) { return c->act_stream; }
+int dqn_ctx_num_actions(const dqn_ctx* c) { return c->A; }
+int dqn_ctx_max_envs(const dqn_ctx* c) { return c->cfg.max_envs; }
+int dqn_ctx_max_batch(const dqn_ctx* c) { return c->cfg.max_batch; }
+
 }  // namespace dqn
 
 extern "C" {

@@ -320,6 +320,7 @@ uint64_t replay_epoch(const replay* rb) { return rb->epoch; }
 
 hipStream_t replay_sample_stream(replay* rb) { return rb->sample_stream; }
 hipStream_t replay_push_stream(replay* rb) { return rb->push_stream; }
+int replay_lanes(const replay* rb) { return rb->L; }
 }  // namespace dqn
 
 extern "C" {

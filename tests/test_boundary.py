@@ -51,3 +51,12 @@ def test_validation_errors_before_device_work():
     assert lib.dqn_train_step(None, None, None, None, None, None, 1, None) == P.DQN_EINVAL
     assert lib.replay_push(None, 0, None, None, None, None, 1) == P.DQN_EINVAL
     assert lib.dqn_destroy(None) == P.DQN_OK and lib.replay_destroy(None) == P.DQN_OK
+    assert lib.dqn_alg1_create(None, None, None, C.byref(out)) == P.DQN_EINVAL
+    lib.dqn_alg1_run.argtypes = P.EXPORTS["dqn_alg1_run"][1]
+    assert lib.dqn_alg1_run(None, 0) == P.DQN_EINVAL and lib.dqn_alg1_flush(None) == P.DQN_EINVAL
+    assert lib.dqn_alg1_destroy(None) == P.DQN_OK
+
+
+def test_alg1_config_struct_matches_header_size():
+    # 4 int32 + float + 3 uint32 + uint64
+    assert C.sizeof(P.dqn_alg1_config) == 40
