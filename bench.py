@@ -354,6 +354,71 @@ def cpu_baseline(args):
                       % (done_steps, args.acts_per_train, W, B, el)}
 
 
+def algorithm1(args):
+    """Algorithm 1 end to end (dqn_alg1_*): W sampler threads on synthetic host environments, the trainer thread,
+    synchronisation every C timesteps.  Prints one JSON line of its own; not the headline metric."""
+    import torch
+    import paper_2111_01264_amd as P
+    from datagen import synth
+    W, C, F, B, A = args.envs, args.alg1_c, args.alg1_f, args.batch, args.actions
+    torch.cuda.set_device(0)
+    sa, stt = torch.cuda.Stream(), torch.cuda.Stream()
+    cfg = P.dqn_config()
+    cfg.num_actions, cfg.max_batch, cfg.max_envs = A, B, W
+    cfg.precision = P.DQN_PRECISION_BF16 if args.precision == "bf16" else P.DQN_PRECISION_FP32
+    cfg.double_dqn, cfg.centered = int(args.double_dqn), 1
+    cfg.gamma, cfg.huber_delta, cfg.lr, cfg.rms_alpha, cfg.rms_eps = 0.99, 1.0, 2.5e-4, 0.95, 0.01
+    cfg.seed = args.seed
+    ctx = P.dqn_create(cfg, sa, stt)
+    theta = synth.init_params(args.seed, A)
+    P.dqn_set_params(ctx, P.DQN_PARAMS_ONLINE, theta)
+    P.dqn_set_params(ctx, P.DQN_PARAMS_TARGET, theta)
+    frames = args.frames - args.frames % W
+    rb = P.replay_create(frames, W, C // W, args.seed, sa, stt)
+    ac = P.dqn_alg1_config()
+    ac.W, ac.C, ac.F, ac.B, ac.epsilon = W, C, F, B, 0.1
+    ac.t_reward_neg, ac.t_reward_pos, ac.t_term = synth.thresholds(args.p_reward, args.p_reward, args.p_term)
+    ac.env_seed = args.seed
+    h = P.dqn_alg1_create(ctx, rb, ac)
+    # prepopulation (Table 5: N = 50000), in pieces the temporary buffers can hold; also the sampler side's rate alone
+    n_pre = args.alg1_prepopulate - args.alg1_prepopulate % C
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(n_pre // C):
+        P.dqn_alg1_prepopulate(h, C)
+    torch.cuda.synchronize()
+    pre_s = time.perf_counter() - t0
+    P.dqn_alg1_run(h, C * max(args.alg1_warmup_blocks, 1))
+    torch.cuda.synchronize()
+    blocks = args.alg1_blocks
+    t0 = time.perf_counter()
+    P.dqn_alg1_run(h, C * blocks)
+    torch.cuda.synchronize()
+    el = time.perf_counter() - t0
+    stats = P.dqn_alg1_stats(h)
+    P.dqn_alg1_destroy(h)
+    P.replay_destroy(rb)
+    P.dqn_destroy(ctx)
+    out = {
+        "metric": "Algorithm 1 timesteps/sec (W=%d synthetic host environments, batch %d)" % (W, B),
+        "value": C * blocks / el, "unit": "timesteps/s",
+        "train_steps_per_sec": C // F * blocks / el, "act_steps_per_sec": C // W * blocks / el,
+        "samplers_alone_timesteps_per_sec": n_pre / pre_s if n_pre else None,
+        "n_gpus": 1, "steps": blocks, "warmup": max(args.alg1_warmup_blocks, 1), "ms_per_step": 1e3 * el / blocks,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if args.precision == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": "Algorithm 1, Table 5 schedule: A=%d, W=%d, C=%d, F=%d, batch %d, replay %d frames, "
+                               "prepopulation %d; a step is one block of C timesteps" % (A, W, C, F, B, frames, n_pre),
+                   "seed": args.seed},
+        "totals": stats,
+        "context": "paper: 200M frames = 50M timesteps in 9 h on one GTX 1080 with the real emulator (about 1,500 "
+                   "timesteps/s); here the environment is a seeded frame generator, so this rate bounds the loop "
+                   "around the emulator, not the emulator",
+    }
+    print(json.dumps(out))
+    return 0
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -378,6 +443,13 @@ def main():
     ap.add_argument("--separate-gather", action="store_true",
                     help="replay_sample_gather and dqn_train_step as two calls instead of dqn_train_step_sampled")
     ap.add_argument("--sweep", action="store_true", help="print the batch/W roofline sweep instead of the JSON line")
+    ap.add_argument("--algorithm1", action="store_true",
+                    help="time the Algorithm 1 orchestrator (dqn_alg1_*) instead: one JSON line of its own")
+    ap.add_argument("--alg1-c", type=int, default=10000, help="target update period C in timesteps (Table 5)")
+    ap.add_argument("--alg1-f", type=int, default=4, help="training period F in timesteps (Table 5)")
+    ap.add_argument("--alg1-prepopulate", type=int, default=50000, help="prepopulation N (Table 5), rounded down to C")
+    ap.add_argument("--alg1-blocks", type=int, default=20, help="timed blocks of C timesteps")
+    ap.add_argument("--alg1-warmup-blocks", type=int, default=2)
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one MI355X: this library runs on one GPU, run with --gpus 1", file=sys.stderr)
@@ -385,6 +457,8 @@ def main():
 
     if args.sweep:
         return sweep(args)
+    if args.algorithm1:
+        return algorithm1(args)
 
     wl = Workload(args)
     groups = 3 if args.double_dqn else 2
