@@ -14,6 +14,16 @@ environments and advances t by W (Section 4), so C must be a multiple of W and o
 run; D is prepopulated by the same loop with epsilon = 1 and no training ("collected randomly"); environment j
 writes lane j of D; the state of an environment is the stack of its four latest observations with those from
 before the latest episode start replaced by zeros -- the same rule the replay gather applies (oracle/replay.py).
+
+The ablation of Section 5.1 switches the two techniques off independently (`Ablation` below):
+  * without Synchronized Execution every sampler queries the network by itself: W evaluations of one state instead
+    of one evaluation of W states per round of W timesteps (Section 4's "asynchronous" samplers).  Reading: the
+    samplers still advance in rounds of W timesteps (the schedule below needs a common clock), and the evaluation of
+    environment j at its n-th step draws its epsilon-greedy numbers at counter n * W + j, index 0;
+  * without Concurrent Training the agent is standard DQN (Section 2.1): it acts from theta, every experience
+    enters D at once (no temporary buffers: a flush after every round), and a train step is due at every F-th
+    timestep -- after a round that ends at t, t // F train steps have been made, each sampling from D as it is
+    after that round; theta^- <- theta every C timesteps.  Sampling cannot run while training does.
 """
 from __future__ import annotations
 
@@ -98,6 +108,53 @@ class Algorithm1:
                 frozen.check_unchanged()
                 self._train_block()
             self.t += self.C
+
+
+class Ablation(Algorithm1):
+    """Algorithm 1 with Concurrent Training and / or Synchronized Execution switched off (Section 5.1)."""
+
+    def __init__(self, dqn, replay, envs, C, F, B, epsilon, concurrent, synchronized):
+        super().__init__(dqn, replay, envs, C, F, B, epsilon)
+        self.concurrent, self.synchronized = concurrent, synchronized
+
+    def _actions(self, epsilon, use_target):
+        if self.synchronized:
+            actions, _ = self.dqn.act(self.envs.states, epsilon, self.act_steps, use_target=use_target)
+            return actions
+        out = np.empty(self.W, dtype=np.int32)
+        for j in range(self.W):                                  # one query per sampler
+            a, _ = self.dqn.act(self.envs.states[j:j + 1], epsilon, self.act_steps * self.W + j, use_target=use_target)
+            out[j] = a[0]
+        return out
+
+    def _round(self, epsilon, use_target):
+        actions = self._actions(epsilon, use_target)
+        self.act_steps += 1                                      # rounds of W timesteps
+        frames, a, r, d = self.envs.step(actions)
+        for j in range(self.W):
+            self.replay.push(j, frames[j:j + 1], a[j:j + 1], r[j:j + 1], d[j:j + 1])
+
+    def _act_block(self, timesteps, epsilon):
+        for _ in range(timesteps // self.W):
+            self._round(epsilon, use_target=True)
+
+    def run(self, timesteps, trainer_first=True):
+        if self.concurrent:
+            return super().run(timesteps, trainer_first)
+        assert timesteps % self.C == 0
+        for _ in range(timesteps // self.C):
+            self.replay.flush()
+            self.dqn.sync_target()                               # t mod C == 0
+            for _ in range(self.C // self.W):
+                self._round(self.epsilon, use_target=False)      # standard DQN acts from theta
+                self.replay.flush()                              # experiences enter D at once
+                self.t += self.W
+                while self.train_steps < self.t // self.F:
+                    idx = self.replay.sample_indices(self.B, self.train_steps)
+                    s, s2, a, r, done = self.replay.gather(idx)
+                    loss, _, _ = self.dqn.train_step(s, a, r, s2, done)
+                    self.losses.append(loss)
+                    self.train_steps += 1
 
 
 class _FrozenView:

@@ -116,3 +116,117 @@ def test_states_acted_from_equal_states_rebuilt_from_the_replay():
                 assert np.array_equal(s2[0], history[j + 1][lane])
             else:                                              # the gather still shows the successor frame; the target ignores it
                 assert np.array_equal(s2[0][3], history[j + 1][lane][3])
+
+
+# ---- the ablation variants (Section 5.1): Concurrent Training / Synchronized Execution switched off ----------------
+
+from oracle.algorithm1 import Ablation  # noqa: E402
+
+
+def make_variant(seed, W, C, F, B, epsilon, concurrent, synchronized, lr=1e-2, p_term=0.1):
+    dqn = odqn.OracleDQN(A, tiny_params(seed), seed=seed, desc=TINY, lr=lr)
+    rep = OracleReplay(W * 64, W, seed)
+    envs = SyntheticEnvs(synth, seed, W, A, 0.3, 0.3, p_term)
+    return Ablation(dqn, rep, envs, C, F, B, epsilon, concurrent, synchronized)
+
+
+def snapshot(alg):
+    alg.replay.flush()
+    r = alg.replay
+    return (r.frames.copy(), r.actions.copy(), r.rewards.copy(), r.terminals.copy(), list(r.count),
+            alg.envs.reward_sum, alg.envs.episodes)
+
+
+def same_snapshot(x, y):
+    return all(np.array_equal(p, q) if isinstance(p, np.ndarray) else p == q for p, q in zip(x, y))
+
+
+@pytest.mark.parametrize("concurrent", [True, False])
+def test_one_query_per_sampler_equals_the_shared_minibatch_when_greedy(concurrent):
+    # Section 4: Synchronized Execution changes how Q is computed (one minibatch of W instead of W queries), not
+    # what; with epsilon = 0 no random number enters, so both must act, store and learn identically
+    W, C, F, B = 4, 8, 4, 4
+    out = []
+    for synchronized in (True, False):
+        alg = make_variant(21, W, C, F, B, 0.0, concurrent, synchronized)
+        alg.synchronized = True                    # the random prepopulation draws depend on the query shape:
+        alg.prepopulate(24)                        # give both runs the same one
+        alg.synchronized = synchronized
+        alg.run(3 * C)
+        out.append((alg.dqn.theta.copy(), alg.dqn.theta_target.copy(), snapshot(alg), alg.train_steps, alg.act_steps))
+    assert np.array_equal(out[0][0], out[1][0]) and np.array_equal(out[0][1], out[1][1])
+    assert same_snapshot(out[0][2], out[1][2]) and out[0][3:] == out[1][3:]
+
+
+def test_unsynchronized_samplers_draw_from_their_own_counters():
+    # with exploration the W single queries use counters n*W + j (index 0), the shared minibatch counter n (index j)
+    W = 4
+    alg = make_variant(22, W, 8, 4, 4, 1.0, True, False)
+    seen = []
+    act0 = alg.dqn.act
+    def recording(states, eps, step, use_target=True):
+        seen.append((states.shape[0], step))
+        return act0(states, eps, step, use_target=use_target)
+    alg.dqn.act = recording
+    alg.prepopulate(3 * W)
+    assert seen == [(1, n * W + j) for n in range(3) for j in range(W)]
+
+
+def test_with_a_zero_step_size_all_four_variants_collect_the_same_experiences():
+    # lr = 0 keeps theta = theta^- forever, so where the parameters are read from and when training happens cannot
+    # matter: the four variants differ only in scheduling
+    W, C, F, B = 2, 8, 2, 4
+    snaps = []
+    for concurrent in (True, False):
+        for synchronized in (True, False):
+            alg = make_variant(23, W, C, F, B, 0.0, concurrent, synchronized, lr=0.0)
+            alg.synchronized = True                # same random prepopulation for all four
+            alg.prepopulate(24)
+            alg.synchronized = synchronized
+            alg.run(2 * C)
+            assert alg.train_steps == 2 * C // F
+            snaps.append(snapshot(alg))
+    assert all(same_snapshot(snaps[0], s) for s in snaps[1:])
+
+
+def test_standard_dqn_schedule():
+    # without Concurrent Training: acts from theta, which changes between rounds; t // F train steps after a round
+    # ending at t; every experience is visible to the very next minibatch
+    W, C, F, B, prepop = 2, 8, 4, 4, 24
+    alg = make_variant(24, W, C, F, B, 0.25, False, True)
+    acts, trains = [], []
+    act0, sample0 = alg.dqn.act, alg.replay.sample_indices
+    def act(states, eps, step, use_target=True):
+        acts.append((use_target, alg.train_steps, alg.dqn.theta.copy()))
+        return act0(states, eps, step, use_target=use_target)
+    def sample(Bn, step):
+        trains.append((step, alg.t, alg.replay.num_valid(), [len(x) for x in alg.replay.staged]))
+        return sample0(Bn, step)
+    alg.dqn.act, alg.replay.sample_indices = act, sample
+    alg.prepopulate(prepop)
+    n_pre = len(acts)
+    alg.run(2 * C)
+    run_acts = acts[n_pre:]
+    assert all(not use_target for use_target, _, _ in run_acts)
+    assert [k for _, k, _ in run_acts] == [(n * W) // F for n in range(2 * C // W)]      # train steps made before round n
+    changed = [not np.array_equal(run_acts[i][2], run_acts[i + 1][2]) for i in range(len(run_acts) - 1)]
+    assert changed == [run_acts[i][1] != run_acts[i + 1][1] for i in range(len(run_acts) - 1)] and any(changed)
+    assert [k for k, _, _, _ in trains] == list(range(2 * C // F))
+    for k, t, valid, staged in trains:
+        assert t == -(-(k + 1) * F // W) * W                    # the first round end with t // F > k
+        assert valid == W * ((prepop + t) // W - 4) and staged == [0] * W
+    # theta^- is theta as of the last multiple of C
+    assert alg.train_steps == 2 * C // F and alg.t == 2 * C
+
+
+def test_concurrent_training_freezes_what_the_minibatches_see():
+    # the counterpart: with Concurrent Training the number of visible transitions changes only at synchronisation points
+    W, C, F, B, prepop = 2, 8, 2, 4, 24
+    alg = make_variant(25, W, C, F, B, 0.25, True, False)
+    seen = []
+    sample0 = alg.replay.sample_indices
+    alg.replay.sample_indices = lambda Bn, step: (seen.append((step, alg.replay.num_valid())), sample0(Bn, step))[1]
+    alg.prepopulate(prepop)
+    alg.run(3 * C)
+    per_block = C // F
+    assert [v for _, v in seen] == [W * ((prepop + (k // per_block) * C) // W - 4) for k in range(3 * per_block)]
