@@ -378,6 +378,7 @@ def algorithm1(args):
     ac = P.dqn_alg1_config()
     ac.W, ac.C, ac.F, ac.B, ac.epsilon = W, C, F, B, 0.1
     ac.t_reward_neg, ac.t_reward_pos, ac.t_term = synth.thresholds(args.p_reward, args.p_reward, args.p_term)
+    ac.concurrent, ac.synchronized, ac.env_step_ns = 1, 1, args.alg1_env_ns
     ac.env_seed = args.seed
     h = P.dqn_alg1_create(ctx, rb, ac)
     # prepopulation (Table 5: N = 50000), in pieces the temporary buffers can hold; also the sampler side's rate alone
@@ -450,6 +451,8 @@ def main():
     ap.add_argument("--alg1-prepopulate", type=int, default=50000, help="prepopulation N (Table 5), rounded down to C")
     ap.add_argument("--alg1-blocks", type=int, default=20, help="timed blocks of C timesteps")
     ap.add_argument("--alg1-warmup-blocks", type=int, default=2)
+    ap.add_argument("--alg1-env-ns", type=int, default=0,
+                    help="busy time per environment step standing in for an emulator's own cost (default: none)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one MI355X: this library runs on one GPU, run with --gpus 1", file=sys.stderr)

@@ -253,8 +253,22 @@ typedef struct {
     int32_t B;             /* minibatch size (Table 5: 32)                                         */
     float epsilon;         /* exploration rate of dqn_alg1_run                                     */
     uint32_t t_reward_neg, t_reward_pos, t_term;   /* thresholds on 24-bit draws, see above        */
+    int32_t concurrent;    /* 1: Concurrent Training (Section 3); 0: standard DQN, see below       */
+    int32_t synchronized;  /* 1: Synchronized Execution (Section 4); 0: one query per sampler      */
+    uint32_t env_step_ns;  /* extra busy time per environment step standing in for an emulator's
+                              own cost (0: none); changes timing only                              */
+    uint32_t reserved;     /* 0                                                                    */
     uint64_t env_seed;     /* seed of the synthetic environments                                   */
 } dqn_alg1_config;
+
+/* The ablation of Section 5.1.  synchronized = 0: in every round of W timesteps each sampler thread makes
+ * its own dqn_act call on its own state (W = 1; environment j at round k uses act_step = k * W + j), its
+ * own download of the action, and after its environment step its own upload and replay_push; the
+ * threads' calls are serialised by a mutex.  concurrent = 0: the policy reads theta (use_target = 0); after
+ * every round the pending experiences are appended and flushed into D (replay_flush) and the calling
+ * thread makes the train steps that have become due -- t / F train steps have been made once the
+ * timestep counter stands at t -- before the next round; theta^- <- theta still every C timesteps; the
+ * trainer thread stays idle. */
 
 typedef struct dqn_alg1 dqn_alg1;
 

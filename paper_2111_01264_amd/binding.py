@@ -27,6 +27,7 @@ class dqn_alg1_config(C.Structure):
     _fields_ = [
         ("W", C.c_int32), ("C", C.c_int32), ("F", C.c_int32), ("B", C.c_int32), ("epsilon", C.c_float),
         ("t_reward_neg", C.c_uint32), ("t_reward_pos", C.c_uint32), ("t_term", C.c_uint32),
+        ("concurrent", C.c_int32), ("synchronized", C.c_int32), ("env_step_ns", C.c_uint32), ("reserved", C.c_uint32),
         ("env_seed", C.c_uint64),
     ]
 

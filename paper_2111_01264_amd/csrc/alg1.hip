@@ -13,7 +13,14 @@
 // flags) and one download (W actions), whatever W is.  The frame stacks themselves stay on the device: a small kernel
 // shifts each stack and appends the new frame, clearing what belongs to a finished episode (the rule the replay
 // gather applies, so the states acted from are the states training later rebuilds).
+//
+// The ablation of Section 5.1 switches the two techniques off independently.  Without Synchronized Execution every
+// sampler thread queries the network by itself (its own batch-1 dqn_act, its own transfers, its own append), the calls
+// serialised by a mutex as a single device serialises them; without Concurrent Training the loop is standard DQN: the
+// policy reads theta, every round's experiences are flushed into D at once and the calling thread itself makes the train
+// steps that have become due (one per F timesteps) before the next round.
 #include <atomic>
+#include <chrono>
 #include <condition_variable>
 #include <mutex>
 #include <new>
@@ -104,8 +111,14 @@ struct dqn_alg1 {
     std::mutex mu;
     std::condition_variable cv_work, cv_done;
     uint64_t sampler_gen = 0, trainer_gen = 0;
-    int sampler_task = 0;     // 0: observation o_0, 1: one environment step
+    int sampler_task = 0;     // 0: observation o_0, 1: one environment step, 2: own network query + environment step
+    float task_epsilon = 0.f; // task 2: exploration rate and parameter set of the query
+    int task_use_target = 1;
     int samplers_done = 0;
+    int sampler_rc = DQN_OK;  // first error of a sampler thread's device calls
+    char sampler_err[256] = {0};
+    std::mutex gpu_mu;        // serialises the sampler threads' device calls (task 2)
+    hipEvent_t ev_query[kMaxLanes] = {};
     bool trainer_busy = false, stop = false;
     int trainer_rc = DQN_OK;
     char trainer_err[256] = {0};
@@ -116,6 +129,60 @@ struct dqn_alg1 {
 };
 
 namespace {
+
+// One step of environment j with the action in the shared array: (r_n, d_n) and o_{n+1} into the shared arrays.
+void sampler_env_step(dqn_alg1* h, int j, int64_t n, int nb)
+{
+    const int W = h->cfg.W;
+    const auto t0 = std::chrono::steady_clock::now();
+    const uint64_t id = static_cast<uint64_t>(n) * W + j;
+    const uint64_t w = mix64_host(mix64_host(h->key_meta + id) + kGammaEnv);
+    const uint32_t rbits = static_cast<uint32_t>(w & 0xFFFFFFu), tbits = static_cast<uint32_t>((w >> 24) & 0xFFFFFFu);
+    const uint32_t abits = static_cast<uint32_t>((w >> 48) & 0xFFFFu);
+    const int good = static_cast<int>((abits * static_cast<uint32_t>(h->A)) >> 16);
+    float r = rbits < h->t_neg ? -1.f : (rbits >= (1u << 24) - h->t_pos ? 1.f : 0.f);
+    if (h->h_actions[j] != good) r = 0.f;
+    h->h_rewards[j] = r;
+    h->h_terminals[j] = tbits < h->t_term ? 1 : 0;
+    env_frame_host(h->key_env, id + W, h->h_frames[nb] + static_cast<size_t>(j) * kFrameBytes);
+    if (h->cfg.env_step_ns) {   // stand-in for the emulator's own time per step
+        const auto until = t0 + std::chrono::nanoseconds(h->cfg.env_step_ns);
+        while (std::chrono::steady_clock::now() < until) {}
+    }
+}
+
+// Without Synchronized Execution: sampler j evaluates its own state (a minibatch of one) and fetches its action.
+int sampler_query(dqn_alg1* h, int j, int64_t n)
+{
+    {
+        std::lock_guard<std::mutex> g(h->gpu_mu);
+        const int rc = dqn_act(h->ctx, h->d_states + static_cast<size_t>(j) * kStateBytes, 1, h->task_epsilon,
+                               static_cast<uint64_t>(h->act_steps) * h->cfg.W + j, h->task_use_target, h->d_actions + j, nullptr);
+        if (rc != DQN_OK) return rc;
+        DQN_HIP(hipMemcpyAsync(h->h_actions + j, h->d_actions + j, sizeof(int32_t), hipMemcpyDeviceToHost, h->act_stream));
+        DQN_HIP(hipEventRecord(h->ev_query[j], h->act_stream));
+    }
+    (void)n;
+    DQN_HIP(hipEventSynchronize(h->ev_query[j]));
+    return DQN_OK;
+}
+
+// ... and hands its experience and its next observation to the device by itself.
+int sampler_commit(dqn_alg1* h, int j, int nb)
+{
+    std::lock_guard<std::mutex> g(h->gpu_mu);
+    uint8_t* stack = h->d_states + static_cast<size_t>(j) * kStateBytes;
+    uint8_t* fresh = h->d_frames[nb] + static_cast<size_t>(j) * kFrameBytes;
+    DQN_HIP(hipMemcpyAsync(fresh, h->h_frames[nb] + static_cast<size_t>(j) * kFrameBytes, kFrameBytes, hipMemcpyHostToDevice, h->act_stream));
+    DQN_HIP(hipMemcpyAsync(h->d_rewards + j, h->h_rewards + j, sizeof(float), hipMemcpyHostToDevice, h->act_stream));
+    DQN_HIP(hipMemcpyAsync(h->d_terminals + j, h->h_terminals + j, 1, hipMemcpyHostToDevice, h->act_stream));
+    // the newest frame of the stack is the observation the action was taken on
+    const int rc = replay_push(h->rb, j, stack + 3 * kFrameBytes, h->d_actions + j, h->d_rewards + j, h->d_terminals + j, 1);
+    if (rc != DQN_OK) return rc;
+    hipLaunchKernelGGL(env_advance_kernel, dim3(1), dim3(256), 0, h->act_stream, stack, fresh, h->d_terminals + j);
+    DQN_LAUNCH_CHECK();
+    return DQN_OK;
+}
 
 void sampler_main(dqn_alg1* h, int j)
 {
@@ -132,20 +199,22 @@ void sampler_main(dqn_alg1* h, int j)
             task = h->sampler_task; n = h->n; nb = h->cur ^ 1;
         }
         const int W = h->cfg.W;
+        int rc = DQN_OK;
         if (task == 0) {
             env_frame_host(h->key_env, static_cast<uint64_t>(j), h->h_frames[h->cur] + static_cast<size_t>(j) * kFrameBytes);
         } else {
-            // one step of environment j with the action the main thread distributed: (r_n, d_n), then o_{n+1}
-            const uint64_t id = static_cast<uint64_t>(n) * W + j;
-            const uint64_t w = mix64_host(mix64_host(h->key_meta + id) + kGammaEnv);
-            const uint32_t rb = static_cast<uint32_t>(w & 0xFFFFFFu), tb = static_cast<uint32_t>((w >> 24) & 0xFFFFFFu);
-            const uint32_t ab = static_cast<uint32_t>((w >> 48) & 0xFFFFu);
-            const int good = static_cast<int>((ab * static_cast<uint32_t>(h->A)) >> 16);
-            float r = rb < h->t_neg ? -1.f : (rb >= (1u << 24) - h->t_pos ? 1.f : 0.f);
-            if (h->h_actions[j] != good) r = 0.f;
-            h->h_rewards[j] = r;
-            h->h_terminals[j] = tb < h->t_term ? 1 : 0;
-            env_frame_host(h->key_env, id + W, h->h_frames[nb] + static_cast<size_t>(j) * kFrameBytes);
+            if (task == 2) rc = sampler_query(h, j, n);
+            if (rc == DQN_OK) {
+                sampler_env_step(h, j, n, nb);
+                if (task == 2) rc = sampler_commit(h, j, nb);
+            }
+        }
+        if (rc != DQN_OK) {
+            std::lock_guard<std::mutex> lk(h->mu);
+            if (h->sampler_rc == DQN_OK) {
+                h->sampler_rc = rc;
+                snprintf(h->sampler_err, sizeof(h->sampler_err), "%s", dqn_last_error());
+            }
         }
         {
             std::lock_guard<std::mutex> lk(h->mu);
@@ -228,19 +297,47 @@ int start_envs(dqn_alg1* h)
     return DQN_OK;
 }
 
-// One act step: Q for all W states in one minibatch, actions to the samplers, one environment step each.
-int act_step(dqn_alg1* h, float epsilon)
+int sampler_error(dqn_alg1* h)
 {
+    std::lock_guard<std::mutex> lk(h->mu);
+    if (h->sampler_rc == DQN_OK) return DQN_OK;
+    const int rc = h->sampler_rc;
+    h->sampler_rc = DQN_OK;
+    return fail(rc, "sampler thread: %s", h->sampler_err);
+}
+
+// One round without Synchronized Execution: every sampler thread queries the network for its own state, steps its
+// environment and hands the experience and the next observation to the device itself.
+int round_unsynchronized(dqn_alg1* h, float epsilon, int use_target)
+{
+    const int W = h->cfg.W;
+    h->task_epsilon = epsilon;
+    h->task_use_target = use_target;
+    run_samplers(h, 2);
+    const int rc = sampler_error(h);
+    if (rc != DQN_OK) return rc;
+    for (int j = 0; j < W; ++j) { h->reward_sum += h->h_rewards[j]; h->episodes += h->h_terminals[j]; }
+    ++h->act_steps;
+    h->cur ^= 1;
+    ++h->n;
+    h->t += W;
+    return DQN_OK;
+}
+
+// One act step: Q for all W states in one minibatch, actions to the samplers, one environment step each.
+int act_step(dqn_alg1* h, float epsilon, int use_target)
+{
+    if (!h->cfg.synchronized) return round_unsynchronized(h, epsilon, use_target);
     const int W = h->cfg.W;
     int rc;
     if (h->pending) {
         // experience n-1 = (o_{n-1}, a_{n-1}, r_{n-1}, d_{n-1}) rides in this step's launches; a_{n-1} is read from the
         // actions buffer before the same call overwrites it with a_n
         rc = dqn_act_push_step(h->ctx, h->rb, h->d_frames[h->cur ^ 1], h->d_actions, h->d_rewards, h->d_terminals, h->d_states, W, epsilon,
-                               static_cast<uint64_t>(h->act_steps), 1, h->d_actions, nullptr);
+                               static_cast<uint64_t>(h->act_steps), use_target, h->d_actions, nullptr);
         h->pending = false;
     } else {
-        rc = dqn_act(h->ctx, h->d_states, W, epsilon, static_cast<uint64_t>(h->act_steps), 1, h->d_actions, nullptr);
+        rc = dqn_act(h->ctx, h->d_states, W, epsilon, static_cast<uint64_t>(h->act_steps), use_target, h->d_actions, nullptr);
     }
     if (rc != DQN_OK) return rc;
     DQN_HIP(hipMemcpyAsync(h->h_actions, h->d_actions, W * sizeof(int32_t), hipMemcpyDeviceToHost, h->act_stream));
@@ -285,6 +382,8 @@ int dqn_alg1_create(dqn_ctx* ctx, replay* rb, const dqn_alg1_config* cfg, dqn_al
     if (cfg->t_reward_neg > (1u << 24) || cfg->t_reward_pos > (1u << 24) || cfg->t_term > (1u << 24) ||
         static_cast<uint64_t>(cfg->t_reward_neg) + cfg->t_reward_pos > (1u << 24))
         return fail(DQN_EINVAL, "dqn_alg1_create: environment thresholds exceed 2^24");
+    if ((cfg->concurrent != 0 && cfg->concurrent != 1) || (cfg->synchronized != 0 && cfg->synchronized != 1))
+        return fail(DQN_EINVAL, "dqn_alg1_create: concurrent and synchronized must be 0 or 1");
     dqn_alg1* h = new (std::nothrow) dqn_alg1();
     if (!h) return fail(DQN_ENOMEM, "dqn_alg1_create: host allocation failed");
     h->ctx = ctx; h->rb = rb; h->cfg = *cfg; h->A = dqn_ctx_num_actions(ctx); h->act_stream = dqn_ctx_act_stream(ctx);
@@ -305,6 +404,7 @@ int dqn_alg1_create(dqn_ctx* ctx, replay* rb, const dqn_alg1_config* cfg, dqn_al
         DQN_HIP(hipMalloc(reinterpret_cast<void**>(&h->d_actions), W * sizeof(int32_t)));
         DQN_HIP(hipMalloc(reinterpret_cast<void**>(&h->d_rewards), W * sizeof(float)));
         DQN_HIP(hipMalloc(reinterpret_cast<void**>(&h->d_terminals), W));
+        for (int j = 0; j < W; ++j) DQN_HIP(hipEventCreateWithFlags(&h->ev_query[j], hipEventDisableTiming));
         DQN_HIP(hipDeviceSynchronize());
         return DQN_OK;
     };
@@ -334,6 +434,8 @@ int dqn_alg1_destroy(dqn_alg1* h)
     if (h->trainer.joinable()) h->trainer.join();
     if (h->act_stream) (void)hipStreamSynchronize(h->act_stream);
     for (int i = 0; i < 2; ++i) { (void)hipHostFree(h->h_frames[i]); (void)hipFree(h->d_frames[i]); }
+    for (int j = 0; j < kMaxLanes; ++j)
+        if (h->ev_query[j]) (void)hipEventDestroy(h->ev_query[j]);
     (void)hipHostFree(h->h_actions); (void)hipHostFree(h->h_rewards); (void)hipHostFree(h->h_terminals);
     (void)hipFree(h->d_states); (void)hipFree(h->d_actions); (void)hipFree(h->d_rewards); (void)hipFree(h->d_terminals);
     delete h;
@@ -349,7 +451,7 @@ int dqn_alg1_prepopulate(dqn_alg1* h, int64_t timesteps)
     if (!h->started && (rc = start_envs(h)) != DQN_OK) return rc;
     const int64_t t0 = h->t;
     for (int64_t k = 0; k < timesteps / h->cfg.W; ++k)
-        if ((rc = act_step(h, 1.f)) != DQN_OK) return rc;
+        if ((rc = act_step(h, 1.f, 1)) != DQN_OK) return rc;
     h->t = t0;   // prepopulation does not count as timesteps of the algorithm
     if ((rc = append_pending(h)) != DQN_OK) return rc;
     return replay_flush(h->rb, 1);
@@ -367,17 +469,31 @@ int dqn_alg1_run(dqn_alg1* h, int64_t timesteps)
         if ((rc = wait_trainer(h)) != DQN_OK) return rc;
         if ((rc = append_pending(h)) != DQN_OK) return rc;
         if ((rc = dqn_sync_target(h->ctx, h->rb, 0)) != DQN_OK) return rc;
-        {
-            std::lock_guard<std::mutex> lk(h->mu);
-            h->trainer_first = h->train_steps;
-            h->trainer_count = C / F;
-            h->trainer_busy = true;
-            ++h->trainer_gen;
-            h->cv_work.notify_all();
+        if (h->cfg.concurrent) {
+            {
+                std::lock_guard<std::mutex> lk(h->mu);
+                h->trainer_first = h->train_steps;
+                h->trainer_count = C / F;
+                h->trainer_busy = true;
+                ++h->trainer_gen;
+                h->cv_work.notify_all();
+            }
+            h->train_steps += C / F;
+            for (int k = 0; k < C / W; ++k)
+                if ((rc = act_step(h, h->cfg.epsilon, 1)) != DQN_OK) return rc;
+            continue;
         }
-        h->train_steps += C / F;
-        for (int k = 0; k < C / W; ++k)
-            if ((rc = act_step(h, h->cfg.epsilon)) != DQN_OK) return rc;
+        // standard DQN (Section 2.1): act from theta; the round's experiences enter D at once; then the train steps that
+        // have become due, on this thread -- the next round's Q evaluation waits for them on the device
+        for (int k = 0; k < C / W; ++k) {
+            if ((rc = act_step(h, h->cfg.epsilon, 0)) != DQN_OK) return rc;
+            if ((rc = append_pending(h)) != DQN_OK) return rc;
+            if ((rc = replay_flush(h->rb, 0)) != DQN_OK) return rc;
+            while (h->train_steps < h->t / F) {
+                if ((rc = dqn_train_step_sampled(h->ctx, h->rb, h->cfg.B, static_cast<uint64_t>(h->train_steps), 0, nullptr)) != DQN_OK) return rc;
+                ++h->train_steps;
+            }
+        }
     }
     return wait_trainer(h);   // every launch of the last block has been issued when this returns
 }

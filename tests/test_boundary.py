@@ -58,5 +58,5 @@ def test_validation_errors_before_device_work():
 
 
 def test_alg1_config_struct_matches_header_size():
-    # 4 int32 + float + 3 uint32 + uint64
-    assert C.sizeof(P.dqn_alg1_config) == 40
+    # 4 int32 + float + 3 uint32 + 2 int32 + 2 uint32 + uint64
+    assert C.sizeof(P.dqn_alg1_config) == 56

@@ -8,7 +8,7 @@ import torch
 import paper_2111_01264_amd as P
 from datagen import synth
 from oracle import dqn as odqn
-from oracle.algorithm1 import Algorithm1, SyntheticEnvs
+from oracle.algorithm1 import Ablation, Algorithm1, SyntheticEnvs
 from oracle.replay import OracleReplay
 from gpu_util import blob_slices, dev, make_cfg, rel_err
 
@@ -17,10 +17,11 @@ pytestmark = pytest.mark.gpu
 P_NEG, P_POS, P_TERM = 0.3, 0.3, 0.1
 
 
-def alg1_cfg(W, C, F, B, epsilon, seed):
+def alg1_cfg(W, C, F, B, epsilon, seed, concurrent=1, synchronized=1):
     c = P.dqn_alg1_config()
     c.W, c.C, c.F, c.B, c.epsilon = W, C, F, B, epsilon
     c.t_reward_neg, c.t_reward_pos, c.t_term = synth.thresholds(P_NEG, P_POS, P_TERM)
+    c.concurrent, c.synchronized = concurrent, synchronized
     c.env_seed = seed
     return c
 
@@ -42,7 +43,7 @@ def read_replay(rb, idx):
     return [x.cpu().numpy() for x in (s, s2, a, r, d)]
 
 
-def run_native(precision, seed, A, W, C, F, B, epsilon, prepop, blocks, M):
+def run_native(precision, seed, A, W, C, F, B, epsilon, prepop, blocks, M, concurrent=1, synchronized=1):
     cfg = make_cfg(A, max_batch=B, max_envs=W, precision=precision, seed=seed)
     sa, stt = torch.cuda.Stream(), torch.cuda.Stream()
     ctx = P.dqn_create(cfg, sa, stt)
@@ -52,7 +53,7 @@ def run_native(precision, seed, A, W, C, F, B, epsilon, prepop, blocks, M):
         theta = synth.init_params(seed, A)
         P.dqn_set_params(ctx, P.DQN_PARAMS_ONLINE, theta)
         P.dqn_set_params(ctx, P.DQN_PARAMS_TARGET, theta)
-        h = P.dqn_alg1_create(ctx, rb, alg1_cfg(W, C, F, B, epsilon, seed))
+        h = P.dqn_alg1_create(ctx, rb, alg1_cfg(W, C, F, B, epsilon, seed, concurrent, synchronized))
         P.dqn_alg1_prepopulate(h, prepop)
         assert P.replay_num_valid(rb) == W * (prepop // W - 4)
         # two calls: the second continues where the first stopped
@@ -63,7 +64,10 @@ def run_native(precision, seed, A, W, C, F, B, epsilon, prepop, blocks, M):
         P.dqn_alg1_flush(h)
         torch.cuda.synchronize()
         counts = [min(M, (prepop + blocks * C) // W)] * W
-        assert before_flush == W * (min(M, (prepop + (blocks - 1) * C) // W) - 4)   # last block still buffered
+        if concurrent:
+            assert before_flush == W * (min(M, (prepop + (blocks - 1) * C) // W) - 4)   # last block still buffered
+        else:
+            assert before_flush == W * (counts[0] - 4)                                  # standard DQN buffers nothing
         assert P.replay_num_valid(rb) == W * (counts[0] - 4)
         rep = read_replay(rb, valid_indices(counts, M))
         th = P.dqn_get_params(ctx, P.DQN_PARAMS_ONLINE)
@@ -176,3 +180,38 @@ def test_algorithm1_threads_equal_call_by_call_bitwise(precision):
     for got, ref in zip(ra, rb_):
         assert np.array_equal(got, ref)
     assert np.array_equal(tha, thb) and np.array_equal(tta, ttb)
+
+
+@pytest.mark.parametrize("concurrent,synchronized", [(0, 0), (0, 1), (1, 0)], ids=["standard", "synchronized", "concurrent"])
+def test_ablation_variants_match_oracle_fp32(concurrent, synchronized):
+    # Section 5.1: the two techniques switched off independently -- per-sampler queries (own epsilon-greedy counters),
+    # standard DQN's schedule (acts from theta, experiences visible at once, train steps due every F timesteps)
+    seed, A, W, C, F, B, epsilon, prepop, blocks, M = 2111012643, 6, 4, 16, 4, 8, 0.2, 48, 2, 64
+    stats, rep, th, tt = run_native(P.DQN_PRECISION_FP32, seed, A, W, C, F, B, epsilon, prepop, blocks, M, concurrent, synchronized)
+    dqn = odqn.OracleDQN(A, synth.init_params(seed, A), seed=seed)
+    orep = OracleReplay(W * M, W, seed)
+    envs = SyntheticEnvs(synth, seed, W, A, P_NEG, P_POS, P_TERM)
+    alg = Ablation(dqn, orep, envs, C, F, B, epsilon, bool(concurrent), bool(synchronized))
+    alg.prepopulate(prepop)
+    alg.run(blocks * C)
+    assert stats == {"t": alg.t, "act_steps": alg.act_steps, "train_steps": alg.train_steps,
+                     "reward_sum": envs.reward_sum, "episodes": envs.episodes}
+    orep.flush()
+    want = orep.gather(valid_indices(list(orep.count), M))
+    for got, ref in zip(rep, want):
+        assert np.array_equal(got, ref)
+    for name, slc in blob_slices(A).items():
+        assert rel_err(th[slc], dqn.theta[slc]) <= 1e-3, name
+        assert rel_err(tt[slc], dqn.theta_target[slc]) <= 1e-3, name
+
+
+@pytest.mark.parametrize("concurrent", [0, 1], ids=["standard", "concurrent"])
+def test_free_running_sampler_threads_are_reproducible_bf16(concurrent):
+    # without Synchronized Execution the W threads reach the device in whatever order the scheduler gives them; nothing
+    # they compute may depend on that order (each owns its state, its lane and its counter), so two runs agree bit for bit
+    args = (P.DQN_PRECISION_BF16, 2111012644, 6, 8, 32, 4, 32, 0.1, 64, 2, 40, concurrent, 0)
+    a, b = run_native(*args), run_native(*args)
+    assert a[0] == b[0] and a[0]["train_steps"] == 2 * 32 // 4 and a[0]["act_steps"] == (64 + 2 * 32) // 8
+    for x, y in zip(a[1], b[1]):
+        assert np.array_equal(x, y)
+    assert np.array_equal(a[2], b[2]) and np.array_equal(a[3], b[3])
