@@ -354,13 +354,12 @@ def cpu_baseline(args):
                       % (done_steps, args.acts_per_train, W, B, el)}
 
 
-def algorithm1(args):
-    """Algorithm 1 end to end (dqn_alg1_*): W sampler threads on synthetic host environments, the trainer thread,
-    synchronisation every C timesteps.  Prints one JSON line of its own; not the headline metric."""
+def run_alg1(args, W, concurrent, synchronized, blocks, warmup_blocks, prepopulate, frames):
+    """One timed run of the orchestrator; returns rates and totals."""
     import torch
     import paper_2111_01264_amd as P
     from datagen import synth
-    W, C, F, B, A = args.envs, args.alg1_c, args.alg1_f, args.batch, args.actions
+    C, F, B, A = args.alg1_c, args.alg1_f, args.batch, args.actions
     torch.cuda.set_device(0)
     sa, stt = torch.cuda.Stream(), torch.cuda.Stream()
     cfg = P.dqn_config()
@@ -373,50 +372,94 @@ def algorithm1(args):
     theta = synth.init_params(args.seed, A)
     P.dqn_set_params(ctx, P.DQN_PARAMS_ONLINE, theta)
     P.dqn_set_params(ctx, P.DQN_PARAMS_TARGET, theta)
-    frames = args.frames - args.frames % W
+    frames -= frames % W
     rb = P.replay_create(frames, W, C // W, args.seed, sa, stt)
     ac = P.dqn_alg1_config()
     ac.W, ac.C, ac.F, ac.B, ac.epsilon = W, C, F, B, 0.1
     ac.t_reward_neg, ac.t_reward_pos, ac.t_term = synth.thresholds(args.p_reward, args.p_reward, args.p_term)
-    ac.concurrent, ac.synchronized, ac.env_step_ns = 1, 1, args.alg1_env_ns
+    ac.concurrent, ac.synchronized, ac.env_step_ns = concurrent, synchronized, args.alg1_env_ns
     ac.env_seed = args.seed
     h = P.dqn_alg1_create(ctx, rb, ac)
-    # prepopulation (Table 5: N = 50000), in pieces the temporary buffers can hold; also the sampler side's rate alone
-    n_pre = args.alg1_prepopulate - args.alg1_prepopulate % C
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(n_pre // C):
-        P.dqn_alg1_prepopulate(h, C)
-    torch.cuda.synchronize()
-    pre_s = time.perf_counter() - t0
-    P.dqn_alg1_run(h, C * max(args.alg1_warmup_blocks, 1))
-    torch.cuda.synchronize()
-    blocks = args.alg1_blocks
-    t0 = time.perf_counter()
-    P.dqn_alg1_run(h, C * blocks)
-    torch.cuda.synchronize()
-    el = time.perf_counter() - t0
-    stats = P.dqn_alg1_stats(h)
-    P.dqn_alg1_destroy(h)
-    P.replay_destroy(rb)
-    P.dqn_destroy(ctx)
+    try:
+        # prepopulation (Table 5: N = 50000), in pieces the temporary buffers can hold; also the sampler side's rate alone
+        n_pre = prepopulate - prepopulate % C
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(n_pre // C):
+            P.dqn_alg1_prepopulate(h, C)
+        torch.cuda.synchronize()
+        pre_s = time.perf_counter() - t0
+        if warmup_blocks:
+            P.dqn_alg1_run(h, C * warmup_blocks)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        P.dqn_alg1_run(h, C * blocks)
+        torch.cuda.synchronize()
+        el = time.perf_counter() - t0
+        stats = P.dqn_alg1_stats(h)
+    finally:
+        torch.cuda.synchronize()
+        P.dqn_alg1_destroy(h)
+        P.replay_destroy(rb)
+        P.dqn_destroy(ctx)
+    return {"elapsed": el, "timesteps_per_sec": C * blocks / el, "train_steps_per_sec": C // F * blocks / el,
+            "act_rounds_per_sec": C // W * blocks / el, "samplers_alone_timesteps_per_sec": n_pre / pre_s if n_pre else None,
+            "prepopulated": n_pre, "frames": frames, "totals": stats}
+
+
+ALG1_CONTEXT = ("paper: 200M frames = 50M timesteps in 9 h on one GTX 1080 with the real emulator (about 1,500 "
+                "timesteps/s); here the environment is a seeded frame generator, so this rate bounds the loop "
+                "around the emulator, not the emulator")
+
+
+def algorithm1(args):
+    """Algorithm 1 end to end (dqn_alg1_*): W sampler threads on synthetic host environments, the trainer thread,
+    synchronisation every C timesteps.  Prints one JSON line of its own; not the headline metric."""
+    W, C, F, B, A = args.envs, args.alg1_c, args.alg1_f, args.batch, args.actions
+    blocks, warm = args.alg1_blocks, max(args.alg1_warmup_blocks, 1)
+    r = run_alg1(args, W, 1, 1, blocks, warm, args.alg1_prepopulate, args.frames)
     out = {
         "metric": "Algorithm 1 timesteps/sec (W=%d synthetic host environments, batch %d)" % (W, B),
-        "value": C * blocks / el, "unit": "timesteps/s",
-        "train_steps_per_sec": C // F * blocks / el, "act_steps_per_sec": C // W * blocks / el,
-        "samplers_alone_timesteps_per_sec": n_pre / pre_s if n_pre else None,
-        "n_gpus": 1, "steps": blocks, "warmup": max(args.alg1_warmup_blocks, 1), "ms_per_step": 1e3 * el / blocks,
+        "value": r["timesteps_per_sec"], "unit": "timesteps/s",
+        "train_steps_per_sec": r["train_steps_per_sec"], "act_steps_per_sec": r["act_rounds_per_sec"],
+        "samplers_alone_timesteps_per_sec": r["samplers_alone_timesteps_per_sec"],
+        "n_gpus": 1, "steps": blocks, "warmup": warm, "ms_per_step": 1e3 * r["elapsed"] / blocks,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if args.precision == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": "Algorithm 1, Table 5 schedule: A=%d, W=%d, C=%d, F=%d, batch %d, replay %d frames, "
-                               "prepopulation %d; a step is one block of C timesteps" % (A, W, C, F, B, frames, n_pre),
+                               "prepopulation %d, %d ns of stand-in emulator time per environment step; a step is one "
+                               "block of C timesteps" % (A, W, C, F, B, r["frames"], r["prepopulated"], args.alg1_env_ns),
                    "seed": args.seed},
-        "totals": stats,
-        "context": "paper: 200M frames = 50M timesteps in 9 h on one GTX 1080 with the real emulator (about 1,500 "
-                   "timesteps/s); here the environment is a seeded frame generator, so this rate bounds the loop "
-                   "around the emulator, not the emulator",
+        "totals": r["totals"], "context": ALG1_CONTEXT,
     }
     print(json.dumps(out))
+    return 0
+
+
+def ablation(args):
+    """The shape of Tables 1-3 (Section 5.1) on synthetic environments: {standard, concurrent, synchronized, both} x
+    W in {1, 2, 4, 8} (synchronization needs W > 1: 14 variants), timesteps/s each and the speed-up over standard
+    DQN with one sampler.  Prints a table, then one JSON line."""
+    C = args.alg1_c
+    rows = []
+    for name, conc, sync in (("standard", 0, 0), ("concurrent", 1, 0), ("synchronized", 0, 1), ("both", 1, 1)):
+        for W in (1, 2, 4, 8):
+            if sync and W == 1:
+                continue
+            r = run_alg1(args, W, conc, sync, args.alg1_blocks, 1, C, min(args.frames, 200000))
+            rows.append({"variant": name, "W": W, "timesteps_per_sec": r["timesteps_per_sec"],
+                         "hours_per_50M_timesteps": 50e6 / r["timesteps_per_sec"] / 3600})
+    base = rows[0]["timesteps_per_sec"]
+    for r in rows:
+        r["speedup"] = r["timesteps_per_sec"] / base
+        print("%-13s W=%d  %9.0f timesteps/s  %6.2f h per 50M timesteps  x%.2f" %
+              (r["variant"], r["W"], r["timesteps_per_sec"], r["hours_per_50M_timesteps"], r["speedup"]), file=sys.stderr)
+    print(json.dumps({"metric": "ablation of Section 5.1 on synthetic environments, timesteps/sec", "unit": "timesteps/s",
+                      "rows": rows, "n_gpus": 1, "data": "synthetic", "dtype": "bf16" if args.precision == "bf16" else "f32",
+                      "config": {"workload": "A=%d, C=%d, F=%d, batch %d, %d timed blocks of C timesteps per variant, %d ns of "
+                                             "stand-in emulator time per environment step"
+                                             % (args.actions, C, args.alg1_f, args.batch, args.alg1_blocks, args.alg1_env_ns)},
+                      "context": ALG1_CONTEXT}))
     return 0
 
 
@@ -446,6 +489,8 @@ def main():
     ap.add_argument("--sweep", action="store_true", help="print the batch/W roofline sweep instead of the JSON line")
     ap.add_argument("--algorithm1", action="store_true",
                     help="time the Algorithm 1 orchestrator (dqn_alg1_*) instead: one JSON line of its own")
+    ap.add_argument("--ablation", action="store_true",
+                    help="the 14 variants of the Section 5.1 ablation on synthetic environments (table + one JSON line)")
     ap.add_argument("--alg1-c", type=int, default=10000, help="target update period C in timesteps (Table 5)")
     ap.add_argument("--alg1-f", type=int, default=4, help="training period F in timesteps (Table 5)")
     ap.add_argument("--alg1-prepopulate", type=int, default=50000, help="prepopulation N (Table 5), rounded down to C")
@@ -462,6 +507,8 @@ def main():
         return sweep(args)
     if args.algorithm1:
         return algorithm1(args)
+    if args.ablation:
+        return ablation(args)
 
     wl = Workload(args)
     groups = 3 if args.double_dqn else 2
