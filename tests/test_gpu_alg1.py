@@ -215,3 +215,55 @@ def test_free_running_sampler_threads_are_reproducible_bf16(concurrent):
     for x, y in zip(a[1], b[1]):
         assert np.array_equal(x, y)
     assert np.array_equal(a[2], b[2]) and np.array_equal(a[3], b[3])
+
+
+def test_algorithm1_argument_and_state_errors():
+    seed, A, W, M = 5, 4, 4, 32
+    cfg = make_cfg(A, max_batch=8, max_envs=W, precision=P.DQN_PRECISION_BF16, seed=seed)
+    sa, stt = torch.cuda.Stream(), torch.cuda.Stream()
+    ctx = P.dqn_create(cfg, sa, stt)
+    rb = P.replay_create(W * M, W, 4, seed, sa, stt)             # temporary buffers hold 4 experiences per lane
+    rb2 = P.replay_create(2 * M, 2, 4, seed, sa, stt)
+    rb3 = P.replay_create(W * M, W, 4, seed, stt, stt)           # pushes on the train stream
+    try:
+        theta = synth.init_params(seed, A)
+        P.dqn_set_params(ctx, P.DQN_PARAMS_ONLINE, theta)
+        P.dqn_set_params(ctx, P.DQN_PARAMS_TARGET, theta)
+        def bad(**kw):
+            base = dict(W=W, C=16, F=4, B=8, epsilon=0.1, seed=seed)
+            rbx = kw.pop("rb", rb)
+            flags = {k: kw.pop(k) for k in ("concurrent", "synchronized") if k in kw}
+            base.update(kw)
+            c = alg1_cfg(**base)
+            for k, v in flags.items():
+                setattr(c, k, v)
+            with pytest.raises(P.DqnError) as e:
+                P.dqn_alg1_create(ctx, rbx, c)
+            assert e.value.code == P.DQN_EINVAL
+        bad(C=18)                 # not a multiple of W
+        bad(C=16, F=3)            # not a multiple of F
+        bad(B=9)                  # above max_batch
+        bad(W=5)                  # above max_envs
+        bad(epsilon=1.5)
+        bad(rb=rb2)               # lanes != W
+        bad(rb=rb3)               # push stream is not the act stream
+        bad(concurrent=2)
+        # temporary buffers too small for a block: the run reports it instead of overwriting anything
+        h = P.dqn_alg1_create(ctx, rb, alg1_cfg(W, 32, 4, 8, 0.1, seed))   # C / W = 8 > 4
+        try:
+            P.dqn_alg1_prepopulate(h, 16)                        # 4 per lane: fits
+            with pytest.raises(P.DqnError):
+                P.dqn_alg1_prepopulate(h, 6)                     # not a multiple of W
+            with pytest.raises(P.DqnError):
+                P.dqn_alg1_run(h, 48)                            # not a multiple of C
+            with pytest.raises(P.DqnError) as e:
+                P.dqn_alg1_run(h, 32)
+            assert e.value.code == P.DQN_ESTATE
+            torch.cuda.synchronize()
+        finally:
+            P.dqn_alg1_destroy(h)
+    finally:
+        torch.cuda.synchronize()
+        for r in (rb, rb2, rb3):
+            P.replay_destroy(r)
+        P.dqn_destroy(ctx)
