@@ -9,10 +9,12 @@
 //
 // The environments are synthetic (a seeded frame generator stands in for the Atari emulator, see the header): they
 // live on the host, as an emulator would, one per sampler thread.  States, actions, rewards and terminal flags cross
-// the bus through pinned "shared arrays" (Section 4) -- per act step one batched upload (W new frames, W rewards, W
-// flags) and one download (W actions), whatever W is.  The frame stacks themselves stay on the device: a small kernel
-// shifts each stack and appends the new frame, clearing what belongs to a finished episode (the rule the replay
-// gather applies, so the states acted from are the states training later rebuilds).
+// the bus through pinned "shared arrays" (Section 4) that both the threads and the kernels address directly: the act
+// step's last kernel stores the W actions into the pinned array, and after the samplers' step one small kernel reads
+// the W new observations, rewards and flags out of the pinned arrays -- no copy commands, two bus crossings per act
+// step whatever W is.  The frame stacks themselves stay on the device: that kernel shifts each stack and appends the
+// new frame, clearing what belongs to a finished episode (the rule the replay gather applies, so the states acted from
+// are the states training later rebuilds), and keeps device copies of what the next append needs.
 //
 // The ablation of Section 5.1 switches the two techniques off independently.  Without Synchronized Execution every
 // sampler thread queries the network by itself (its own batch-1 dqn_act, its own transfers, its own append), the calls
@@ -44,6 +46,7 @@ inline uint64_t mix64_host(uint64_t z)
 constexpr uint32_t kStreamEnv = 3, kStreamEnvMeta = 4;   // stream tags of the synthetic environments
 constexpr uint32_t kPixThreshold = 838861;               // ceil(0.05 * 2^24)
 constexpr uint32_t kBackground = 40;
+constexpr std::chrono::microseconds kSpin(200);          // how long a thread polls for its next task before it blocks
 
 // Observation `id` of the environment stream: the frame generator of the header, on the host.
 void env_frame_host(uint64_t stream_key, uint64_t id, uint8_t* dst)
@@ -76,6 +79,46 @@ __global__ __launch_bounds__(256) void env_advance_kernel(uint8_t* __restrict__ 
     }
 }
 
+// The same for a synchronized round, fed straight from the pinned host arrays: workgroup j reads environment j's new
+// observation once over the bus, appends it to the stack and keeps a device copy of it (it is the frame of the next
+// experience to be appended), and thread 0 keeps device copies of (a, r, d) of the step just taken.
+__global__ __launch_bounds__(256) void env_round_kernel(uint8_t* __restrict__ states, const uint8_t* __restrict__ host_frames,
+                                                        const float* __restrict__ host_rewards, const uint8_t* __restrict__ host_terminals,
+                                                        const int32_t* __restrict__ host_actions, uint8_t* __restrict__ frames_out,
+                                                        float* __restrict__ rewards_out, uint8_t* __restrict__ terminals_out,
+                                                        int32_t* __restrict__ actions_out)
+{
+    const int j = blockIdx.x;
+    uint4* st = reinterpret_cast<uint4*>(states + static_cast<size_t>(j) * kStateBytes);
+    const uint4* nf = reinterpret_cast<const uint4*>(host_frames + static_cast<size_t>(j) * kFrameBytes);
+    uint4* keep = reinterpret_cast<uint4*>(frames_out + static_cast<size_t>(j) * kFrameBytes);
+    uint4 fresh[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {   // 441 vectors, 256 threads: both bus reads in flight before anything else
+        const int v = threadIdx.x + i * 256;
+        fresh[i] = nf[v < kFrameVec16 ? v : kFrameVec16 - 1];
+    }
+    const uint8_t term = host_terminals[j];
+    const uint32_t keep_old = term ? 0u : 0xFFFFFFFFu;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int v = threadIdx.x + i * 256;
+        if (v >= kFrameVec16) break;
+        uint4 f1 = st[kFrameVec16 + v], f2 = st[2 * kFrameVec16 + v], f3 = st[3 * kFrameVec16 + v];
+        f1.x &= keep_old; f1.y &= keep_old; f1.z &= keep_old; f1.w &= keep_old;
+        f2.x &= keep_old; f2.y &= keep_old; f2.z &= keep_old; f2.w &= keep_old;
+        f3.x &= keep_old; f3.y &= keep_old; f3.z &= keep_old; f3.w &= keep_old;
+        st[v] = f1; st[kFrameVec16 + v] = f2; st[2 * kFrameVec16 + v] = f3;
+        st[3 * kFrameVec16 + v] = fresh[i];
+        keep[v] = fresh[i];
+    }
+    if (threadIdx.x == 0) {
+        terminals_out[j] = term;
+        rewards_out[j] = host_rewards[j];
+        actions_out[j] = host_actions[j];
+    }
+}
+
 }  // namespace
 }  // namespace dqn
 
@@ -94,6 +137,11 @@ struct dqn_alg1 {
     int32_t* h_actions = nullptr;
     float* h_rewards = nullptr;
     uint8_t* h_terminals = nullptr;
+    // the pinned arrays as the device addresses them
+    uint8_t* hd_frames[2] = {nullptr, nullptr};
+    int32_t* hd_actions = nullptr;
+    float* hd_rewards = nullptr;
+    uint8_t* hd_terminals = nullptr;
     // device side of the same
     uint8_t* d_frames[2] = {nullptr, nullptr};
     uint8_t* d_states = nullptr;                 // [W][4][84][84]
@@ -110,16 +158,18 @@ struct dqn_alg1 {
     // worker threads: tasks are handed out by generation number
     std::mutex mu;
     std::condition_variable cv_work, cv_done;
-    uint64_t sampler_gen = 0, trainer_gen = 0;
+    std::atomic<uint64_t> sampler_gen{0};   // written under mu; the samplers first spin on it, then block on cv_work
+    uint64_t trainer_gen = 0;
     int sampler_task = 0;     // 0: observation o_0, 1: one environment step, 2: own network query + environment step
     float task_epsilon = 0.f; // task 2: exploration rate and parameter set of the query
     int task_use_target = 1;
-    int samplers_done = 0;
+    std::atomic<int> samplers_done{0};
     int sampler_rc = DQN_OK;  // first error of a sampler thread's device calls
     char sampler_err[256] = {0};
     std::mutex gpu_mu;        // serialises the sampler threads' device calls (task 2)
     hipEvent_t ev_query[kMaxLanes] = {};
-    bool trainer_busy = false, stop = false;
+    bool trainer_busy = false;
+    std::atomic<bool> stop{false};
     int trainer_rc = DQN_OK;
     char trainer_err[256] = {0};
     int64_t trainer_first = 0;
@@ -192,11 +242,20 @@ void sampler_main(dqn_alg1* h, int j)
         int64_t n;
         int nb;
         {
-            std::unique_lock<std::mutex> lk(h->mu);
-            h->cv_work.wait(lk, [&] { return h->stop || h->sampler_gen != seen; });
-            if (h->stop) return;
-            seen = h->sampler_gen;
-            task = h->sampler_task; n = h->n; nb = h->cur ^ 1;
+            // a round follows the last one within tens of microseconds: spin that long before going to sleep
+            const auto t0 = std::chrono::steady_clock::now();
+            bool go = false;
+            while (!(go = h->stop.load(std::memory_order_acquire) || h->sampler_gen.load(std::memory_order_acquire) != seen)) {
+                __builtin_ia32_pause();
+                if (std::chrono::steady_clock::now() - t0 > kSpin) break;
+            }
+            if (!go) {
+                std::unique_lock<std::mutex> lk(h->mu);
+                h->cv_work.wait(lk, [&] { return h->stop.load() || h->sampler_gen.load() != seen; });
+            }
+            if (h->stop.load(std::memory_order_acquire)) return;
+            seen = h->sampler_gen.load(std::memory_order_acquire);
+            task = h->sampler_task; n = h->n; nb = h->cur ^ 1;   // written before the generation was published
         }
         const int W = h->cfg.W;
         int rc = DQN_OK;
@@ -216,9 +275,9 @@ void sampler_main(dqn_alg1* h, int j)
                 snprintf(h->sampler_err, sizeof(h->sampler_err), "%s", dqn_last_error());
             }
         }
-        {
-            std::lock_guard<std::mutex> lk(h->mu);
-            if (++h->samplers_done == W) h->cv_done.notify_all();
+        if (h->samplers_done.fetch_add(1, std::memory_order_acq_rel) + 1 == W) {
+            { std::lock_guard<std::mutex> lk(h->mu); }   // the main thread is either still spinning or already inside wait()
+            h->cv_done.notify_all();
         }
     }
 }
@@ -231,8 +290,8 @@ void trainer_main(dqn_alg1* h)
         int count;
         {
             std::unique_lock<std::mutex> lk(h->mu);
-            h->cv_work.wait(lk, [&] { return h->stop || h->trainer_gen != seen; });
-            if (h->stop) return;
+            h->cv_work.wait(lk, [&] { return h->stop.load() || h->trainer_gen != seen; });
+            if (h->stop.load()) return;
             seen = h->trainer_gen;
             first = h->trainer_first; count = h->trainer_count;
         }
@@ -251,12 +310,23 @@ void trainer_main(dqn_alg1* h)
 
 void run_samplers(dqn_alg1* h, int task)
 {
-    std::unique_lock<std::mutex> lk(h->mu);
-    h->sampler_task = task;
-    h->samplers_done = 0;
-    ++h->sampler_gen;
+    const int W = h->cfg.W;
+    {
+        std::lock_guard<std::mutex> lk(h->mu);
+        h->sampler_task = task;
+        h->samplers_done.store(0, std::memory_order_relaxed);
+        h->sampler_gen.fetch_add(1, std::memory_order_release);
+    }
     h->cv_work.notify_all();
-    h->cv_done.wait(lk, [&] { return h->samplers_done == h->cfg.W; });
+    const auto t0 = std::chrono::steady_clock::now();
+    while (h->samplers_done.load(std::memory_order_acquire) != W) {
+        __builtin_ia32_pause();
+        if (std::chrono::steady_clock::now() - t0 > kSpin) {
+            std::unique_lock<std::mutex> lk(h->mu);
+            h->cv_done.wait(lk, [&] { return h->samplers_done.load(std::memory_order_acquire) == W; });
+            break;
+        }
+    }
 }
 
 int wait_trainer(dqn_alg1* h)
@@ -271,14 +341,12 @@ int wait_trainer(dqn_alg1* h)
     return DQN_OK;
 }
 
-// Uploads what the samplers just produced for step n (r_n, d_n, o_{n+1}) and advances the frame stacks.
-int upload_and_advance(dqn_alg1* h)
+// Hands what the samplers just produced for step n (a_n, r_n, d_n, o_{n+1}) to the device and advances the frame stacks.
+int advance_round(dqn_alg1* h)
 {
     const int W = h->cfg.W, nb = h->cur ^ 1;
-    DQN_HIP(hipMemcpyAsync(h->d_frames[nb], h->h_frames[nb], static_cast<size_t>(W) * kFrameBytes, hipMemcpyHostToDevice, h->act_stream));
-    DQN_HIP(hipMemcpyAsync(h->d_rewards, h->h_rewards, W * sizeof(float), hipMemcpyHostToDevice, h->act_stream));
-    DQN_HIP(hipMemcpyAsync(h->d_terminals, h->h_terminals, W, hipMemcpyHostToDevice, h->act_stream));
-    hipLaunchKernelGGL(env_advance_kernel, dim3(W), dim3(256), 0, h->act_stream, h->d_states, h->d_frames[nb], h->d_terminals);
+    hipLaunchKernelGGL(env_round_kernel, dim3(W), dim3(256), 0, h->act_stream, h->d_states, h->hd_frames[nb], h->hd_rewards, h->hd_terminals,
+                       h->hd_actions, h->d_frames[nb], h->d_rewards, h->d_terminals, h->d_actions);
     DQN_LAUNCH_CHECK();
     return DQN_OK;
 }
@@ -331,21 +399,20 @@ int act_step(dqn_alg1* h, float epsilon, int use_target)
     const int W = h->cfg.W;
     int rc;
     if (h->pending) {
-        // experience n-1 = (o_{n-1}, a_{n-1}, r_{n-1}, d_{n-1}) rides in this step's launches; a_{n-1} is read from the
-        // actions buffer before the same call overwrites it with a_n
+        // experience n-1 = (o_{n-1}, a_{n-1}, r_{n-1}, d_{n-1}) rides in this step's launches, from the device copies the last
+        // round left; the new actions go straight into the pinned array
         rc = dqn_act_push_step(h->ctx, h->rb, h->d_frames[h->cur ^ 1], h->d_actions, h->d_rewards, h->d_terminals, h->d_states, W, epsilon,
-                               static_cast<uint64_t>(h->act_steps), use_target, h->d_actions, nullptr);
+                               static_cast<uint64_t>(h->act_steps), use_target, h->hd_actions, nullptr);
         h->pending = false;
     } else {
-        rc = dqn_act(h->ctx, h->d_states, W, epsilon, static_cast<uint64_t>(h->act_steps), use_target, h->d_actions, nullptr);
+        rc = dqn_act(h->ctx, h->d_states, W, epsilon, static_cast<uint64_t>(h->act_steps), use_target, h->hd_actions, nullptr);
     }
     if (rc != DQN_OK) return rc;
-    DQN_HIP(hipMemcpyAsync(h->h_actions, h->d_actions, W * sizeof(int32_t), hipMemcpyDeviceToHost, h->act_stream));
     DQN_HIP(hipStreamSynchronize(h->act_stream));
     ++h->act_steps;
     run_samplers(h, 1);
     for (int j = 0; j < W; ++j) { h->reward_sum += h->h_rewards[j]; h->episodes += h->h_terminals[j]; }
-    rc = upload_and_advance(h);
+    rc = advance_round(h);
     if (rc != DQN_OK) return rc;
     h->cur ^= 1;
     ++h->n;
@@ -404,6 +471,10 @@ int dqn_alg1_create(dqn_ctx* ctx, replay* rb, const dqn_alg1_config* cfg, dqn_al
         DQN_HIP(hipMalloc(reinterpret_cast<void**>(&h->d_actions), W * sizeof(int32_t)));
         DQN_HIP(hipMalloc(reinterpret_cast<void**>(&h->d_rewards), W * sizeof(float)));
         DQN_HIP(hipMalloc(reinterpret_cast<void**>(&h->d_terminals), W));
+        for (int i = 0; i < 2; ++i) DQN_HIP(hipHostGetDevicePointer(reinterpret_cast<void**>(&h->hd_frames[i]), h->h_frames[i], 0));
+        DQN_HIP(hipHostGetDevicePointer(reinterpret_cast<void**>(&h->hd_actions), h->h_actions, 0));
+        DQN_HIP(hipHostGetDevicePointer(reinterpret_cast<void**>(&h->hd_rewards), h->h_rewards, 0));
+        DQN_HIP(hipHostGetDevicePointer(reinterpret_cast<void**>(&h->hd_terminals), h->h_terminals, 0));
         for (int j = 0; j < W; ++j) DQN_HIP(hipEventCreateWithFlags(&h->ev_query[j], hipEventDisableTiming));
         DQN_HIP(hipDeviceSynchronize());
         return DQN_OK;
@@ -427,7 +498,7 @@ int dqn_alg1_destroy(dqn_alg1* h)
     {
         std::unique_lock<std::mutex> lk(h->mu);
         h->cv_done.wait(lk, [&] { return !h->trainer_busy; });
-        h->stop = true;
+        h->stop.store(true, std::memory_order_release);
         h->cv_work.notify_all();
     }
     for (std::thread& t : h->samplers) t.join();
