@@ -222,18 +222,62 @@ int synth_transitions(int32_t* actions, float* rewards, uint8_t* terminals, int6
                       uint64_t id0, uint64_t id_step, uint64_t seed, int32_t num_actions,
                       uint32_t t_neg, uint32_t t_pos, uint32_t t_term, void* stream);
 
+/* ---- shared arrays of the synchronized samplers (Section 4) --------------------------------- */
+
+/* W environments stepped by the CALLER's sampler threads (an emulator each), acting through one
+ * minibatch per step.  The handle owns (a) pinned host arrays that the sampler threads and the
+ * kernels both address -- observations [W,84,84] uint8, actions [W] int32, rewards [W] float32,
+ * terminals [W] uint8, q [W,A] float32 -- so that an act step crosses the bus twice whatever W is and
+ * needs no copy command, and (b) the W frame stacks [W,4,84,84] on the device.  The state of
+ * environment j is the stack of its four latest observations, those from before its latest episode
+ * start replaced by zeros (the states replay_sample_gather later rebuilds).  Protocol:
+ *     write o_0 of every environment into observations;  dqn_envs_reset
+ *     loop:  dqn_envs_act          -> actions (and q) are in the arrays when it returns
+ *            every sampler j steps its environment with actions[j] and writes rewards[j],
+ *            terminals[j] (1: the episode ended with this step) and its next observation
+ *            (the first observation of the next episode after a terminal step) into observations[j]
+ *            dqn_envs_observe      -> experiences appended, stacks advanced (enqueued)
+ * The arrays must not be written between dqn_envs_observe / dqn_envs_reset and the return of the next
+ * dqn_envs_act (the kernels that read them have finished by then).
+ * rb (may be NULL: nothing is stored) needs W lanes and the context's act stream as push stream;
+ * W <= max_envs.  All device work runs on the act stream.  Errors: DQN_EINVAL, DQN_ENOMEM, DQN_EHIP. */
+typedef struct dqn_envs dqn_envs;
+int dqn_envs_create(dqn_ctx* ctx, replay* rb, int32_t W, dqn_envs** host_out);
+int dqn_envs_destroy(dqn_envs* e);
+
+/* Host addresses of the shared arrays (owned by e, valid until dqn_envs_destroy); any argument may be
+ * NULL. */
+int dqn_envs_arrays(dqn_envs* e, uint8_t** host_observations, int32_t** host_actions,
+                    float** host_rewards, uint8_t** host_terminals, float** host_q);
+
+/* Every environment starts an episode with the observation in the shared array: stack j becomes
+ * (0, 0, 0, observations[j]); nothing is stored.  Enqueues only. */
+int dqn_envs_reset(dqn_envs* e);
+
+/* dqn_act on the W stacks (same epsilon-greedy definition and counters) with the actions -- and the Q
+ * rows if want_q != 0 -- stored into the shared arrays; waits for the act stream, so they are there on
+ * return.  Errors: those of dqn_act; DQN_ESTATE before dqn_envs_reset. */
+int dqn_envs_act(dqn_envs* e, float epsilon, uint64_t act_step, int32_t use_target, int32_t want_q);
+
+/* After every sampler has stepped: for each environment j, appends the experience (the observation the
+ * action was taken on, actions[j], rewards[j], terminals[j]) to lane j of rb's temporary buffers (what
+ * replay_push_step does; the action is read from the shared array, so a sampler that overrode it
+ * stores what it actually did), then shifts stack j by one and appends observations[j], keeping only
+ * that observation if terminals[j] is set.  One launch; enqueues only.  Errors: DQN_ESTATE (a
+ * temporary buffer is full, or dqn_envs_reset has not run). */
+int dqn_envs_observe(dqn_envs* e);
+
 /* ---- Algorithm 1: the main loop around the calls above (Sections 3 and 4) ------------------- */
 
 /* The paper's host program: W sampler threads, one trainer thread and the main thread that
  * synchronises them.  The samplers step W synthetic environments that live on the host like an emulator
  * would (seeded stand-ins for it, defined below); everything else is the calls above.
- *   every C timesteps   wait for trainer and samplers; append what is pending; flush the temporary
- *                       buffers into D; theta^- <- theta (dqn_sync_target); hand the trainer thread
- *                       C / F minibatches (dqn_train_step_sampled, sample_step = train steps so far);
- *   every W timesteps   one dqn_act_push_step for all W states from theta^- at the given epsilon
- *                       (act_step = act steps so far; the previous step's experiences ride along),
- *                       one download of the W actions, each sampler thread steps its environment, one
- *                       upload of the W new observations, rewards and terminal flags.
+ *   every C timesteps   wait for trainer and samplers; flush the temporary buffers into D;
+ *                       theta^- <- theta (dqn_sync_target); hand the trainer thread C / F minibatches
+ *                       (dqn_train_step_sampled, sample_step = train steps so far);
+ *   every W timesteps   dqn_envs_act for all W states from theta^- at the given epsilon (act_step =
+ *                       act steps so far), each sampler thread steps its environment,
+ *                       dqn_envs_observe.
  * Timesteps count single environment steps, so one act step advances t by W (Section 4); the
  * synchronisation happens when t mod C == 0 with t counted from 0.
  *
@@ -263,9 +307,9 @@ typedef struct {
 
 /* The ablation of Section 5.1.  synchronized = 0: in every round of W timesteps each sampler thread makes
  * its own dqn_act call on its own state (W = 1; environment j at round k uses act_step = k * W + j), its
- * own download of the action, and after its environment step its own upload and replay_push; the
- * threads' calls are serialised by a mutex.  concurrent = 0: the policy reads theta (use_target = 0); after
- * every round the pending experiences are appended and flushed into D (replay_flush) and the calling
+ * own download of the action, and after its environment step its own upload and replay_push (copy
+ * commands instead of shared arrays); the threads' calls are serialised by a mutex.  concurrent = 0: the
+ * policy reads theta (use_target = 0); after every round the experiences are flushed into D (replay_flush) and the calling
  * thread makes the train steps that have become due -- t / F train steps have been made once the
  * timestep counter stands at t -- before the next round; theta^- <- theta still every C timesteps; the
  * trainer thread stays idle. */
@@ -289,13 +333,11 @@ int dqn_alg1_prepopulate(dqn_alg1* h, int64_t timesteps);
 
 /* Runs timesteps (a multiple of C) of the loop above, continuing from where the last call stopped.
  * Returns when every launch has been enqueued and the trainer thread is idle; the experiences of the
- * last block are still in the temporary buffers (one of them pending on the device), as they would be
- * at that instant of the paper's loop.  An error inside the trainer thread is reported by the next
+ * last block are still in the temporary buffers, as they would be at that instant of the paper's loop.  An error inside the trainer thread is reported by the next
  * synchronisation point or by this call's return. */
 int dqn_alg1_run(dqn_alg1* h, int64_t timesteps);
 
-/* Appends the pending experience and flushes the temporary buffers into D (blocking), so that D can be
- * inspected; the next dqn_alg1_run starts with its own synchronisation point as usual. */
+/* Flushes the temporary buffers into D (blocking), so that D can be inspected; the next dqn_alg1_run starts with its own synchronisation point as usual. */
 int dqn_alg1_flush(dqn_alg1* h);
 
 /* Host-side counters (any pointer may be NULL): timesteps of dqn_alg1_run so far, act steps and train

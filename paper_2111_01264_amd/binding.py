@@ -78,6 +78,13 @@ EXPORTS = {
     "synth_transitions": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_uint64,
                                     C.c_uint64, C.c_uint64, C.c_int32, C.c_uint32, C.c_uint32,
                                     C.c_uint32, C.c_void_p]),
+    "dqn_envs_create": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.POINTER(C.c_void_p)]),
+    "dqn_envs_destroy": (C.c_int, [C.c_void_p]),
+    "dqn_envs_arrays": (C.c_int, [C.c_void_p, C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), C.POINTER(C.c_void_p),
+                                  C.POINTER(C.c_void_p), C.POINTER(C.c_void_p)]),
+    "dqn_envs_reset": (C.c_int, [C.c_void_p]),
+    "dqn_envs_act": (C.c_int, [C.c_void_p, C.c_float, C.c_uint64, C.c_int32, C.c_int32]),
+    "dqn_envs_observe": (C.c_int, [C.c_void_p]),
     "dqn_alg1_create": (C.c_int, [C.c_void_p, C.c_void_p, C.POINTER(dqn_alg1_config), C.POINTER(C.c_void_p)]),
     "dqn_alg1_destroy": (C.c_int, [C.c_void_p]),
     "dqn_alg1_prepopulate": (C.c_int, [C.c_void_p, C.c_int64]),
@@ -226,6 +233,37 @@ def synth_transitions(actions, rewards, terminals, n, id0, id_step, seed, num_ac
                       t_term, stream):
     _check(_lib.synth_transitions(_ptr(actions), _ptr(rewards), _ptr(terminals), n, id0, id_step, seed,
                                   num_actions, t_neg, t_pos, t_term, _stream(stream)))
+
+
+def dqn_envs_create(ctx, rb, W):
+    out = C.c_void_p()
+    _check(_lib.dqn_envs_create(ctx, rb, W, C.byref(out)))
+    return out
+
+
+def dqn_envs_destroy(e):
+    _check(_lib.dqn_envs_destroy(e))
+
+
+def dqn_envs_arrays(e, W, A):
+    """numpy views of the pinned shared arrays: observations [W,84,84] u8, actions [W] i32, rewards [W] f32,
+    terminals [W] u8, q [W,A] f32 (valid until dqn_envs_destroy)."""
+    p = [C.c_void_p() for _ in range(5)]
+    _check(_lib.dqn_envs_arrays(e, *[C.byref(x) for x in p]))
+    spec = [(C.c_uint8, (W, 84, 84)), (C.c_int32, (W,)), (C.c_float, (W,)), (C.c_uint8, (W,)), (C.c_float, (W, A))]
+    return tuple(np.ctypeslib.as_array(C.cast(x, C.POINTER(t)), shape=shape) for x, (t, shape) in zip(p, spec))
+
+
+def dqn_envs_reset(e):
+    _check(_lib.dqn_envs_reset(e))
+
+
+def dqn_envs_act(e, epsilon, act_step, use_target, want_q=0):
+    _check(_lib.dqn_envs_act(e, epsilon, act_step, use_target, want_q))
+
+
+def dqn_envs_observe(e):
+    _check(_lib.dqn_envs_observe(e))
 
 
 def dqn_alg1_create(ctx, rb, cfg: dqn_alg1_config):

@@ -1,20 +1,15 @@
 // Algorithm 1 (DQN with Concurrent Training and Synchronized Execution, main thread) as a native host orchestrator:
 // W sampler threads and one trainer thread around the hot-path calls of this library.
 //
-//   * every C timesteps: wait for the trainer and the samplers, append what is pending, flush the temporary buffers
-//     into D, theta^- <- theta (dqn_sync_target), dispatch the trainer thread for C / F minibatches;
-//   * every W timesteps: wait for the samplers, evaluate Q(s^(j), .) for all W states in one minibatch (Section 4) --
-//     with the previous step's experiences riding in the same launches --, hand every sampler its action;
+//   * every C timesteps: wait for the trainer and the samplers, flush the temporary buffers into D, theta^- <- theta
+//     (dqn_sync_target), dispatch the trainer thread for C / F minibatches;
+//   * every W timesteps: wait for the samplers, evaluate Q(s^(j), .) for all W states in one minibatch (Section 4),
+//     hand every sampler its action;
 //   * a sampler thread takes one step in its environment with that action.
 //
 // The environments are synthetic (a seeded frame generator stands in for the Atari emulator, see the header): they
-// live on the host, as an emulator would, one per sampler thread.  States, actions, rewards and terminal flags cross
-// the bus through pinned "shared arrays" (Section 4) that both the threads and the kernels address directly: the act
-// step's last kernel stores the W actions into the pinned array, and after the samplers' step one small kernel reads
-// the W new observations, rewards and flags out of the pinned arrays -- no copy commands, two bus crossings per act
-// step whatever W is.  The frame stacks themselves stay on the device: that kernel shifts each stack and appends the
-// new frame, clearing what belongs to a finished episode (the rule the replay gather applies, so the states acted from
-// are the states training later rebuilds), and keeps device copies of what the next append needs.
+// live on the host, as an emulator would, one per sampler thread, and talk to the device through the shared arrays of
+// dqn_envs (pinned memory that threads and kernels both address; the frame stacks stay on the device).
 //
 // The ablation of Section 5.1 switches the two techniques off independently.  Without Synchronized Execution every
 // sampler thread queries the network by itself (its own batch-1 dqn_act, its own transfers, its own append), the calls
@@ -29,10 +24,9 @@
 #include <thread>
 #include <vector>
 
-#include "common.h"
+#include "envs.h"
 
 namespace dqn {
-
 namespace {
 
 constexpr uint64_t kGammaEnv = 0x9E3779B97F4A7C15ull;
@@ -60,62 +54,21 @@ void env_frame_host(uint64_t stream_key, uint64_t id, uint8_t* dst)
     }
 }
 
-// Shift every environment's frame stack by one and append its new observation; a stack whose previous step ended
-// an episode keeps only the new observation.  One workgroup per environment, thread -> 16-byte vector of a frame.
-__global__ __launch_bounds__(256) void env_advance_kernel(uint8_t* __restrict__ states, const uint8_t* __restrict__ new_frames,
-                                                          const uint8_t* __restrict__ terminals)
+// Without Synchronized Execution: shift ONE environment's frame stack and append its new observation from a device
+// copy; a stack whose previous step ended an episode keeps only the new observation.
+__global__ __launch_bounds__(256) void env_advance_kernel(uint8_t* __restrict__ stack, const uint8_t* __restrict__ new_frame,
+                                                          const uint8_t* __restrict__ terminal)
 {
-    const int j = blockIdx.x;
-    uint4* st = reinterpret_cast<uint4*>(states + static_cast<size_t>(j) * kStateBytes);
-    const uint4* nf = reinterpret_cast<const uint4*>(new_frames + static_cast<size_t>(j) * kFrameBytes);
-    const bool reset = terminals[j] != 0;
-    const uint4 z = make_uint4(0, 0, 0, 0);
+    uint4* st = reinterpret_cast<uint4*>(stack);
+    const uint4* nf = reinterpret_cast<const uint4*>(new_frame);
+    const uint32_t keep_old = terminal[0] ? 0u : 0xFFFFFFFFu;
     for (int v = threadIdx.x; v < kFrameVec16; v += blockDim.x) {
-        const uint4 f1 = st[kFrameVec16 + v], f2 = st[2 * kFrameVec16 + v], f3 = st[3 * kFrameVec16 + v];
-        st[v] = reset ? z : f1;
-        st[kFrameVec16 + v] = reset ? z : f2;
-        st[2 * kFrameVec16 + v] = reset ? z : f3;
-        st[3 * kFrameVec16 + v] = nf[v];
-    }
-}
-
-// The same for a synchronized round, fed straight from the pinned host arrays: workgroup j reads environment j's new
-// observation once over the bus, appends it to the stack and keeps a device copy of it (it is the frame of the next
-// experience to be appended), and thread 0 keeps device copies of (a, r, d) of the step just taken.
-__global__ __launch_bounds__(256) void env_round_kernel(uint8_t* __restrict__ states, const uint8_t* __restrict__ host_frames,
-                                                        const float* __restrict__ host_rewards, const uint8_t* __restrict__ host_terminals,
-                                                        const int32_t* __restrict__ host_actions, uint8_t* __restrict__ frames_out,
-                                                        float* __restrict__ rewards_out, uint8_t* __restrict__ terminals_out,
-                                                        int32_t* __restrict__ actions_out)
-{
-    const int j = blockIdx.x;
-    uint4* st = reinterpret_cast<uint4*>(states + static_cast<size_t>(j) * kStateBytes);
-    const uint4* nf = reinterpret_cast<const uint4*>(host_frames + static_cast<size_t>(j) * kFrameBytes);
-    uint4* keep = reinterpret_cast<uint4*>(frames_out + static_cast<size_t>(j) * kFrameBytes);
-    uint4 fresh[2];
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {   // 441 vectors, 256 threads: both bus reads in flight before anything else
-        const int v = threadIdx.x + i * 256;
-        fresh[i] = nf[v < kFrameVec16 ? v : kFrameVec16 - 1];
-    }
-    const uint8_t term = host_terminals[j];
-    const uint32_t keep_old = term ? 0u : 0xFFFFFFFFu;
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-        const int v = threadIdx.x + i * 256;
-        if (v >= kFrameVec16) break;
         uint4 f1 = st[kFrameVec16 + v], f2 = st[2 * kFrameVec16 + v], f3 = st[3 * kFrameVec16 + v];
         f1.x &= keep_old; f1.y &= keep_old; f1.z &= keep_old; f1.w &= keep_old;
         f2.x &= keep_old; f2.y &= keep_old; f2.z &= keep_old; f2.w &= keep_old;
         f3.x &= keep_old; f3.y &= keep_old; f3.z &= keep_old; f3.w &= keep_old;
         st[v] = f1; st[kFrameVec16 + v] = f2; st[2 * kFrameVec16 + v] = f3;
-        st[3 * kFrameVec16 + v] = fresh[i];
-        keep[v] = fresh[i];
-    }
-    if (threadIdx.x == 0) {
-        terminals_out[j] = term;
-        rewards_out[j] = host_rewards[j];
-        actions_out[j] = host_actions[j];
+        st[3 * kFrameVec16 + v] = nf[v];
     }
 }
 
@@ -127,38 +80,28 @@ using namespace dqn;
 struct dqn_alg1 {
     dqn_ctx* ctx = nullptr;
     replay* rb = nullptr;
+    dqn_envs* envs = nullptr;   // shared arrays and frame stacks
     dqn_alg1_config cfg{};
     int A = 0;
     hipStream_t act_stream = nullptr;
     uint64_t key_env = 0, key_meta = 0;
     uint32_t t_neg = 0, t_pos = 0, t_term = 0;
-    // pinned host arrays shared between the main thread and the sampler threads
-    uint8_t* h_frames[2] = {nullptr, nullptr};   // [W][84*84]: observations o_n / o_{n+1}, alternating
-    int32_t* h_actions = nullptr;
-    float* h_rewards = nullptr;
-    uint8_t* h_terminals = nullptr;
-    // the pinned arrays as the device addresses them
-    uint8_t* hd_frames[2] = {nullptr, nullptr};
-    int32_t* hd_actions = nullptr;
-    float* hd_rewards = nullptr;
-    uint8_t* hd_terminals = nullptr;
-    // device side of the same
-    uint8_t* d_frames[2] = {nullptr, nullptr};
-    uint8_t* d_states = nullptr;                 // [W][4][84][84]
+    // without Synchronized Execution every sampler moves its own data with copy commands: device staging for them
+    uint8_t* d_frames = nullptr;   // [W][84*84]
     int32_t* d_actions = nullptr;
     float* d_rewards = nullptr;
     uint8_t* d_terminals = nullptr;
+    hipEvent_t ev_query[kMaxLanes] = {};
+    std::mutex gpu_mu;        // serialises the sampler threads' device calls
     // progress
     int64_t n = 0;            // steps every environment has taken
-    int cur = 0;              // d_frames[cur] holds o_n
-    bool started = false;     // o_0 generated, states initialised
-    bool pending = false;     // experience n-1 is complete on the device and not yet appended
+    bool started = false;     // o_0 generated, stacks initialised
     int64_t t = 0, act_steps = 0, train_steps = 0, episodes = 0;
     double reward_sum = 0.0;
     // worker threads: tasks are handed out by generation number
     std::mutex mu;
     std::condition_variable cv_work, cv_done;
-    std::atomic<uint64_t> sampler_gen{0};   // written under mu; the samplers first spin on it, then block on cv_work
+    std::atomic<uint64_t> sampler_gen{0};   // written under mu; the samplers first poll it, then block on cv_work
     uint64_t trainer_gen = 0;
     int sampler_task = 0;     // 0: observation o_0, 1: one environment step, 2: own network query + environment step
     float task_epsilon = 0.f; // task 2: exploration rate and parameter set of the query
@@ -166,8 +109,6 @@ struct dqn_alg1 {
     std::atomic<int> samplers_done{0};
     int sampler_rc = DQN_OK;  // first error of a sampler thread's device calls
     char sampler_err[256] = {0};
-    std::mutex gpu_mu;        // serialises the sampler threads' device calls (task 2)
-    hipEvent_t ev_query[kMaxLanes] = {};
     bool trainer_busy = false;
     std::atomic<bool> stop{false};
     int trainer_rc = DQN_OK;
@@ -181,9 +122,10 @@ struct dqn_alg1 {
 namespace {
 
 // One step of environment j with the action in the shared array: (r_n, d_n) and o_{n+1} into the shared arrays.
-void sampler_env_step(dqn_alg1* h, int j, int64_t n, int nb)
+void sampler_env_step(dqn_alg1* h, int j, int64_t n)
 {
     const int W = h->cfg.W;
+    dqn_envs* e = h->envs;
     const auto t0 = std::chrono::steady_clock::now();
     const uint64_t id = static_cast<uint64_t>(n) * W + j;
     const uint64_t w = mix64_host(mix64_host(h->key_meta + id) + kGammaEnv);
@@ -191,10 +133,10 @@ void sampler_env_step(dqn_alg1* h, int j, int64_t n, int nb)
     const uint32_t abits = static_cast<uint32_t>((w >> 48) & 0xFFFFu);
     const int good = static_cast<int>((abits * static_cast<uint32_t>(h->A)) >> 16);
     float r = rbits < h->t_neg ? -1.f : (rbits >= (1u << 24) - h->t_pos ? 1.f : 0.f);
-    if (h->h_actions[j] != good) r = 0.f;
-    h->h_rewards[j] = r;
-    h->h_terminals[j] = tbits < h->t_term ? 1 : 0;
-    env_frame_host(h->key_env, id + W, h->h_frames[nb] + static_cast<size_t>(j) * kFrameBytes);
+    if (e->h_actions[j] != good) r = 0.f;
+    e->h_rewards[j] = r;
+    e->h_terminals[j] = tbits < h->t_term ? 1 : 0;
+    env_frame_host(h->key_env, id + W, e->h_obs + static_cast<size_t>(j) * kFrameBytes);
     if (h->cfg.env_step_ns) {   // stand-in for the emulator's own time per step
         const auto until = t0 + std::chrono::nanoseconds(h->cfg.env_step_ns);
         while (std::chrono::steady_clock::now() < until) {}
@@ -202,35 +144,38 @@ void sampler_env_step(dqn_alg1* h, int j, int64_t n, int nb)
 }
 
 // Without Synchronized Execution: sampler j evaluates its own state (a minibatch of one) and fetches its action.
-int sampler_query(dqn_alg1* h, int j, int64_t n)
+int sampler_query(dqn_alg1* h, int j)
 {
+    dqn_envs* e = h->envs;
     {
         std::lock_guard<std::mutex> g(h->gpu_mu);
-        const int rc = dqn_act(h->ctx, h->d_states + static_cast<size_t>(j) * kStateBytes, 1, h->task_epsilon,
+        const int rc = dqn_act(h->ctx, e->d_states + static_cast<size_t>(j) * kStateBytes, 1, h->task_epsilon,
                                static_cast<uint64_t>(h->act_steps) * h->cfg.W + j, h->task_use_target, h->d_actions + j, nullptr);
         if (rc != DQN_OK) return rc;
-        DQN_HIP(hipMemcpyAsync(h->h_actions + j, h->d_actions + j, sizeof(int32_t), hipMemcpyDeviceToHost, h->act_stream));
+        DQN_HIP(hipMemcpyAsync(e->h_actions + j, h->d_actions + j, sizeof(int32_t), hipMemcpyDeviceToHost, h->act_stream));
         DQN_HIP(hipEventRecord(h->ev_query[j], h->act_stream));
     }
-    (void)n;
     DQN_HIP(hipEventSynchronize(h->ev_query[j]));
     return DQN_OK;
 }
 
 // ... and hands its experience and its next observation to the device by itself.
-int sampler_commit(dqn_alg1* h, int j, int nb)
+int sampler_commit(dqn_alg1* h, int j)
 {
+    dqn_envs* e = h->envs;
     std::lock_guard<std::mutex> g(h->gpu_mu);
-    uint8_t* stack = h->d_states + static_cast<size_t>(j) * kStateBytes;
-    uint8_t* fresh = h->d_frames[nb] + static_cast<size_t>(j) * kFrameBytes;
-    DQN_HIP(hipMemcpyAsync(fresh, h->h_frames[nb] + static_cast<size_t>(j) * kFrameBytes, kFrameBytes, hipMemcpyHostToDevice, h->act_stream));
-    DQN_HIP(hipMemcpyAsync(h->d_rewards + j, h->h_rewards + j, sizeof(float), hipMemcpyHostToDevice, h->act_stream));
-    DQN_HIP(hipMemcpyAsync(h->d_terminals + j, h->h_terminals + j, 1, hipMemcpyHostToDevice, h->act_stream));
+    uint8_t* stack = e->d_states + static_cast<size_t>(j) * kStateBytes;
+    uint8_t* fresh = h->d_frames + static_cast<size_t>(j) * kFrameBytes;
+    DQN_HIP(hipMemcpyAsync(fresh, e->h_obs + static_cast<size_t>(j) * kFrameBytes, kFrameBytes, hipMemcpyHostToDevice, h->act_stream));
+    DQN_HIP(hipMemcpyAsync(h->d_rewards + j, e->h_rewards + j, sizeof(float), hipMemcpyHostToDevice, h->act_stream));
+    DQN_HIP(hipMemcpyAsync(h->d_terminals + j, e->h_terminals + j, 1, hipMemcpyHostToDevice, h->act_stream));
     // the newest frame of the stack is the observation the action was taken on
     const int rc = replay_push(h->rb, j, stack + 3 * kFrameBytes, h->d_actions + j, h->d_rewards + j, h->d_terminals + j, 1);
     if (rc != DQN_OK) return rc;
     hipLaunchKernelGGL(env_advance_kernel, dim3(1), dim3(256), 0, h->act_stream, stack, fresh, h->d_terminals + j);
     DQN_LAUNCH_CHECK();
+    // the pinned arrays are rewritten in the next round: the copies out of them must have been made by then
+    DQN_HIP(hipEventRecord(h->ev_query[j], h->act_stream));
     return DQN_OK;
 }
 
@@ -240,9 +185,8 @@ void sampler_main(dqn_alg1* h, int j)
     for (;;) {
         int task;
         int64_t n;
-        int nb;
         {
-            // a round follows the last one within tens of microseconds: spin that long before going to sleep
+            // a round follows the last one within tens of microseconds: poll that long before going to sleep
             const auto t0 = std::chrono::steady_clock::now();
             bool go = false;
             while (!(go = h->stop.load(std::memory_order_acquire) || h->sampler_gen.load(std::memory_order_acquire) != seen)) {
@@ -255,17 +199,17 @@ void sampler_main(dqn_alg1* h, int j)
             }
             if (h->stop.load(std::memory_order_acquire)) return;
             seen = h->sampler_gen.load(std::memory_order_acquire);
-            task = h->sampler_task; n = h->n; nb = h->cur ^ 1;   // written before the generation was published
+            task = h->sampler_task; n = h->n;   // written before the generation was published
         }
         const int W = h->cfg.W;
         int rc = DQN_OK;
         if (task == 0) {
-            env_frame_host(h->key_env, static_cast<uint64_t>(j), h->h_frames[h->cur] + static_cast<size_t>(j) * kFrameBytes);
+            env_frame_host(h->key_env, static_cast<uint64_t>(j), h->envs->h_obs + static_cast<size_t>(j) * kFrameBytes);
         } else {
-            if (task == 2) rc = sampler_query(h, j, n);
+            if (task == 2) rc = sampler_query(h, j);
             if (rc == DQN_OK) {
-                sampler_env_step(h, j, n, nb);
-                if (task == 2) rc = sampler_commit(h, j, nb);
+                sampler_env_step(h, j, n);
+                if (task == 2) rc = sampler_commit(h, j);
             }
         }
         if (rc != DQN_OK) {
@@ -276,7 +220,7 @@ void sampler_main(dqn_alg1* h, int j)
             }
         }
         if (h->samplers_done.fetch_add(1, std::memory_order_acq_rel) + 1 == W) {
-            { std::lock_guard<std::mutex> lk(h->mu); }   // the main thread is either still spinning or already inside wait()
+            { std::lock_guard<std::mutex> lk(h->mu); }   // the main thread is either still polling or already inside wait()
             h->cv_done.notify_all();
         }
     }
@@ -341,30 +285,6 @@ int wait_trainer(dqn_alg1* h)
     return DQN_OK;
 }
 
-// Hands what the samplers just produced for step n (a_n, r_n, d_n, o_{n+1}) to the device and advances the frame stacks.
-int advance_round(dqn_alg1* h)
-{
-    const int W = h->cfg.W, nb = h->cur ^ 1;
-    hipLaunchKernelGGL(env_round_kernel, dim3(W), dim3(256), 0, h->act_stream, h->d_states, h->hd_frames[nb], h->hd_rewards, h->hd_terminals,
-                       h->hd_actions, h->d_frames[nb], h->d_rewards, h->d_terminals, h->d_actions);
-    DQN_LAUNCH_CHECK();
-    return DQN_OK;
-}
-
-int start_envs(dqn_alg1* h)
-{
-    const int W = h->cfg.W;
-    run_samplers(h, 0);   // o_0 of every environment into h_frames[cur]
-    for (int j = 0; j < W; ++j) h->h_terminals[j] = 1;   // "episode start": the stack keeps only the new observation
-    DQN_HIP(hipMemcpyAsync(h->d_frames[h->cur], h->h_frames[h->cur], static_cast<size_t>(W) * kFrameBytes, hipMemcpyHostToDevice, h->act_stream));
-    DQN_HIP(hipMemcpyAsync(h->d_terminals, h->h_terminals, W, hipMemcpyHostToDevice, h->act_stream));
-    hipLaunchKernelGGL(env_advance_kernel, dim3(W), dim3(256), 0, h->act_stream, h->d_states, h->d_frames[h->cur], h->d_terminals);
-    DQN_LAUNCH_CHECK();
-    DQN_HIP(hipStreamSynchronize(h->act_stream));   // h_terminals is reused by the samplers
-    h->started = true;
-    return DQN_OK;
-}
-
 int sampler_error(dqn_alg1* h)
 {
     std::lock_guard<std::mutex> lk(h->mu);
@@ -374,60 +294,41 @@ int sampler_error(dqn_alg1* h)
     return fail(rc, "sampler thread: %s", h->sampler_err);
 }
 
-// One round without Synchronized Execution: every sampler thread queries the network for its own state, steps its
-// environment and hands the experience and the next observation to the device itself.
-int round_unsynchronized(dqn_alg1* h, float epsilon, int use_target)
+int start_envs(dqn_alg1* h)
 {
-    const int W = h->cfg.W;
-    h->task_epsilon = epsilon;
-    h->task_use_target = use_target;
-    run_samplers(h, 2);
-    const int rc = sampler_error(h);
+    run_samplers(h, 0);   // o_0 of every environment into the shared array
+    const int rc = dqn_envs_reset(h->envs);
     if (rc != DQN_OK) return rc;
-    for (int j = 0; j < W; ++j) { h->reward_sum += h->h_rewards[j]; h->episodes += h->h_terminals[j]; }
-    ++h->act_steps;
-    h->cur ^= 1;
-    ++h->n;
-    h->t += W;
+    DQN_HIP(hipStreamSynchronize(h->act_stream));   // the shared array is rewritten by the first step
+    h->started = true;
     return DQN_OK;
 }
 
-// One act step: Q for all W states in one minibatch, actions to the samplers, one environment step each.
+// One round of W timesteps: an action for every environment, one environment step each, the experiences and the next
+// observations handed to the device.
 int act_step(dqn_alg1* h, float epsilon, int use_target)
 {
-    if (!h->cfg.synchronized) return round_unsynchronized(h, epsilon, use_target);
     const int W = h->cfg.W;
+    dqn_envs* e = h->envs;
     int rc;
-    if (h->pending) {
-        // experience n-1 = (o_{n-1}, a_{n-1}, r_{n-1}, d_{n-1}) rides in this step's launches, from the device copies the last
-        // round left; the new actions go straight into the pinned array
-        rc = dqn_act_push_step(h->ctx, h->rb, h->d_frames[h->cur ^ 1], h->d_actions, h->d_rewards, h->d_terminals, h->d_states, W, epsilon,
-                               static_cast<uint64_t>(h->act_steps), use_target, h->hd_actions, nullptr);
-        h->pending = false;
+    if (h->cfg.synchronized) {
+        // Q for all W stacks in one minibatch; returns when the actions are in the shared array
+        if ((rc = dqn_envs_act(e, epsilon, static_cast<uint64_t>(h->act_steps), use_target, 0)) != DQN_OK) return rc;
+        run_samplers(h, 1);
+        if ((rc = dqn_envs_observe(e)) != DQN_OK) return rc;
     } else {
-        rc = dqn_act(h->ctx, h->d_states, W, epsilon, static_cast<uint64_t>(h->act_steps), use_target, h->hd_actions, nullptr);
+        // every sampler thread queries the network for its own state, steps its environment and hands the experience
+        // and the next observation to the device itself
+        h->task_epsilon = epsilon;
+        h->task_use_target = use_target;
+        run_samplers(h, 2);
+        if ((rc = sampler_error(h)) != DQN_OK) return rc;
+        for (int j = 0; j < W; ++j) DQN_HIP(hipEventSynchronize(h->ev_query[j]));
     }
-    if (rc != DQN_OK) return rc;
-    DQN_HIP(hipStreamSynchronize(h->act_stream));
+    for (int j = 0; j < W; ++j) { h->reward_sum += e->h_rewards[j]; h->episodes += e->h_terminals[j]; }
     ++h->act_steps;
-    run_samplers(h, 1);
-    for (int j = 0; j < W; ++j) { h->reward_sum += h->h_rewards[j]; h->episodes += h->h_terminals[j]; }
-    rc = advance_round(h);
-    if (rc != DQN_OK) return rc;
-    h->cur ^= 1;
     ++h->n;
-    h->pending = true;
     h->t += W;
-    return DQN_OK;
-}
-
-// Appends the pending experience by itself (in front of a flush).
-int append_pending(dqn_alg1* h)
-{
-    if (!h->pending) return DQN_OK;
-    const int rc = replay_push_step(h->rb, h->d_frames[h->cur ^ 1], h->d_actions, h->d_rewards, h->d_terminals);
-    if (rc != DQN_OK) return rc;
-    h->pending = false;
     return DQN_OK;
 }
 
@@ -458,24 +359,15 @@ int dqn_alg1_create(dqn_ctx* ctx, replay* rb, const dqn_alg1_config* cfg, dqn_al
     h->key_meta = mix64_host(cfg->env_seed + kGammaEnv * (kStreamEnvMeta + 1ull));
     h->t_neg = cfg->t_reward_neg; h->t_pos = cfg->t_reward_pos; h->t_term = cfg->t_term;
     auto body = [&]() -> int {
-        const size_t fb = static_cast<size_t>(W) * kFrameBytes;
-        for (int i = 0; i < 2; ++i) {
-            DQN_HIP(hipHostMalloc(reinterpret_cast<void**>(&h->h_frames[i]), fb, hipHostMallocDefault));
-            DQN_HIP(hipMalloc(reinterpret_cast<void**>(&h->d_frames[i]), fb));
+        const int rc = dqn_envs_create(ctx, rb, W, &h->envs);
+        if (rc != DQN_OK) return rc;
+        if (!cfg->synchronized) {
+            DQN_HIP(hipMalloc(reinterpret_cast<void**>(&h->d_frames), static_cast<size_t>(W) * kFrameBytes));
+            DQN_HIP(hipMalloc(reinterpret_cast<void**>(&h->d_actions), W * sizeof(int32_t)));
+            DQN_HIP(hipMalloc(reinterpret_cast<void**>(&h->d_rewards), W * sizeof(float)));
+            DQN_HIP(hipMalloc(reinterpret_cast<void**>(&h->d_terminals), W));
+            for (int j = 0; j < W; ++j) DQN_HIP(hipEventCreateWithFlags(&h->ev_query[j], hipEventDisableTiming));
         }
-        DQN_HIP(hipHostMalloc(reinterpret_cast<void**>(&h->h_actions), W * sizeof(int32_t), hipHostMallocDefault));
-        DQN_HIP(hipHostMalloc(reinterpret_cast<void**>(&h->h_rewards), W * sizeof(float), hipHostMallocDefault));
-        DQN_HIP(hipHostMalloc(reinterpret_cast<void**>(&h->h_terminals), W, hipHostMallocDefault));
-        DQN_HIP(hipMalloc(reinterpret_cast<void**>(&h->d_states), static_cast<size_t>(W) * kStateBytes));
-        DQN_HIP(hipMemset(h->d_states, 0, static_cast<size_t>(W) * kStateBytes));
-        DQN_HIP(hipMalloc(reinterpret_cast<void**>(&h->d_actions), W * sizeof(int32_t)));
-        DQN_HIP(hipMalloc(reinterpret_cast<void**>(&h->d_rewards), W * sizeof(float)));
-        DQN_HIP(hipMalloc(reinterpret_cast<void**>(&h->d_terminals), W));
-        for (int i = 0; i < 2; ++i) DQN_HIP(hipHostGetDevicePointer(reinterpret_cast<void**>(&h->hd_frames[i]), h->h_frames[i], 0));
-        DQN_HIP(hipHostGetDevicePointer(reinterpret_cast<void**>(&h->hd_actions), h->h_actions, 0));
-        DQN_HIP(hipHostGetDevicePointer(reinterpret_cast<void**>(&h->hd_rewards), h->h_rewards, 0));
-        DQN_HIP(hipHostGetDevicePointer(reinterpret_cast<void**>(&h->hd_terminals), h->h_terminals, 0));
-        for (int j = 0; j < W; ++j) DQN_HIP(hipEventCreateWithFlags(&h->ev_query[j], hipEventDisableTiming));
         DQN_HIP(hipDeviceSynchronize());
         return DQN_OK;
     };
@@ -504,11 +396,10 @@ int dqn_alg1_destroy(dqn_alg1* h)
     for (std::thread& t : h->samplers) t.join();
     if (h->trainer.joinable()) h->trainer.join();
     if (h->act_stream) (void)hipStreamSynchronize(h->act_stream);
-    for (int i = 0; i < 2; ++i) { (void)hipHostFree(h->h_frames[i]); (void)hipFree(h->d_frames[i]); }
+    (void)dqn_envs_destroy(h->envs);
+    (void)hipFree(h->d_frames); (void)hipFree(h->d_actions); (void)hipFree(h->d_rewards); (void)hipFree(h->d_terminals);
     for (int j = 0; j < kMaxLanes; ++j)
         if (h->ev_query[j]) (void)hipEventDestroy(h->ev_query[j]);
-    (void)hipHostFree(h->h_actions); (void)hipHostFree(h->h_rewards); (void)hipHostFree(h->h_terminals);
-    (void)hipFree(h->d_states); (void)hipFree(h->d_actions); (void)hipFree(h->d_rewards); (void)hipFree(h->d_terminals);
     delete h;
     return DQN_OK;
 }
@@ -524,7 +415,6 @@ int dqn_alg1_prepopulate(dqn_alg1* h, int64_t timesteps)
     for (int64_t k = 0; k < timesteps / h->cfg.W; ++k)
         if ((rc = act_step(h, 1.f, 1)) != DQN_OK) return rc;
     h->t = t0;   // prepopulation does not count as timesteps of the algorithm
-    if ((rc = append_pending(h)) != DQN_OK) return rc;
     return replay_flush(h->rb, 1);
 }
 
@@ -538,7 +428,6 @@ int dqn_alg1_run(dqn_alg1* h, int64_t timesteps)
     for (int64_t block = 0; block < timesteps / C; ++block) {
         // t mod C == 0: the samplers are idle (they only run inside act_step); wait for the trainer, then synchronise
         if ((rc = wait_trainer(h)) != DQN_OK) return rc;
-        if ((rc = append_pending(h)) != DQN_OK) return rc;
         if ((rc = dqn_sync_target(h->ctx, h->rb, 0)) != DQN_OK) return rc;
         if (h->cfg.concurrent) {
             {
@@ -558,7 +447,6 @@ int dqn_alg1_run(dqn_alg1* h, int64_t timesteps)
         // have become due, on this thread -- the next round's Q evaluation waits for them on the device
         for (int k = 0; k < C / W; ++k) {
             if ((rc = act_step(h, h->cfg.epsilon, 0)) != DQN_OK) return rc;
-            if ((rc = append_pending(h)) != DQN_OK) return rc;
             if ((rc = replay_flush(h->rb, 0)) != DQN_OK) return rc;
             while (h->train_steps < h->t / F) {
                 if ((rc = dqn_train_step_sampled(h->ctx, h->rb, h->cfg.B, static_cast<uint64_t>(h->train_steps), 0, nullptr)) != DQN_OK) return rc;
@@ -572,9 +460,8 @@ int dqn_alg1_run(dqn_alg1* h, int64_t timesteps)
 int dqn_alg1_flush(dqn_alg1* h)
 {
     if (!h) return fail(DQN_EINVAL, "dqn_alg1_flush: handle is null");
-    int rc = wait_trainer(h);
+    const int rc = wait_trainer(h);
     if (rc != DQN_OK) return rc;
-    if ((rc = append_pending(h)) != DQN_OK) return rc;
     return replay_flush(h->rb, 1);
 }
 

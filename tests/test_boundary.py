@@ -55,6 +55,8 @@ def test_validation_errors_before_device_work():
     lib.dqn_alg1_run.argtypes = P.EXPORTS["dqn_alg1_run"][1]
     assert lib.dqn_alg1_run(None, 0) == P.DQN_EINVAL and lib.dqn_alg1_flush(None) == P.DQN_EINVAL
     assert lib.dqn_alg1_destroy(None) == P.DQN_OK
+    assert lib.dqn_envs_create(None, None, 1, C.byref(out)) == P.DQN_EINVAL
+    assert lib.dqn_envs_observe(None) == P.DQN_EINVAL and lib.dqn_envs_destroy(None) == P.DQN_OK
 
 
 def test_alg1_config_struct_matches_header_size():

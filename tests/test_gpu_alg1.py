@@ -267,3 +267,123 @@ def test_algorithm1_argument_and_state_errors():
         for r in (rb, rb2, rb3):
             P.replay_destroy(r)
         P.dqn_destroy(ctx)
+
+
+def run_python_samplers(precision, seed, A, W, C, F, B, epsilon, prepop, blocks, M):
+    """Algorithm 1's schedule with the samplers in Python: the environments of the shared generator write into the pinned
+    arrays of dqn_envs; one thread, train steps before the act steps of a block."""
+    cfg = make_cfg(A, max_batch=B, max_envs=W, precision=precision, seed=seed)
+    sa, stt = torch.cuda.Stream(), torch.cuda.Stream()
+    ctx = P.dqn_create(cfg, sa, stt)
+    rb = P.replay_create(W * M, W, max(C, prepop) // W, seed, sa, stt)
+    e = None
+    try:
+        theta = synth.init_params(seed, A)
+        P.dqn_set_params(ctx, P.DQN_PARAMS_ONLINE, theta)
+        P.dqn_set_params(ctx, P.DQN_PARAMS_TARGET, theta)
+        e = P.dqn_envs_create(ctx, rb, W)
+        obs, actions, rewards, terminals, q = P.dqn_envs_arrays(e, W, A)
+        st = {"n": 0, "act": 0, "train": 0, "reward": 0.0, "episodes": 0}
+        greedy_checked = [0]
+
+        def rounds(count, eps):
+            for _ in range(count):
+                P.dqn_envs_act(e, eps, st["act"], 1, 1)
+                if eps == 0.0:
+                    assert np.array_equal(actions, q.argmax(axis=1))
+                    greedy_checked[0] += 1
+                r, d = synth.env_outcomes(seed, W, st["n"], actions.copy(), A, P_NEG, P_POS, P_TERM)
+                rewards[:], terminals[:] = r, d
+                st["n"] += 1
+                st["act"] += 1
+                obs[:] = synth.env_frames(seed, W, st["n"])
+                st["reward"] += float(r.sum())
+                st["episodes"] += int(d.sum())
+                P.dqn_envs_observe(e)
+
+        obs[:] = synth.env_frames(seed, W, 0)
+        P.dqn_envs_reset(e)
+        rounds(prepop // W, 1.0)
+        P.replay_flush(rb, 1)
+        for _ in range(blocks):
+            P.dqn_sync_target(ctx, rb, 1)
+            for i in range(C // F):
+                P.dqn_train_step_sampled(ctx, rb, B, st["train"], 0, None)
+                st["train"] += 1
+            rounds(C // W, epsilon)
+        P.replay_flush(rb, 1)
+        torch.cuda.synchronize()
+        counts = [min(M, (prepop + blocks * C) // W)] * W
+        rep = read_replay(rb, valid_indices(counts, M))
+        stats = {"t": blocks * C, "act_steps": st["act"], "train_steps": st["train"], "reward_sum": st["reward"],
+                 "episodes": st["episodes"]}
+        return stats, rep, P.dqn_get_params(ctx, P.DQN_PARAMS_ONLINE), P.dqn_get_params(ctx, P.DQN_PARAMS_TARGET), greedy_checked[0]
+    finally:
+        torch.cuda.synchronize()
+        if e is not None:
+            P.dqn_envs_destroy(e)
+        P.replay_destroy(rb)
+        P.dqn_destroy(ctx)
+
+
+@pytest.mark.parametrize("epsilon", [0.1, 0.0])
+def test_shared_arrays_with_python_samplers_equal_the_native_loop_bitwise(epsilon):
+    # dqn_envs_* driven by samplers that live in Python (as a real emulator binding would) reproduces dqn_alg1_run
+    args = (P.DQN_PRECISION_BF16, 2111012645, 6, 8, 32, 4, 32, epsilon, 64, 3, 20)
+    sa, ra, tha, tta = run_native(*args)
+    sb, rb_, thb, ttb, greedy = run_python_samplers(*args)
+    assert sa == sb
+    for got, ref in zip(ra, rb_):
+        assert np.array_equal(got, ref)
+    assert np.array_equal(tha, thb) and np.array_equal(tta, ttb)
+    assert greedy == (3 * 32 // 8 if epsilon == 0.0 else 0)     # the Q rows in the shared array explain the actions
+
+
+def test_shared_arrays_protocol_errors():
+    seed, A, W = 3, 4, 4
+    cfg = make_cfg(A, max_batch=8, max_envs=W, precision=P.DQN_PRECISION_BF16, seed=seed)
+    sa, stt = torch.cuda.Stream(), torch.cuda.Stream()
+    ctx = P.dqn_create(cfg, sa, stt)
+    rb = P.replay_create(W * 16, W, 2, seed, sa, stt)
+    rb2 = P.replay_create(2 * 16, 2, 2, seed, sa, stt)
+    try:
+        P.dqn_set_params(ctx, P.DQN_PARAMS_TARGET, synth.init_params(seed, A))
+        for bad_rb, bad_w in ((rb2, W), (rb, W + 1), (rb, 0)):
+            with pytest.raises(P.DqnError) as err:
+                P.dqn_envs_create(ctx, bad_rb, bad_w)
+            assert err.value.code == P.DQN_EINVAL
+        e = P.dqn_envs_create(ctx, rb, W)
+        e2 = P.dqn_envs_create(ctx, None, W)                      # no replay memory: acting only
+        try:
+            with pytest.raises(P.DqnError) as err:
+                P.dqn_envs_act(e, 0.1, 0, 1)
+            assert err.value.code == P.DQN_ESTATE                 # before reset
+            obs, actions, rewards, terminals, q = P.dqn_envs_arrays(e, W, A)
+            obs[:] = synth.env_frames(seed, W, 0)
+            rewards[:], terminals[:] = 0.0, 0
+            P.dqn_envs_reset(e)
+            for k in range(2):
+                P.dqn_envs_act(e, 0.1, k, 1)
+                assert ((0 <= actions) & (actions < A)).all()
+                P.dqn_envs_observe(e)
+            P.dqn_envs_act(e, 0.1, 2, 1)
+            with pytest.raises(P.DqnError) as err:
+                P.dqn_envs_observe(e)                             # temporary buffers hold two experiences per lane
+            assert err.value.code == P.DQN_ESTATE
+            P.replay_flush(rb, 1)
+            P.dqn_envs_observe(e)                                 # room again
+            obs2 = P.dqn_envs_arrays(e2, W, A)[0]
+            obs2[:] = synth.env_frames(seed, W, 0)
+            P.dqn_envs_reset(e2)
+            P.dqn_envs_act(e2, 0.0, 0, 1, 1)
+            P.dqn_envs_observe(e2)
+            P.dqn_envs_act(e2, 0.0, 1, 1, 1)
+            torch.cuda.synchronize()
+        finally:
+            P.dqn_envs_destroy(e)
+            P.dqn_envs_destroy(e2)
+    finally:
+        torch.cuda.synchronize()
+        P.replay_destroy(rb)
+        P.replay_destroy(rb2)
+        P.dqn_destroy(ctx)
