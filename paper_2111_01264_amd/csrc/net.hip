@@ -155,6 +155,12 @@ static int wgrad_splits(int K, int n_blocks, int max_splits)
 
 // Number of fc1 k-slices for n rows per group: enough workgroups to fill the chip, few enough that
 // the consumer's slice sum stays small.
+// Largest batch whose next-minibatch gather rides in the head kernel.  Beyond it the gather outlasts the head kernel and
+// rides at the end of the weight-gradient kernel instead: there it is not hidden either (its workgroups inherit that
+// kernel's register allocation, two wavefronts per SIMD, and run as its tail), but it still saves a launch (batch 512:
+// 166 -> 159 us per step; at batch 128 and 256 the head kernel is the better host: 76.5 / 122.8 against 78.3 / 122.2 us).
+constexpr int kRideInHeadMax = 256;
+
 static int fc1_slices(int n, int groups)
 {
     const int row_tiles = (n + 31) / 32;
@@ -334,6 +340,8 @@ static int train_impl(dqn_ctx* c, const uint8_t* s, const int32_t* a, const floa
     T* dz2 = static_cast<T*>(c->dz2); T* dz1 = static_cast<T*>(c->dz1);
 
     int wg_splits[3] = {1, 1, 1};
+    // where the gather of the next minibatch rides: in the head kernel, or for large batches in the weight-gradient kernel
+    const bool ride_in_wgrad = ride && std::is_same<T, bf16_t>::value && B > kRideInHeadMax;
     {
         const ProfPair pr = prof_pair(c, K_FC2_TD);
         if (pr.begin) (void)hipEventRecord(pr.begin, st);
@@ -347,7 +355,7 @@ static int train_impl(dqn_ctx* c, const uint8_t* s, const int32_t* a, const floa
         ha.h_online = h; ha.dzh = dzh; ha.q_all = ws.q; ha.dqv = c->dqv; ha.lossv = c->lossv;
         ha.head_blocks = (B + kHeadRows - 1) / kHeadRows;
         ha.gather.B = 0;
-        if (ride) ha.gather = *ride;
+        if (ride && !ride_in_wgrad) ha.gather = *ride;
         hipLaunchKernelGGL((head_fwd_kernel<T, kHeadTrain>), dim3(ha.head_blocks + 5 * ha.gather.B), dim3(256), 0, st, ha);
         if (pr.end) (void)hipEventRecord(pr.end, st);
         DQN_LAUNCH_CHECK();
@@ -452,7 +460,9 @@ static int train_impl(dqn_ctx* c, const uint8_t* s, const int32_t* a, const floa
         wa.first[5] = wa.first[4] + 2 * wa.splits1;
         const ProfPair pr = prof_pair(c, K_WGRAD_ALL);
         if (pr.begin) (void)hipEventRecord(pr.begin, st);
-        hipLaunchKernelGGL(wgrad_all_kernel, dim3(wa.first[5]), dim3(256), kWgradAllSmem, st, wa);
+        wa.gather.B = 0;
+        if (ride_in_wgrad) wa.gather = *ride;
+        hipLaunchKernelGGL(wgrad_all_kernel, dim3(wa.first[5] + 5 * wa.gather.B), dim3(256), kWgradAllSmem, st, wa);
         if (pr.end) (void)hipEventRecord(pr.end, st);
         DQN_LAUNCH_CHECK();
     } else {
@@ -807,8 +817,8 @@ int dqn_train_step_sampled(dqn_ctx* c, replay* rb, int32_t B, uint64_t sample_st
     c->pre_valid = false;
     GatherPlan plan;
     const GatherPlan* ride = nullptr;
-    // beyond a few hundred samples the gather is longer than the kernel it would ride in (measured: batch 512 loses 7 us)
-    if (prefetch_next && B <= 256) {
+    // fp32 mode has only the head kernel to ride in, and beyond a few hundred samples the gather outlasts it
+    if (prefetch_next && (c->cfg.precision == DQN_PRECISION_BF16 || B <= 256)) {
         const int nb = buf ^ 1;
         const int rc = replay_plan_sample_gather(rb, B, sample_step + 1, nullptr, c->mb_s[nb], c->mb_s2[nb], c->mb_a[nb], c->mb_r[nb],
                                                  c->mb_d[nb], nullptr, &plan);

@@ -19,6 +19,7 @@ struct WgradAllArgs {
     DenseM<bf16_t> af, bf; EpiGrad epf; int Kf;
     BiasGradArgs small;
     int first[6];   // first block of: small reductions, conv3, conv2, fc1, conv1, end
+    GatherPlan gather;   // workgroups from first[5] on gather the next minibatch (5 per sample; gather.B == 0: none)
 };
 
 constexpr int kWg1BN = 128, kWg2BN = 256, kWg3BN = 192, kWgfBN = 128;   // column blocks: 2, 2, 3, 25 per slice
@@ -33,9 +34,13 @@ __global__ __launch_bounds__(256) void wgrad_all_kernel(WgradAllArgs a)
     const int blk = blockIdx.x;
     const EpiGrad none{nullptr, 0, 1.f};
     // the four boundaries in one scalar load (read one by one, each is a load-wait-branch step of its own)
-    const int f1 = a.first[1], f2 = a.first[2], f3 = a.first[3], f4 = a.first[4];
-    asm volatile("" :: "s"(f1), "s"(f2), "s"(f3), "s"(f4));
-    if (blk < f1) {
+    const int f1 = a.first[1], f2 = a.first[2], f3 = a.first[3], f4 = a.first[4], f5 = a.first[5];
+    asm volatile("" :: "s"(f1), "s"(f2), "s"(f3), "s"(f4), "s"(f5));
+    if (blk >= f5) {
+        // byte copies that no part of this step depends on: they fill the memory pipes this kernel leaves idle
+        const int i = blk - f5;
+        gather_block(a.gather, i % 5, i / 5);
+    } else if (blk < f1) {
         small_grads_block<bf16_t>(a.small, blk - a.first[0], wg_smem);
     } else if (blk < f2) {
         const int i = blk - a.first[1];

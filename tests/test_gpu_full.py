@@ -305,13 +305,15 @@ def test_act_push_step_equals_the_two_calls(precision):
     assert rep_a[2].min() >= 0            # real transitions, not the invalid-index marker
 
 
+@pytest.mark.parametrize("B", [24, 300], ids=["b24", "b300"])
 @pytest.mark.parametrize("precision", [P.DQN_PRECISION_BF16, P.DQN_PRECISION_FP32], ids=["bf16", "fp32"])
-def test_train_step_sampled_equals_the_two_calls(precision):
+def test_train_step_sampled_equals_the_two_calls(precision, B):
     """dqn_train_step_sampled == replay_sample_gather + dqn_train_step, bit for bit (parameters and loss after every
-    step), also when the minibatch gathered ahead goes stale (a flush in between) or is not the one asked for next."""
-    seed, A, B, lanes, per_lane = 2111012662, 6, 24, 4, 300
+    step), also when the minibatch gathered ahead goes stale (a flush in between) or is not the one asked for next.
+    The two batch sizes take the two kernels the gather can ride in (small: head kernel, large: weight-gradient kernel)."""
+    seed, A, lanes, per_lane = 2111012662, 6, 4, 300
     N = lanes * 1024
-    cfg = make_cfg(A, max_batch=32, max_envs=8, precision=precision, seed=seed)
+    cfg = make_cfg(A, max_batch=max(B, 32), max_envs=8, precision=precision, seed=seed)
     theta = synth.init_params(seed, A)
     sample_steps = [0, 1, 2, 3, 5, 6, 7]      # after 3 comes 5: the minibatch of 4 was gathered ahead and is dropped
     flush_before = {2, 6}                     # new experiences become visible before these positions
