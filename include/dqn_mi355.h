@@ -199,8 +199,8 @@ int replay_sample_gather(replay* rb, int32_t B, uint64_t sample_step, const int6
  * buffer sets (the replay memory is constant between synchronisation points, Section 3 / Algorithm 1), and
  * the next call, if it asks for exactly that minibatch (same rb, B, sample_step + 1, and no replay_flush /
  * dqn_sync_target in between), finds it there.  Any other call gathers first, as the two separate calls
- * would (so does every call with B > 256, where riding along does not pay): results are identical to theirs
- * in every case.  The replay's sample_stream must be ctx's
+ * would (so does every call with B > 256 in the fp32 mode, which has no kernel long enough to ride in):
+ * results are identical to theirs in every case.  The replay's sample_stream must be ctx's
  * train_stream.  Errors: those of the two calls. */
 int dqn_train_step_sampled(dqn_ctx* ctx, replay* rb, int32_t B, uint64_t sample_step,
                            int32_t prefetch_next, float* loss_out);
