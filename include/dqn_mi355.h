@@ -359,6 +359,11 @@ const char* dqn_profile_kernel_name(int kernel_id);
  * timed).  Selecting resets the collected data. */
 int dqn_profile_select(dqn_ctx* ctx, int kernel_id);
 
+/* The same with only every `every`-th launch of the kernel bracketed (every >= 1): a pair of event
+ * records costs the stream a few microseconds, so a long timed run samples its launches instead of
+ * bracketing each (and the 4096 kept samples then span the whole run). */
+int dqn_profile_select_every(dqn_ctx* ctx, int kernel_id, int32_t every);
+
 /* Waits for train_stream, then returns the summed duration in milliseconds and the number of
  * timed launches of the selected kernel since dqn_profile_select. */
 int dqn_profile_read(dqn_ctx* ctx, double* host_total_ms, int64_t* host_launches);

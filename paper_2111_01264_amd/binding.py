@@ -95,6 +95,7 @@ EXPORTS = {
     "dqn_profile_kernel_count": (C.c_int, []),
     "dqn_profile_kernel_name": (C.c_char_p, [C.c_int]),
     "dqn_profile_select": (C.c_int, [C.c_void_p, C.c_int]),
+    "dqn_profile_select_every": (C.c_int, [C.c_void_p, C.c_int, C.c_int32]),
     "dqn_profile_read": (C.c_int, [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_int64)]),
     "dqn_last_error": (C.c_char_p, []),
 }
@@ -306,6 +307,10 @@ def dqn_profile_kernel_name(kernel_id):
 
 def dqn_profile_select(ctx, kernel_id):
     _check(_lib.dqn_profile_select(ctx, kernel_id))
+
+
+def dqn_profile_select_every(ctx, kernel_id, every):
+    _check(_lib.dqn_profile_select_every(ctx, kernel_id, every))
 
 
 def dqn_profile_read(ctx):

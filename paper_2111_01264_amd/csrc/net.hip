@@ -86,6 +86,8 @@ struct dqn_ctx {
     int prof_id = 0;
     std::vector<hipEvent_t> prof_events;   // pairs
     size_t prof_used = 0;                  // pairs recorded since the last select
+    int prof_every = 1;                    // every prof_every-th launch of the selected kernel is bracketed
+    int64_t prof_seen = 0;                 // its launches since the last select
 };
 
 namespace dqn {
@@ -123,7 +125,7 @@ struct ProfPair { hipEvent_t begin = nullptr, end = nullptr; };
 static ProfPair prof_pair(dqn_ctx* c, int id)
 {
     ProfPair p;
-    if (c->prof_id == id && c->prof_used < c->prof_events.size() / 2) {
+    if (c->prof_id == id && c->prof_seen++ % c->prof_every == 0 && c->prof_used < c->prof_events.size() / 2) {
         p.begin = c->prof_events[2 * c->prof_used];
         p.end = c->prof_events[2 * c->prof_used + 1];
         ++c->prof_used;
@@ -864,10 +866,13 @@ const char* dqn_profile_kernel_name(int kernel_id)
     return kernel_id >= 1 && kernel_id < K_COUNT ? kKernelNames[kernel_id] : nullptr;
 }
 
-int dqn_profile_select(dqn_ctx* c, int kernel_id)
+int dqn_profile_select(dqn_ctx* c, int kernel_id) { return dqn_profile_select_every(c, kernel_id, 1); }
+
+int dqn_profile_select_every(dqn_ctx* c, int kernel_id, int32_t every)
 {
     if (!c) return fail(DQN_EINVAL, "dqn_profile_select: ctx is null");
     if (kernel_id < 0 || kernel_id >= K_COUNT) return fail(DQN_EINVAL, "dqn_profile_select: kernel id %d", kernel_id);
+    if (every < 1) return fail(DQN_EINVAL, "dqn_profile_select_every: every = %d", every);
     DQN_HIP(hipStreamSynchronize(c->train_stream));
     if (kernel_id != 0 && c->prof_events.empty()) {
         c->prof_events.reserve(2 * kProfPairs);
@@ -879,6 +884,8 @@ int dqn_profile_select(dqn_ctx* c, int kernel_id)
     }
     c->prof_id = kernel_id;
     c->prof_used = 0;
+    c->prof_every = every;
+    c->prof_seen = 0;
     return DQN_OK;
 }
 
