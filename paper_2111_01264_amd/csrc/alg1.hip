@@ -40,7 +40,8 @@ inline uint64_t mix64_host(uint64_t z)
 constexpr uint32_t kStreamEnv = 3, kStreamEnvMeta = 4;   // stream tags of the synthetic environments
 constexpr uint32_t kPixThreshold = 838861;               // ceil(0.05 * 2^24)
 constexpr uint32_t kBackground = 40;
-constexpr std::chrono::microseconds kSpin(200);          // how long a thread polls for its next task before it blocks
+constexpr std::chrono::microseconds kSpin(200);          // how long a thread polls for its next task before it blocks ...
+constexpr int kSpinMaxSamplers = 12;                     // ... if the sampler threads are few enough to have a core each while polling
 
 // Observation `id` of the environment stream: the frame generator of the header, on the host.
 void env_frame_host(uint64_t stream_key, uint64_t id, uint8_t* dst)
@@ -111,6 +112,7 @@ struct dqn_alg1 {
     char sampler_err[256] = {0};
     bool trainer_busy = false;
     std::atomic<bool> stop{false};
+    std::chrono::microseconds spin{0};   // polling time before a thread blocks (0: block at once)
     int trainer_rc = DQN_OK;
     char trainer_err[256] = {0};
     int64_t trainer_first = 0;
@@ -191,7 +193,7 @@ void sampler_main(dqn_alg1* h, int j)
             bool go = false;
             while (!(go = h->stop.load(std::memory_order_acquire) || h->sampler_gen.load(std::memory_order_acquire) != seen)) {
                 __builtin_ia32_pause();
-                if (std::chrono::steady_clock::now() - t0 > kSpin) break;
+                if (std::chrono::steady_clock::now() - t0 > h->spin) break;
             }
             if (!go) {
                 std::unique_lock<std::mutex> lk(h->mu);
@@ -265,7 +267,7 @@ void run_samplers(dqn_alg1* h, int task)
     const auto t0 = std::chrono::steady_clock::now();
     while (h->samplers_done.load(std::memory_order_acquire) != W) {
         __builtin_ia32_pause();
-        if (std::chrono::steady_clock::now() - t0 > kSpin) {
+        if (std::chrono::steady_clock::now() - t0 > h->spin) {
             std::unique_lock<std::mutex> lk(h->mu);
             h->cv_done.wait(lk, [&] { return h->samplers_done.load(std::memory_order_acquire) == W; });
             break;
@@ -358,6 +360,7 @@ int dqn_alg1_create(dqn_ctx* ctx, replay* rb, const dqn_alg1_config* cfg, dqn_al
     h->key_env = mix64_host(cfg->env_seed + kGammaEnv * (kStreamEnv + 1ull));
     h->key_meta = mix64_host(cfg->env_seed + kGammaEnv * (kStreamEnvMeta + 1ull));
     h->t_neg = cfg->t_reward_neg; h->t_pos = cfg->t_reward_pos; h->t_term = cfg->t_term;
+    h->spin = W <= kSpinMaxSamplers ? kSpin : std::chrono::microseconds(0);
     auto body = [&]() -> int {
         const int rc = dqn_envs_create(ctx, rb, W, &h->envs);
         if (rc != DQN_OK) return rc;

@@ -387,3 +387,15 @@ def test_shared_arrays_protocol_errors():
         P.replay_destroy(rb)
         P.replay_destroy(rb2)
         P.dqn_destroy(ctx)
+
+
+def test_many_samplers_blocking_handoffs_equal_python_samplers_bitwise():
+    # above a dozen sampler threads the hand-offs block on condition variables instead of polling; W = 16 also takes the
+    # shared arrays and the stack kernel past one wavefront's worth of environments per launch dimension
+    args = (P.DQN_PRECISION_BF16, 2111012646, 6, 16, 32, 4, 16, 0.1, 96, 3, 16)
+    sa, ra, tha, tta = run_native(*args)
+    sb, rb_, thb, ttb, _ = run_python_samplers(*args)
+    assert sa == sb
+    for got, ref in zip(ra, rb_):
+        assert np.array_equal(got, ref)
+    assert np.array_equal(tha, thb) and np.array_equal(tta, ttb)
