@@ -30,14 +30,19 @@ __global__ __launch_bounds__(256) void envs_observe_kernel(const ObserveArgs a)
     const int j = blockIdx.x;
     uint4* st = reinterpret_cast<uint4*>(a.states + static_cast<size_t>(j) * kStateBytes);
     const uint4* nf = reinterpret_cast<const uint4*>(a.host_obs + static_cast<size_t>(j) * kFrameBytes);
+    // every read that crosses the bus is requested here, before anything waits: a bus round trip is 2-3 us, and a read
+    // requested later (the three scalars, by one thread, at the end) would add another one to the kernel
     uint4 fresh[2];
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {   // both bus reads in flight before anything else
+    for (int i = 0; i < 2; ++i) {
         const int v = threadIdx.x + i * 256;
         fresh[i] = nf[v < kFrameVec16 ? v : kFrameVec16 - 1];
     }
+    const uint32_t term_in = a.host_terminals[j];
+    const int32_t act_in = a.host_actions[j];
+    const float rew_in = a.host_rewards[j];
     const bool store = !a.start && a.push.L > 0;
-    const uint32_t term = a.start ? 1u : a.host_terminals[j];
+    const uint32_t term = a.start ? 1u : term_in;
     const uint32_t keep_old = term ? 0u : 0xFFFFFFFFu;
     const int64_t dst = store ? static_cast<int64_t>(j) * a.push.S + a.push.slot[j] : 0;
     uint4* staged = reinterpret_cast<uint4*>(a.push.st_frames + dst * kFrameBytes);
@@ -54,8 +59,8 @@ __global__ __launch_bounds__(256) void envs_observe_kernel(const ObserveArgs a)
         st[3 * kFrameVec16 + v] = fresh[i];
     }
     if (store && threadIdx.x == 0) {
-        a.push.st_actions[dst] = a.host_actions[j];
-        a.push.st_rewards[dst] = a.host_rewards[j];
+        a.push.st_actions[dst] = act_in;
+        a.push.st_rewards[dst] = rew_in;
         a.push.st_terminals[dst] = static_cast<uint8_t>(term != 0);
     }
 }
