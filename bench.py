@@ -347,7 +347,7 @@ def cpu_baseline(args):
         agent.train_step(s, a, r, s2, d)
         done_steps += 1
         el = time.perf_counter() - t0
-        if el >= budget or done_steps >= 50:
+        if el >= budget or done_steps >= 1000:
             break
     return {"value": done_steps / el, "unit": "train steps/s", "cores": odqn.max_threads(), "kind": "oracle",
             "sample": "%d steps (each: %d act steps of W=%d + gather + train step at batch %d) in %.1f s"
