@@ -43,8 +43,8 @@ def read_replay(rb, idx):
     return [x.cpu().numpy() for x in (s, s2, a, r, d)]
 
 
-def run_native(precision, seed, A, W, C, F, B, epsilon, prepop, blocks, M, concurrent=1, synchronized=1):
-    cfg = make_cfg(A, max_batch=B, max_envs=W, precision=precision, seed=seed)
+def run_native(precision, seed, A, W, C, F, B, epsilon, prepop, blocks, M, concurrent=1, synchronized=1, double_dqn=0):
+    cfg = make_cfg(A, max_batch=B, max_envs=W, precision=precision, seed=seed, double_dqn=double_dqn)
     sa, stt = torch.cuda.Stream(), torch.cuda.Stream()
     ctx = P.dqn_create(cfg, sa, stt)
     rb = P.replay_create(W * M, W, max(C, prepop) // W, seed, sa, stt)
@@ -145,10 +145,11 @@ def run_call_by_call(precision, seed, A, W, C, F, B, epsilon, prepop, blocks, M)
         P.dqn_destroy(ctx)
 
 
-def test_algorithm1_matches_oracle_fp32():
+@pytest.mark.parametrize("double_dqn", [0, 1], ids=["eq1", "double"])
+def test_algorithm1_matches_oracle_fp32(double_dqn):
     seed, A, W, C, F, B, epsilon, prepop, blocks, M = 2111012641, 6, 4, 16, 4, 8, 0.2, 48, 3, 64
-    stats, rep, th, tt = run_native(P.DQN_PRECISION_FP32, seed, A, W, C, F, B, epsilon, prepop, blocks, M)
-    dqn = odqn.OracleDQN(A, synth.init_params(seed, A), seed=seed)
+    stats, rep, th, tt = run_native(P.DQN_PRECISION_FP32, seed, A, W, C, F, B, epsilon, prepop, blocks, M, double_dqn=double_dqn)
+    dqn = odqn.OracleDQN(A, synth.init_params(seed, A), seed=seed, double_dqn=bool(double_dqn))
     orep = OracleReplay(W * M, W, seed)
     envs = SyntheticEnvs(synth, seed, W, A, P_NEG, P_POS, P_TERM)
     alg = Algorithm1(dqn, orep, envs, C, F, B, epsilon)
