@@ -180,3 +180,43 @@ def init_params(seed: int, num_actions: int) -> np.ndarray:
         parts.append(rng.uniform(-bound, bound, size=int(np.prod(shape))).astype(np.float32))
         parts.append(rng.uniform(-bound, bound, size=shape[0]).astype(np.float32))
     return np.concatenate(parts)
+
+
+# ---- inputs on which no ReLU can change state under operand rounding ---------------------------------------
+
+def block_frames(seed: int, n: int) -> np.ndarray:
+    """[n, 84, 84] uint8 frames with large-scale structure: a random 4x4 grid of 21x21-pixel blocks at brightness
+    0 / 48 / 96 / 144, plus per-pixel noise uniform in [0, 63] (numpy default_rng(seed)).  Windows of every conv
+    layer then see clearly different sums at different positions (relative spread over the pixels of a channel of
+    roughly 15 % / 10 % / 6 % after conv1 / conv2 / conv3 with margin_params below)."""
+    rng = np.random.default_rng(seed)
+    base = rng.integers(0, 4, size=(n, 4, 4), dtype=np.int64) * 48
+    noise = rng.integers(0, 64, size=(n, FRAME_H, FRAME_W), dtype=np.int64)
+    return (np.repeat(np.repeat(base, 21, axis=1), 21, axis=2) + noise).astype(np.uint8)
+
+
+MARGIN_BIAS = 0.5
+MARGIN_SCALE = {"conv1": 0.25, "conv2": 0.2, "conv3": 0.1, "fc1": 0.02, "fc2": 0.02}
+
+
+def margin_params(seed: int, num_actions: int, split_channels: bool) -> np.ndarray:
+    """Parameter blob for which every hidden pre-activation is at least MARGIN_BIAS away from zero on ANY
+    non-negative input, by construction: hidden channel o has sign s_o (+1; with split_channels -1 for odd o), bias
+    s_o * MARGIN_BIAS and weights s_o * |w| * scale with w from init_params(seed) -- a channel's weighted sum of
+    non-negative inputs has the sign of its bias.  Odd channels are then switched off for every input, even ones
+    are on.  fc2 keeps mixed signs (scaled so that |Q| stays well below the reward magnitudes used with it)."""
+    theta = init_params(seed, num_actions).copy()
+    off = 0
+    for name, shape, _ in layer_shapes(num_actions):
+        n = int(np.prod(shape))
+        w = theta[off:off + n].reshape(shape[0], -1)
+        if name == "fc2":
+            w *= np.float32(MARGIN_SCALE[name])
+        else:
+            sign = np.ones(shape[0], dtype=np.float32)
+            if split_channels:
+                sign[1::2] = -1.0
+            w[:] = np.abs(w) * np.float32(MARGIN_SCALE[name]) * sign[:, None]
+            theta[off + n:off + n + shape[0]] = sign * np.float32(MARGIN_BIAS)
+        off += n + shape[0]
+    return theta

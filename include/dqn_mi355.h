@@ -94,7 +94,9 @@ int dqn_get_params(dqn_ctx* ctx, int which, float* host_dst, size_t n);
  * float(x0 >> 8) * 2^-24 < epsilon (float32 compare), and the random action is (x1 * A) >> 32.
  *   states   [W,4,84,84] uint8, scaled by 1/255 inside.
  *   use_target  1: parameters theta^- (Concurrent Training, Section 3); 0: theta (standard DQN);
- *               with 0 the call first waits, on the device, for the last enqueued train step.
+ *               with 0 the call first waits, on the device, for the last enqueued train step; if another host
+ *               thread is enqueuing a train step at that moment, the two calls take turns (a host-side lock),
+ *               so the policy never reads parameters that a running update is overwriting.
  *   actions  [W] int32 out.   q_out  [W,A] float32 out, or NULL.
  * Runs on act_stream.  Errors: DQN_EINVAL (W < 1, W > max_envs, null/misaligned pointer,
  * epsilon outside [0,1]). */
@@ -110,6 +112,8 @@ int dqn_act(dqn_ctx* ctx, const uint8_t* states, int32_t W, float epsilon, uint6
  *   theta <- RMSProp(theta, dloss/dtheta).   theta^- is not touched.
  *   s, s2 [B,4,84,84] uint8;  a [B] int32 in [0,A);  r, done [B] float32 (done is 0 or 1);
  *   loss_out: device float32 scalar, or NULL.
+ * A row whose action lies outside [0,A) (replay_sample_gather marks a row it could not assemble with -1) is
+ * checked on the device and contributes nothing: loss term 0, gradient 0; the mean still divides by B.
  * Runs on train_stream.  Errors: DQN_EINVAL (B < 1, B > max_batch, null/misaligned pointer). */
 int dqn_train_step(dqn_ctx* ctx, const uint8_t* s, const int32_t* a, const float* r,
                    const uint8_t* s2, const float* done, int32_t B, float* loss_out);

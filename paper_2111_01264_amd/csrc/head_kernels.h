@@ -149,9 +149,15 @@ __global__ __launch_bounds__(256) void head_fwd_kernel(HeadArgs a)
     const int trow_c = row0 + trow_ < a.rows ? row0 + trow_ : a.rows - 1;
     int act_taken = 0, act_tail = 0;
     float rew_tail = 0.f, done_tail = 0.f;
+    bool act_ok = true;   // tail: the stored action of this lane's row lies in [0, A)
     if constexpr (MODE == kHeadTrain) {
+        // A stored action outside [0, A) (replay_sample_gather marks a row it could not assemble with -1) must not
+        // address anything: such a row gets loss 0 and gradient 0, and every index derived from it is clamped.
         act_taken = a.act[hrow];
+        act_taken = static_cast<unsigned>(act_taken) < static_cast<unsigned>(a.A) ? act_taken : 0;
         act_tail = a.act[trow_c];
+        act_ok = static_cast<unsigned>(act_tail) < static_cast<unsigned>(a.A);
+        act_tail = act_ok ? act_tail : 0;
         rew_tail = a.rew[trow_c];
         done_tail = a.done[trow_c];
     }
@@ -304,7 +310,8 @@ __global__ __launch_bounds__(256) void head_fwd_kernel(HeadArgs a)
             if (tk == 0) {
                 float dq = 0.f;
                 int act_b = 0;
-                if (live) {
+                if (live && !act_ok) { a.lossv[row] = 0.f; a.dqv[row] = 0.f; }
+                if (live && act_ok) {
                     const float y = rew_tail + a.gamma * (1.f - done_tail) * q1_star;
                     act_b = act_tail;
                     const float delta = q0_taken - y;
@@ -380,7 +387,12 @@ __device__ inline void small_grads_block(const BiasGradArgs& args, int block, un
         const int B = args.B, A = args.A;
         const T* h = static_cast<const T*>(args.h);
         float* s_loss = &red[0][0];   // 256 * 9 floats: room for kMaxBatch loss terms
-        for (int b = tid; b < B; b += 256) { s_dq[b] = args.dqv[b]; s_a[b] = args.act[b]; s_loss[b] = args.lossv[b]; }
+        for (int b = tid; b < B; b += 256) {
+            // a row whose stored action lies outside [0, A) has dq = 0 (head kernel); its index must still not leave s_acc
+            const int ab = args.act[b];
+            const bool ok = static_cast<unsigned>(ab) < static_cast<unsigned>(A);
+            s_dq[b] = ok ? args.dqv[b] : 0.f; s_a[b] = ok ? ab : 0; s_loss[b] = args.lossv[b];
+        }
         for (int a = 0; a < A; ++a) s_acc[a][tid] = 0.f;
         __syncthreads();
         // 16 columns per block; thread (o, part): samples b = part (mod 16) in increasing order.

@@ -5,6 +5,7 @@
 #include <string.h>
 
 #include <atomic>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -69,7 +70,11 @@ struct dqn_ctx {
     float* wg_partial = nullptr;
     hipEvent_t ev_train = nullptr, ev_act = nullptr, ev_sync = nullptr;
     std::atomic<bool> train_unrecorded{false};   // a train step has been enqueued since ev_train was last recorded
-    bool act_reads_online = false;   // an act step with use_target = 0 is in flight
+    // Held while a train step is being enqueued, and by an act step that reads theta (use_target = 0) from its wait for
+    // the train stream to the record of its own event: such an act step then sees whole train steps only, also when
+    // another host thread drives the train stream.  Act steps on theta^- (Concurrent Training) never take it.
+    std::mutex online_mu;
+    std::atomic<bool> act_reads_online{false};   // an act step with use_target = 0 has been enqueued since the train stream last waited for ev_act
     // dqn_train_step_sampled: two sets of minibatch buffers; `pre_*` describes the minibatch gathered ahead, if any
     uint8_t* mb_s[2] = {nullptr, nullptr};
     uint8_t* mb_s2[2] = {nullptr, nullptr};
@@ -118,6 +123,20 @@ static void free_ws(Workspace& ws)
 {
     (void)hipFree(ws.act1); (void)hipFree(ws.act2); (void)hipFree(ws.act3); (void)hipFree(ws.h);
     (void)hipFree(ws.q); (void)hipFree(ws.partial);
+}
+
+// The two fused conv kernels need more dynamic LDS than the default limit: raised once per process, whichever host
+// thread gets there first (the act and the train thread may both be on their first call).
+static hipError_t raise_lds_limits()
+{
+    static std::once_flag once;
+    static hipError_t result = hipSuccess;
+    std::call_once(once, [] {
+        result = hipFuncSetAttribute(reinterpret_cast<const void*>(conv_tower_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, kTowerSmem);
+        if (result == hipSuccess)
+            result = hipFuncSetAttribute(reinterpret_cast<const void*>(conv_tower_bwd_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, kTowerBwdSmem);
+    });
+    return result;
 }
 
 // Event pair for a launch of kernel `id`, or nulls if that kernel is not the selected one.
@@ -197,11 +216,7 @@ static int forward_to_fc1(dqn_ctx* c, hipStream_t st, Workspace& ws, int groups,
             a.act3[g] = act3 + g * e_act3;
         }
         a.n = n; a.groups = groups;
-        static bool attr_set = false;
-        if (!attr_set) {
-            DQN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(conv_tower_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, kTowerSmem));
-            attr_set = true;
-        }
+        DQN_HIP(raise_lds_limits());
         const int total = n * groups, grid = total < c->num_cus ? total : c->num_cus;
         a.per = (total + grid - 1) / grid;
         a.tower_blocks = grid;
@@ -293,18 +308,25 @@ static hipError_t wait_for_train(dqn_ctx* c)
     return hipStreamWaitEvent(c->act_stream, c->ev_train, 0);
 }
 
+// train_stream waits for the last act step that read theta (use_target = 0): it must finish before theta is overwritten.
+static hipError_t wait_for_online_act(dqn_ctx* c)
+{
+    if (!c->act_reads_online.exchange(false, std::memory_order_acq_rel)) return hipSuccess;
+    return hipStreamWaitEvent(c->train_stream, c->ev_act, 0);
+}
+
 template <typename T>
-static int act_impl(dqn_ctx* c, const uint8_t* states, int W, float epsilon, uint64_t act_step, int use_target,
+static int act_impl(dqn_ctx* c, Workspace& ws, const uint8_t* states, int W, float epsilon, uint64_t act_step, int use_target,
                     int32_t* actions, float* q_out, const PushStepPlan* push = nullptr)
 {
     const uint8_t* x[1] = {states};
     const void* shadow[1] = {use_target ? c->sh_t : c->sh};
     const float* master[1] = {use_target ? c->theta_t : c->theta};
     int slices = 0;
-    const int rc = forward_to_fc1<T>(c, c->act_stream, c->act_ws, 1, x, shadow, master, W, false, &slices, push);
+    const int rc = forward_to_fc1<T>(c, c->act_stream, ws, 1, x, shadow, master, W, false, &slices, push);
     if (rc != DQN_OK) return rc;
     HeadArgs ha{};
-    ha.partial = c->act_ws.partial; ha.slices = slices; ha.rows = W; ha.A = c->A; ha.groups = 1;
+    ha.partial = ws.partial; ha.slices = slices; ha.rows = W; ha.A = c->A; ha.groups = 1;
     ha.b1[0] = master[0] + c->off.bf1; ha.w2[0] = static_cast<const T*>(shadow[0]) + c->off.wf2; ha.b2[0] = master[0] + c->off.bf2;
     ha.epsilon = epsilon; ha.seed = c->cfg.seed; ha.act_step = act_step; ha.actions = actions; ha.q_out = q_out;
     ha.head_blocks = (W + kHeadRows - 1) / kHeadRows;
@@ -386,11 +408,7 @@ static int train_impl(dqn_ctx* c, const uint8_t* s, const int32_t* a, const floa
         TowerBwdArgs ta{};
         ta.dz3 = dz3; ta.act2 = act2; ta.act1 = act1; ta.w3d = bsh + kBshW3; ta.w2d = bsh + kBshW2;
         ta.dz2 = dz2; ta.dz1 = dz1; ta.n = B;
-        static bool attr_set = false;
-        if (!attr_set) {
-            DQN_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(conv_tower_bwd_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, kTowerBwdSmem));
-            attr_set = true;
-        }
+        DQN_HIP(raise_lds_limits());
         const int grid = B < c->num_cus ? B : c->num_cus;
         ta.per = (B + grid - 1) / grid;
         const ProfPair pr = prof_pair(c, K_TOWER_BWD);
@@ -729,27 +747,36 @@ int dqn_get_params(dqn_ctx* c, int which, float* host_dst, size_t n)
     return DQN_OK;
 }
 
+// dqn_act on the given workspace (the context's own); W has been checked.
+static int act_call(dqn_ctx* c, Workspace& ws, const char* who, const uint8_t* states, int32_t W, float epsilon,
+                    uint64_t act_step, int32_t use_target, int32_t* actions, float* q_out)
+{
+    if (!states || !actions) return fail(DQN_EINVAL, "%s: null pointer", who);
+    if (!aligned16(states)) return fail(DQN_EINVAL, "%s: states not 16-byte aligned", who);
+    if (!(epsilon >= 0.f && epsilon <= 1.f)) return fail(DQN_EINVAL, "%s: epsilon outside [0,1]", who);
+    std::unique_lock<std::mutex> online_lock(c->online_mu, std::defer_lock);
+    if (!use_target) {
+        online_lock.lock();
+        // standard DQN: the policy needs the parameters the last update produced (Section 3)
+        DQN_HIP(wait_for_train(c));
+    }
+    const int rc = c->cfg.precision == DQN_PRECISION_BF16
+                       ? act_impl<bf16_t>(c, ws, states, W, epsilon, act_step, use_target, actions, q_out)
+                       : act_impl<float>(c, ws, states, W, epsilon, act_step, use_target, actions, q_out);
+    if (rc != DQN_OK) return rc;
+    if (!use_target) {
+        DQN_HIP(hipEventRecord(c->ev_act, c->act_stream));
+        c->act_reads_online.store(true, std::memory_order_release);
+    }
+    return DQN_OK;
+}
+
 int dqn_act(dqn_ctx* c, const uint8_t* states, int32_t W, float epsilon, uint64_t act_step, int32_t use_target,
             int32_t* actions, float* q_out)
 {
     if (!c) return fail(DQN_EINVAL, "dqn_act: ctx is null");
     if (W < 1 || W > c->cfg.max_envs) return fail(DQN_EINVAL, "dqn_act: W = %d outside 1..%d", W, c->cfg.max_envs);
-    if (!states || !actions) return fail(DQN_EINVAL, "dqn_act: null pointer");
-    if (!aligned16(states)) return fail(DQN_EINVAL, "dqn_act: states not 16-byte aligned");
-    if (!(epsilon >= 0.f && epsilon <= 1.f)) return fail(DQN_EINVAL, "dqn_act: epsilon outside [0,1]");
-    if (!use_target) {
-        // standard DQN: the policy needs the parameters the last update produced (Section 3)
-        DQN_HIP(wait_for_train(c));
-    }
-    const int rc = c->cfg.precision == DQN_PRECISION_BF16
-                       ? act_impl<bf16_t>(c, states, W, epsilon, act_step, use_target, actions, q_out)
-                       : act_impl<float>(c, states, W, epsilon, act_step, use_target, actions, q_out);
-    if (rc != DQN_OK) return rc;
-    if (!use_target) {
-        DQN_HIP(hipEventRecord(c->ev_act, c->act_stream));
-        c->act_reads_online = true;
-    }
-    return DQN_OK;
+    return act_call(c, c->act_ws, "dqn_act", states, W, epsilon, act_step, use_target, actions, q_out);
 }
 
 int dqn_act_push_step(dqn_ctx* c, replay* rb, const uint8_t* push_frames, const int32_t* push_actions,
@@ -771,13 +798,17 @@ int dqn_act_push_step(dqn_ctx* c, replay* rb, const uint8_t* push_frames, const 
     PushStepPlan plan;
     int rc = replay_plan_push_step(rb, push_frames, push_actions, push_rewards, push_terminals, &plan);
     if (rc != DQN_OK) return rc;
-    if (!use_target) DQN_HIP(wait_for_train(c));
-    rc = act_impl<bf16_t>(c, states, W, epsilon, act_step, use_target, actions, q_out, &plan);
+    std::unique_lock<std::mutex> online_lock(c->online_mu, std::defer_lock);
+    if (!use_target) {
+        online_lock.lock();
+        DQN_HIP(wait_for_train(c));
+    }
+    rc = act_impl<bf16_t>(c, c->act_ws, states, W, epsilon, act_step, use_target, actions, q_out, &plan);
     if (rc != DQN_OK) return rc;
     replay_commit_push_step(rb);
     if (!use_target) {
         DQN_HIP(hipEventRecord(c->ev_act, c->act_stream));
-        c->act_reads_online = true;
+        c->act_reads_online.store(true, std::memory_order_release);
     }
     return DQN_OK;
 }
@@ -789,11 +820,8 @@ int dqn_train_step(dqn_ctx* c, const uint8_t* s, const int32_t* a, const float* 
     if (B < 1 || B > c->cfg.max_batch) return fail(DQN_EINVAL, "dqn_train_step: B = %d outside 1..%d", B, c->cfg.max_batch);
     if (!s || !a || !r || !s2 || !done) return fail(DQN_EINVAL, "dqn_train_step: null pointer");
     if (!aligned16(s) || !aligned16(s2)) return fail(DQN_EINVAL, "dqn_train_step: s/s2 not 16-byte aligned");
-    if (c->act_reads_online) {
-        // an act step that reads theta must finish before theta is overwritten
-        DQN_HIP(hipStreamWaitEvent(c->train_stream, c->ev_act, 0));
-        c->act_reads_online = false;
-    }
+    std::lock_guard<std::mutex> online_lock(c->online_mu);
+    DQN_HIP(wait_for_online_act(c));
     int rc;
     if (c->cfg.precision == DQN_PRECISION_BF16) rc = train_impl<bf16_t, true>(c, s, a, r, s2, done, B, loss_out);
     else rc = train_impl<float, false>(c, s, a, r, s2, done, B, loss_out);
@@ -809,6 +837,7 @@ int dqn_train_step_sampled(dqn_ctx* c, replay* rb, int32_t B, uint64_t sample_st
     if (B < 1 || B > c->cfg.max_batch) return fail(DQN_EINVAL, "dqn_train_step_sampled: B = %d outside 1..%d", B, c->cfg.max_batch);
     if (replay_sample_stream(rb) != c->train_stream)
         return fail(DQN_EINVAL, "dqn_train_step_sampled: the replay's sample stream must be the train stream");
+    std::lock_guard<std::mutex> online_lock(c->online_mu);
     int buf = 0;
     if (c->pre_valid && c->pre_rb == rb && c->pre_B == B && c->pre_step == sample_step && c->pre_epoch == replay_epoch(rb)) {
         buf = c->pre_buf;   // gathered inside the previous call's launches, and no flush since
@@ -827,10 +856,7 @@ int dqn_train_step_sampled(dqn_ctx* c, replay* rb, int32_t B, uint64_t sample_st
         if (rc != DQN_OK) return rc;
         ride = &plan;
     }
-    if (c->act_reads_online) {
-        DQN_HIP(hipStreamWaitEvent(c->train_stream, c->ev_act, 0));
-        c->act_reads_online = false;
-    }
+    DQN_HIP(wait_for_online_act(c));
     int rc;
     if (c->cfg.precision == DQN_PRECISION_BF16)
         rc = train_impl<bf16_t, true>(c, c->mb_s[buf], c->mb_a[buf], c->mb_r[buf], c->mb_s2[buf], c->mb_d[buf], B, loss_out, ride);
@@ -912,7 +938,7 @@ int dqn_sync_target(dqn_ctx* c, replay* rb, int32_t blocking)
     // wait: train_stream <- act_stream
     DQN_HIP(hipEventRecord(c->ev_act, c->act_stream));
     DQN_HIP(hipStreamWaitEvent(c->train_stream, c->ev_act, 0));
-    c->act_reads_online = false;
+    c->act_reads_online.store(false, std::memory_order_release);
     if (rb) {
         const int rc = replay_flush_ordered(rb);   // also orders the replay's push stream around the flush
         if (rc != DQN_OK) return rc;
