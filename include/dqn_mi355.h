@@ -103,6 +103,19 @@ int dqn_get_params(dqn_ctx* ctx, int which, float* host_dst, size_t n);
 int dqn_act(dqn_ctx* ctx, const uint8_t* states, int32_t W, float epsilon, uint64_t act_step,
             int32_t use_target, int32_t* actions, float* q_out);
 
+/* For callers that cannot allocate device memory or keep a workspace of their own alive: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results and errors as dqn_act,
+ * but every intermediate of the call (the activations between the layers and fc1's partial sums) lives in ONE
+ * fixed array inside the library's device image (about 3 MiB per GPU, held until the process ends) instead of in
+ * the buffers dqn_create allocated; the call itself allocates and frees nothing.  W <= DQN_ACT_STATIC_MAX_ENVS
+ * (and <= max_envs), else DQN_EINVAL.  Every call on a GPU, from any context, shares that GPU's array: two such
+ * calls that overlap on one GPU (different contexts or streams) race on it; calls on one act stream are ordered
+ * by the stream.  Nothing in the array needs clearing between calls (every element read was written by the same
+ * call).  ctx must have been created with the current device current. */
+#define DQN_ACT_STATIC_MAX_ENVS 32
+int dqn_act_static(dqn_ctx* ctx, const uint8_t* states, int32_t W, float epsilon, uint64_t act_step,
+                   int32_t use_target, int32_t* actions, float* q_out);
+
 /* ---- minibatch train step (Section 2.1, Eq. 1; Appendix B) -------------------------------- */
 
 /* One gradient update of theta on a minibatch of B transitions:

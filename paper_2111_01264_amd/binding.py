@@ -20,6 +20,7 @@ LIB_PATH = os.path.join(HERE, "libdqn_mi355.so")
 
 DQN_OK, DQN_EINVAL, DQN_EHIP, DQN_ENOMEM, DQN_ESTATE = 0, -1, -2, -3, -4
 DQN_PRECISION_FP32, DQN_PRECISION_BF16 = 0, 1
+DQN_ACT_STATIC_MAX_ENVS = 32
 DQN_PARAMS_ONLINE, DQN_PARAMS_TARGET, DQN_PARAMS_RMS_V, DQN_PARAMS_RMS_M, DQN_PARAMS_GRAD = range(5)
 
 
@@ -55,6 +56,8 @@ EXPORTS = {
     "dqn_get_params": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_size_t]),
     "dqn_act": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_float, C.c_uint64, C.c_int32,
                           C.c_void_p, C.c_void_p]),
+    "dqn_act_static": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_float, C.c_uint64, C.c_int32,
+                                 C.c_void_p, C.c_void_p]),
     "dqn_train_step": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                  C.c_void_p, C.c_int32, C.c_void_p]),
     "dqn_get_train_q": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
@@ -163,6 +166,10 @@ def dqn_get_params(ctx, which):
 
 def dqn_act(ctx, states, W, epsilon, act_step, use_target, actions, q_out=None):
     _check(_lib.dqn_act(ctx, _ptr(states), W, epsilon, act_step, use_target, _ptr(actions), _ptr(q_out)))
+
+
+def dqn_act_static(ctx, states, W, epsilon, act_step, use_target, actions, q_out=None):
+    _check(_lib.dqn_act_static(ctx, _ptr(states), W, epsilon, act_step, use_target, _ptr(actions), _ptr(q_out)))
 
 
 def dqn_train_step(ctx, s, a, r, s2, done, B, loss_out=None):

@@ -54,8 +54,47 @@ struct Workspace {
 
 };
 
+// ---- dqn_act_static: the act step's intermediates in a fixed array of the device image ------------------------
+// Sub-buffers for up to kActStaticMaxEnvs states in either precision (fp32 sizes; the 16-bit mode uses half of the
+// activation bytes): act1, act2, act3 and the seven fc1 k-slices of a minibatch of at most 32 rows.
+constexpr int kActStaticMaxEnvs = DQN_ACT_STATIC_MAX_ENVS;
+constexpr size_t align256(size_t n) { return (n + 255) / 256 * 256; }
+constexpr size_t kActStaticAct1 = 0;
+constexpr size_t kActStaticAct2 = kActStaticAct1 + align256(static_cast<size_t>(kActStaticMaxEnvs) * 12800 * 4);
+constexpr size_t kActStaticAct3 = kActStaticAct2 + align256(static_cast<size_t>(kActStaticMaxEnvs) * 5184 * 4);
+constexpr size_t kActStaticPartial = kActStaticAct3 + align256(static_cast<size_t>(kActStaticMaxEnvs) * 3136 * 4);
+constexpr size_t kActStaticBytes = kActStaticPartial + align256(static_cast<size_t>(7) * kActStaticMaxEnvs * 512 * 4);
+static_assert(kActStaticMaxEnvs <= 32, "the k-slice area assumes the small-batch fc1 kernel (seven slices)");
+static __device__ __align__(256) unsigned char scratch[kActStaticBytes];   // about 3 MiB per GPU, for the life of the process
+
+// In host code `scratch` is only a handle for the symbol: its device address differs per GPU and is looked up once
+// per device, with that device current (dqn_create does it for the device it runs on).
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mu;
+static void* g_scratch_ptr[kMaxDevices] = {};
+
+static hipError_t static_scratch_of(int device, void** out)
+{
+    if (device < 0 || device >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_ptr[device]) {
+        int current = -1;
+        hipError_t e = hipGetDevice(&current);
+        if (e != hipSuccess) return e;
+        if (current != device) return hipErrorInvalidDevice;   // resolved for the current device only
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        g_scratch_ptr[device] = p;
+    }
+    *out = g_scratch_ptr[device];
+    return hipSuccess;
+}
+
 struct dqn_ctx {
     dqn_config cfg;
+    int device = 0;
     int A;
     Offsets off;
     size_t esize;           // bytes per operand element
@@ -622,6 +661,9 @@ int dqn_create(const dqn_config* cfg, void* act_stream, void* train_stream, dqn_
     auto body = [&]() -> int {
         int dev = 0;
         DQN_HIP(hipGetDevice(&dev));
+        c->device = dev;
+        void* static_scratch = nullptr;
+        DQN_HIP(static_scratch_of(dev, &static_scratch));   // dqn_act_static's array on this device
         DQN_HIP(hipDeviceGetAttribute(&c->num_cus, hipDeviceAttributeMultiprocessorCount, dev));
         if (c->num_cus < 1) c->num_cus = 1;
         float** blobs[5] = {&c->theta, &c->theta_t, &c->v, &c->m, &c->grad};
@@ -747,7 +789,7 @@ int dqn_get_params(dqn_ctx* c, int which, float* host_dst, size_t n)
     return DQN_OK;
 }
 
-// dqn_act on the given workspace (the context's own); W has been checked.
+// dqn_act on the given workspace (the context's own, or the fixed array of dqn_act_static); W has been checked.
 static int act_call(dqn_ctx* c, Workspace& ws, const char* who, const uint8_t* states, int32_t W, float epsilon,
                     uint64_t act_step, int32_t use_target, int32_t* actions, float* q_out)
 {
@@ -777,6 +819,23 @@ int dqn_act(dqn_ctx* c, const uint8_t* states, int32_t W, float epsilon, uint64_
     if (!c) return fail(DQN_EINVAL, "dqn_act: ctx is null");
     if (W < 1 || W > c->cfg.max_envs) return fail(DQN_EINVAL, "dqn_act: W = %d outside 1..%d", W, c->cfg.max_envs);
     return act_call(c, c->act_ws, "dqn_act", states, W, epsilon, act_step, use_target, actions, q_out);
+}
+
+int dqn_act_static(dqn_ctx* c, const uint8_t* states, int32_t W, float epsilon, uint64_t act_step, int32_t use_target,
+                   int32_t* actions, float* q_out)
+{
+    if (!c) return fail(DQN_EINVAL, "dqn_act_static: ctx is null");
+    if (W < 1 || W > c->cfg.max_envs || W > kActStaticMaxEnvs)
+        return fail(DQN_EINVAL, "dqn_act_static: W = %d outside 1..%d (the fixed array holds at most %d states)", W,
+                    c->cfg.max_envs < kActStaticMaxEnvs ? c->cfg.max_envs : kActStaticMaxEnvs, kActStaticMaxEnvs);
+    void* base = nullptr;
+    DQN_HIP(static_scratch_of(c->device, &base));   // looked up by dqn_create; here only a table read
+    unsigned char* p = static_cast<unsigned char*>(base);
+    Workspace ws;
+    ws.act1 = p + kActStaticAct1; ws.act2 = p + kActStaticAct2; ws.act3 = p + kActStaticAct3;
+    ws.partial = reinterpret_cast<float*>(p + kActStaticPartial);
+    ws.partial_cap = static_cast<size_t>(7) * kActStaticMaxEnvs * 512;
+    return act_call(c, ws, "dqn_act_static", states, W, epsilon, act_step, use_target, actions, q_out);
 }
 
 int dqn_act_push_step(dqn_ctx* c, replay* rb, const uint8_t* push_frames, const int32_t* push_actions,
