@@ -9,8 +9,8 @@ act stream + one replay sample/gather and one train step on the train stream; ev
 train steps the synchronisation point of Algorithm 1 (flush, theta^- <- theta).  As in the paper, a
 trainer thread drives the train stream while the sampler side drives the act stream.
 
-Prints ONE JSON line.  `--sweep` instead prints the batch/W sweep table (bf16 MFMA utilisation per
-kernel and gather bandwidth) as plain text.
+Prints ONE JSON line.  `--sweep` instead prints one JSON line per point of the batch/W sweep (bf16 MFMA
+utilisation per kernel and gather bandwidth; a readable table goes to stderr).
 """
 from __future__ import annotations
 
@@ -46,9 +46,9 @@ def kernel_work(name, B, A, groups, precision):
         "fc1_wgrad": (2.0 * 512 * 3136 * B, 512 * 3136 * 4 + B * (3136 + 512) * e),
         "fc1_dgrad": (2.0 * B * 3136 * 512, 512 * 3136 * e + B * (3136 * 2 + 512) * e),
         "conv3_wgrad": (2.0 * 64 * 576 * B * 49, B * (5184 + 3136) * e + 64 * 576 * 4),
-        "conv3_dgrad": (2.0 * B * 81 * 64 * 576, B * (3136 + 2 * 5184) * e),
+        "conv3_dgrad": (2.0 * B * 49 * 64 * 576, B * (3136 + 2 * 5184) * e),      # the method's MACs (= the forward layer's), not the zero-padded gather form
         "conv2_wgrad": (2.0 * 64 * 512 * B * 81, B * (12800 + 5184) * e + 64 * 512 * 4),
-        "conv2_dgrad": (2.0 * B * 400 * 32 * 256, B * (5184 + 2 * 12800) * e),
+        "conv2_dgrad": (2.0 * B * 81 * 64 * 512, B * (5184 + 2 * 12800) * e),
         "conv1_wgrad": (2.0 * 32 * 256 * B * 400, B * (28224 + 12800 * e) + 32 * 256 * 4),
         "small_grads": (1.0 * B * (12800 + 5184 + 3136 + 512), B * (12800 + 5184 + 3136 + 512 + 512) * e),
         "rmsprop": (10.0 * n_par, n_par * (28 + (2 if precision == "bf16" else 0))),
@@ -68,9 +68,9 @@ _C = "paper_2111_01264_amd/csrc/"
 _RMS_SRC = (_C + "head_kernels.h", _C + "net.hip")   # net.hip fixes the number of split-K slices the optimiser reads
 _WG_SRC = (_C + "wgrad_all.h", _C + "gemm_tn_tr.h", _C + "layers.h", _C + "head_kernels.h", _C + "gemm_mfma.h", _C + "net.hip")
 TRAFFIC = {
-    ("rmsprop", 32, "bf16"): (63.13e6, _RMS_SRC, "35f437d786b773e56b045051089c5feeb26a9a4a"),
-    ("rmsprop", 256, "bf16"): (68.03e6, _RMS_SRC, "35f437d786b773e56b045051089c5feeb26a9a4a"),
-    ("wgrad_all", 256, "bf16"): (94.22e6, _WG_SRC, "8b76f8619971fd80526af12eda5aecb5c2f095ee"),
+    ("rmsprop", 32, "bf16"): (63.13e6, _RMS_SRC, "35f437d786b773e56b045051089c5feeb26a9a4a", "profiles/hbm_traffic_b32.txt"),
+    ("rmsprop", 256, "bf16"): (68.03e6, _RMS_SRC, "35f437d786b773e56b045051089c5feeb26a9a4a", "profiles/hbm_traffic_b256.txt"),
+    ("wgrad_all", 256, "bf16"): (94.22e6, _WG_SRC, "8b76f8619971fd80526af12eda5aecb5c2f095ee", "profiles/hbm_traffic_b256.txt"),
 }
 
 
@@ -78,16 +78,16 @@ def measured_traffic(name, B, precision):
     import hashlib
     ent = TRAFFIC.get((name, B, precision))
     if not ent:
-        return None
-    nbytes, srcs, sha = ent
+        return None, None
+    nbytes, srcs, sha, where = ent
     h = hashlib.sha1()
     try:
         for src in srcs:
             with open(os.path.join(ROOT, src), "rb") as f:
                 h.update(f.read())
     except OSError:
-        return None
-    return nbytes if h.hexdigest() == sha else None
+        return None, None
+    return (nbytes, where) if h.hexdigest() == sha else (None, None)
 
 
 def roofline_for(name, avg_ms, B, A, groups, precision):
@@ -338,20 +338,28 @@ def cpu_baseline(args):
     rep.flush()
     agent = odqn.OracleDQN(A, synth.init_params(seed, A), seed=seed, double_dqn=bool(args.double_dqn))
     states = synth.act_states(seed, 0, W)
-    budget, done_steps = args.cpu_seconds, 0
-    t0 = time.perf_counter()
-    while True:
-        for k in range(args.acts_per_train):
-            agent.act(states, 0.1, done_steps * args.acts_per_train + k, use_target=True)
-        s, s2, a, r, d = rep.gather(rep.sample_indices(B, done_steps))
-        agent.train_step(s, a, r, s2, d)
-        done_steps += 1
-        el = time.perf_counter() - t0
-        if el >= budget or done_steps >= 1000:
-            break
-    return {"value": done_steps / el, "unit": "train steps/s", "cores": odqn.max_threads(), "kind": "oracle",
-            "sample": "%d steps (each: %d act steps of W=%d + gather + train step at batch %d) in %.1f s"
-                      % (done_steps, args.acts_per_train, W, B, el)}
+    def timed(budget, step0):
+        done, t0 = 0, time.perf_counter()
+        while True:
+            for k in range(args.acts_per_train):
+                agent.act(states, 0.1, (step0 + done) * args.acts_per_train + k, use_target=True)
+            s, s2, a, r, d = rep.gather(rep.sample_indices(B, step0 + done))
+            agent.train_step(s, a, r, s2, d)
+            done += 1
+            el = time.perf_counter() - t0
+            if el >= budget or done >= 1000:
+                return done, el
+
+    n_all, el_all = timed(args.cpu_seconds, 0)
+    # the same loop on one thread (results are bitwise those of any thread count)
+    cores = odqn.set_threads(1)
+    n_one, el_one = timed(args.cpu_seconds * 0.6, n_all)
+    odqn.set_threads(cores)
+    what = "each: %d act steps of W=%d + gather + train step at batch %d" % (args.acts_per_train, W, B)
+    return {"value": n_all / el_all, "unit": "train steps/s", "cores": cores, "kind": "oracle",
+            "sample": "%d steps (%s) in %.1f s on %d threads; single thread: %d steps in %.1f s"
+                      % (n_all, what, el_all, cores, n_one, el_one),
+            "single_thread": {"value": n_one / el_one, "unit": "train steps/s", "cores": 1}}
 
 
 def run_alg1(args, W, concurrent, synchronized, blocks, warmup_blocks, prepopulate, frames):
@@ -486,7 +494,7 @@ def main():
                     help="replay_push_step and dqn_act as two calls per act step instead of dqn_act_push_step")
     ap.add_argument("--separate-gather", action="store_true",
                     help="replay_sample_gather and dqn_train_step as two calls instead of dqn_train_step_sampled")
-    ap.add_argument("--sweep", action="store_true", help="print the batch/W roofline sweep instead of the JSON line")
+    ap.add_argument("--sweep", action="store_true", help="the batch/W roofline sweep: one JSON line per point")
     ap.add_argument("--algorithm1", action="store_true",
                     help="time the Algorithm 1 orchestrator (dqn_alg1_*) instead: one JSON line of its own")
     ap.add_argument("--ablation", action="store_true",
@@ -515,25 +523,25 @@ def main():
     time_steps(wl, max(args.warmup // 2, 1))
     # find the dominant train-step kernel before the timed region, then time it inside the region
     breakdown = kernel_breakdown(wl, max(min(args.warmup // 30, 50), 5))
-    pair_ms = breakdown.pop("event_pair", 0.0)
+    breakdown.pop("event_pair", None)
     dominant = max(breakdown, key=breakdown.get)
     time_steps(wl, max(args.warmup // 2, 1))
     kid = [wl.P.dqn_profile_kernel_name(i) for i in range(wl.P.dqn_profile_kernel_count() + 1)].index(dominant)
-    # a sample of the dominant kernel's launches spread over the whole timed region (at most 4096 brackets are kept)
+    # a sample of the dominant kernel's launches spread over the whole timed region (at most 4096 are kept); the
+    # timing events are bound to the kernel's own dispatch, so the average is the kernel's begin-to-end time on the
+    # GPU -- the duration rocprofv3's kernel trace reports for it
     every = max(1, -(-args.steps // 2048))
     wl.P.dqn_profile_select_every(wl.ctx, kid, every)
     elapsed = time_steps(wl, args.steps)
     ms, n = wl.P.dqn_profile_read(wl.ctx)
     wl.P.dqn_profile_select(wl.ctx, 0)
-    # an event bracket also spans the two event records themselves: an empty bracket measures that share
-    roof = roofline_for(dominant, max(ms / max(n, 1) - pair_ms, 1e-6), args.batch, args.actions, groups, args.precision)
-    roof["traffic"] = measured_traffic(dominant, args.batch, args.precision)
+    roof = roofline_for(dominant, max(ms / max(n, 1), 1e-6), args.batch, args.actions, groups, args.precision)
+    roof["traffic"], roof["traffic_source"] = measured_traffic(dominant, args.batch, args.precision)
     roof["timed_launches"] = n
-    roof["bracketed_every"] = every
-    roof["bracket_us"] = ms / max(n, 1) * 1e3
-    roof["empty_bracket_us"] = pair_ms * 1e3
+    roof["timed_every"] = every
+    roof["timing"] = "HIP events bound to the kernel's dispatch on the train stream (hipExtLaunchKernel), live in the timed region"
     # each side alone (what the overlap hides): short runs outside the timed region
-    alone_steps = max(min(args.steps // 5, 2000), 1)
+    alone_steps = max(min(args.steps // 5, 2000), 200)
     train_alone = alone_steps / time_steps(wl, alone_steps, "train")
     act_alone = (alone_steps * args.acts_per_train * args.envs / time_steps(wl, alone_steps, "act")) if args.acts_per_train else 0.0
     wl.close()
@@ -555,7 +563,7 @@ def main():
                                % (args.actions, args.envs, args.frames, args.lanes, args.batch, args.acts_per_train,
                                   args.sync_every),
                    "double_dqn": bool(args.double_dqn), "seed": args.seed},
-        "kernel_avg_us": {k: round(max(v - pair_ms, 0.0) * 1e3, 2) for k, v in breakdown.items()},
+        "kernel_avg_us": {k: round(v * 1e3, 2) for k, v in breakdown.items()},
         "roofline": roof,
         "context": "paper: 25 h -> 9 h for 200M frames on one GTX 1080 (end to end, emulator included)",
     }
@@ -566,23 +574,23 @@ def main():
 
 
 def sweep(args):
-    """Batch in {128,256,512} x W in {32,64,128}, bf16: per-kernel time and roofline fractions."""
+    """Batch in {128,256,512} x W in {32,64,128}, bf16: one JSON line per point with the per-kernel durations (events
+    bound to each kernel's dispatch), their roofline fractions on algorithmic FLOPs / bytes, the gather's bandwidth
+    and a `roofline` object for the point's longest train-step kernel; a readable table goes to stderr."""
     import copy
-    rows = []
     for B, W in ((128, 32), (256, 64), (512, 128)):
         a = copy.copy(args)
         a.batch, a.envs, a.acts_per_train = B, W, 1
         a.frames = min(args.frames, 200000)
         wl = Workload(a)
         groups = 3 if a.double_dqn else 2
-        time_steps(wl, 20)
-        br = kernel_breakdown(wl, 20)
-        pair_ms = br.pop("event_pair", 0.0)
-        br = {k: max(v - pair_ms, 1e-6) for k, v in br.items()}   # net of the empty event bracket
-        steps = 200
+        time_steps(wl, 30)
+        br = kernel_breakdown(wl, 30)
+        br.pop("event_pair", None)
+        steps = 300
         el = time_steps(wl, steps)
         torch = wl.torch
-        # gather alone, timed with events on the train stream
+        # the stand-alone gather kernel, timed with events on the train stream over 50 back-to-back launches
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record(wl.train_stream)
         for i in range(50):
@@ -591,13 +599,30 @@ def sweep(args):
         torch.cuda.synchronize()
         g_ms = e0.elapsed_time(e1) / 50
         wl.close()
+        kernels = {name: roofline_for(name, ms, B, a.actions, groups, a.precision) for name, ms in br.items()}
+        longest = max(br, key=br.get)
+        roof = dict(kernels[longest])
+        roof["traffic"], roof["traffic_source"] = measured_traffic(longest, B, a.precision)
         print("B=%d W=%d  %.1f train steps/s  %.1f us/step  gather %.1f us = %.0f GB/s" %
-              (B, W, steps / el, 1e6 * el / steps, g_ms * 1e3, 91728 * B / (g_ms * 1e-3) / 1e9))
-        for name, ms in br.items():
-            r = roofline_for(name, ms, B, a.actions, groups, a.precision)
-            print("   %-12s %8.1f us  %-4s %9.1f %-7s  %5.1f %%" % (name, ms * 1e3, r["bound"], r["achieved"],
-                                                                   r["unit"], 100 * r["frac"]))
-        rows.append((B, W))
+              (B, W, steps / el, 1e6 * el / steps, g_ms * 1e3, 91728 * B / (g_ms * 1e-3) / 1e9), file=sys.stderr)
+        for name, r in kernels.items():
+            print("   %-14s %8.1f us  %-4s %9.1f %-7s  %5.1f %%" % (name, r["avg_launch_us"], r["bound"], r["achieved"],
+                                                                     r["unit"], 100 * r["frac"]), file=sys.stderr)
+        print(json.dumps({
+            "metric": "train steps/sec (batch %d) + act states/sec" % B, "value": steps / el, "unit": "train steps/s",
+            "act_states_per_sec": steps * W / el, "n_gpus": 1, "steps": steps, "warmup": 30, "ms_per_step": 1e3 * el / steps,
+            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if a.precision == "bf16" else "f32",
+            "data": "synthetic",
+            "config": {"workload": "roofline scaling point: A=%d, batch %d, W=%d, 1 act step per train step on a concurrent "
+                                   "stream, replay %d frames" % (a.actions, B, W, a.frames), "double_dqn": bool(a.double_dqn),
+                       "seed": a.seed},
+            "roofline": roof,
+            "kernels": {k: {"avg_launch_us": round(v["avg_launch_us"], 2), "bound": v["bound"], "frac": round(v["frac"], 4)}
+                        for k, v in kernels.items()},
+            "gather": {"avg_launch_us": g_ms * 1e3, "achieved": 91728 * B / (g_ms * 1e-3) / 1e9, "unit": "GB/s",
+                       "frac": 91728 * B / (g_ms * 1e-3) / 1e9 / PEAK["hbm"][0],
+                       "note": "stand-alone replay_sample_gather, 50 back-to-back launches between two event records"},
+        }))
     return 0
 
 

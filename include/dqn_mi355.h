@@ -365,20 +365,20 @@ int dqn_alg1_stats(const dqn_alg1* h, int64_t* host_t, int64_t* host_act_steps, 
 
 /* ---- per-kernel timing (measurement support) ------------------------------------------------- */
 
-/* Number of distinct kernels a train step launches, and their names (id 1 .. count).  The last id,
- * "event_pair", is not a kernel: selecting it brackets nothing, so that its average is what the two
- * event records of a bracket cost by themselves (subtract it from a kernel's bracketed time). */
+/* Number of distinct kernels a train step launches, and their names (id 1 .. count).  The id named
+ * "event_pair" is not a kernel: selecting it times a pair of event records with nothing in between (what an
+ * event bracket around a launch would add; the timing below does not use brackets). */
 int dqn_profile_kernel_count(void);
 const char* dqn_profile_kernel_name(int kernel_id);
 
-/* Selects one kernel of dqn_train_step (0 = none): from now on each of its launches is bracketed
- * by a pair of HIP events on train_stream (up to 4096 launches are kept, later ones are not
- * timed).  Selecting resets the collected data. */
+/* Selects one kernel of dqn_train_step (0 = none): from now on each of its launches carries a pair of HIP
+ * events bound to the kernel's own dispatch (hipExtLaunchKernel), so that the time between them is the
+ * kernel's begin-to-end time on the GPU -- the duration a kernel trace reports for it (up to 4096 launches
+ * are kept, later ones are not timed).  Selecting resets the collected data. */
 int dqn_profile_select(dqn_ctx* ctx, int kernel_id);
 
-/* The same with only every `every`-th launch of the kernel bracketed (every >= 1): a pair of event
- * records costs the stream a few microseconds, so a long timed run samples its launches instead of
- * bracketing each (and the 4096 kept samples then span the whole run). */
+/* The same with only every `every`-th launch of the kernel timed (every >= 1), so that the 4096 kept
+ * samples span a long run. */
 int dqn_profile_select_every(dqn_ctx* ctx, int kernel_id, int32_t every);
 
 /* Waits for train_stream, then returns the summed duration in milliseconds and the number of

@@ -75,12 +75,19 @@ def lib():
                                    C.c_int]
         L.oracle_max_threads.restype = C.c_int
         L.oracle_max_threads.argtypes = []
+        L.oracle_set_threads.restype = C.c_int
+        L.oracle_set_threads.argtypes = [C.c_int]
         _lib = L
     return _lib
 
 
 def max_threads() -> int:
     return int(lib().oracle_max_threads())
+
+
+def set_threads(n: int) -> int:
+    """Thread count of the C loops from now on (timing only: results are independent of it); returns the previous one."""
+    return int(lib().oracle_set_threads(int(n)))
 
 
 def _dp(a):

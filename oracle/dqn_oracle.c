@@ -325,6 +325,9 @@ void rmsprop_step(double *theta, const double *g, double *v, double *m, size_t n
 #ifdef _OPENMP
 #include <omp.h>
 int oracle_max_threads(void) { return omp_get_max_threads(); }
+/* Thread count of the loops above from now on (n >= 1); results do not depend on it.  Returns the previous count. */
+int oracle_set_threads(int n) { int old = omp_get_max_threads(); if (n >= 1) omp_set_num_threads(n); return old; }
 #else
 int oracle_max_threads(void) { return 1; }
+int oracle_set_threads(int n) { (void)n; return 1; }
 #endif

@@ -107,6 +107,72 @@ struct GatherPlan {
     int32_t B;                  // 0 = nothing to gather
 };
 
+// Global index of the transition that draw b of the call selects (or that idx_in names).
+__device__ inline int64_t sampled_index(const GatherPlan& p, int b)
+{
+    if (p.idx_in) return p.idx_in[b];
+    const Philox4 d = philox_draw(p.seed, kTagSample, p.sample_step, static_cast<uint32_t>(b));
+    const uint64_t u = (static_cast<uint64_t>(d.x[1]) << 32) | d.x[0];
+    int64_t k = static_cast<int64_t>(__umul64hi(u, static_cast<uint64_t>(p.V)));
+    int lane = 0;
+    for (;;) {
+        const int64_t v = p.tab.count[lane] > 4 ? p.tab.count[lane] - 4 : 0;
+        if (k < v || lane == p.L - 1) break;
+        k -= v;
+        ++lane;
+    }
+    return lane * p.M + 3 + k;
+}
+
+// The minibatch row of sample b as a DESCRIPTOR instead of copied frames: desc[0..3] = replay slots of the four frames
+// of s, desc[4..7] = those of s', -1 for a frame that is all zeros (a terminal flag lies between it and the stack's
+// newest frame, or the index is invalid); a, r, done (and idx_out) are written as gather_block writes them.  A kernel
+// that consumes states can then read the frames straight from the replay memory (Section 2.1: states are stacks of
+// the four latest frames), and the 56 KB per sample that a materialised (s, s') pair costs are never written.
+constexpr int kDescInts = 8;
+__device__ inline void sample_desc(const GatherPlan& p, int b, int32_t* __restrict__ desc)
+{
+    const int64_t idx = sampled_index(p, b);
+    bool ok = idx >= 0 && idx < static_cast<int64_t>(p.L) * p.M;
+    int lane = 0;
+    int64_t j = 0;
+    if (ok) {
+        lane = static_cast<int>(idx / p.M);
+        j = idx % p.M;
+        ok = j >= 3 && j <= static_cast<int64_t>(p.tab.count[lane]) - 2;
+    }
+    if (p.idx_out) p.idx_out[b] = idx;
+    if (!ok) {
+#pragma unroll
+        for (int f = 0; f < kDescInts; ++f) desc[f] = -1;
+        p.a[b] = -1; p.r[b] = 0.f; p.done[b] = 0.f;
+        return;
+    }
+    const int64_t base = static_cast<int64_t>(p.tab.head[lane]) - p.tab.count[lane] + p.M;  // >= 0
+    const int64_t lane0 = lane * p.M;
+    uint32_t t[4];   // terminal flags of ages j-3 .. j
+#pragma unroll
+    for (int u = 0; u < 4; ++u) t[u] = p.terminals[lane0 + (base + j - 3 + u) % p.M];
+    int32_t slot[5];
+#pragma unroll
+    for (int f = 0; f < 5; ++f) slot[f] = static_cast<int32_t>(lane0 + (base + j - 3 + f) % p.M);
+#pragma unroll
+    for (int f = 0; f < 4; ++f) {
+        uint32_t any_s = 0, any_s2 = 0;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            if (u >= f && u <= 2) any_s |= t[u];          // frame f of s: ages j-3+f .. j-1
+            if (u >= f + 1) any_s2 |= t[u];               // frame f of s' is window frame f+1: ages j-2+f .. j
+        }
+        desc[f] = any_s ? -1 : slot[f];
+        desc[4 + f] = any_s2 ? -1 : slot[f + 1];
+    }
+    const int64_t tslot = lane0 + (base + j) % p.M;
+    p.a[b] = p.actions[tslot];
+    p.r[b] = p.rewards[tslot];
+    p.done[b] = t[3] ? 1.f : 0.f;
+}
+
 // Workgroup (frame f of the five-frame window ages j-3 .. j+1, sample b), 256 threads.  The frame is read once and
 // written into s (position f, f <= 3) and s2 (position f-1, f >= 1), each zeroed if a terminal flag lies between
 // the frame and the newest frame of that stack (Section 2.1: states are stacks of the four latest frames).
@@ -118,22 +184,7 @@ __device__ inline void gather_block(const GatherPlan& p, int f, int b)
     const int32_t L = p.L; const int64_t M = p.M, V = p.V; const uint64_t seed = p.seed, sample_step = p.sample_step;
     const int64_t* __restrict__ idx_in = p.idx_in; uint8_t* __restrict__ s = p.s; uint8_t* __restrict__ s2 = p.s2;
     int32_t* __restrict__ a = p.a; float* __restrict__ r = p.r; float* __restrict__ done = p.done; int64_t* __restrict__ idx_out = p.idx_out;
-    int64_t idx;
-    if (idx_in) {
-        idx = idx_in[b];
-    } else {
-        const Philox4 d = philox_draw(seed, kTagSample, sample_step, static_cast<uint32_t>(b));
-        const uint64_t u = (static_cast<uint64_t>(d.x[1]) << 32) | d.x[0];
-        int64_t k = static_cast<int64_t>(__umul64hi(u, static_cast<uint64_t>(V)));
-        int lane = 0;
-        for (;;) {
-            const int64_t v = tab.count[lane] > 4 ? tab.count[lane] - 4 : 0;
-            if (k < v || lane == L - 1) break;
-            k -= v;
-            ++lane;
-        }
-        idx = lane * M + 3 + k;
-    }
+    const int64_t idx = sampled_index(p, b);
     bool ok = idx >= 0 && idx < static_cast<int64_t>(L) * M;
     int lane = 0;
     int64_t j = 0;
@@ -195,6 +246,8 @@ int replay_plan_sample_gather(replay* rb, int32_t B, uint64_t sample_step, const
 // Changes with every flush (and differs between replay memories): two gathers of the same sample step read the same
 // minibatch iff their epochs are equal.
 uint64_t replay_epoch(const replay* rb);
+// The ring's frame array [capacity][84][84] (device memory owned by rb).
+const uint8_t* replay_ring_frames(const replay* rb);
 
 // Validates a replay_push_step call and fills `plan` without enqueuing anything; replay_commit_push_step then
 // records that the experiences have been appended (call it once the kernel carrying the plan is enqueued).

@@ -98,7 +98,12 @@ struct TowerArgs {
     int n, groups;
     int per;                    // items per workgroup = ceil(n * groups / grid size), computed by the host
     int tower_blocks;           // workgroups [0, tower_blocks) run the tower, the next push.L ones the append below
-    const uint8_t* x[kMaxGroups];      // [n][4][84][84], 16-byte aligned
+    const uint8_t* x[kMaxGroups];      // [n][4][84][84], 16-byte aligned (unused with a descriptor table)
+    // Minibatch given as per-sample descriptors (sample_desc in common.h: replay slots of the frames of s and s', -1 =
+    // zero frame) instead of assembled states: group 0 reads the four frames of s, every other group those of s',
+    // straight from the replay memory's frame array.  Null: states come from x.
+    const int32_t* desc;               // [n][8]
+    const uint8_t* ring;               // [capacity][84][84]
     const _Float16* w1[kMaxGroups];    // fragment order, fp16
     const float* b1[kMaxGroups];
     const float* b2[kMaxGroups];
@@ -108,6 +113,7 @@ struct TowerArgs {
     bf16_t* act1[kMaxGroups];   // [n][400][32] or null
     bf16_t* act2[kMaxGroups];   // [n][81][64] or null
     bf16_t* act3[kMaxGroups];   // [n][49][64]
+    uint8_t* s_out;             // with desc: group 0 also stores the state it assembled, [n][4][84][84] (the weight gradient of conv1 reads it)
     PushStepPlan push;          // optional (L = 0: none): one experience per lane into the temporary buffers
 };
 
@@ -147,20 +153,51 @@ __global__ __launch_bounds__(kTowerThreads) void conv_tower_kernel(TowerArgs a)
     if (first >= last) return;
 
     // The state of item (g_, b_), 16 bytes per lane and load (the last load is clamped, not predicated);
-    // named registers rather than an array, which the compiler would keep in scratch memory.
+    // named registers rather than an array, which the compiler would keep in scratch memory.  With a descriptor table
+    // the four frames of the state sit anywhere in the replay memory: vector v of the state belongs to frame v / 441
+    // (a frame is 441 vectors), so each of a thread's four loads chooses between two neighbouring frames; a zero frame
+    // (slot -1) is loaded from slot 0 and ANDed away.  The descriptor of an item is requested a whole item before its
+    // frames are (dn*: the item after next), so that the frames never wait for it.
     constexpr int kXVecs = kTowerXBytes / 16;   // 1764
     const int last_vec = tid + 1536 < kXVecs ? tid + 1536 : kXVecs - 1;
-#define DQN_TOWER_FETCH_STATE(g_, b_)                                                                        \
+    const bool use_desc = a.desc != nullptr;
+    const bool hi0 = tid >= 441, hi1 = tid + 512 >= 882, hi2 = tid + 1024 >= 1323;         // second of the two candidate frames
+    const int w0 = tid - (hi0 ? 441 : 0), w1 = tid + 512 - (hi1 ? 882 : 441), w2 = tid + 1024 - (hi2 ? 1323 : 882), w3 = last_vec - 1323;
+    V8 wf2[8], wf3[9];
+    uint4 xv0, xv1, xv2, xv3;
+    int dn0 = 0, dn1 = 0, dn2 = 0, dn3 = 0;   // descriptor (four slots) of the item whose frames are requested next
+#define DQN_TOWER_FETCH_DESC(g_, b_)                                                                          \
     {                                                                                                        \
+        const int32_t* dp_ = a.desc + static_cast<size_t>(b_) * kDescInts + ((g_) > 0 ? 4 : 0);                \
+        dn0 = dp_[0]; dn1 = dp_[1]; dn2 = dp_[2]; dn3 = dp_[3];                                                \
+    }
+#define DQN_TOWER_FETCH_STATE(g_, b_)                                                                        \
+    if (use_desc) {                                                                                          \
+        const int s0_ = hi0 ? dn1 : dn0, s1_ = hi1 ? dn2 : dn1, s2_ = hi2 ? dn3 : dn2, s3_ = dn3;              \
+        const uint4* r_ = reinterpret_cast<const uint4*>(a.ring);                                            \
+        xv0 = r_[static_cast<size_t>(s0_ < 0 ? 0 : s0_) * kFrameVec16 + w0];                                  \
+        xv1 = r_[static_cast<size_t>(s1_ < 0 ? 0 : s1_) * kFrameVec16 + w1];                                  \
+        xv2 = r_[static_cast<size_t>(s2_ < 0 ? 0 : s2_) * kFrameVec16 + w2];                                  \
+        xv3 = r_[static_cast<size_t>(s3_ < 0 ? 0 : s3_) * kFrameVec16 + w3];                                  \
+        const uint32_t m0_ = s0_ < 0 ? 0u : ~0u, m1_ = s1_ < 0 ? 0u : ~0u, m2_ = s2_ < 0 ? 0u : ~0u, m3_ = s3_ < 0 ? 0u : ~0u; \
+        xv0.x &= m0_; xv0.y &= m0_; xv0.z &= m0_; xv0.w &= m0_;                                              \
+        xv1.x &= m1_; xv1.y &= m1_; xv1.z &= m1_; xv1.w &= m1_;                                              \
+        xv2.x &= m2_; xv2.y &= m2_; xv2.z &= m2_; xv2.w &= m2_;                                              \
+        xv3.x &= m3_; xv3.y &= m3_; xv3.z &= m3_; xv3.w &= m3_;                                              \
+    } else {                                                                                                 \
         const uint4* xs_ = reinterpret_cast<const uint4*>(a.x[g_] + static_cast<size_t>(b_) * kTowerXBytes);  \
         xv0 = xs_[tid]; xv1 = xs_[tid + 512]; xv2 = xs_[tid + 1024]; xv3 = xs_[last_vec];                      \
     }
 
-    V8 wf2[8], wf3[9];
-    uint4 xv0, xv1, xv2, xv3;
     int g = 0, b = first;   // item = (group, sample); no run-time division (groups <= 4)
     while (b >= a.n) { b -= a.n; ++g; }
+    if (use_desc) {
+        DQN_TOWER_FETCH_DESC(g, b)
+    }
     DQN_TOWER_FETCH_STATE(g, b)   // first thing on the way: everything below it is address arithmetic
+    if (use_desc && first + 1 < last) {
+        if (b + 1 < a.n) DQN_TOWER_FETCH_DESC(g, b + 1) else DQN_TOWER_FETCH_DESC(g + 1, 0)
+    }
 
     // conv3 k-steps of this wavefront's quarter: offsets inside a pixel's window (wavefront-uniform, plain scalar
     // arithmetic -- written as a choice between per-quarter constants it compiled to a chain of ~30 branches in
@@ -196,6 +233,10 @@ __global__ __launch_bounds__(kTowerThreads) void conv_tower_kernel(TowerArgs a)
         {
             uint4* d = reinterpret_cast<uint4*>(sX);
             d[tid] = xv0; d[tid + 512] = xv1; d[tid + 1024] = xv2; d[last_vec] = xv3;   // clamped lanes rewrite the last vector with itself
+            if (use_desc && g == 0 && a.s_out) {   // the assembled state, kept for the weight gradient of conv1
+                uint4* so = reinterpret_cast<uint4*>(a.s_out + static_cast<size_t>(b) * kTowerXBytes);
+                so[tid] = xv0; so[tid + 512] = xv1; so[tid + 1024] = xv2; so[last_vec] = xv3;
+            }
         }
         // conv2/conv3 fragments of a new group: requested a few k-steps apart inside conv1's (conv2's weights) and conv2's
         // (conv3's weights) MFMA streams (17 KB per wavefront -- requested in one go they hold every wavefront ~0.5 us in
@@ -204,6 +245,11 @@ __global__ __launch_bounds__(kTowerThreads) void conv_tower_kernel(TowerArgs a)
         const T* p3 = a.w3[g] + (static_cast<size_t>(nt * 36 + kq * 9) * 64 + lane) * 8;
         if (it + 1 < last) {   // the next item's state: in flight while this item computes
             if (b + 1 < a.n) DQN_TOWER_FETCH_STATE(g, b + 1) else DQN_TOWER_FETCH_STATE(g + 1, 0)
+            if (use_desc && it + 2 < last) {   // and the descriptor of the item after it
+                int g2 = g, b2 = b + 2;
+                while (b2 >= a.n) { b2 -= a.n; ++g2; }
+                DQN_TOWER_FETCH_DESC(g2, b2)
+            }
         }
         __syncthreads();
 
@@ -380,6 +426,7 @@ __global__ __launch_bounds__(kTowerThreads) void conv_tower_kernel(TowerArgs a)
         __syncthreads();   // the exchange block is read until here; its head is the next item's state buffer
     }
 #undef DQN_TOWER_FETCH_STATE
+#undef DQN_TOWER_FETCH_DESC
 }
 
 }  // namespace dqn

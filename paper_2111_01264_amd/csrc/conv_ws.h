@@ -370,7 +370,6 @@ inline hipError_t launch_conv_ws(hipStream_t st, const ConvWsArgs<T, Geo>& a, in
     // flight, but the grid must still cover the chip about twice.
     const int max_blocks = 512 / (groups > 0 ? groups : 1);
     hipError_t e = hipSuccess;
-    if (ev_begin) (void)hipEventRecord(ev_begin, st);
     const int tiles32 = (a.M + 31) / 32;
     auto launch_ws = [&](auto kern, int waves) {
         static bool attr_set = false;   // one flag per kernel instantiation (generic lambda)
@@ -381,15 +380,14 @@ inline hipError_t launch_conv_ws(hipStream_t st, const ConvWsArgs<T, Geo>& a, in
         }
         int tiles = (a.M + waves * 32 - 1) / (waves * 32);
         if (tiles > max_blocks) tiles = max_blocks;
-        hipLaunchKernelGGL(kern, dim3(tiles, groups), dim3(waves * 64), smem, st, a);
+        launch_timed(kern, dim3(tiles, groups), dim3(waves * 64), smem, st, ev_begin, ev_end, a);
     };
-    if (tiles32 * groups <= 1024) hipLaunchKernelGGL((conv_sk_kernel<T, Geo, EPI>), dim3(tiles32, groups), dim3(256), 0, st, a);
+    if (tiles32 * groups <= 1024) launch_timed(conv_sk_kernel<T, Geo, EPI>, dim3(tiles32, groups), dim3(256), 0, st, ev_begin, ev_end, a);
     else if (tiles32 * groups >= 16 * 512) launch_ws(conv_ws_kernel<T, Geo, EPI, 1, 16>, 16);
     else if (tiles32 * groups >= 8 * 512) launch_ws(conv_ws_kernel<T, Geo, EPI, 1, 8>, 8);
     else launch_ws(conv_ws_kernel<T, Geo, EPI, 1, 4>, 4);
     if (e != hipSuccess) return e;
     e = hipGetLastError();
-    if (ev_end) (void)hipEventRecord(ev_end, st);
     return e;
 }
 

@@ -224,7 +224,6 @@ inline hipError_t launch_fc_as(hipStream_t st, FcAsArgs<T> a, int K, int groups,
     a.slices = slices;
     const int n_blocks = (a.N + WAVES * 32 - 1) / (WAVES * 32);
     hipError_t e = hipSuccess;
-    if (ev_begin) (void)hipEventRecord(ev_begin, st);
     {
         // One 32-row tile of X per workgroup: with two, the grid of a batch-256 step was 100-224 workgroups on 256 CUs,
         // one per CU, and nothing overlapped a workgroup's staging, streaming and storing phases.
@@ -237,10 +236,9 @@ inline hipError_t launch_fc_as(hipStream_t st, FcAsArgs<T> a, int K, int groups,
             if (e != hipSuccess) return e;
             attr_smem = smem;
         }
-        hipLaunchKernelGGL(kern, dim3(n_blocks, (a.M + TB * 32 - 1) / (TB * 32), groups * slices), dim3(WAVES * 64), smem, st, a);
+        launch_timed(kern, dim3(n_blocks, (a.M + TB * 32 - 1) / (TB * 32), groups * slices), dim3(WAVES * 64), smem, st, ev_begin, ev_end, a);
     }
     e = hipGetLastError();
-    if (ev_end) (void)hipEventRecord(ev_end, st);
     return e;
 }
 

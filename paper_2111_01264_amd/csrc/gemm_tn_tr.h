@@ -37,12 +37,29 @@ __device__ inline bf16x8 tr_fragment(const bf16_t* p, int pitch4 /* elements bet
     return r;
 }
 
-// Bytes of LDS one workgroup of gemm_tn_tr_block needs.
-template <int BM, int BN> constexpr size_t gemm_tn_tr_smem() { return static_cast<size_t>(2) * 32 * ((BM + 16) + (BN + 16)) * 2; }
+// Contraction rows covered by one fill of the k-offset table, and the table's slack for the prefetch ring.
+constexpr int kTnTrKChunk = 1024, kTnTrKSlack = 6 * 32;
+
+// Bytes of LDS one workgroup of gemm_tn_tr_block needs: two buffers of each operand tile, then the k-offset table.
+template <int BM, int BN> constexpr size_t gemm_tn_tr_smem()
+{
+    return static_cast<size_t>(2) * 32 * ((BM + 16) + (BN + 16)) * 2 + static_cast<size_t>(kTnTrKChunk + kTnTrKSlack) * sizeof(int);
+}
 
 // One workgroup's share: column block bx, split-K slice `split`, row block bz.  D = k-tiles of operand
 // vectors in flight per thread (registers); LDS (smem, gemm_tn_tr_smem bytes, 16-byte aligned) is
 // double-buffered.  to_partial: write fp32 slices [split][M][N] instead of calling the epilogue.
+//
+// Global loads: vector v of a k-tile = (contraction row v / CV, eight operand rows starting at 8 * (v % CV)), CV =
+// vectors per contraction row, so the lanes of a wavefront walk ALONG a contraction row: a row of dY is 64-128
+// contiguous bytes, a row of an im2col matrix a few contiguous runs of 256-384 bytes, a row of act3 / dZ of fc1
+// 256 bytes -- a wavefront's load touches 8-16 cache lines.  (Walking down the contraction index instead, one
+// line per lane, kept the address unit busy for 64 passes per load and set the time of a k-tile.)  What an
+// operand row contributes to the address is fixed per thread; what the contraction row contributes (sample, output
+// row, output column of an implicit-GEMM operand: three divisions) is computed once per workgroup into an LDS table
+// and read one k-tile ahead.  Every thread issues every load (surplus threads repeat the last vector, rows past the
+// end are clamped and their value masked): the number of loads in flight is the same for all wavefronts and known
+// to the compiler, which can then wait for one ring slot instead of for everything outstanding.
 template <class AL, class BL, class EP, int BM, int BN, int D>
 __device__ inline void gemm_tn_tr_block(const AL& al, const BL& bl, const EP& ep, int M, int N, int K, int k_per_split,
                                         float* __restrict__ partial, bool to_partial, int bx, int split, int bz,
@@ -51,10 +68,14 @@ __device__ inline void gemm_tn_tr_block(const AL& al, const BL& bl, const EP& ep
     constexpr int KT = 32;
     constexpr int LDA = BM + 16, LDB = BN + 16;     // row pitch = 32 (mod 128) bytes: conflict-free transposing reads
     constexpr int MT = BM / 32, NT = BN / 32, NTW = (NT + 3) / 4;
-    constexpr int VA = KT * BM / 8, VB = KT * BN / 8;
+    constexpr int CVA = BM / 8, CVB = BN / 8;
+    constexpr int VA = KT * CVA, VB = KT * CVB;
     constexpr int NA = (VA + 255) / 256, NB = (VB + 255) / 256;
+    static_assert(D % 2 == 0 && D <= 4, "the LDS buffer index must be a compile-time function of the ring slot; table slack");
+    static_assert(!AL::kTableK, "only the B operand goes through the k-offset table");
     bf16_t (*sA)[KT * LDA] = reinterpret_cast<bf16_t (*)[KT * LDA]>(smem);
     bf16_t (*sB)[KT * LDB] = reinterpret_cast<bf16_t (*)[KT * LDB]>(smem + static_cast<size_t>(2) * KT * LDA * 2);
+    int* s_ktab = reinterpret_cast<int*>(smem + static_cast<size_t>(2) * KT * (LDA + LDB) * 2);
 
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int n0 = bx * BN, m0 = bz * BM;
@@ -69,67 +90,89 @@ __device__ inline void gemm_tn_tr_block(const AL& al, const BL& bl, const EP& ep
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-    static_assert(D % 2 == 0, "the LDS buffer index must be a compile-time function of the ring slot");
-    bf16x8 ra[D][NA], rb[D][NB];
-    // Vector v of a k-tile = (k row v % KT, eight columns v / KT): a thread's vectors share their k row, so the
-    // loader's decomposition of k (sample, pixel row, pixel column -- divisions) is computed once per thread and
-    // k-tile.  Every thread issues every load (surplus threads repeat the last vector; only `stash` is
-    // predicated): the number of loads in flight is then the same for all wavefronts and known to the compiler,
-    // which can wait for one ring slot instead of for everything outstanding.
-    auto fetch = [&](int slot, int k0) {
+    // per-thread constants of its vectors: contraction row inside the tile, operand-row part of the address, LDS slot
+    int ka[NA], roa[NA], sa[NA], kb[NB], rob[NB], sb[NB];
+    bool oka[NA], okb[NB];
 #pragma unroll
-        for (int i = 0; i < NA; ++i) {
-            const int v = VA % 256 == 0 ? tid + i * 256 : min(tid + i * 256, VA - 1);
-            ra[slot][i] = al.load(0, m0 + (v / KT) * 8, k0 + v % KT, M, k_end);
-        }
+    for (int i = 0; i < NA; ++i) {
+        const int v = VA % 256 == 0 ? tid + i * 256 : min(tid + i * 256, VA - 1);
+        const int row0 = m0 + (v % CVA) * 8;
+        ka[i] = v / CVA; oka[i] = row0 < M; roa[i] = al.row_offset(oka[i] ? row0 : 0); sa[i] = (v / CVA) * LDA + (v % CVA) * 8;
+    }
 #pragma unroll
-        for (int i = 0; i < NB; ++i) {
-            const int v = VB % 256 == 0 ? tid + i * 256 : min(tid + i * 256, VB - 1);
-            rb[slot][i] = bl.load(0, n0 + (v / KT) * 8, k0 + v % KT, N, k_end);
-        }
-    };
-    auto stash = [&](int slot, int buf) {
-#pragma unroll
-        for (int i = 0; i < NA; ++i) {
-            const int v = tid + i * 256;
-            if (VA % 256 == 0 || v < VA) *reinterpret_cast<bf16x8*>(&sA[buf][(v % KT) * LDA + (v / KT) * 8]) = ra[slot][i];
-        }
-#pragma unroll
-        for (int i = 0; i < NB; ++i) {
-            const int v = tid + i * 256;
-            if (VB % 256 == 0 || v < VB) *reinterpret_cast<bf16x8*>(&sB[buf][(v % KT) * LDB + (v / KT) * 8]) = rb[slot][i];
-        }
-    };
+    for (int i = 0; i < NB; ++i) {
+        const int v = VB % 256 == 0 ? tid + i * 256 : min(tid + i * 256, VB - 1);
+        const int row0 = n0 + (v % CVB) * 8;
+        kb[i] = v / CVB; okb[i] = row0 < N; rob[i] = bl.row_offset(okb[i] ? row0 : 0); sb[i] = (v / CVB) * LDB + (v % CVB) * 8;
+    }
 
     const int G = lane >> 4, s = lane & 15;
     const int frag_row = 8 * (G >> 1) + (s >> 2);      // + 16 * ks (+4 for the second read)
     const int frag_col = 16 * (G & 1) + 4 * (s & 3);   // + 32 * tile
 
-    // tiles beyond k_end load zeros (the loaders bound-check k), so the ring needs no tail logic
+    for (int kc0 = k_begin; kc0 < k_end; kc0 += kTnTrKChunk) {
+        const int kc_end = min(k_end, kc0 + kTnTrKChunk);
+        if (kc0 != k_begin) __syncthreads();   // the last tile of the previous chunk has been read; the table may change
+        if constexpr (BL::kTableK) {
+            for (int e = tid; e < kTnTrKChunk + kTnTrKSlack; e += 256) s_ktab[e] = bl.k_offset(min(kc0 + e, k_end - 1));
+            __syncthreads();
+        }
+        bf16x8 ra[D][NA], rb[D][NB];
+        int kofb[NB];   // B's contraction-row offsets of the NEXT tile to be requested
+        auto ktab_read = [&](int k0) {
 #pragma unroll
-    for (int u = 0; u < D - 1; ++u) fetch(u, k_begin + u * KT);
-    for (int kb = k_begin; kb < k_end; kb += D * KT) {
+            for (int i = 0; i < NB; ++i) {
+                if constexpr (BL::kTableK) kofb[i] = s_ktab[k0 - kc0 + kb[i]];
+                else kofb[i] = bl.k_offset(min(k0 + kb[i], k_end - 1));
+            }
+        };
+        // requests tile k0 into ring slot `slot`; calls come with k0 ascending by KT
+        auto fetch = [&](int slot, int k0) {
 #pragma unroll
-        for (int u = 0; u < D; ++u) {
-            const int k0 = kb + u * KT;
-            fetch((u + D - 1) % D, k0 + (D - 1) * KT);   // unconditional: see fetch
-            if (k0 < k_end) {                 // uniform across the workgroup
-                const int buf = u & 1;
-                stash(u, buf);
-                __syncthreads();     // also: every wavefront is done reading the other buffer
+            for (int i = 0; i < NA; ++i) {
+                const int k = k0 + ka[i];
+                ra[slot][i] = vec8_keep<bf16_t>(al.load_at(0, al.k_offset(min(k, k_end - 1)), roa[i]), oka[i] && k < k_end);
+            }
 #pragma unroll
-                for (int ks = 0; ks < KT / 16; ++ks) {
-                    bf16x8 fa[MT];
+            for (int i = 0; i < NB; ++i) rb[slot][i] = vec8_keep<bf16_t>(bl.load_at(0, kofb[i], rob[i]), okb[i] && k0 + kb[i] < k_end);
+            ktab_read(k0 + KT);
+        };
+        auto stash = [&](int slot, int buf) {
 #pragma unroll
-                    for (int i = 0; i < MT; ++i)
-                        fa[i] = tr_fragment(&sA[buf][(ks * 16 + frag_row) * LDA + i * 32 + frag_col], 4 * LDA);
+            for (int i = 0; i < NA; ++i)
+                if (VA % 256 == 0 || tid + i * 256 < VA) *reinterpret_cast<bf16x8*>(&sA[buf][sa[i]]) = ra[slot][i];
 #pragma unroll
-                    for (int j = 0; j < NTW; ++j) {
-                        const int nt = wave + 4 * j;
-                        if (NT % 4 == 0 || nt < NT) {
-                            const bf16x8 fb = tr_fragment(&sB[buf][(ks * 16 + frag_row) * LDB + nt * 32 + frag_col], 4 * LDB);
+            for (int i = 0; i < NB; ++i)
+                if (VB % 256 == 0 || tid + i * 256 < VB) *reinterpret_cast<bf16x8*>(&sB[buf][sb[i]]) = rb[slot][i];
+        };
+
+        // tiles beyond k_end load zeros, so the ring needs no tail logic
+        ktab_read(kc0);
 #pragma unroll
-                            for (int i = 0; i < MT; ++i) mma_32x32x16(acc[i][j], fa[i], fb);
+        for (int u = 0; u < D - 1; ++u) fetch(u, kc0 + u * KT);
+        for (int kb0 = kc0; kb0 < kc_end; kb0 += D * KT) {
+#pragma unroll
+            for (int u = 0; u < D; ++u) {
+                const int k0 = kb0 + u * KT;
+                fetch((u + D - 1) % D, k0 + (D - 1) * KT);   // unconditional: see above
+                if (k0 < kc_end) {                 // uniform across the workgroup
+                    const int buf = u & 1;
+                    stash(u, buf);
+                    __syncthreads();     // also: every wavefront is done reading the other buffer
+#pragma unroll
+                    for (int ks = 0; ks < KT / 16; ++ks) {
+                        bf16x8 fa[MT];
+#pragma unroll
+                        for (int i = 0; i < MT; ++i)
+                            fa[i] = tr_fragment(&sA[buf][(ks * 16 + frag_row) * LDA + i * 32 + frag_col], 4 * LDA);
+#pragma unroll
+                        for (int j = 0; j < NTW; ++j) {
+                            const int nt = wave + 4 * j;
+                            if (NT % 4 == 0 || nt < NT) {
+                                const bf16x8 fb = tr_fragment(&sB[buf][(ks * 16 + frag_row) * LDB + nt * 32 + frag_col], 4 * LDB);
+#pragma unroll
+                                for (int i = 0; i < MT; ++i) mma_32x32x16(acc[i][j], fa[i], fb);
+                            }
                         }
                     }
                 }

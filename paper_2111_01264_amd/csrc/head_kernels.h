@@ -112,7 +112,11 @@ struct HeadArgs {
     float* lossv;
     // Train step: workgroups [head_blocks, head_blocks + 5 * gather.B) gather the NEXT minibatch from the replay memory
     // (D is constant between synchronisation points, Section 3): independent byte copies that would otherwise cost a
-    // dependent launch of their own in front of every train step.  (Last in the struct: the act step never reads it.)
+    // dependent launch of their own in front of every train step.  With desc_out set, the minibatch is only DESCRIBED
+    // (sample_desc: replay slots per frame, a, r, done), by ceil(gather.B / 256) workgroups instead: the kernel that
+    // consumes the states then reads the frames from the replay memory itself.  (Last in the struct: the act step
+    // never reads it.)
+    int32_t* desc_out;           // [gather.B][kDescInts] or null
     GatherPlan gather;
 };
 
@@ -130,7 +134,10 @@ __global__ __launch_bounds__(256) void head_fwd_kernel(HeadArgs a)
     if constexpr (MODE == kHeadTrain) {
         if (static_cast<int>(blockIdx.x) >= a.head_blocks) {
             const int i = static_cast<int>(blockIdx.x) - a.head_blocks;
-            gather_block(a.gather, i % 5, i / 5);
+            if (a.desc_out) {
+                const int b = i * 256 + static_cast<int>(threadIdx.x);
+                if (b < a.gather.B) sample_desc(a.gather, b, a.desc_out + static_cast<size_t>(b) * kDescInts);
+            } else gather_block(a.gather, i % 5, i / 5);
             return;
         }
     }

@@ -71,6 +71,15 @@ template <typename T> struct DenseM {
         const typename Vec8<T>::type v = *reinterpret_cast<const typename Vec8<T>::type*>(p[g] + static_cast<size_t>(kc) * ld + rc);
         return vec8_keep<T>(v, ok);
     }
+    // The same load split into its contraction-row part (changes per k-tile) and its row part (fixed per thread):
+    // element (row0 .. row0+7, k) sits at k_offset(k) + row_offset(row0).  kTableK: k_offset is worth caching.
+    static constexpr bool kTableK = false;
+    __device__ int k_offset(int k) const { return k * ld; }
+    __device__ int row_offset(int row0) const { return row0; }
+    __device__ typename Vec8<T>::type load_at(int g, int koff, int roff) const
+    {
+        return *reinterpret_cast<const typename Vec8<T>::type*>(p[g] + koff + roff);
+    }
 };
 
 // ---- backward operands ----------------------------------------------------------------------------
@@ -124,6 +133,21 @@ template <typename T, int CIN, int HIN, int WIN, int HOUT, int WOUT, int KS, int
             x + (static_cast<size_t>(b * HIN + i * S + p) * WIN + j * S + q) * CIN + c0);
         return vec8_keep<T>(v, ok);
     }
+    static constexpr bool kTableK = true;   // k -> (sample, output row, output column): three divisions
+    __device__ int k_offset(int k) const
+    {
+        const int b = k / (HOUT * WOUT), ij = k % (HOUT * WOUT), i = ij / WOUT, j = ij % WOUT;
+        return ((b * HIN + i * S) * WIN + j * S) * CIN;
+    }
+    __device__ int row_offset(int row0) const
+    {
+        const int c0 = row0 % CIN, pq = row0 / CIN, q = pq % KS, p = pq / KS;
+        return (p * WIN + q) * CIN + c0;
+    }
+    __device__ typename Vec8<T>::type load_at(int, int koff, int roff) const
+    {
+        return *reinterpret_cast<const typename Vec8<T>::type*>(x + koff + roff);
+    }
 };
 
 // conv1 weight gradient, B-operand on the raw uint8 state: rows n = (c, p, q), k = (b, i, j).
@@ -141,6 +165,18 @@ template <typename T> struct Conv1WgradB {
         const uint32_t lo = ptr[0], hi = ptr[1];
         const uint32_t m = ok ? 0xFFFFFFFFu : 0u;   // byte 0 converts to 0.0
         return vec8_from_u8<T>(lo & m, hi & m);
+    }
+    static constexpr bool kTableK = true;
+    __device__ int k_offset(int k) const   // byte offsets
+    {
+        const int b = k / 400, ij = k % 400, i = ij / 20, j = ij % 20;
+        return (b * 4 * 84 + 4 * i) * 84 + 4 * j;
+    }
+    __device__ int row_offset(int row0) const { return ((row0 >> 6) * 84 + ((row0 >> 3) & 7)) * 84; }
+    __device__ typename Vec8<T>::type load_at(int, int koff, int roff) const
+    {
+        const uint32_t* ptr = reinterpret_cast<const uint32_t*>(x + koff + roff);
+        return vec8_from_u8<T>(ptr[0], ptr[1]);
     }
 };
 

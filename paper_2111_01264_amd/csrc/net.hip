@@ -120,6 +120,7 @@ struct dqn_ctx {
     int32_t* mb_a[2] = {nullptr, nullptr};
     float* mb_r[2] = {nullptr, nullptr};
     float* mb_d[2] = {nullptr, nullptr};
+    int32_t* mb_desc[2] = {nullptr, nullptr};   // reduced precision: the minibatch as per-sample descriptors (sample_desc)
     bool pre_valid = false;
     const replay* pre_rb = nullptr;
     int pre_B = 0, pre_buf = 0;
@@ -138,8 +139,14 @@ namespace dqn {
 
 constexpr int kMaxFc1Slices = 49;
 // deferred split-K scratch of the three conv weight gradients
-constexpr size_t kWgMaxSplits = 32, kWgMaxSplits1 = 128;   // conv1's gradient is small: more slices are cheap
+constexpr size_t kWgMaxSplits = 64, kWgMaxSplits1 = 128;   // conv1's gradient is small: more slices are cheap
 constexpr size_t kWgFp32Splits = 32;                       // fp32 mode (separate launches per layer)
+constexpr int kWgSlices1 = 128, kWgSlices23 = 64;           // reduced precision: workgroups (= slices) per conv layer at most
+// Smallest minibatch handled through descriptors.  Below it the assembled states are the faster form: the byte gather
+// rides for free in the previous step's head kernel (which leaves most of the chip idle at small batches), and the
+// fused conv kernel starts on states that are contiguous and cache-warm instead of after a descriptor round trip
+// (batch 32: 56.9 us per train step through descriptors, 55.5 us through assembled states; batch 128: 75.6 against 77.7).
+constexpr int kDescMinBatch = 96;
 constexpr size_t kWgOff1 = 0, kWgOff2 = kWgMaxSplits1 * 32 * 256, kWgOff3 = kWgOff2 + kWgMaxSplits * 64 * 512;
 constexpr size_t kWgTotal = kWgOff3 + kWgMaxSplits * 64 * 576;
 
@@ -215,12 +222,6 @@ static int wgrad_splits(int K, int n_blocks, int max_splits)
 
 // Number of fc1 k-slices for n rows per group: enough workgroups to fill the chip, few enough that
 // the consumer's slice sum stays small.
-// Largest batch whose next-minibatch gather rides in the head kernel.  Beyond it the gather outlasts the head kernel and
-// rides at the end of the weight-gradient kernel instead: there it is not hidden either (its workgroups inherit that
-// kernel's register allocation, two wavefronts per SIMD, and run as its tail), but it still saves a launch (batch 512:
-// 166 -> 159 us per step; at batch 128 and 256 the head kernel is the better host: 76.5 / 122.8 against 78.3 / 122.2 us).
-constexpr int kRideInHeadMax = 256;
-
 static int fc1_slices(int n, int groups)
 {
     const int row_tiles = (n + 31) / 32;
@@ -231,12 +232,26 @@ static int fc1_slices(int n, int groups)
     return s;
 }
 
+// A minibatch given by descriptors (sample_desc) instead of assembled states: the fused conv kernel reads the frames
+// from the replay memory's frame array itself and leaves the state of the online pass in s_out.
+struct StateSource {
+    const int32_t* desc;
+    const uint8_t* ring;
+    uint8_t* s_out;
+};
+
+__global__ __launch_bounds__(256) void sample_desc_kernel(GatherPlan plan, int32_t* desc)
+{
+    const int b = blockIdx.x * 256 + threadIdx.x;
+    if (b < plan.B) sample_desc(plan, b, desc + static_cast<size_t>(b) * kDescInts);
+}
+
 // Forward pass of `groups` independent (input, parameter set) pairs with n samples each, up to the
 // fc1 k-slices; the number of slices comes back through *slices_out.
 template <typename T>
 static int forward_to_fc1(dqn_ctx* c, hipStream_t st, Workspace& ws, int groups, const uint8_t* const* x,
                           const void* const* shadow, const float* const* master, int n, bool timed, int* slices_out,
-                          const PushStepPlan* push = nullptr)
+                          const PushStepPlan* push = nullptr, const StateSource* src = nullptr)
 {
     const Offsets& o = c->off;
     auto pp = [&](int id) { return timed ? prof_pair(c, id) : ProfPair(); };
@@ -255,6 +270,7 @@ static int forward_to_fc1(dqn_ctx* c, hipStream_t st, Workspace& ws, int groups,
             a.act3[g] = act3 + g * e_act3;
         }
         a.n = n; a.groups = groups;
+        if (src) { a.desc = src->desc; a.ring = src->ring; a.s_out = src->s_out; }
         DQN_HIP(raise_lds_limits());
         const int total = n * groups, grid = total < c->num_cus ? total : c->num_cus;
         a.per = (total + grid - 1) / grid;
@@ -262,9 +278,7 @@ static int forward_to_fc1(dqn_ctx* c, hipStream_t st, Workspace& ws, int groups,
         a.push.L = 0;
         if (push) a.push = *push;
         const ProfPair pr = pp(K_CONV1_FWD);
-        if (pr.begin) (void)hipEventRecord(pr.begin, st);
-        hipLaunchKernelGGL(conv_tower_kernel, dim3(grid + a.push.L), dim3(kTowerThreads), kTowerSmem, st, a);
-        if (pr.end) (void)hipEventRecord(pr.end, st);
+        launch_timed(conv_tower_kernel, dim3(grid + a.push.L), dim3(kTowerThreads), kTowerSmem, st, pr.begin, pr.end, a);
         DQN_LAUNCH_CHECK();
     } else {
         // fp32 mode: layer by layer; the event pair brackets all three launches
@@ -314,9 +328,7 @@ static int forward_to_fc1(dqn_ctx* c, hipStream_t st, Workspace& ws, int groups,
         a.partial = ws.partial;
         a.M = n; a.N = 512; a.ldx = 3136; a.ldw = 3136;
         const ProfPair pr = pp(K_FC1_FWD);
-        if (pr.begin) (void)hipEventRecord(pr.begin, st);
-        hipLaunchKernelGGL((fc_sk_kernel<T, kFcPartial, 7, 7>), dim3(16, groups, 7), dim3(256), 0, st, a);
-        if (pr.end) (void)hipEventRecord(pr.end, st);
+        launch_timed(fc_sk_kernel<T, kFcPartial, 7, 7>, dim3(16, groups, 7), dim3(256), 0, st, pr.begin, pr.end, a);
         DQN_LAUNCH_CHECK();
         *slices_out = 7;
     } else {
@@ -377,7 +389,8 @@ static int act_impl(dqn_ctx* c, Workspace& ws, const uint8_t* states, int W, flo
 
 template <typename T, bool SHADOW>
 static int train_impl(dqn_ctx* c, const uint8_t* s, const int32_t* a, const float* r, const uint8_t* s2,
-                      const float* done, int B, float* loss_out, const GatherPlan* ride = nullptr)
+                      const float* done, int B, float* loss_out, const GatherPlan* ride = nullptr, int32_t* ride_desc = nullptr,
+                      const StateSource* src = nullptr)
 {
     const Offsets& o = c->off;
     hipStream_t st = c->train_stream;
@@ -391,7 +404,7 @@ static int train_impl(dqn_ctx* c, const uint8_t* s, const int32_t* a, const floa
         if (pr.begin) { (void)hipEventRecord(pr.begin, st); (void)hipEventRecord(pr.end, st); }
     }
     int slices = 0;
-    int rc = forward_to_fc1<T>(c, st, ws, groups, x, shadow, master, B, true, &slices);
+    int rc = forward_to_fc1<T>(c, st, ws, groups, x, shadow, master, B, true, &slices, nullptr, src);
     if (rc != DQN_OK) return rc;
 
     const T* sh = static_cast<const T*>(c->sh);
@@ -403,11 +416,8 @@ static int train_impl(dqn_ctx* c, const uint8_t* s, const int32_t* a, const floa
     T* dz2 = static_cast<T*>(c->dz2); T* dz1 = static_cast<T*>(c->dz1);
 
     int wg_splits[3] = {1, 1, 1};
-    // where the gather of the next minibatch rides: in the head kernel, or for large batches in the weight-gradient kernel
-    const bool ride_in_wgrad = ride && std::is_same<T, bf16_t>::value && B > kRideInHeadMax;
     {
         const ProfPair pr = prof_pair(c, K_FC2_TD);
-        if (pr.begin) (void)hipEventRecord(pr.begin, st);
         HeadArgs ha{};
         ha.partial = ws.partial; ha.slices = slices; ha.rows = B; ha.A = c->A; ha.groups = groups;
         for (int g = 0; g < groups; ++g) {
@@ -417,10 +427,12 @@ static int train_impl(dqn_ctx* c, const uint8_t* s, const int32_t* a, const floa
         ha.gamma = c->cfg.gamma; ha.huber = c->cfg.huber_delta;
         ha.h_online = h; ha.dzh = dzh; ha.q_all = ws.q; ha.dqv = c->dqv; ha.lossv = c->lossv;
         ha.head_blocks = (B + kHeadRows - 1) / kHeadRows;
+        // the next minibatch rides along: as a descriptor table (ride_desc, a few workgroups) or as assembled states (5 per sample)
         ha.gather.B = 0;
-        if (ride && !ride_in_wgrad) ha.gather = *ride;
-        hipLaunchKernelGGL((head_fwd_kernel<T, kHeadTrain>), dim3(ha.head_blocks + 5 * ha.gather.B), dim3(256), 0, st, ha);
-        if (pr.end) (void)hipEventRecord(pr.end, st);
+        ha.desc_out = ride_desc;
+        if (ride) ha.gather = *ride;
+        const int riders = !ride ? 0 : (ride_desc ? (ride->B + 255) / 256 : 5 * ride->B);
+        launch_timed(head_fwd_kernel<T, kHeadTrain>, dim3(ha.head_blocks + riders), dim3(256), 0, st, pr.begin, pr.end, ha);
         DQN_LAUNCH_CHECK();
     }
     // ---- data-gradient chain: fc1 -> conv3 -> conv2 ------------------------------------------------
@@ -429,9 +441,7 @@ static int train_impl(dqn_ctx* c, const uint8_t* s, const int32_t* a, const floa
         fa.x[0] = dzh; fa.w[0] = bsh + kBshWf1; fa.dz = dz3; fa.mask = act3;
         fa.M = B; fa.N = 3136; fa.ldx = 512; fa.ldw = 512;
         const ProfPair pr = prof_pair(c, K_FC1_DGRAD);
-        if (pr.begin) (void)hipEventRecord(pr.begin, st);
-        hipLaunchKernelGGL((fc_sk_kernel<T, kFcReluMask, 8, 1>), dim3(98, 1, 1), dim3(256), 0, st, fa);
-        if (pr.end) (void)hipEventRecord(pr.end, st);
+        launch_timed(fc_sk_kernel<T, kFcReluMask, 8, 1>, dim3(98, 1, 1), dim3(256), 0, st, pr.begin, pr.end, fa);
         DQN_LAUNCH_CHECK();
     } else {
         FcAsArgs<T> fa{};
@@ -451,9 +461,7 @@ static int train_impl(dqn_ctx* c, const uint8_t* s, const int32_t* a, const floa
         const int grid = B < c->num_cus ? B : c->num_cus;
         ta.per = (B + grid - 1) / grid;
         const ProfPair pr = prof_pair(c, K_TOWER_BWD);
-        if (pr.begin) (void)hipEventRecord(pr.begin, st);
-        hipLaunchKernelGGL(conv_tower_bwd_kernel, dim3(grid), dim3(kTowerThreads), kTowerBwdSmem, st, ta);
-        if (pr.end) (void)hipEventRecord(pr.end, st);
+        launch_timed(conv_tower_bwd_kernel, dim3(grid), dim3(kTowerThreads), kTowerBwdSmem, st, pr.begin, pr.end, ta);
         DQN_LAUNCH_CHECK();
     } else {
         {   // conv3 data gradient through conv2's ReLU
@@ -501,28 +509,32 @@ static int train_impl(dqn_ctx* c, const uint8_t* s, const int32_t* a, const floa
     if constexpr (std::is_same<T, bf16_t>::value) {
         // one launch: conv1/conv2/conv3/fc1 weight gradients (transposing LDS reads) + the small reductions
         WgradAllArgs wa{};
-        wa.a1.p[0] = dz1; wa.a1.ld = 32; wa.b1.x = s; wa.K1 = B * 400; wa.p1 = c->wg_partial + kWgOff1;
-        wa.a2.p[0] = dz2; wa.a2.ld = 64; wa.b2.x = act1; wa.K2 = B * 81; wa.p2 = c->wg_partial + kWgOff2;
-        wa.a3.p[0] = dz3; wa.a3.ld = 64; wa.b3.x = act2; wa.K3 = B * 49; wa.p3 = c->wg_partial + kWgOff3;
-        tn_tr_splits(wa.K1, wgrad_splits(wa.K1, 2, wa.K1 <= 16384 ? 64 : static_cast<int>(kWgMaxSplits1))   /* small batch: the optimiser's reads of the slices weigh more than shorter workgroups here */, 32 * 256, kWgMaxSplits1 * 32 * 256, &wa.kps1, &wa.splits1);
-        tn_tr_splits(wa.K2, wgrad_splits(wa.K2, 2, static_cast<int>(kWgMaxSplits)), 64 * 512, kWgMaxSplits * 64 * 512, &wa.kps2, &wa.splits2);
-        tn_tr_splits(wa.K3, wgrad_splits(wa.K3, 3, static_cast<int>(kWgMaxSplits)), 64 * 576, kWgMaxSplits * 64 * 576, &wa.kps3, &wa.splits3);
-        wg_splits[0] = wa.splits1; wg_splits[1] = wa.splits2; wg_splits[2] = wa.splits3;
+        // conv layers: split-K over samples, workgroup j writes slice j (conv1's unit is half a sample)
+        // (items per workgroup: even, because the kernel walks them in pairs -- an odd range costs a padding item)
+        auto split = [](int items, int max_slices, int* per, int* slices) {
+            *per = ((items + max_slices - 1) / max_slices + 1) / 2 * 2;
+            *slices = (items + *per - 1) / *per;
+        };
+        int n1 = 0, n2 = 0, n3 = 0;
+        wa.c1.dz = dz1; wa.c1.in = s; wa.c1.partial = c->wg_partial + kWgOff1; wa.c1.n = B;
+        wa.c1.desc = src ? src->desc : nullptr; wa.c1.ring = src ? src->ring : nullptr;
+        split(2 * B, kWgSlices1, &wa.c1.per, &n1);
+        wa.c2.dz = dz2; wa.c2.in = act1; wa.c2.partial = c->wg_partial + kWgOff2; wa.c2.n = B;
+        split(B, kWgSlices23, &wa.c2.per, &n2);
+        wa.c3.dz = dz3; wa.c3.in = act2; wa.c3.partial = c->wg_partial + kWgOff3; wa.c3.n = B;
+        split(B, kWgSlices23, &wa.c3.per, &n3);
+        wg_splits[0] = n1; wg_splits[1] = n2; wg_splits[2] = n3;
         wa.af.p[0] = dzh; wa.af.ld = 512; wa.bf.p[0] = act3; wa.bf.ld = 3136; wa.Kf = B;
         wa.epf = EpiGrad{c->grad + o.wf1, 3136, 1.f};
         wa.small = bg;
         wa.first[0] = 0;
         wa.first[1] = wa.first[0] + small_blocks;
-        wa.first[2] = wa.first[1] + 3 * wa.splits3;
-        wa.first[3] = wa.first[2] + 2 * wa.splits2;
-        wa.first[4] = wa.first[3] + 25 * 8;
-        wa.first[5] = wa.first[4] + 2 * wa.splits1;
+        wa.first[2] = wa.first[1] + n3 * WgConv3::CS;
+        wa.first[3] = wa.first[2] + n2 * WgConv2::CS;
+        wa.first[4] = wa.first[3] + kWgfCols * 8;
+        wa.first[5] = wa.first[4] + n1;
         const ProfPair pr = prof_pair(c, K_WGRAD_ALL);
-        if (pr.begin) (void)hipEventRecord(pr.begin, st);
-        wa.gather.B = 0;
-        if (ride_in_wgrad) wa.gather = *ride;
-        hipLaunchKernelGGL(wgrad_all_kernel, dim3(wa.first[5] + 5 * wa.gather.B), dim3(256), kWgradAllSmem, st, wa);
-        if (pr.end) (void)hipEventRecord(pr.end, st);
+        launch_timed(wgrad_all_kernel, dim3(wa.first[5]), dim3(256), kWgradAllSmem, st, pr.begin, pr.end, wa);
         DQN_LAUNCH_CHECK();
     } else {
         {   // fc1 weight gradient: dW[o][f] = sum_b dZ[b][o] act3[b][f]
@@ -553,9 +565,7 @@ static int train_impl(dqn_ctx* c, const uint8_t* s, const int32_t* a, const floa
                                                      c->wg_partial + kWgOff1, kWgMaxSplits * 32 * 256, pr.begin, pr.end, &wg_splits[0])));
         }
         const ProfPair pr = prof_pair(c, K_BIAS_GRAD);
-        if (pr.begin) (void)hipEventRecord(pr.begin, st);
-        hipLaunchKernelGGL((bias_grad_kernel<T>), dim3(small_blocks), dim3(256), kSmallGradsSmem, st, bg);
-        if (pr.end) (void)hipEventRecord(pr.end, st);
+        launch_timed(bias_grad_kernel<T>, dim3(small_blocks), dim3(256), kSmallGradsSmem, st, pr.begin, pr.end, bg);
         DQN_LAUNCH_CHECK();
     }
     {
@@ -572,9 +582,7 @@ static int train_impl(dqn_ctx* c, const uint8_t* s, const int32_t* a, const floa
         ra.bias_partial = c->bias_partial;
         for (int l = 0; l < 4; ++l) { ra.bias_chunks[l] = bias_chunks[l]; ra.bias_first[l] = bias_first[l]; }
         const ProfPair pr = prof_pair(c, K_RMSPROP);
-        if (pr.begin) (void)hipEventRecord(pr.begin, st);
-        hipLaunchKernelGGL((rmsprop_kernel<T, SHADOW>), dim3(kRmsConvBlocks + ra.flat_blocks + 16 * 49 + kRmsBiasBlocks), dim3(256), 0, st, ra);
-        if (pr.end) (void)hipEventRecord(pr.end, st);
+        launch_timed(rmsprop_kernel<T, SHADOW>, dim3(kRmsConvBlocks + ra.flat_blocks + 16 * 49 + kRmsBiasBlocks), dim3(256), 0, st, pr.begin, pr.end, ra);
         DQN_LAUNCH_CHECK();
     }
     return DQN_OK;
@@ -701,6 +709,7 @@ int dqn_create(const dqn_config* cfg, void* act_stream, void* train_stream, dqn_
             DQN_HIP(hipMalloc((void**)&c->mb_a[i], B * sizeof(int32_t)));
             DQN_HIP(hipMalloc((void**)&c->mb_r[i], B * sizeof(float)));
             DQN_HIP(hipMalloc((void**)&c->mb_d[i], B * sizeof(float)));
+            DQN_HIP(hipMalloc((void**)&c->mb_desc[i], B * kDescInts * sizeof(int32_t)));
         }
         DQN_HIP(hipEventCreateWithFlags(&c->ev_train, hipEventDisableTiming));
         DQN_HIP(hipEventCreateWithFlags(&c->ev_act, hipEventDisableTiming));
@@ -734,6 +743,7 @@ int dqn_destroy(dqn_ctx* c)
     (void)hipFree(c->bsh); (void)hipFree(c->bias_partial); (void)hipFree(c->wg_partial);
     for (int i = 0; i < 2; ++i) {
         (void)hipFree(c->mb_s[i]); (void)hipFree(c->mb_s2[i]); (void)hipFree(c->mb_a[i]); (void)hipFree(c->mb_r[i]); (void)hipFree(c->mb_d[i]);
+        (void)hipFree(c->mb_desc[i]);
     }
     if (c->ev_train) (void)hipEventDestroy(c->ev_train);
     if (c->ev_act) (void)hipEventDestroy(c->ev_act);
@@ -897,9 +907,19 @@ int dqn_train_step_sampled(dqn_ctx* c, replay* rb, int32_t B, uint64_t sample_st
     if (replay_sample_stream(rb) != c->train_stream)
         return fail(DQN_EINVAL, "dqn_train_step_sampled: the replay's sample stream must be the train stream");
     std::lock_guard<std::mutex> online_lock(c->online_mu);
+    // Reduced precision, large minibatch: the minibatch is only DESCRIBED (replay slots per frame, a, r, done); the fused
+    // conv kernel and conv1's weight gradient read the frames from the replay memory themselves.  Otherwise the states are
+    // assembled (replay_sample_gather's kernel, riding in the previous step's head kernel where it can).
+    const bool by_desc = c->cfg.precision == DQN_PRECISION_BF16 && B >= kDescMinBatch;
     int buf = 0;
     if (c->pre_valid && c->pre_rb == rb && c->pre_B == B && c->pre_step == sample_step && c->pre_epoch == replay_epoch(rb)) {
-        buf = c->pre_buf;   // gathered inside the previous call's launches, and no flush since
+        buf = c->pre_buf;   // prepared inside the previous call's launches, and no flush since
+    } else if (by_desc) {
+        GatherPlan now;
+        const int rc = replay_plan_sample_gather(rb, B, sample_step, nullptr, c->mb_s[0], c->mb_s2[0], c->mb_a[0], c->mb_r[0], c->mb_d[0], nullptr, &now);
+        if (rc != DQN_OK) return rc;
+        hipLaunchKernelGGL(sample_desc_kernel, dim3((B + 255) / 256), dim3(256), 0, c->train_stream, now, c->mb_desc[0]);
+        DQN_LAUNCH_CHECK();
     } else {
         const int rc = replay_sample_gather(rb, B, sample_step, nullptr, c->mb_s[0], c->mb_s2[0], c->mb_a[0], c->mb_r[0], c->mb_d[0], nullptr);
         if (rc != DQN_OK) return rc;
@@ -907,8 +927,8 @@ int dqn_train_step_sampled(dqn_ctx* c, replay* rb, int32_t B, uint64_t sample_st
     c->pre_valid = false;
     GatherPlan plan;
     const GatherPlan* ride = nullptr;
-    // fp32 mode has only the head kernel to ride in, and beyond a few hundred samples the gather outlasts it
-    if (prefetch_next && (c->cfg.precision == DQN_PRECISION_BF16 || B <= 256)) {
+    // full precision has only the head kernel to ride in, and beyond a few hundred samples the byte gather outlasts it
+    if (prefetch_next && (by_desc || B <= 256)) {
         const int nb = buf ^ 1;
         const int rc = replay_plan_sample_gather(rb, B, sample_step + 1, nullptr, c->mb_s[nb], c->mb_s2[nb], c->mb_a[nb], c->mb_r[nb],
                                                  c->mb_d[nb], nullptr, &plan);
@@ -917,7 +937,11 @@ int dqn_train_step_sampled(dqn_ctx* c, replay* rb, int32_t B, uint64_t sample_st
     }
     DQN_HIP(wait_for_online_act(c));
     int rc;
-    if (c->cfg.precision == DQN_PRECISION_BF16)
+    if (by_desc) {
+        const StateSource src{c->mb_desc[buf], replay_ring_frames(rb), nullptr};   // nobody needs the assembled state
+        rc = train_impl<bf16_t, true>(c, c->mb_s[buf], c->mb_a[buf], c->mb_r[buf], c->mb_s2[buf], c->mb_d[buf], B, loss_out, ride,
+                                      ride ? c->mb_desc[buf ^ 1] : nullptr, &src);
+    } else if (c->cfg.precision == DQN_PRECISION_BF16)
         rc = train_impl<bf16_t, true>(c, c->mb_s[buf], c->mb_a[buf], c->mb_r[buf], c->mb_s2[buf], c->mb_d[buf], B, loss_out, ride);
     else
         rc = train_impl<float, false>(c, c->mb_s[buf], c->mb_a[buf], c->mb_r[buf], c->mb_s2[buf], c->mb_d[buf], B, loss_out, ride);

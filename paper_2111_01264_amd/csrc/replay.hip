@@ -317,6 +317,7 @@ int replay_plan_sample_gather(replay* rb, int32_t B, uint64_t sample_step, const
 }
 
 uint64_t replay_epoch(const replay* rb) { return rb->epoch; }
+const uint8_t* replay_ring_frames(const replay* rb) { return rb->frames; }
 
 hipStream_t replay_sample_stream(replay* rb) { return rb->sample_stream; }
 hipStream_t replay_push_stream(replay* rb) { return rb->push_stream; }
