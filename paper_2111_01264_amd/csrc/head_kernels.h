@@ -362,6 +362,7 @@ struct BiasGradArgs {
     int rows[4];
     int chans[4];
     int chunks[4];
+    int chunk_rows[4];      // rows per chunk (a workgroup sums one chunk of one layer)
     int first_block[5];
     int first_partial[4];   // offsets into `partial` (floats)
     float* partial;
@@ -459,12 +460,13 @@ __device__ inline void small_grads_block(const BiasGradArgs& args, int block, un
     const int C = args.chans[layer], rows = args.rows[layer], VR = C / 8, RP = 256 / VR;
     const int vec = tid % VR, rsub = tid / VR;
     const T* dz = static_cast<const T*>(args.dz[layer]) + vec * 8;
-    const int r_end = min(rows, (chunk + 1) * kBiasRows);
+    const int crows = args.chunk_rows[layer];
+    const int r_end = min(rows, (chunk + 1) * crows);
     float acc[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) acc[e] = 0.f;
     // sixteen rows in flight per thread (clamped address, masked value: no load is ever skipped)
-    for (int r = chunk * kBiasRows + rsub; r < r_end; r += 16 * RP) {
+    for (int r = chunk * crows + rsub; r < r_end; r += 16 * RP) {
         V8 v[16];
 #pragma unroll
         for (int u = 0; u < 16; ++u) {
@@ -510,7 +512,8 @@ struct RmsArgs {
     Offsets off;
     float lr, alpha, eps;
     int centered;
-    int flat_blocks; // after the kRmsConvBlocks conv-weight blocks: [0, flat_blocks) elementwise, then 16*49 fc1.w tiles, then the bias blocks
+    int flat_blocks; // after the kRmsConvBlocks conv-weight blocks: [0, flat_blocks) elementwise, then fc1_tiles fc1.w tiles, then the bias blocks
+    int fc1_tiles;   // 16 * 49 (32 x 64 tiles of fc1.w)
     // second stage of the bias gradients (conv1..3, fc1): chunk sums written by bias_grad_kernel
     const float* bias_partial;
     int bias_chunks[4];
@@ -651,11 +654,11 @@ __global__ __launch_bounds__(256) void rmsprop_kernel(RmsArgs a)
         }
         return;
     }
-    if (block >= a.flat_blocks + 16 * 49) {
+    if (block >= a.flat_blocks + a.fc1_tiles) {
         // hidden-layer biases: finish the gradient, then update.  Eight adjacent lanes share a channel: lane j
         // adds chunks j, j + 8, ... in order, then the eight sums meet in a fixed tree -- a large batch has
         // hundreds of chunks and one lane walking them alone was the tail of this kernel.
-        const int idx = (block - a.flat_blocks - 16 * 49) * 256 + tid;
+        const int idx = (block - a.flat_blocks - a.fc1_tiles) * 256 + tid;
         const int ch = idx / kRmsBiasLanes, j = idx % kRmsBiasLanes;
         const bool live = ch < 32 + 64 + 64 + 512;
         int layer = 3, c = 0;

@@ -489,11 +489,15 @@ static int train_impl(dqn_ctx* c, const uint8_t* s, const int32_t* a, const floa
     bg.dz[1] = dz2; bg.rows[1] = B * 81;  bg.chans[1] = 64;
     bg.dz[2] = dz3; bg.rows[2] = B * 49;  bg.chans[2] = 64;
     bg.dz[3] = dzh; bg.rows[3] = B;       bg.chans[3] = 512;
+    // reduced precision: the conv layers' bias gradients come out of their weight-gradient workgroups (dZ is in LDS there)
+    if (std::is_same<T, bf16_t>::value) bg.rows[0] = bg.rows[1] = bg.rows[2] = 0;
     bg.first_block[0] = 0;
     {
         int pofs = 0;
         for (int l = 0; l < 4; ++l) {
-            bg.chunks[l] = (bg.rows[l] + kBiasRows - 1) / kBiasRows;
+            // fc1's dZ is [B][512]: a workgroup covers four rows per pass, so 64 rows per chunk are one round trip of 16 loads in flight
+            bg.chunk_rows[l] = l == 3 ? 64 : kBiasRows;
+            bg.chunks[l] = (bg.rows[l] + bg.chunk_rows[l] - 1) / bg.chunk_rows[l];
             bg.first_block[l + 1] = bg.first_block[l] + bg.chunks[l];
             bg.first_partial[l] = pofs;
             pofs += bg.chunks[l] * bg.chans[l];
@@ -506,8 +510,24 @@ static int train_impl(dqn_ctx* c, const uint8_t* s, const int32_t* a, const floa
     bg.g_w2 = c->grad + o.wf2; bg.g_b2 = c->grad + o.bf2; bg.loss_out = loss_out; bg.loss_keep = c->loss_keep;
     const int small_blocks = bg.first_block[4] + kSmallGradsExtraBlocks;
 
+    RmsArgs ra;
+    ra.theta = c->theta; ra.grad = c->grad; ra.v = c->v; ra.m = c->m;
+    ra.sh = SHADOW ? c->sh : nullptr; ra.bsh = c->bsh; ra.off = o;
+    ra.lr = c->cfg.lr; ra.alpha = c->cfg.rms_alpha; ra.eps = c->cfg.rms_eps; ra.centered = c->cfg.centered;
+    {
+        const size_t n_flat = o.total - static_cast<size_t>(512) * 3136;
+        ra.flat_blocks = static_cast<int>((n_flat / 4 + 4 + 255) / 256);
+    }
+    ra.fc1_tiles = 16 * 49;
+    ra.bias_partial = c->bias_partial;
+    ra.wg_partial[0] = c->wg_partial + kWgOff1; ra.wg_partial[1] = c->wg_partial + kWgOff2;
+    ra.wg_partial[2] = c->wg_partial + kWgOff3;
+    for (int l = 0; l < 3; ++l) { ra.wg_splits[l] = 1; ra.wg_scale[l] = 1.f; }
+    ra.wg_scale[0] = 1.f / 255.f;   // conv1 reads raw bytes: the input scale is applied to its gradient by the optimiser
+    for (int l = 0; l < 4; ++l) { ra.bias_chunks[l] = 0; ra.bias_first[l] = 0; }
+
     if constexpr (std::is_same<T, bf16_t>::value) {
-        // one launch: conv1/conv2/conv3/fc1 weight gradients (transposing LDS reads) + the small reductions
+        // one launch: conv1/conv2/conv3/fc1 weight gradients and the small reductions
         WgradAllArgs wa{};
         // conv layers: split-K over samples, workgroup j writes slice j (conv1's unit is half a sample)
         // (items per workgroup: even, because the kernel walks them in pairs -- an odd range costs a padding item)
@@ -524,15 +544,23 @@ static int train_impl(dqn_ctx* c, const uint8_t* s, const int32_t* a, const floa
         wa.c3.dz = dz3; wa.c3.in = act2; wa.c3.partial = c->wg_partial + kWgOff3; wa.c3.n = B;
         split(B, kWgSlices23, &wa.c3.per, &n3);
         wg_splits[0] = n1; wg_splits[1] = n2; wg_splits[2] = n3;
-        wa.af.p[0] = dzh; wa.af.ld = 512; wa.bf.p[0] = act3; wa.bf.ld = 3136; wa.Kf = B;
-        wa.epf = EpiGrad{c->grad + o.wf1, 3136, 1.f};
+        // their bias gradients: one partial row [C_out] per slice, added in slice order by the optimiser kernel
+        constexpr int kConvBiasOff = 16384;
+        bias_chunks[0] = n1; bias_first[0] = kConvBiasOff;
+        bias_chunks[1] = n2; bias_first[1] = bias_first[0] + kWgSlices1 * 32;
+        bias_chunks[2] = n3; bias_first[2] = bias_first[1] + kWgSlices23 * 64;
+        static_assert(kConvBiasOff + kWgSlices1 * 32 + 2 * kWgSlices23 * 64 <= 65536, "bias partials fit their buffer");
+        wa.c1.bias_partial = c->bias_partial + bias_first[0];
+        wa.c2.bias_partial = c->bias_partial + bias_first[1];
+        wa.c3.bias_partial = c->bias_partial + bias_first[2];
+        wa.f1.dz = dzh; wa.f1.x = act3; wa.f1.B = B; wa.f1.grad = c->grad + o.wf1;
         wa.small = bg;
         wa.first[0] = 0;
-        wa.first[1] = wa.first[0] + small_blocks;
-        wa.first[2] = wa.first[1] + n3 * WgConv3::CS;
-        wa.first[3] = wa.first[2] + n2 * WgConv2::CS;
-        wa.first[4] = wa.first[3] + kWgfCols * 8;
-        wa.first[5] = wa.first[4] + n1;
+        wa.first[1] = wa.first[0] + n1;
+        wa.first[2] = wa.first[1] + n2 * WgConv2::CS;
+        wa.first[3] = wa.first[2] + n3 * WgConv3::CS;
+        wa.first[4] = wa.first[3] + kWgF1Cols * kWgF1Rows;
+        wa.first[5] = wa.first[4] + small_blocks;
         const ProfPair pr = prof_pair(c, K_WGRAD_ALL);
         launch_timed(wgrad_all_kernel, dim3(wa.first[5]), dim3(256), kWgradAllSmem, st, pr.begin, pr.end, wa);
         DQN_LAUNCH_CHECK();
@@ -569,20 +597,10 @@ static int train_impl(dqn_ctx* c, const uint8_t* s, const int32_t* a, const floa
         DQN_LAUNCH_CHECK();
     }
     {
-        RmsArgs ra;
-        ra.theta = c->theta; ra.grad = c->grad; ra.v = c->v; ra.m = c->m;
-        ra.sh = SHADOW ? c->sh : nullptr; ra.bsh = c->bsh; ra.off = o;
-        ra.lr = c->cfg.lr; ra.alpha = c->cfg.rms_alpha; ra.eps = c->cfg.rms_eps; ra.centered = c->cfg.centered;
-        const size_t n_flat = o.total - static_cast<size_t>(512) * 3136;
-        ra.flat_blocks = static_cast<int>((n_flat / 4 + 4 + 255) / 256);
-        ra.wg_partial[0] = c->wg_partial + kWgOff1; ra.wg_partial[1] = c->wg_partial + kWgOff2;
-        ra.wg_partial[2] = c->wg_partial + kWgOff3;
-        for (int l = 0; l < 3; ++l) { ra.wg_splits[l] = wg_splits[l]; ra.wg_scale[l] = 1.f; }
-        ra.wg_scale[0] = 1.f / 255.f;   // conv1 reads raw bytes: the input scale is applied to its gradient here
-        ra.bias_partial = c->bias_partial;
-        for (int l = 0; l < 4; ++l) { ra.bias_chunks[l] = bias_chunks[l]; ra.bias_first[l] = bias_first[l]; }
         const ProfPair pr = prof_pair(c, K_RMSPROP);
-        launch_timed(rmsprop_kernel<T, SHADOW>, dim3(kRmsConvBlocks + ra.flat_blocks + 16 * 49 + kRmsBiasBlocks), dim3(256), 0, st, pr.begin, pr.end, ra);
+        for (int l = 0; l < 3; ++l) ra.wg_splits[l] = wg_splits[l];
+        for (int l = 0; l < 4; ++l) { ra.bias_chunks[l] = bias_chunks[l]; ra.bias_first[l] = bias_first[l]; }
+        launch_timed(rmsprop_kernel<T, SHADOW>, dim3(kRmsConvBlocks + ra.flat_blocks + ra.fc1_tiles + kRmsBiasBlocks), dim3(256), 0, st, pr.begin, pr.end, ra);
         DQN_LAUNCH_CHECK();
     }
     return DQN_OK;

@@ -63,6 +63,7 @@ struct WgConvArgs {
     const bf16_t* dz;        // [n][HOUT][WOUT][COUT]
     const void* in;          // conv2 / conv3: bf16 [n][HIN][WIN][CIN];  conv1: uint8 [n][4][84][84], unused with desc
     float* partial;          // [slices][COUT][N] fp32
+    float* bias_partial;     // [slices][COUT] fp32: column sums of dZ over the slice's items (the bias gradient)
     int n;                   // samples
     int per;                 // items per workgroup (the host sizes the grid so that every workgroup has at least one)
     const int32_t* desc;     // conv1: [n][kDescInts] (entries 0..3: replay slots of the frames of s, -1 = zero frame) or null
@@ -155,6 +156,12 @@ __device__ inline void wgrad_conv_block(const WgConvArgs& a, int wg, int cb, uns
         for (int j = 0; j < NTW; ++j)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+    // The bias gradient (column sums of dZ) is taken on the way: a thread's dZ vectors all belong to the same eight
+    // channels (256 is a multiple of the vectors per row), so it adds them up in eight registers while it stores them to
+    // LDS; the threads' sums meet in LDS once, at the end, in thread order.  (A reduction kernel of its own read every
+    // dZ tensor from memory a second time.)
+    float bsum[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    static_assert(256 % (G::COUT / 8) == 0, "a thread's dZ vectors share their channel chunk");
 
     // Operands are requested TWO items ahead into registers (one dependent round trip to memory takes about as long as
     // two items' matrix work; with one item ahead every item waited for its loads).
@@ -215,7 +222,14 @@ __device__ inline void wgrad_conv_block(const WgConvArgs& a, int wg, int cb, uns
 #pragma unroll
         for (int u = 0; u < NVD; ++u) {
             const int v = min(tid + u * 256, G::DZ_VECS - 1);
-            *reinterpret_cast<wg_u32x4*>(sDz + (v / (G::COUT / 8)) * LDA + (v % (G::COUT / 8)) * 8) = pdz[ps][u] & live[ps];
+            const wg_u32x4 d = pdz[ps][u] & live[ps];
+            *reinterpret_cast<wg_u32x4*>(sDz + (v / (G::COUT / 8)) * LDA + (v % (G::COUT / 8)) * 8) = d;
+            if (cb == 0) {
+                const bf16x8 dv = __builtin_bit_cast(bf16x8, d);
+                const float w = (G::DZ_VECS % 256 == 0 || tid + u * 256 < G::DZ_VECS) ? 1.f : 0.f;   // surplus threads hold a copy
+#pragma unroll
+                for (int e = 0; e < 8; ++e) bsum[e] += w * static_cast<float>(dv[e]);
+            }
         }
 #pragma unroll
         for (int u = 0; u < NVI; ++u) {
@@ -276,6 +290,19 @@ __device__ inline void wgrad_conv_block(const WgConvArgs& a, int wg, int cb, uns
         contract();
     }
 
+    if (cb == 0) {   // workgroup-uniform
+        __syncthreads();   // the last item has been read; sIn is free
+        float* sSum = reinterpret_cast<float*>(smem);   // [256 threads][8]
+#pragma unroll
+        for (int e = 0; e < 8; ++e) sSum[tid * 8 + e] = bsum[e];
+        __syncthreads();
+        if (tid < G::COUT) {
+            constexpr int CH = G::COUT / 8;   // threads t with t % CH == channel / 8 hold that channel's partial sums
+            float sum = 0.f;
+            for (int t = tid / 8; t < 256; t += CH) sum += sSum[t * 8 + (tid & 7)];
+            a.bias_partial[static_cast<size_t>(wg) * G::COUT + tid] = sum;
+        }
+    }
     float* out = a.partial + static_cast<size_t>(wg) * G::COUT * G::N;
 #pragma unroll
     for (int i = 0; i < MT; ++i)
