@@ -125,6 +125,9 @@ constexpr int kTowerXchgBytes = 2 * 3 * 4 * 3 * 64 * 16;   // row exchange, [nt]
 constexpr size_t kTowerSmem = kTowerXchgBytes + 32 * 256 * 2 + 400 * kTowerP1 * 2 + 81 * kTowerP2 * 2 + kTowerThreads * 4;   // biases: 160 floats used, one slot per thread
 static_assert(kTowerXBytes <= kTowerXchgBytes, "the state buffer overlays the exchange block");
 
+// DESC: the minibatch comes as a descriptor table (a.desc, a.ring) instead of assembled states (a.x); a separate
+// instantiation, so that the act step and small minibatches run the kernel without any of the descriptor logic.
+template <bool DESC>
 __global__ __launch_bounds__(kTowerThreads) void conv_tower_kernel(TowerArgs a)
 {
     typedef bf16_t T;
@@ -160,7 +163,7 @@ __global__ __launch_bounds__(kTowerThreads) void conv_tower_kernel(TowerArgs a)
     // frames are (dn*: the item after next), so that the frames never wait for it.
     constexpr int kXVecs = kTowerXBytes / 16;   // 1764
     const int last_vec = tid + 1536 < kXVecs ? tid + 1536 : kXVecs - 1;
-    const bool use_desc = a.desc != nullptr;
+    constexpr bool use_desc = DESC;
     const bool hi0 = tid >= 441, hi1 = tid + 512 >= 882, hi2 = tid + 1024 >= 1323;         // second of the two candidate frames
     const int w0 = tid - (hi0 ? 441 : 0), w1 = tid + 512 - (hi1 ? 882 : 441), w2 = tid + 1024 - (hi2 ? 1323 : 882), w3 = last_vec - 1323;
     V8 wf2[8], wf3[9];
@@ -172,7 +175,7 @@ __global__ __launch_bounds__(kTowerThreads) void conv_tower_kernel(TowerArgs a)
         dn0 = dp_[0]; dn1 = dp_[1]; dn2 = dp_[2]; dn3 = dp_[3];                                                \
     }
 #define DQN_TOWER_FETCH_STATE(g_, b_)                                                                        \
-    if (use_desc) {                                                                                          \
+    if constexpr (use_desc) {                                                                                \
         const int s0_ = hi0 ? dn1 : dn0, s1_ = hi1 ? dn2 : dn1, s2_ = hi2 ? dn3 : dn2, s3_ = dn3;              \
         const uint4* r_ = reinterpret_cast<const uint4*>(a.ring);                                            \
         xv0 = r_[static_cast<size_t>(s0_ < 0 ? 0 : s0_) * kFrameVec16 + w0];                                  \
@@ -191,7 +194,7 @@ __global__ __launch_bounds__(kTowerThreads) void conv_tower_kernel(TowerArgs a)
 
     int g = 0, b = first;   // item = (group, sample); no run-time division (groups <= 4)
     while (b >= a.n) { b -= a.n; ++g; }
-    if (use_desc) {
+    if constexpr (use_desc) {
         DQN_TOWER_FETCH_DESC(g, b)
     }
     DQN_TOWER_FETCH_STATE(g, b)   // first thing on the way: everything below it is address arithmetic

@@ -59,7 +59,7 @@ __global__ __launch_bounds__(WAVES * 64) void fc_as_kernel(FcAsArgs<T> a)
     // The weight stream: a ring of D k-steps of fragments in flight per wavefront, requested before the slab of X
     // is staged so that both latencies overlap.  Loads are never skipped (the k-step is clamped): the count of
     // loads in flight stays known to the compiler, which then waits for one slot only.
-    constexpr int D = 8;
+    constexpr int D = sizeof(T) == 2 ? 16 : 8;   // 16 KB per wavefront in flight: a step waits for the fragment requested D steps earlier, so the stream runs at D fragments per memory round trip
     const int steps = klen >> 4;
     auto wload = [&](int st) {
         return *reinterpret_cast<const V8*>(fc_weight_fragment<T>(a.w[g], ntile, ks0 + (st < steps ? st : steps - 1), a.ldw, lane));
@@ -97,7 +97,7 @@ __global__ __launch_bounds__(WAVES * 64) void fc_as_kernel(FcAsArgs<T> a)
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[t][v] = 0.f;
 
-    // steps is a multiple of 4 (k per slice is a multiple of 64): whole chunks of D = 8 steps, then possibly four more
+    // steps is a multiple of 4 (k per slice is a multiple of 64): whole chunks of D steps, then the rest
     const T* xrow[TB];
 #pragma unroll
     for (int t = 0; t < TB; ++t) xrow[t] = &sX[(t * 32 + lane_r) * ldk + kg * 8];
@@ -112,12 +112,15 @@ __global__ __launch_bounds__(WAVES * 64) void fc_as_kernel(FcAsArgs<T> a)
             __builtin_amdgcn_sched_barrier(0);
         }
     }
-    if (base < steps) {
+    // what is left (fewer than D steps, a multiple of four) sits in the ring already
 #pragma unroll
-        for (int u = 0; u < 4; ++u)
+    for (int u = 0; u < D; u += 4)
+        if (base + u < steps) {
 #pragma unroll
-            for (int t = 0; t < TB; ++t) mma_32x32x16(acc[t], ring[u], *reinterpret_cast<const V8*>(xrow[t] + (base + u) * 16));
-    }
+            for (int w = 0; w < 4; ++w)
+#pragma unroll
+                for (int t = 0; t < TB; ++t) mma_32x32x16(acc[t], ring[u + w], *reinterpret_cast<const V8*>(xrow[t] + (base + u + w) * 16));
+        }
 
     // lane: sample b = m0 + t*32 + lane_r; values: features 8*q + 4*kg + e of this wavefront's 32
     const int n_base = (blockIdx.x * WAVES + wave) * 32;

@@ -178,7 +178,9 @@ static hipError_t raise_lds_limits()
     static std::once_flag once;
     static hipError_t result = hipSuccess;
     std::call_once(once, [] {
-        result = hipFuncSetAttribute(reinterpret_cast<const void*>(conv_tower_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, kTowerSmem);
+        result = hipFuncSetAttribute(reinterpret_cast<const void*>(conv_tower_kernel<false>), hipFuncAttributeMaxDynamicSharedMemorySize, kTowerSmem);
+        if (result == hipSuccess)
+            result = hipFuncSetAttribute(reinterpret_cast<const void*>(conv_tower_kernel<true>), hipFuncAttributeMaxDynamicSharedMemorySize, kTowerSmem);
         if (result == hipSuccess)
             result = hipFuncSetAttribute(reinterpret_cast<const void*>(conv_tower_bwd_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, kTowerBwdSmem);
     });
@@ -278,7 +280,8 @@ static int forward_to_fc1(dqn_ctx* c, hipStream_t st, Workspace& ws, int groups,
         a.push.L = 0;
         if (push) a.push = *push;
         const ProfPair pr = pp(K_CONV1_FWD);
-        launch_timed(conv_tower_kernel, dim3(grid + a.push.L), dim3(kTowerThreads), kTowerSmem, st, pr.begin, pr.end, a);
+        if (a.desc) launch_timed(conv_tower_kernel<true>, dim3(grid + a.push.L), dim3(kTowerThreads), kTowerSmem, st, pr.begin, pr.end, a);
+        else launch_timed(conv_tower_kernel<false>, dim3(grid + a.push.L), dim3(kTowerThreads), kTowerSmem, st, pr.begin, pr.end, a);
         DQN_LAUNCH_CHECK();
     } else {
         // fp32 mode: layer by layer; the event pair brackets all three launches
@@ -530,9 +533,10 @@ static int train_impl(dqn_ctx* c, const uint8_t* s, const int32_t* a, const floa
         // one launch: conv1/conv2/conv3/fc1 weight gradients and the small reductions
         WgradAllArgs wa{};
         // conv layers: split-K over samples, workgroup j writes slice j (conv1's unit is half a sample)
-        // (items per workgroup: even, because the kernel walks them in pairs -- an odd range costs a padding item)
+        // (items per workgroup: one, or an even number, because the kernel walks several in pairs -- an odd range costs a padding item)
         auto split = [](int items, int max_slices, int* per, int* slices) {
-            *per = ((items + max_slices - 1) / max_slices + 1) / 2 * 2;
+            *per = (items + max_slices - 1) / max_slices;
+            if (*per > 1) *per = (*per + 1) / 2 * 2;
             *slices = (items + *per - 1) / *per;
         };
         int n1 = 0, n2 = 0, n3 = 0;

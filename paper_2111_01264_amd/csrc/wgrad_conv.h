@@ -273,21 +273,30 @@ __device__ inline void wgrad_conv_block(const WgConvArgs& a, int wg, int cb, uns
 
     typedef std::integral_constant<int, 0> P0;
     typedef std::integral_constant<int, 1> P1;
-    // items in pairs, one per register set; an odd range ends with a padding item whose dZ is zero
-    fetch_slots(P0{}, first);
-    fetch(P0{}, first);
-    fetch(P1{}, first + 1);
-    for (int it = first; it < last; it += 2) {
-        if (it != first) __syncthreads();   // every wavefront has finished reading the previous item
+    if (last - first == 1) {
+        // a single item (small minibatches: one workgroup per item keeps the chain of dependent steps shortest)
+        fetch_slots(P0{}, first);
+        fetch(P0{}, first);
         stash(P0{});
-        fetch(P0{}, it + 2);
         __syncthreads();
         contract();
-        __syncthreads();
-        stash(P1{});
-        fetch(P1{}, it + 3);
-        __syncthreads();
-        contract();
+    } else {
+        // items in pairs, one per register set; an odd range ends with a padding item whose dZ is zero
+        fetch_slots(P0{}, first);
+        fetch(P0{}, first);
+        fetch(P1{}, first + 1);
+        for (int it = first; it < last; it += 2) {
+            if (it != first) __syncthreads();   // every wavefront has finished reading the previous item
+            stash(P0{});
+            fetch(P0{}, it + 2);
+            __syncthreads();
+            contract();
+            __syncthreads();
+            stash(P1{});
+            fetch(P1{}, it + 3);
+            __syncthreads();
+            contract();
+        }
     }
 
     if (cb == 0) {   // workgroup-uniform
