@@ -65,12 +65,19 @@ def kernel_work(name, B, A, groups, precision):
 # {(kernel, batch, precision): (bytes, source files of the kernel, sha1 over their concatenation when the counters
 # were taken)}.  Reported only while the kernel's sources still hash to that value.
 _C = "paper_2111_01264_amd/csrc/"
-_RMS_SRC = (_C + "head_kernels.h", _C + "net.hip")   # net.hip fixes the number of split-K slices the optimiser reads
-_WG_SRC = (_C + "wgrad_all.h", _C + "gemm_tn_tr.h", _C + "layers.h", _C + "head_kernels.h", _C + "gemm_mfma.h", _C + "net.hip")
+_RMS_SRC = (_C + "head_kernels.h", _C + "net.hip")
+_WG_SRC = (_C + "wgrad_all.h", _C + "wgrad_conv.h", _C + "wgrad_fc1.h", _C + "gemm_tn_tr.h", _C + "gemm_mfma.h", _C + "head_kernels.h", _C + "common.h", _C + "net.hip")
+_TOWER_SRC = (_C + "conv_tower.h", _C + "conv_ws.h", _C + "gemm_mfma.h", _C + "common.h", _C + "net.hip")
+_TOWER_BWD_SRC = (_C + "conv_tower_bwd.h", _C + "conv_tower.h", _C + "conv_ws.h", _C + "gemm_mfma.h", _C + "net.hip")
 TRAFFIC = {
-    ("rmsprop", 32, "bf16"): (63.13e6, _RMS_SRC, "35f437d786b773e56b045051089c5feeb26a9a4a", "profiles/hbm_traffic_b32.txt"),
-    ("rmsprop", 256, "bf16"): (68.03e6, _RMS_SRC, "35f437d786b773e56b045051089c5feeb26a9a4a", "profiles/hbm_traffic_b256.txt"),
-    ("wgrad_all", 256, "bf16"): (94.22e6, _WG_SRC, "8b76f8619971fd80526af12eda5aecb5c2f095ee", "profiles/hbm_traffic_b256.txt"),
+    ("rmsprop", 32, "bf16"): (66.19e6, _RMS_SRC, "12b5ec73c928cd04c04ce0e273e6352d01765cf5", "profiles/hbm_traffic_b32.txt"),
+    ("wgrad_all", 32, "bf16"): (25.63e6, _WG_SRC, "f1c74116b33dae499575b6002689f88e4e66c5d3", "profiles/hbm_traffic_b32.txt"),
+    ("conv_tower", 32, "bf16"): (6.09e6, _TOWER_SRC, "40e4189d5706aa3e778eb7d2e7bff2e9d25d6fa0", "profiles/hbm_traffic_b32.txt"),
+    ("conv_tower_bwd", 32, "bf16"): (3.75e6, _TOWER_BWD_SRC, "b033647d1f68e4ec20a83b39633d4c9bce30e31c", "profiles/hbm_traffic_b32.txt"),
+    ("rmsprop", 256, "bf16"): (77.22e6, _RMS_SRC, "12b5ec73c928cd04c04ce0e273e6352d01765cf5", "profiles/hbm_traffic_b256.txt"),
+    ("wgrad_all", 256, "bf16"): (92.22e6, _WG_SRC, "f1c74116b33dae499575b6002689f88e4e66c5d3", "profiles/hbm_traffic_b256.txt"),
+    ("conv_tower", 256, "bf16"): (24.21e6, _TOWER_SRC, "40e4189d5706aa3e778eb7d2e7bff2e9d25d6fa0", "profiles/hbm_traffic_b256.txt"),
+    ("conv_tower_bwd", 256, "bf16"): (21.25e6, _TOWER_BWD_SRC, "b033647d1f68e4ec20a83b39633d4c9bce30e31c", "profiles/hbm_traffic_b256.txt"),
 }
 
 

@@ -210,15 +210,18 @@ int replay_sample_gather(replay* rb, int32_t B, uint64_t sample_step, const int6
                          uint8_t* s, uint8_t* s2, int32_t* a, float* r, float* done,
                          int64_t* idx_out);
 
-/* replay_sample_gather(rb, B, sample_step, NULL, ...) into buffers owned by ctx, followed by dqn_train_step on
- * them -- with the gather taken out of the chain of dependent launches: if prefetch_next != 0, workgroups
- * riding in one of this step's kernels already gather the minibatch of sample_step + 1 into the other of two
- * buffer sets (the replay memory is constant between synchronisation points, Section 3 / Algorithm 1), and
- * the next call, if it asks for exactly that minibatch (same rb, B, sample_step + 1, and no replay_flush /
- * dqn_sync_target in between), finds it there.  Any other call gathers first, as the two separate calls
- * would (so does every call with B > 256 in the fp32 mode, which has no kernel long enough to ride in):
- * results are identical to theirs in every case.  The replay's sample_stream must be ctx's
- * train_stream.  Errors: those of the two calls. */
+/* replay_sample_gather(rb, B, sample_step, NULL, ...) followed by dqn_train_step on that minibatch -- with the
+ * assembly of the minibatch taken out of the chain of dependent launches: if prefetch_next != 0, workgroups
+ * riding in one of this step's kernels already prepare the minibatch of sample_step + 1 (the replay memory is
+ * constant between synchronisation points, Section 3 / Algorithm 1), and the next call, if it asks for exactly
+ * that minibatch (same rb, B, sample_step + 1, and no replay_flush / dqn_sync_target in between), finds it
+ * prepared.  Any other call prepares it first, as the two separate calls would: results are identical to
+ * theirs in every case.  "Prepared" means, in the reduced-precision mode at B >= 96: DESCRIBED -- the replay
+ * slots of the eight frames of (s, s') per sample, with a, r, done -- and the kernels that consume states read
+ * the frames straight from D, so the 56 KB per sample of an assembled (s, s') pair are never written; otherwise:
+ * assembled into one of two buffer sets owned by ctx (in the full-precision mode only up to B = 256: beyond it
+ * no kernel of the step is long enough to ride in, and every call assembles first).  The replay's
+ * sample_stream must be ctx's train_stream.  Errors: those of the two calls. */
 int dqn_train_step_sampled(dqn_ctx* ctx, replay* rb, int32_t B, uint64_t sample_step,
                            int32_t prefetch_next, float* loss_out);
 
