@@ -310,7 +310,9 @@ def test_act_push_step_equals_the_two_calls(precision):
 def test_train_step_sampled_equals_the_two_calls(precision, B):
     """dqn_train_step_sampled == replay_sample_gather + dqn_train_step, bit for bit (parameters and loss after every
     step), also when the minibatch gathered ahead goes stale (a flush in between) or is not the one asked for next.
-    The two batch sizes take the two kernels the gather can ride in (small: head kernel, large: weight-gradient kernel)."""
+    Batch 24 assembles the next minibatch with extra workgroups of the head kernel; batch 300 does the same in full
+    precision and, in reduced precision, takes the descriptor path (no assembled states: the conv kernels read the replay
+    memory's frames themselves)."""
     seed, A, lanes, per_lane = 2111012662, 6, 4, 300
     N = lanes * 1024
     cfg = make_cfg(A, max_batch=max(B, 32), max_envs=8, precision=precision, seed=seed)
