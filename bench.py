@@ -591,8 +591,8 @@ def sweep(args):
         a.frames = min(args.frames, 200000)
         wl = Workload(a)
         groups = 3 if a.double_dqn else 2
-        time_steps(wl, 30)
-        br = kernel_breakdown(wl, 30)
+        time_steps(wl, 60)
+        br = kernel_breakdown(wl, 100)
         br.pop("event_pair", None)
         steps = 300
         el = time_steps(wl, steps)
@@ -617,7 +617,7 @@ def sweep(args):
                                                                      r["unit"], 100 * r["frac"]), file=sys.stderr)
         print(json.dumps({
             "metric": "train steps/sec (batch %d) + act states/sec" % B, "value": steps / el, "unit": "train steps/s",
-            "act_states_per_sec": steps * W / el, "n_gpus": 1, "steps": steps, "warmup": 30, "ms_per_step": 1e3 * el / steps,
+            "act_states_per_sec": steps * W / el, "n_gpus": 1, "steps": steps, "warmup": 60, "ms_per_step": 1e3 * el / steps,
             "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if a.precision == "bf16" else "f32",
             "data": "synthetic",
             "config": {"workload": "roofline scaling point: A=%d, batch %d, W=%d, 1 act step per train step on a concurrent "

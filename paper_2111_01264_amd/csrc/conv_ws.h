@@ -18,6 +18,8 @@
 // predicated to zero, the LDS-resident matrix is the transposed filter of that class, and the
 // epilogue applies the ReLU mask of the layer below.
 #pragma once
+#include <atomic>
+
 #include "gemm_mfma.h"
 
 namespace dqn {
@@ -372,11 +374,13 @@ inline hipError_t launch_conv_ws(hipStream_t st, const ConvWsArgs<T, Geo>& a, in
     hipError_t e = hipSuccess;
     const int tiles32 = (a.M + 31) / 32;
     auto launch_ws = [&](auto kern, int waves) {
-        static bool attr_set = false;   // one flag per kernel instantiation (generic lambda)
-        if (!attr_set) {
+        // one flag per kernel instantiation (generic lambda); the act thread and the train thread both come here, and
+        // setting the attribute twice is harmless
+        static std::atomic<bool> attr_set{false};
+        if (!attr_set.load(std::memory_order_acquire)) {
             e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, smem);
             if (e != hipSuccess) return;
-            attr_set = true;
+            attr_set.store(true, std::memory_order_release);
         }
         int tiles = (a.M + waves * 32 - 1) / (waves * 32);
         if (tiles > max_blocks) tiles = max_blocks;

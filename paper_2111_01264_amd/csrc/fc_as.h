@@ -15,6 +15,8 @@
 // K may be split over blockIdx.z: each slice then writes fp32 partial sums [slice][b][n], which the
 // consumer kernel adds in slice order while it loads them (no separate reduction pass).
 #pragma once
+#include <atomic>
+
 #include "conv_ws.h"
 
 namespace dqn {
@@ -67,6 +69,18 @@ __global__ __launch_bounds__(WAVES * 64) void fc_as_kernel(FcAsArgs<T> a)
     V8 ring[D];
 #pragma unroll
     for (int u = 0; u < D; ++u) ring[u] = wload(u);
+    // kFcReluMask: the activations that mask this lane's outputs are requested now, not in the epilogue (there they were one
+    // more dependent round trip to memory at the end of every workgroup); clamped addresses, no load is skipped
+    [[maybe_unused]] float mask[TB][4][4];
+    if constexpr (EPI == kFcReluMask) {
+#pragma unroll
+        for (int t = 0; t < TB; ++t) {
+            const int b = min(m0 + t * 32 + lane_r, a.M - 1);
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                load4<T>(a.mask + static_cast<size_t>(b) * a.N + min(static_cast<int>(blockIdx.x * WAVES + wave) * 32 + 8 * q + 4 * kg, a.N - 4), mask[t][q]);
+        }
+    }
     __builtin_amdgcn_sched_barrier(0);
     {
         // the slab of X: eight 16-byte vectors in flight per thread (clamped address, masked value), then their LDS stores --
@@ -137,8 +151,7 @@ __global__ __launch_bounds__(WAVES * 64) void fc_as_kernel(FcAsArgs<T> a)
                 *reinterpret_cast<float4*>(dst) = make_float4(acc[t][4 * q], acc[t][4 * q + 1], acc[t][4 * q + 2], acc[t][4 * q + 3]);
             } else {
                 const size_t idx = static_cast<size_t>(b) * a.N + nn;
-                float m[4];
-                load4<T>(a.mask + idx, m);
+                const float* m = mask[t][q];
                 store4<T>(a.dz + idx, m[0] > 0.f ? acc[t][4 * q] : 0.f, m[1] > 0.f ? acc[t][4 * q + 1] : 0.f,
                           m[2] > 0.f ? acc[t][4 * q + 2] : 0.f, m[3] > 0.f ? acc[t][4 * q + 3] : 0.f);
             }
@@ -233,11 +246,11 @@ inline hipError_t launch_fc_as(hipStream_t st, FcAsArgs<T> a, int K, int groups,
         constexpr int TB = 1;
         const size_t smem = static_cast<size_t>(TB) * 32 * (kc + 8) * sizeof(T);
         auto kern = fc_as_kernel<T, EPI, TB, WAVES>;
-        static size_t attr_smem = 0;
-        if (smem > attr_smem) {
+        static std::atomic<size_t> attr_smem{0};   // launches come from the act thread and the train thread; setting the attribute twice is harmless
+        if (smem > attr_smem.load(std::memory_order_relaxed)) {
             e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, smem);
             if (e != hipSuccess) return e;
-            attr_smem = smem;
+            attr_smem.store(smem, std::memory_order_relaxed);
         }
         launch_timed(kern, dim3(n_blocks, (a.M + TB * 32 - 1) / (TB * 32), groups * slices), dim3(WAVES * 64), smem, st, ev_begin, ev_end, a);
     }

@@ -301,15 +301,28 @@ __device__ inline void wgrad_conv_block(const WgConvArgs& a, int wg, int cb, uns
 
     if (cb == 0) {   // workgroup-uniform
         __syncthreads();   // the last item has been read; sIn is free
-        float* sSum = reinterpret_cast<float*>(smem);   // [256 threads][8]
+        constexpr int LDS_E = 256 + 8;                  // padded: the reads below stride through the threads in steps of CH
+        float* sSum = reinterpret_cast<float*>(smem);   // [8][256 threads]
+        static_assert(8 * LDS_E * 4 <= G::SMEM, "the partial sums fit the operand buffers");
 #pragma unroll
-        for (int e = 0; e < 8; ++e) sSum[tid * 8 + e] = bsum[e];
+        for (int e = 0; e < 8; ++e) sSum[e * LDS_E + tid] = bsum[e];
         __syncthreads();
-        if (tid < G::COUT) {
-            constexpr int CH = G::COUT / 8;   // threads t with t % CH == channel / 8 hold that channel's partial sums
+        // channel ch is held by the threads t = ch / 8 + CH * k (k = 0 .. 256 / CH - 1).  P adjacent lanes share a channel:
+        // lane p adds eight consecutive k (eight independent LDS reads), the P sums meet in a fixed shuffle tree.  (One lane
+        // per channel walking all 256 / CH values was a chain of dependent LDS reads: 1.5 - 2.4 us at the end of every block.)
+        {
+            constexpr int CH = G::COUT / 8, P = 256 / G::COUT, PER = 256 / CH / P;
+            static_assert(PER == 8 && (P == 4 || P == 8), "eight values per lane, a power-of-two group of lanes per channel");
+            const int ch = tid / P, p = tid % P;
+            float v[PER];
+#pragma unroll
+            for (int k = 0; k < PER; ++k) v[k] = sSum[(ch & 7) * LDS_E + (ch >> 3) + CH * (p * PER + k)];
             float sum = 0.f;
-            for (int t = tid / 8; t < 256; t += CH) sum += sSum[t * 8 + (tid & 7)];
-            a.bias_partial[static_cast<size_t>(wg) * G::COUT + tid] = sum;
+#pragma unroll
+            for (int k = 0; k < PER; ++k) sum += v[k];
+#pragma unroll
+            for (int d = P / 2; d >= 1; d >>= 1) sum += __shfl_down(sum, d, P);
+            if (p == 0) a.bias_partial[static_cast<size_t>(wg) * G::COUT + ch] = sum;
         }
     }
     float* out = a.partial + static_cast<size_t>(wg) * G::COUT * G::N;
