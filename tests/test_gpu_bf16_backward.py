@@ -86,7 +86,10 @@ def compare_step(ctx, orc, A, B, double_dqn, loss_dev, wloss, q_sa, first_step, 
         assert np.abs(d_gpu - d_ref).max() <= bound, ("update", name, np.abs(d_gpu - d_ref).max(), bound)
 
 
-@pytest.mark.parametrize("B,split,double_dqn", [(32, False, 0), (32, True, 1), (300, True, 0), (256, False, 1)])
+# 45 and 97: the conv weight-gradient workgroups walk two / four samples each and the last one gets a single sample (the
+# padding item of an odd range); 32: one sample per workgroup; 300, 256: many per workgroup, ragged and even
+@pytest.mark.parametrize("B,split,double_dqn", [(32, False, 0), (32, True, 1), (45, False, 0), (97, True, 1), (300, True, 0),
+                                                (256, False, 1)])
 def test_bf16_train_step_max_norm_no_relu_flips(B, split, double_dqn):
     A, seed = 18, 4100 + B
     cfg = make_cfg(A, max_batch=B, max_envs=8, precision=P.DQN_PRECISION_BF16, double_dqn=double_dqn, seed=seed)
@@ -119,10 +122,12 @@ def test_bf16_train_step_max_norm_no_relu_flips(B, split, double_dqn):
         P.dqn_destroy(ctx)
 
 
-def test_bf16_sampled_train_step_max_norm_no_relu_flips_batch_512():
-    # through the replay memory and dqn_train_step_sampled at batch 512 (the minibatch is assembled inside the
-    # step's own launches), two steps in a row so that the second one uses what the first one prepared
-    A, B, lanes, per_lane, seed = 18, 512, 8, 160, 777
+@pytest.mark.parametrize("B", [512, 101])
+def test_bf16_sampled_train_step_max_norm_no_relu_flips(B):
+    # through the replay memory and dqn_train_step_sampled (at these sizes the minibatch exists only as replay slots: the
+    # conv kernels read the frames from the replay memory), two steps in a row so that the second one uses what the
+    # first one prepared; 101 leaves the last conv workgroups a single sample
+    A, lanes, per_lane, seed = 18, 8, 160, 777 + B
     N = lanes * per_lane
     cfg = make_cfg(A, max_batch=B, max_envs=8, precision=P.DQN_PRECISION_BF16, double_dqn=0, seed=seed)
     cfg.lr, cfg.huber_delta = LR, HUBER
