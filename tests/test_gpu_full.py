@@ -305,13 +305,13 @@ def test_act_push_step_equals_the_two_calls(precision):
     assert rep_a[2].min() >= 0            # real transitions, not the invalid-index marker
 
 
-@pytest.mark.parametrize("B", [24, 300], ids=["b24", "b300"])
+@pytest.mark.parametrize("B", [24, 96, 300], ids=["b24", "b96", "b300"])
 @pytest.mark.parametrize("precision", [P.DQN_PRECISION_BF16, P.DQN_PRECISION_FP32], ids=["bf16", "fp32"])
 def test_train_step_sampled_equals_the_two_calls(precision, B):
     """dqn_train_step_sampled == replay_sample_gather + dqn_train_step, bit for bit (parameters and loss after every
     step), also when the minibatch gathered ahead goes stale (a flush in between) or is not the one asked for next.
-    Batch 24 assembles the next minibatch with extra workgroups of the head kernel; batch 300 does the same in full
-    precision and, in reduced precision, takes the descriptor path (no assembled states: the conv kernels read the replay
+    Batch 24 assembles the next minibatch with extra workgroups of the head kernel; batches 96 (the smallest such size)
+    and 300 do the same in full precision and, in reduced precision, take the descriptor path (no assembled states: the conv kernels read the replay
     memory's frames themselves)."""
     seed, A, lanes, per_lane = 2111012662, 6, 4, 300
     N = lanes * 1024
