@@ -196,6 +196,14 @@ __global__ __launch_bounds__(256) void fc_sk_kernel(FcSkArgs<T> a)
         wf[s] = *reinterpret_cast<const V8*>(fc_weight_fragment<T>(a.w[g], ntile, ks0 + s, a.ldw, lane));
         xf[s] = *reinterpret_cast<const V8*>(xp + s * 16);
     }
+    // thread t finishes accumulator slots (v, l) = (4*(t/64) + e, t%64), e = 0..3: one quad of features of one sample.
+    // kFcReluMask: the activations that mask them are requested now (clamped address), behind the operands -- in the
+    // epilogue they were one more dependent round trip to memory at the end of a two-microsecond kernel
+    const int q = tid >> 6, l = tid & 63;
+    const int sample = l & 31;
+    const int nn = n0 + 8 * q + 4 * (l >> 5);
+    [[maybe_unused]] float m[4];
+    if constexpr (EPI == kFcReluMask) load4<T>(a.mask + static_cast<size_t>(min(sample, a.M - 1)) * a.N + min(nn, a.N - 4), m);
     __builtin_amdgcn_sched_barrier(0);
     f32x16 acc;
 #pragma unroll
@@ -205,22 +213,16 @@ __global__ __launch_bounds__(256) void fc_sk_kernel(FcSkArgs<T> a)
 #pragma unroll
     for (int v = 0; v < 16; ++v) red[wave][v][lane] = acc[v];
     __syncthreads();
-    // thread t owns accumulator slots (v, l) = (4*(t/64) + e, t%64), e = 0..3: one quad of features
-    const int q = tid >> 6, l = tid & 63;
     float v4[4];
 #pragma unroll
     for (int e = 0; e < 4; ++e)
         v4[e] = ((red[0][4 * q + e][l] + red[1][4 * q + e][l]) + red[2][4 * q + e][l]) + red[3][4 * q + e][l];
-    const int sample = l & 31;
-    const int nn = n0 + 8 * q + 4 * (l >> 5);
     if (sample >= a.M || nn >= a.N) return;
     if constexpr (EPI == kFcPartial) {
         float* dst = a.partial + ((static_cast<size_t>(g) * KSLICES + slice) * a.M + sample) * a.N + nn;
         *reinterpret_cast<float4*>(dst) = make_float4(v4[0], v4[1], v4[2], v4[3]);
     } else {
         const size_t idx = static_cast<size_t>(sample) * a.N + nn;
-        float m[4];
-        load4<T>(a.mask + idx, m);
         store4<T>(a.dz + idx, m[0] > 0.f ? v4[0] : 0.f, m[1] > 0.f ? v4[1] : 0.f, m[2] > 0.f ? v4[2] : 0.f,
                   m[3] > 0.f ? v4[3] : 0.f);
     }
