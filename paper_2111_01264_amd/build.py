@@ -11,7 +11,10 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdqn_mi355.so")
 SOURCES = ["error.hip", "replay.hip", "net.hip", "envs.hip", "alg1.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",
-         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument"]
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument",
+         # the first kernel arguments arrive in scalar registers with the wavefront instead of through a load from cold
+         # memory (14 dwords on gfx950; the hot kernels' signatures lead with what they need first)
+         "-mllvm", "-amdgpu-kernarg-preload-count=16"]
 
 
 def _compile(src: str) -> str:

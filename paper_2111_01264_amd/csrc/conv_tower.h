@@ -127,8 +127,15 @@ static_assert(kTowerXBytes <= kTowerXchgBytes, "the state buffer overlays the ex
 
 // DESC: the minibatch comes as a descriptor table (a.desc, a.ring) instead of assembled states (a.x); a separate
 // instantiation, so that the act step and small minibatches run the kernel without any of the descriptor logic.
+//
+// The leading scalar parameters repeat what a workgroup needs before its first load (TowerArgs::n, groups, per,
+// tower_blocks, x[0], x[1], desc, ring, w1[0]): the first 14 dwords of the kernel arguments are preloaded into scalar
+// registers when a wavefront starts (build option amdgpu-kernarg-preload-count), while a field of the struct is a load
+// from cold memory in front of everything that depends on it.
 template <bool DESC>
-__global__ __launch_bounds__(kTowerThreads) void conv_tower_kernel(TowerArgs a)
+__global__ __launch_bounds__(kTowerThreads) void conv_tower_kernel(int n_, int groups_, int per_, int tower_blocks_, const uint8_t* x0_,
+                                                                   const uint8_t* x1_, const int32_t* desc_, const uint8_t* ring_,
+                                                                   const _Float16* w1_0_, TowerArgs a)
 {
     typedef bf16_t T;
     typedef bf16x8 V8;
@@ -142,17 +149,17 @@ __global__ __launch_bounds__(kTowerThreads) void conv_tower_kernel(TowerArgs a)
     float* sB2 = sB1 + 32;
     float* sB3 = sB2 + 64;
 
-    if (static_cast<int>(blockIdx.x) >= a.tower_blocks) {
+    if (static_cast<int>(blockIdx.x) >= tower_blocks_) {
         // An act step's launch sequence also carries the append of the previous step's experiences (Section 3:
         // temporary buffers): independent byte copies that would otherwise cost a dependent launch of their own.
-        push_step_block(a.push, static_cast<int>(blockIdx.x) - a.tower_blocks);
+        push_step_block(a.push, static_cast<int>(blockIdx.x) - tower_blocks_);
         return;
     }
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lp = lane & 31, kg = lane >> 5;
     const int nt = wave >> 2, kq = wave & 3;
-    const int total = a.n * a.groups;
-    const int first = blockIdx.x * a.per, last = min(total, first + a.per);
+    const int total = n_ * groups_;
+    const int first = blockIdx.x * per_, last = min(total, first + per_);
     if (first >= last) return;
 
     // The state of item (g_, b_), 16 bytes per lane and load (the last load is clamped, not predicated);
@@ -171,13 +178,13 @@ __global__ __launch_bounds__(kTowerThreads) void conv_tower_kernel(TowerArgs a)
     int dn0 = 0, dn1 = 0, dn2 = 0, dn3 = 0;   // descriptor (four slots) of the item whose frames are requested next
 #define DQN_TOWER_FETCH_DESC(g_, b_)                                                                          \
     {                                                                                                        \
-        const int32_t* dp_ = a.desc + static_cast<size_t>(b_) * kDescInts + ((g_) > 0 ? 4 : 0);                \
+        const int32_t* dp_ = desc_ + static_cast<size_t>(b_) * kDescInts + ((g_) > 0 ? 4 : 0);                \
         dn0 = dp_[0]; dn1 = dp_[1]; dn2 = dp_[2]; dn3 = dp_[3];                                                \
     }
 #define DQN_TOWER_FETCH_STATE(g_, b_)                                                                        \
     if constexpr (use_desc) {                                                                                \
         const int s0_ = hi0 ? dn1 : dn0, s1_ = hi1 ? dn2 : dn1, s2_ = hi2 ? dn3 : dn2, s3_ = dn3;              \
-        const uint4* r_ = reinterpret_cast<const uint4*>(a.ring);                                            \
+        const uint4* r_ = reinterpret_cast<const uint4*>(ring_);                                             \
         xv0 = r_[static_cast<size_t>(s0_ < 0 ? 0 : s0_) * kFrameVec16 + w0];                                  \
         xv1 = r_[static_cast<size_t>(s1_ < 0 ? 0 : s1_) * kFrameVec16 + w1];                                  \
         xv2 = r_[static_cast<size_t>(s2_ < 0 ? 0 : s2_) * kFrameVec16 + w2];                                  \
@@ -188,18 +195,19 @@ __global__ __launch_bounds__(kTowerThreads) void conv_tower_kernel(TowerArgs a)
         xv2.x &= m2_; xv2.y &= m2_; xv2.z &= m2_; xv2.w &= m2_;                                              \
         xv3.x &= m3_; xv3.y &= m3_; xv3.z &= m3_; xv3.w &= m3_;                                              \
     } else {                                                                                                 \
-        const uint4* xs_ = reinterpret_cast<const uint4*>(a.x[g_] + static_cast<size_t>(b_) * kTowerXBytes);  \
+        const uint8_t* xg_ = (g_) == 0 ? x0_ : (g_) == 1 ? x1_ : a.x[g_];                                     \
+        const uint4* xs_ = reinterpret_cast<const uint4*>(xg_ + static_cast<size_t>(b_) * kTowerXBytes);      \
         xv0 = xs_[tid]; xv1 = xs_[tid + 512]; xv2 = xs_[tid + 1024]; xv3 = xs_[last_vec];                      \
     }
 
     int g = 0, b = first;   // item = (group, sample); no run-time division (groups <= 4)
-    while (b >= a.n) { b -= a.n; ++g; }
+    while (b >= n_) { b -= n_; ++g; }
     if constexpr (use_desc) {
         DQN_TOWER_FETCH_DESC(g, b)
     }
     DQN_TOWER_FETCH_STATE(g, b)   // first thing on the way: everything below it is address arithmetic
     if (use_desc && first + 1 < last) {
-        if (b + 1 < a.n) DQN_TOWER_FETCH_DESC(g, b + 1) else DQN_TOWER_FETCH_DESC(g + 1, 0)
+        if (b + 1 < n_) DQN_TOWER_FETCH_DESC(g, b + 1) else DQN_TOWER_FETCH_DESC(g + 1, 0)
     }
 
     // conv3 k-steps of this wavefront's quarter: offsets inside a pixel's window (wavefront-uniform, plain scalar
@@ -214,7 +222,7 @@ __global__ __launch_bounds__(kTowerThreads) void conv_tower_kernel(TowerArgs a)
 
     int cur_g = -1;
     for (int it = first; it < last; ++it, ++b) {
-        if (b == a.n) { b = 0; ++g; }
+        if (b == n_) { b = 0; ++g; }
         // First item, or the range crosses into the next group: (re)load the weights (every wavefront has passed the
         // barrier that ends the previous item).  What conv1 needs -- its own 16 KB of weights and the state -- is requested
         // and parked in LDS first; the 139 KB of conv2/conv3 fragments are requested after that and arrive while conv1 runs
@@ -222,8 +230,9 @@ __global__ __launch_bounds__(kTowerThreads) void conv_tower_kernel(TowerArgs a)
         const bool new_group = g != cur_g;
         if (new_group) {
             cur_g = g;
-            const f16x8 w1a = *reinterpret_cast<const f16x8*>(a.w1[g] + tid * 8);
-            const f16x8 w1b = *reinterpret_cast<const f16x8*>(a.w1[g] + (tid + 512) * 8);
+            const _Float16* w1g = g == 0 ? w1_0_ : a.w1[g];
+            const f16x8 w1a = *reinterpret_cast<const f16x8*>(w1g + tid * 8);
+            const f16x8 w1b = *reinterpret_cast<const f16x8*>(w1g + (tid + 512) * 8);
             // biases: every thread loads one (address chosen without a branch, clamped) and stores it to a slot of its own --
             // behind a condition the compiler sinks the load to the store, a dependent round trip of its own
             const int bt = tid < 160 ? tid : 159;
@@ -247,10 +256,10 @@ __global__ __launch_bounds__(kTowerThreads) void conv_tower_kernel(TowerArgs a)
         const T* p2 = a.w2[g] + (static_cast<size_t>(nt * 32 + kq * 8) * 64 + lane) * 8;
         const T* p3 = a.w3[g] + (static_cast<size_t>(nt * 36 + kq * 9) * 64 + lane) * 8;
         if (it + 1 < last) {   // the next item's state: in flight while this item computes
-            if (b + 1 < a.n) DQN_TOWER_FETCH_STATE(g, b + 1) else DQN_TOWER_FETCH_STATE(g + 1, 0)
+            if (b + 1 < n_) DQN_TOWER_FETCH_STATE(g, b + 1) else DQN_TOWER_FETCH_STATE(g + 1, 0)
             if (use_desc && it + 2 < last) {   // and the descriptor of the item after it
                 int g2 = g, b2 = b + 2;
-                while (b2 >= a.n) { b2 -= a.n; ++g2; }
+                while (b2 >= n_) { b2 -= n_; ++g2; }
                 DQN_TOWER_FETCH_DESC(g2, b2)
             }
         }

@@ -71,7 +71,10 @@ template <int KH> __device__ inline float4 tower_sum_half(const float4* theirs, 
     return v;
 }
 
-__global__ __launch_bounds__(kTowerThreads) void conv_tower_bwd_kernel(TowerBwdArgs a)
+// The arguments are TowerBwdArgs' fields one by one, in the order a workgroup needs them: the first 14 dwords of the
+// kernel arguments are preloaded into scalar registers when a wavefront starts (see conv_tower_kernel).
+__global__ __launch_bounds__(kTowerThreads) void conv_tower_bwd_kernel(int n_, int per_, const bf16_t* dz3_, const bf16_t* w3d_, const bf16_t* w2d_,
+                                                                       const bf16_t* act2_, const bf16_t* act1_, bf16_t* dz2_, bf16_t* dz1_)
 {
     typedef bf16_t T;
     typedef bf16x8 V8;
@@ -84,13 +87,13 @@ __global__ __launch_bounds__(kTowerThreads) void conv_tower_bwd_kernel(TowerBwdA
     const int lp = lane & 31, kg = lane >> 5;
     const int nt = wave >> 2, kq = wave & 3;     // conv3 stage
     const int cls = wave >> 1, kh = wave & 1;    // conv2 stage: class (py, px) = (cls >> 1, cls & 1)
-    const int first = blockIdx.x * a.per, last = min(a.n, first + a.per);
+    const int first = blockIdx.x * per_, last = min(n_, first + per_);
     if (first >= last) return;
 
     // a sample's dz3: 49 pixels x 128 bytes = 392 vectors, one per thread, fetched one sample ahead.  The first sample's is
     // requested before the weights: loads return in order, and behind 139 KB of fragments the staging below waited ~1 us
     uint4 xv = make_uint4(0, 0, 0, 0);
-    if (tid < 392) xv = reinterpret_cast<const uint4*>(a.dz3 + static_cast<size_t>(first) * 3136)[tid];
+    if (tid < 392) xv = reinterpret_cast<const uint4*>(dz3_ + static_cast<size_t>(first) * 3136)[tid];
     __builtin_amdgcn_sched_barrier(0);
 
     // zero both images once: the borders are never written again
@@ -98,10 +101,10 @@ __global__ __launch_bounds__(kTowerThreads) void conv_tower_bwd_kernel(TowerBwdA
 
     V8 wf3[9], wf2[8];
     {
-        const T* p3 = a.w3d + (static_cast<size_t>(nt * 36 + kq * 9) * 64 + lane) * 8;
+        const T* p3 = w3d_ + (static_cast<size_t>(nt * 36 + kq * 9) * 64 + lane) * 8;
 #pragma unroll
         for (int k = 0; k < 9; ++k) wf3[k] = *reinterpret_cast<const V8*>(p3 + k * 512);
-        const T* p2 = a.w2d + static_cast<size_t>(cls) * 32 * 256 + (static_cast<size_t>(kh * 8) * 64 + lane) * 8;
+        const T* p2 = w2d_ + static_cast<size_t>(cls) * 32 * 256 + (static_cast<size_t>(kh * 8) * 64 + lane) * 8;
 #pragma unroll
         for (int k = 0; k < 8; ++k) wf2[k] = *reinterpret_cast<const V8*>(p2 + k * 512);
     }
@@ -120,7 +123,7 @@ __global__ __launch_bounds__(kTowerThreads) void conv_tower_bwd_kernel(TowerBwdA
 
     for (int b = first; b < last; ++b) {
         if (tid < 392) *reinterpret_cast<uint4*>(sP3 + my_dst) = xv;
-        if (b + 1 < last && tid < 392) xv = reinterpret_cast<const uint4*>(a.dz3 + static_cast<size_t>(b + 1) * 3136)[tid];
+        if (b + 1 < last && tid < 392) xv = reinterpret_cast<const uint4*>(dz3_ + static_cast<size_t>(b + 1) * 3136)[tid];
         // ReLU masks of both stages: requested now, used after the exchanges
         uint2 m2[3], m1[4][2];
         {
@@ -128,7 +131,7 @@ __global__ __launch_bounds__(kTowerThreads) void conv_tower_bwd_kernel(TowerBwdA
 #pragma unroll
             for (int t = 0; t < 3; ++t) {
                 const int px = t * 32 + lp;
-                m2[t] = *reinterpret_cast<const uint2*>(a.act2 + (static_cast<size_t>(b) * 81 + (px < 81 ? px : 80)) * 64 + ch);
+                m2[t] = *reinterpret_cast<const uint2*>(act2_ + (static_cast<size_t>(b) * 81 + (px < 81 ? px : 80)) * 64 + ch);
             }
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
@@ -136,7 +139,7 @@ __global__ __launch_bounds__(kTowerThreads) void conv_tower_bwd_kernel(TowerBwdA
                 const int pix = (2 * (pc / 10) + (cls >> 1)) * 20 + 2 * (pc % 10) + (cls & 1);
 #pragma unroll
                 for (int h = 0; h < 2; ++h)
-                    m1[t][h] = *reinterpret_cast<const uint2*>(a.act1 + (static_cast<size_t>(b) * 400 + pix) * 32 + 8 * (2 * kh + h) + 4 * kg);
+                    m1[t][h] = *reinterpret_cast<const uint2*>(act1_ + (static_cast<size_t>(b) * 400 + pix) * 32 + 8 * (2 * kh + h) + 4 * kg);
             }
         }
         __syncthreads();
@@ -188,7 +191,7 @@ __global__ __launch_bounds__(kTowerThreads) void conv_tower_bwd_kernel(TowerBwdA
                     const float v0 = static_cast<int16_t>(lo & 0xFFFF) > 0 ? v.x : 0.f, v1 = static_cast<int16_t>(lo >> 16) > 0 ? v.y : 0.f;
                     const float v2 = static_cast<int16_t>(hi & 0xFFFF) > 0 ? v.z : 0.f, v3 = static_cast<int16_t>(hi >> 16) > 0 ? v.w : 0.f;
                     store4<T>(sP2 + ((px / 9 + 1) * 11 + px % 9 + 1) * kTbPitch + ch, v0, v1, v2, v3);
-                    store4<T>(a.dz2 + (static_cast<size_t>(b) * 81 + px) * 64 + ch, v0, v1, v2, v3);
+                    store4<T>(dz2_ + (static_cast<size_t>(b) * 81 + px) * 64 + ch, v0, v1, v2, v3);
                 }
             }
         }
@@ -241,7 +244,7 @@ __global__ __launch_bounds__(kTowerThreads) void conv_tower_bwd_kernel(TowerBwdA
                     if (px < 100) {
                         const int pix = (2 * (px / 10) + (cls >> 1)) * 20 + 2 * (px % 10) + (cls & 1);
                         const uint32_t lo = m1[t][h].x, hi = m1[t][h].y;
-                        store4<T>(a.dz1 + (static_cast<size_t>(b) * 400 + pix) * 32 + 8 * (2 * kh + h) + 4 * kg,
+                        store4<T>(dz1_ + (static_cast<size_t>(b) * 400 + pix) * 32 + 8 * (2 * kh + h) + 4 * kg,
                                   static_cast<int16_t>(lo & 0xFFFF) > 0 ? v.x : 0.f, static_cast<int16_t>(lo >> 16) > 0 ? v.y : 0.f,
                                   static_cast<int16_t>(hi & 0xFFFF) > 0 ? v.z : 0.f, static_cast<int16_t>(hi >> 16) > 0 ? v.w : 0.f);
                     }

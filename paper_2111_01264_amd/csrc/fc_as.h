@@ -176,8 +176,11 @@ template <typename T> struct FcSkArgs {
     int M, N, ldx, ldw;
 };
 
+// The leading scalar parameters repeat FcSkArgs::x[0], x[1], w[0], w[1], M, N, ldx, ldw, partial: the kernel arguments'
+// first 14 dwords are preloaded into scalar registers when a wavefront starts (see conv_tower_kernel).
 template <typename T, int EPI, int KPW, int KSLICES>
-__global__ __launch_bounds__(256) void fc_sk_kernel(FcSkArgs<T> a)
+__global__ __launch_bounds__(256) void fc_sk_kernel(const T* x0_, const T* x1_, const T* w0_, const T* w1_, int M_, int N_, int ldx_, int ldw_,
+                                                    float* partial_, FcSkArgs<T> a)
 {
     typedef typename Vec8<T>::type V8;
     static_assert(EPI == kFcPartial || KSLICES == 1, "only partial sums can be split over workgroups");
@@ -187,13 +190,15 @@ __global__ __launch_bounds__(256) void fc_sk_kernel(FcSkArgs<T> a)
     const int lr = lane & 31, kg = lane >> 5;
     const int n = n0 + lr;
     const int k0 = (slice * 4 + wave) * (KPW * 16) + kg * 8;
-    const int ntile = n < a.N ? blockIdx.x : 0, ks0 = (slice * 4 + wave) * KPW;   // N is a multiple of 32
-    const bool x_ok = lr < a.M;
-    const T* xp = a.x[g] + static_cast<size_t>(x_ok ? lr : 0) * a.ldx + k0;
+    const int ntile = n < N_ ? blockIdx.x : 0, ks0 = (slice * 4 + wave) * KPW;   // N is a multiple of 32
+    const bool x_ok = lr < M_;
+    const T* xg = g == 0 ? x0_ : g == 1 ? x1_ : a.x[g];
+    const T* wg = g == 0 ? w0_ : g == 1 ? w1_ : a.w[g];
+    const T* xp = xg + static_cast<size_t>(x_ok ? lr : 0) * ldx_ + k0;
     V8 wf[KPW], xf[KPW];
 #pragma unroll
     for (int s = 0; s < KPW; ++s) {
-        wf[s] = *reinterpret_cast<const V8*>(fc_weight_fragment<T>(a.w[g], ntile, ks0 + s, a.ldw, lane));
+        wf[s] = *reinterpret_cast<const V8*>(fc_weight_fragment<T>(wg, ntile, ks0 + s, ldw_, lane));
         xf[s] = *reinterpret_cast<const V8*>(xp + s * 16);
     }
     // thread t finishes accumulator slots (v, l) = (4*(t/64) + e, t%64), e = 0..3: one quad of features of one sample.
@@ -203,7 +208,7 @@ __global__ __launch_bounds__(256) void fc_sk_kernel(FcSkArgs<T> a)
     const int sample = l & 31;
     const int nn = n0 + 8 * q + 4 * (l >> 5);
     [[maybe_unused]] float m[4];
-    if constexpr (EPI == kFcReluMask) load4<T>(a.mask + static_cast<size_t>(min(sample, a.M - 1)) * a.N + min(nn, a.N - 4), m);
+    if constexpr (EPI == kFcReluMask) load4<T>(a.mask + static_cast<size_t>(min(sample, M_ - 1)) * N_ + min(nn, N_ - 4), m);
     __builtin_amdgcn_sched_barrier(0);
     f32x16 acc;
 #pragma unroll
@@ -217,12 +222,12 @@ __global__ __launch_bounds__(256) void fc_sk_kernel(FcSkArgs<T> a)
 #pragma unroll
     for (int e = 0; e < 4; ++e)
         v4[e] = ((red[0][4 * q + e][l] + red[1][4 * q + e][l]) + red[2][4 * q + e][l]) + red[3][4 * q + e][l];
-    if (sample >= a.M || nn >= a.N) return;
+    if (sample >= M_ || nn >= N_) return;
     if constexpr (EPI == kFcPartial) {
-        float* dst = a.partial + ((static_cast<size_t>(g) * KSLICES + slice) * a.M + sample) * a.N + nn;
+        float* dst = partial_ + ((static_cast<size_t>(g) * KSLICES + slice) * M_ + sample) * N_ + nn;
         *reinterpret_cast<float4*>(dst) = make_float4(v4[0], v4[1], v4[2], v4[3]);
     } else {
-        const size_t idx = static_cast<size_t>(sample) * a.N + nn;
+        const size_t idx = static_cast<size_t>(sample) * N_ + nn;
         store4<T>(a.dz + idx, m[0] > 0.f ? v4[0] : 0.f, m[1] > 0.f ? v4[1] : 0.f, m[2] > 0.f ? v4[2] : 0.f,
                   m[3] > 0.f ? v4[3] : 0.f);
     }

@@ -122,8 +122,12 @@ struct HeadArgs {
 
 constexpr int kHeadAct = 0, kHeadTrain = 1;
 
+// The leading scalar parameters repeat HeadArgs::partial, slices, rows, A, groups, head_blocks, w2[0], b1[0], b2[0] and
+// epsilon: the kernel arguments' first 14 dwords are preloaded into scalar registers when a wavefront starts (see
+// conv_tower_kernel); everything else is read from the struct.
 template <typename T, int MODE>
-__global__ __launch_bounds__(256) void head_fwd_kernel(HeadArgs a)
+__global__ __launch_bounds__(256) void head_fwd_kernel(const float* partial_, int slices_, int rows_, int A_, int groups_, int head_blocks_,
+                                                       const void* w2_0_, const float* b1_0_, const float* b2_0_, float epsilon_, HeadArgs a)
 {
     typedef typename Vec8<T>::type V8;
     constexpr int G = MODE == kHeadAct ? 1 : 3;
@@ -132,8 +136,8 @@ __global__ __launch_bounds__(256) void head_fwd_kernel(HeadArgs a)
     __shared__ float s_red[G][4][16][64];   // fc2 partial accumulators: [group][k-quarter wavefront][slot][lane]
     __shared__ float s_dq[kHeadRows];
     if constexpr (MODE == kHeadTrain) {
-        if (static_cast<int>(blockIdx.x) >= a.head_blocks) {
-            const int i = static_cast<int>(blockIdx.x) - a.head_blocks;
+        if (static_cast<int>(blockIdx.x) >= head_blocks_) {
+            const int i = static_cast<int>(blockIdx.x) - head_blocks_;
             if (a.desc_out) {
                 const int b = i * 256 + static_cast<int>(threadIdx.x);
                 if (b < a.gather.B) sample_desc(a.gather, b, a.desc_out + static_cast<size_t>(b) * kDescInts);
@@ -145,15 +149,15 @@ __global__ __launch_bounds__(256) void head_fwd_kernel(HeadArgs a)
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int row0 = blockIdx.x * kHeadRows;
     const int lr = lane & 31, kg = lane >> 5;
-    const int arow = lr < a.A ? lr : a.A - 1;
+    const int arow = lr < A_ ? lr : A_ - 1;
 
     // Every global operand is requested here, before anything waits: a cold round trip to memory costs
     // over a microsecond, and the stages below would otherwise pay one each (fc2's bias, the transition's
     // reward / terminal flag / action, the taken action's row of W2).
     const int hr = tid >> 7, hf0 = (tid & 127) * 4;                 // stage (1) and the dzh epilogue: row, features
-    const int hrow = row0 + hr < a.rows ? row0 + hr : a.rows - 1;
+    const int hrow = row0 + hr < rows_ ? row0 + hr : rows_ - 1;
     const int trow_ = lane >> 5;                                      // tail: row of this lane
-    const int trow_c = row0 + trow_ < a.rows ? row0 + trow_ : a.rows - 1;
+    const int trow_c = row0 + trow_ < rows_ ? row0 + trow_ : rows_ - 1;
     int act_taken = 0, act_tail = 0;
     float rew_tail = 0.f, done_tail = 0.f;
     bool act_ok = true;   // tail: the stored action of this lane's row lies in [0, A)
@@ -161,9 +165,9 @@ __global__ __launch_bounds__(256) void head_fwd_kernel(HeadArgs a)
         // A stored action outside [0, A) (replay_sample_gather marks a row it could not assemble with -1) must not
         // address anything: such a row gets loss 0 and gradient 0, and every index derived from it is clamped.
         act_taken = a.act[hrow];
-        act_taken = static_cast<unsigned>(act_taken) < static_cast<unsigned>(a.A) ? act_taken : 0;
+        act_taken = static_cast<unsigned>(act_taken) < static_cast<unsigned>(A_) ? act_taken : 0;
         act_tail = a.act[trow_c];
-        act_ok = static_cast<unsigned>(act_tail) < static_cast<unsigned>(a.A);
+        act_ok = static_cast<unsigned>(act_tail) < static_cast<unsigned>(A_);
         act_tail = act_ok ? act_tail : 0;
         rew_tail = a.rew[trow_c];
         done_tail = a.done[trow_c];
@@ -171,14 +175,14 @@ __global__ __launch_bounds__(256) void head_fwd_kernel(HeadArgs a)
     Philox4 draw{};   // act step: the exploration draw of this lane's row
     float b2_tail[G];   // fc2 bias of this lane's action in the tail (which reads its Q values straight from the partials)
 #pragma unroll
-    for (int g = 0; g < G; ++g) b2_tail[g] = a.b2[g < a.groups ? g : 0][(lane & 31) < a.A ? (lane & 31) : a.A - 1];   // never skipped
+    for (int g = 0; g < G; ++g) b2_tail[g] = (g == 0 || g >= groups_ ? b2_0_ : a.b2[g])[(lane & 31) < A_ ? (lane & 31) : A_ - 1];   // never skipped
     __builtin_amdgcn_sched_barrier(0);
     // fc2 weight fragments of every group: consumed last
     V8 wf[G][8];
 #pragma unroll
     for (int g = 0; g < G; ++g)
-        if (g < a.groups) {
-            const T* wp = static_cast<const T*>(a.w2[g]) + static_cast<size_t>(arow) * 512 + wave * 128 + kg * 8;
+        if (g < groups_) {
+            const T* wp = static_cast<const T*>(g == 0 ? w2_0_ : a.w2[g]) + static_cast<size_t>(arow) * 512 + wave * 128 + kg * 8;
 #pragma unroll
             for (int s = 0; s < 8; ++s) wf[g][s] = *reinterpret_cast<const V8*>(wp + s * 16);
         }
@@ -186,7 +190,7 @@ __global__ __launch_bounds__(256) void head_fwd_kernel(HeadArgs a)
     float4 b1v[G];
 #pragma unroll
     for (int g = 0; g < G; ++g)
-        if (g < a.groups) b1v[g] = *reinterpret_cast<const float4*>(a.b1[g] + hf0);
+        if (g < groups_) b1v[g] = *reinterpret_cast<const float4*>((g == 0 ? b1_0_ : a.b1[g]) + hf0);
     float4 w2row = make_float4(0.f, 0.f, 0.f, 0.f);   // train step: the taken action's row of W2 at this thread's features
     __builtin_amdgcn_sched_barrier(0);
 
@@ -197,19 +201,19 @@ __global__ __launch_bounds__(256) void head_fwd_kernel(HeadArgs a)
     {
         const int r = hr, f0 = hf0;
         const int row = row0 + r;
-        const size_t sstride = static_cast<size_t>(a.rows) * 512, gstride = sstride * a.slices;
-        const float* p0 = a.partial + static_cast<size_t>(hrow) * 512 + f0;
+        const size_t sstride = static_cast<size_t>(rows_) * 512, gstride = sstride * slices_;
+        const float* p0 = partial_ + static_cast<size_t>(hrow) * 512 + f0;
         float4 acc[G];
 #pragma unroll
         for (int g = 0; g < G; ++g) acc[g] = make_float4(0.f, 0.f, 0.f, 0.f);
-        for (int s0 = 0; s0 < a.slices; s0 += 7) {
+        for (int s0 = 0; s0 < slices_; s0 += 7) {
             float4 v[G][7];
 #pragma unroll
             for (int g = 0; g < G; ++g)
-                if (g < a.groups) {
+                if (g < groups_) {
 #pragma unroll
                     for (int u = 0; u < 7; ++u) {
-                        const int sl = s0 + u < a.slices ? s0 + u : a.slices - 1;
+                        const int sl = s0 + u < slices_ ? s0 + u : slices_ - 1;
                         v[g][u] = *reinterpret_cast<const float4*>(p0 + g * gstride + sl * sstride);
                     }
                 }
@@ -217,29 +221,29 @@ __global__ __launch_bounds__(256) void head_fwd_kernel(HeadArgs a)
             if (s0 == 0) {
                 if constexpr (MODE == kHeadTrain) {
                     float w[4];
-                    load4<T>(static_cast<const T*>(a.w2[0]) + static_cast<size_t>(act_taken) * 512 + hf0, w);
+                    load4<T>(static_cast<const T*>(w2_0_) + static_cast<size_t>(act_taken) * 512 + hf0, w);
                     w2row = make_float4(w[0], w[1], w[2], w[3]);
                 } else draw = philox_draw(a.seed, kTagAct, a.act_step, static_cast<uint32_t>(row0 + trow_));
             }
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int g = 0; g < G; ++g)
-                if (g < a.groups) {
+                if (g < groups_) {
 #pragma unroll
                     for (int u = 0; u < 7; ++u)
-                        if (s0 + u < a.slices) { acc[g].x += v[g][u].x; acc[g].y += v[g][u].y; acc[g].z += v[g][u].z; acc[g].w += v[g][u].w; }
+                        if (s0 + u < slices_) { acc[g].x += v[g][u].x; acc[g].y += v[g][u].y; acc[g].z += v[g][u].z; acc[g].w += v[g][u].w; }
                 }
         }
 #pragma unroll
         for (int g = 0; g < G; ++g)
-            if (g < a.groups) {
+            if (g < groups_) {
                 const float4 bv = b1v[g];
                 const float4 hv = make_float4(fmaxf(acc[g].x + bv.x, 0.f), fmaxf(acc[g].y + bv.y, 0.f), fmaxf(acc[g].z + bv.z, 0.f),
                                               fmaxf(acc[g].w + bv.w, 0.f));
                 store4<T>(&s_h[g][r][f0], hv.x, hv.y, hv.z, hv.w);   // a row past the batch repeats the last one; nobody reads its Q
                 if (MODE == kHeadTrain && g == 0) {
                     h0[0] = hv.x; h0[1] = hv.y; h0[2] = hv.z; h0[3] = hv.w;
-                    if (row < a.rows)
+                    if (row < rows_)
                         store4<T>(static_cast<T*>(a.h_online) + static_cast<size_t>(row) * 512 + f0, hv.x, hv.y, hv.z, hv.w);
                 }
             }
@@ -248,7 +252,7 @@ __global__ __launch_bounds__(256) void head_fwd_kernel(HeadArgs a)
     // (2) fc2 per group: every wavefront's k-quarter of the accumulator goes to LDS, one barrier for all groups
 #pragma unroll
     for (int g = 0; g < G; ++g)
-        if (g < a.groups) {
+        if (g < groups_) {
             f32x16 acc;
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[v] = 0.f;
@@ -280,7 +284,7 @@ __global__ __launch_bounds__(256) void head_fwd_kernel(HeadArgs a)
     const float kNegInf = -__builtin_huge_valf();
     // Q_g(row trow, action tk): accumulator layout is sample lane % 32, action 8*(v/4) + 4*(lane/32) + (v%4); the four
     // k-quarter partials of that slot are added in wavefront order, then the bias
-    const int tkc = tk < a.A ? tk : a.A - 1;
+    const int tkc = tk < A_ ? tk : A_ - 1;
     const int qslot = 4 * (tkc >> 3) + (tkc & 3), qsrc = ((tkc >> 2) & 1) * 32 + trow;
     auto q_of = [&](int g) {
         return (((s_red[g][0][qslot][qsrc] + s_red[g][1][qslot][qsrc]) + s_red[g][2][qslot][qsrc]) + s_red[g][3][qslot][qsrc]) + b2_tail[g];
@@ -288,29 +292,29 @@ __global__ __launch_bounds__(256) void head_fwd_kernel(HeadArgs a)
     if constexpr (MODE == kHeadAct) {
         if (wave != 0) return;
         const int row = row0 + trow;
-        const float qv = tk < a.A ? q_of(0) : kNegInf;
+        const float qv = tk < A_ ? q_of(0) : kNegInf;
         int act = argmax_lowest(qv, tk);
-        if (row >= a.rows) return;
-        if (a.q_out && tk < a.A) a.q_out[static_cast<size_t>(row) * a.A + tk] = qv;
+        if (row >= rows_) return;
+        if (a.q_out && tk < A_) a.q_out[static_cast<size_t>(row) * A_ + tk] = qv;
         if (tk == 0) {
             const Philox4 d = draw;
             const float u = static_cast<float>(d.x[0] >> 8) * 0x1p-24f;
-            if (u < a.epsilon) act = static_cast<int>((static_cast<uint64_t>(d.x[1]) * static_cast<uint32_t>(a.A)) >> 32);
+            if (u < epsilon_) act = static_cast<int>((static_cast<uint64_t>(d.x[1]) * static_cast<uint32_t>(A_)) >> 32);
             a.actions[row] = act;
         }
     } else {
         if (wave == 0) {
             const int row = row0 + trow;
-            const bool live = row < a.rows;
+            const bool live = row < rows_;
             const float q0 = q_of(0), q1 = q_of(1);
-            const float q2 = a.groups > 2 ? q_of(G - 1) : 0.f;   // Double DQN: Q(s', .; theta) selects the action
-            const float qt = tk < a.A ? q1 : kNegInf;
-            const float qsel = a.double_dqn ? (tk < a.A ? q2 : kNegInf) : qt;
+            const float q2 = groups_ > 2 ? q_of(G - 1) : 0.f;   // Double DQN: Q(s', .; theta) selects the action
+            const float qt = tk < A_ ? q1 : kNegInf;
+            const float qsel = a.double_dqn ? (tk < A_ ? q2 : kNegInf) : qt;
             const int astar = argmax_lowest(qsel, tk);
-            if (live && tk < a.A) {
-                a.q_all[(static_cast<size_t>(0) * a.rows + row) * a.A + tk] = q0;
-                a.q_all[(static_cast<size_t>(1) * a.rows + row) * a.A + tk] = q1;
-                if (a.groups > 2) a.q_all[(static_cast<size_t>(2) * a.rows + row) * a.A + tk] = q2;
+            if (live && tk < A_) {
+                a.q_all[(static_cast<size_t>(0) * rows_ + row) * A_ + tk] = q0;
+                a.q_all[(static_cast<size_t>(1) * rows_ + row) * A_ + tk] = q1;
+                if (groups_ > 2) a.q_all[(static_cast<size_t>(2) * rows_ + row) * A_ + tk] = q2;
             }
             // the two values the TD error needs sit in other lanes of this row: Q(s', a*; theta^-) and Q(s, a_b; theta)
             const float q1_star = __shfl(q1, astar, 32), q0_taken = __shfl(q0, act_tail, 32);
@@ -324,7 +328,7 @@ __global__ __launch_bounds__(256) void head_fwd_kernel(HeadArgs a)
                     const float delta = q0_taken - y;
                     const float ad = fabsf(delta);
                     a.lossv[row] = ad <= a.huber ? 0.5f * delta * delta : a.huber * (ad - 0.5f * a.huber);
-                    dq = fminf(fmaxf(delta, -a.huber), a.huber) / static_cast<float>(a.rows);
+                    dq = fminf(fmaxf(delta, -a.huber), a.huber) / static_cast<float>(rows_);
                     a.dqv[row] = dq;
                 }
                 s_dq[trow] = dq;
@@ -334,7 +338,7 @@ __global__ __launch_bounds__(256) void head_fwd_kernel(HeadArgs a)
         // fc2's data gradient through fc1's ReLU for this workgroup's rows: dQ has one non-zero per row
         const int r = tid >> 7, f0 = (tid & 127) * 4;
         const int row = row0 + r;
-        if (row < a.rows) {
+        if (row < rows_) {
             const float w[4] = {w2row.x, w2row.y, w2row.z, w2row.w};
             const float dq = s_dq[r];
             store4<T>(static_cast<T*>(a.dzh) + static_cast<size_t>(row) * 512 + f0, h0[0] > 0.f ? dq * w[0] : 0.f,
@@ -557,8 +561,12 @@ __device__ inline void publish(const RmsArgs& a, size_t e, float th)
 // (their gradient is finished here from split-K slices), elementwise blocks cover the rest except fc1.w and the
 // hidden-layer biases; fc1.w is walked in 32 x 64 tiles whose two 16-bit copies (forward [o][f] and backward
 // [f][o], both in fragment order; fp32: the row-major [f][o] copy) are written in whole 512-byte pieces via LDS.
+// The leading scalar parameters repeat RmsArgs::theta, grad, v, m, flat_blocks, fc1_tiles and off.wf1 (what the fc1.w
+// tiles, 95 % of the parameters, need before their first load): the kernel arguments' first 14 dwords are preloaded into
+// scalar registers when a wavefront starts (see conv_tower_kernel).
 template <typename T, bool SHADOW>
-__global__ __launch_bounds__(256) void rmsprop_kernel(RmsArgs a)
+__global__ __launch_bounds__(256) void rmsprop_kernel(float* theta_, const float* grad_, float* v_, float* m_, int flat_blocks_,
+                                                      int fc1_tiles_, size_t wf1_, RmsArgs a)
 {
     __shared__ T tile[64][32 + 8];
     const int tid = threadIdx.x;
@@ -578,9 +586,9 @@ __global__ __launch_bounds__(256) void rmsprop_kernel(RmsArgs a)
         const int ns = a.wg_splits[conv];
         float4 th = make_float4(0.f, 0.f, 0.f, 0.f), vv = th, mm = th;
         if (j == 0) {
-            th = *reinterpret_cast<float4*>(a.theta + e);
-            vv = *reinterpret_cast<float4*>(a.v + e);
-            mm = *reinterpret_cast<float4*>(a.m + e);
+            th = *reinterpret_cast<float4*>(theta_ + e);
+            vv = *reinterpret_cast<float4*>(v_ + e);
+            mm = *reinterpret_cast<float4*>(m_ + e);
         }
         constexpr int kPerLane = 8;       // slices per lane and round trip: one trip up to 64 slices, two up to 128
         float4 sum = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -604,14 +612,14 @@ __global__ __launch_bounds__(256) void rmsprop_kernel(RmsArgs a)
         if (j != 0) return;
         const float sc = a.wg_scale[conv];
         const float4 g = make_float4(sum.x * sc, sum.y * sc, sum.z * sc, sum.w * sc);
-        *reinterpret_cast<float4*>(const_cast<float*>(a.grad) + e) = g;   // kept for readers of the gradient
+        *reinterpret_cast<float4*>(const_cast<float*>(grad_) + e) = g;   // kept for readers of the gradient
         rms_update(a, th.x, g.x, vv.x, mm.x);
         rms_update(a, th.y, g.y, vv.y, mm.y);
         rms_update(a, th.z, g.z, vv.z, mm.z);
         rms_update(a, th.w, g.w, vv.w, mm.w);
-        *reinterpret_cast<float4*>(a.theta + e) = th;
-        *reinterpret_cast<float4*>(a.v + e) = vv;
-        if (a.centered) *reinterpret_cast<float4*>(a.m + e) = mm;
+        *reinterpret_cast<float4*>(theta_ + e) = th;
+        *reinterpret_cast<float4*>(v_ + e) = vv;
+        if (a.centered) *reinterpret_cast<float4*>(m_ + e) = mm;
         publish<T, SHADOW>(a, e, th.x);
         publish<T, SHADOW>(a, e + 1, th.y);
         publish<T, SHADOW>(a, e + 2, th.z);
@@ -619,46 +627,46 @@ __global__ __launch_bounds__(256) void rmsprop_kernel(RmsArgs a)
         return;
     }
     const int block = static_cast<int>(blockIdx.x) - kRmsConvBlocks;
-    if (block < a.flat_blocks) {
+    if (block < flat_blocks_) {
         const size_t n_flat = a.off.total - static_cast<size_t>(512) * 3136;
         const size_t n4 = n_flat / 4;
         const size_t i = block * static_cast<size_t>(256) + tid;
-        auto to_blob = [&](size_t f) { return f < a.off.wf1 ? f : f + static_cast<size_t>(512) * 3136; };
+        auto to_blob = [&](size_t f) { return f < wf1_ ? f : f + static_cast<size_t>(512) * 3136; };
         if (i < n4) {
             const size_t e = to_blob(4 * i);
             if (hidden_bias_layer(a.off, e) >= 0) return;   // bias vectors are 4-aligned: handled by the bias blocks
             if (e < a.off.b1 || (e >= a.off.w2 && e < a.off.b2) || (e >= a.off.w3 && e < a.off.b3)) return;   // conv weights: the blocks above
-            float4 th = *reinterpret_cast<float4*>(a.theta + e);
-            const float4 g = *reinterpret_cast<const float4*>(a.grad + e);
-            float4 vv = *reinterpret_cast<float4*>(a.v + e);
-            float4 mm = *reinterpret_cast<float4*>(a.m + e);
+            float4 th = *reinterpret_cast<float4*>(theta_ + e);
+            const float4 g = *reinterpret_cast<const float4*>(grad_ + e);
+            float4 vv = *reinterpret_cast<float4*>(v_ + e);
+            float4 mm = *reinterpret_cast<float4*>(m_ + e);
             rms_update(a, th.x, g.x, vv.x, mm.x);
             rms_update(a, th.y, g.y, vv.y, mm.y);
             rms_update(a, th.z, g.z, vv.z, mm.z);
             rms_update(a, th.w, g.w, vv.w, mm.w);
-            *reinterpret_cast<float4*>(a.theta + e) = th;
-            *reinterpret_cast<float4*>(a.v + e) = vv;
-            if (a.centered) *reinterpret_cast<float4*>(a.m + e) = mm;
+            *reinterpret_cast<float4*>(theta_ + e) = th;
+            *reinterpret_cast<float4*>(v_ + e) = vv;
+            if (a.centered) *reinterpret_cast<float4*>(m_ + e) = mm;
             publish<T, SHADOW>(a, e, th.x);
             publish<T, SHADOW>(a, e + 1, th.y);
             publish<T, SHADOW>(a, e + 2, th.z);
             publish<T, SHADOW>(a, e + 3, th.w);
         } else if (i < n4 + (n_flat - 4 * n4)) {
             const size_t e = to_blob(4 * n4 + (i - n4));
-            float th = a.theta[e], vv = a.v[e], mm = a.m[e];
-            rms_update(a, th, a.grad[e], vv, mm);
-            a.theta[e] = th;
-            a.v[e] = vv;
-            if (a.centered) a.m[e] = mm;
+            float th = theta_[e], vv = v_[e], mm = m_[e];
+            rms_update(a, th, grad_[e], vv, mm);
+            theta_[e] = th;
+            v_[e] = vv;
+            if (a.centered) m_[e] = mm;
             publish<T, SHADOW>(a, e, th);
         }
         return;
     }
-    if (block >= a.flat_blocks + a.fc1_tiles) {
+    if (block >= flat_blocks_ + fc1_tiles_) {
         // hidden-layer biases: finish the gradient, then update.  Eight adjacent lanes share a channel: lane j
         // adds chunks j, j + 8, ... in order, then the eight sums meet in a fixed tree -- a large batch has
         // hundreds of chunks and one lane walking them alone was the tail of this kernel.
-        const int idx = (block - a.flat_blocks - a.fc1_tiles) * 256 + tid;
+        const int idx = (block - flat_blocks_ - fc1_tiles_) * 256 + tid;
         const int ch = idx / kRmsBiasLanes, j = idx % kRmsBiasLanes;
         const bool live = ch < 32 + 64 + 64 + 512;
         int layer = 3, c = 0;
@@ -676,34 +684,34 @@ __global__ __launch_bounds__(256) void rmsprop_kernel(RmsArgs a)
         g += __shfl_down(g, 2, kRmsBiasLanes);
         g += __shfl_down(g, 1, kRmsBiasLanes);
         if (!live || j != 0) return;
-        const_cast<float*>(a.grad)[e] = g;
-        float th = a.theta[e], vv = a.v[e], mm = a.m[e];
+        const_cast<float*>(grad_)[e] = g;
+        float th = theta_[e], vv = v_[e], mm = m_[e];
         rms_update(a, th, g, vv, mm);
-        a.theta[e] = th;
-        a.v[e] = vv;
-        if (a.centered) a.m[e] = mm;
+        theta_[e] = th;
+        v_[e] = vv;
+        if (a.centered) m_[e] = mm;
         if (SHADOW) static_cast<T*>(a.sh)[e] = from_float<T>(th);
         return;
     }
     // fc1.w tile: rows o0 .. o0+31, columns f0 .. f0+63
-    const int t = block - a.flat_blocks;
+    const int t = block - flat_blocks_;
     const int o0 = (t / 49) * 32, f0 = (t % 49) * 64;
 #pragma unroll
     for (int u = 0; u < 2; ++u) {
         const int v4 = tid + u * 256;            // 512 float4 per tile
         const int r = v4 / 16, c4 = (v4 % 16) * 4;
-        const size_t e = a.off.wf1 + static_cast<size_t>(o0 + r) * 3136 + f0 + c4;
-        float4 th = *reinterpret_cast<float4*>(a.theta + e);
-        const float4 g = *reinterpret_cast<const float4*>(a.grad + e);
-        float4 vv = *reinterpret_cast<float4*>(a.v + e);
-        float4 mm = *reinterpret_cast<float4*>(a.m + e);
+        const size_t e = wf1_ + static_cast<size_t>(o0 + r) * 3136 + f0 + c4;
+        float4 th = *reinterpret_cast<float4*>(theta_ + e);
+        const float4 g = *reinterpret_cast<const float4*>(grad_ + e);
+        float4 vv = *reinterpret_cast<float4*>(v_ + e);
+        float4 mm = *reinterpret_cast<float4*>(m_ + e);
         rms_update(a, th.x, g.x, vv.x, mm.x);
         rms_update(a, th.y, g.y, vv.y, mm.y);
         rms_update(a, th.z, g.z, vv.z, mm.z);
         rms_update(a, th.w, g.w, vv.w, mm.w);
-        *reinterpret_cast<float4*>(a.theta + e) = th;
-        *reinterpret_cast<float4*>(a.v + e) = vv;
-        if (a.centered) *reinterpret_cast<float4*>(a.m + e) = mm;
+        *reinterpret_cast<float4*>(theta_ + e) = th;
+        *reinterpret_cast<float4*>(v_ + e) = vv;
+        if (a.centered) *reinterpret_cast<float4*>(m_ + e) = mm;
         tile[c4 + 0][r] = from_float<T>(th.x);
         tile[c4 + 1][r] = from_float<T>(th.y);
         tile[c4 + 2][r] = from_float<T>(th.z);
@@ -725,7 +733,7 @@ __global__ __launch_bounds__(256) void rmsprop_kernel(RmsArgs a)
             V8 val;
 #pragma unroll
             for (int j = 0; j < 8; ++j) val[j] = tile[k8 + j][rr];
-            *reinterpret_cast<V8*>(static_cast<T*>(a.sh) + a.off.wf1 + tower_frag_index(o0 + rr, f0 + k8, 3136)) = val;
+            *reinterpret_cast<V8*>(static_cast<T*>(a.sh) + wf1_ + tower_frag_index(o0 + rr, f0 + k8, 3136)) = val;
         }
     } else {
         const int f = tid / 4, part = (tid % 4) * 8;

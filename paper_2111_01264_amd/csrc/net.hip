@@ -284,8 +284,9 @@ static int forward_to_fc1(dqn_ctx* c, hipStream_t st, Workspace& ws, int groups,
         a.push.L = 0;
         if (push) a.push = *push;
         const ProfPair pr = pp(K_CONV1_FWD);
-        if (a.desc) launch_timed(conv_tower_kernel<true>, dim3(grid + a.push.L), dim3(kTowerThreads), kTowerSmem, st, pr.begin, pr.end, a);
-        else launch_timed(conv_tower_kernel<false>, dim3(grid + a.push.L), dim3(kTowerThreads), kTowerSmem, st, pr.begin, pr.end, a);
+        // (the leading arguments repeat the fields a workgroup needs first: see the kernel)
+        if (a.desc) launch_timed(conv_tower_kernel<true>, dim3(grid + a.push.L), dim3(kTowerThreads), kTowerSmem, st, pr.begin, pr.end, a.n, a.groups, a.per, a.tower_blocks, a.x[0], a.x[1], a.desc, a.ring, a.w1[0], a);
+        else launch_timed(conv_tower_kernel<false>, dim3(grid + a.push.L), dim3(kTowerThreads), kTowerSmem, st, pr.begin, pr.end, a.n, a.groups, a.per, a.tower_blocks, a.x[0], a.x[1], a.desc, a.ring, a.w1[0], a);
         DQN_LAUNCH_CHECK();
     } else {
         // fp32 mode: layer by layer; the event pair brackets all three launches
@@ -335,7 +336,8 @@ static int forward_to_fc1(dqn_ctx* c, hipStream_t st, Workspace& ws, int groups,
         a.partial = ws.partial;
         a.M = n; a.N = 512; a.ldx = 3136; a.ldw = 3136;
         const ProfPair pr = pp(K_FC1_FWD);
-        launch_timed(fc_sk_kernel<T, kFcPartial, 7, 7>, dim3(16, groups, 7), dim3(256), 0, st, pr.begin, pr.end, a);
+        launch_timed(fc_sk_kernel<T, kFcPartial, 7, 7>, dim3(16, groups, 7), dim3(256), 0, st, pr.begin, pr.end, a.x[0], a.x[1], a.w[0], a.w[1], a.M, a.N,
+                     a.ldx, a.ldw, a.partial, a);
         DQN_LAUNCH_CHECK();
         *slices_out = 7;
     } else {
@@ -389,7 +391,8 @@ static int act_impl(dqn_ctx* c, Workspace& ws, const uint8_t* states, int W, flo
     ha.epsilon = epsilon; ha.seed = c->cfg.seed; ha.act_step = act_step; ha.actions = actions; ha.q_out = q_out;
     ha.head_blocks = (W + kHeadRows - 1) / kHeadRows;
     ha.gather.B = 0;
-    hipLaunchKernelGGL((head_fwd_kernel<T, kHeadAct>), dim3(ha.head_blocks), dim3(256), 0, c->act_stream, ha);
+    hipLaunchKernelGGL((head_fwd_kernel<T, kHeadAct>), dim3(ha.head_blocks), dim3(256), 0, c->act_stream, ha.partial, ha.slices, ha.rows, ha.A, ha.groups,
+                       ha.head_blocks, ha.w2[0], ha.b1[0], ha.b2[0], ha.epsilon, ha);
     DQN_LAUNCH_CHECK();
     return DQN_OK;
 }
@@ -439,7 +442,8 @@ static int train_impl(dqn_ctx* c, const uint8_t* s, const int32_t* a, const floa
         ha.desc_out = ride_desc;
         if (ride) ha.gather = *ride;
         const int riders = !ride ? 0 : (ride_desc ? (ride->B + 255) / 256 : 5 * ride->B);
-        launch_timed(head_fwd_kernel<T, kHeadTrain>, dim3(ha.head_blocks + riders), dim3(256), 0, st, pr.begin, pr.end, ha);
+        launch_timed(head_fwd_kernel<T, kHeadTrain>, dim3(ha.head_blocks + riders), dim3(256), 0, st, pr.begin, pr.end, ha.partial, ha.slices, ha.rows, ha.A,
+                     ha.groups, ha.head_blocks, ha.w2[0], ha.b1[0], ha.b2[0], ha.epsilon, ha);
         DQN_LAUNCH_CHECK();
     }
     // ---- data-gradient chain: fc1 -> conv3 -> conv2 ------------------------------------------------
@@ -448,7 +452,8 @@ static int train_impl(dqn_ctx* c, const uint8_t* s, const int32_t* a, const floa
         fa.x[0] = dzh; fa.w[0] = bsh + kBshWf1; fa.dz = dz3; fa.mask = act3;
         fa.M = B; fa.N = 3136; fa.ldx = 512; fa.ldw = 512;
         const ProfPair pr = prof_pair(c, K_FC1_DGRAD);
-        launch_timed(fc_sk_kernel<T, kFcReluMask, 8, 1>, dim3(98, 1, 1), dim3(256), 0, st, pr.begin, pr.end, fa);
+        launch_timed(fc_sk_kernel<T, kFcReluMask, 8, 1>, dim3(98, 1, 1), dim3(256), 0, st, pr.begin, pr.end, fa.x[0], fa.x[1], fa.w[0], fa.w[1], fa.M, fa.N,
+                     fa.ldx, fa.ldw, fa.partial, fa);
         DQN_LAUNCH_CHECK();
     } else {
         FcAsArgs<T> fa{};
@@ -468,7 +473,8 @@ static int train_impl(dqn_ctx* c, const uint8_t* s, const int32_t* a, const floa
         const int grid = B < c->num_cus ? B : c->num_cus;
         ta.per = (B + grid - 1) / grid;
         const ProfPair pr = prof_pair(c, K_TOWER_BWD);
-        launch_timed(conv_tower_bwd_kernel, dim3(grid), dim3(kTowerThreads), kTowerBwdSmem, st, pr.begin, pr.end, ta);
+        launch_timed(conv_tower_bwd_kernel, dim3(grid), dim3(kTowerThreads), kTowerBwdSmem, st, pr.begin, pr.end, ta.n, ta.per, ta.dz3, ta.w3d, ta.w2d, ta.act2,
+                     ta.act1, ta.dz2, ta.dz1);
         DQN_LAUNCH_CHECK();
     } else {
         {   // conv3 data gradient through conv2's ReLU
@@ -570,7 +576,8 @@ static int train_impl(dqn_ctx* c, const uint8_t* s, const int32_t* a, const floa
         wa.first[4] = wa.first[3] + kWgF1Cols * kWgF1Rows;
         wa.first[5] = wa.first[4] + small_blocks;
         const ProfPair pr = prof_pair(c, K_WGRAD_ALL);
-        launch_timed(wgrad_all_kernel, dim3(wa.first[5]), dim3(256), kWgradAllSmem, st, pr.begin, pr.end, wa);
+        launch_timed(wgrad_all_kernel, dim3(wa.first[5]), dim3(256), kWgradAllSmem, st, pr.begin, pr.end, wa.first[1], wa.first[2], wa.first[3], wa.first[4],
+                     wa.c1.dz, wa.c1.in, wa.c1.n, wa.c1.per, wa.c1.desc, wa.c1.ring, wa);
         DQN_LAUNCH_CHECK();
     } else {
         {   // fc1 weight gradient: dW[o][f] = sum_b dZ[b][o] act3[b][f]
@@ -608,7 +615,8 @@ static int train_impl(dqn_ctx* c, const uint8_t* s, const int32_t* a, const floa
         const ProfPair pr = prof_pair(c, K_RMSPROP);
         for (int l = 0; l < 3; ++l) ra.wg_splits[l] = wg_splits[l];
         for (int l = 0; l < 4; ++l) { ra.bias_chunks[l] = bias_chunks[l]; ra.bias_first[l] = bias_first[l]; }
-        launch_timed(rmsprop_kernel<T, SHADOW>, dim3(kRmsConvBlocks + ra.flat_blocks + ra.fc1_tiles + kRmsBiasBlocks), dim3(256), 0, st, pr.begin, pr.end, ra);
+        launch_timed(rmsprop_kernel<T, SHADOW>, dim3(kRmsConvBlocks + ra.flat_blocks + ra.fc1_tiles + kRmsBiasBlocks), dim3(256), 0, st, pr.begin, pr.end, ra.theta,
+                     ra.grad, ra.v, ra.m, ra.flat_blocks, ra.fc1_tiles, ra.off.wf1, ra);
         DQN_LAUNCH_CHECK();
     }
     return DQN_OK;

@@ -29,17 +29,21 @@ constexpr size_t kWgradAllSmem = []() {
     return (m + 15) / 16 * 16;
 }();
 
-__global__ __launch_bounds__(256, 2) void wgrad_all_kernel(WgradAllArgs a)
+// The leading scalar parameters repeat the four block boundaries (first[1..4]) and what conv1's workgroups -- the longest
+// ones -- need before their first load (c1.dz, in, n, per, desc, ring): the kernel arguments' first 14 dwords are preloaded
+// into scalar registers when a wavefront starts (see conv_tower_kernel); the other layers read their part of the struct.
+__global__ __launch_bounds__(256, 2) void wgrad_all_kernel(int f1, int f2, int f3, int f4, const bf16_t* c1_dz, const void* c1_in, int c1_n, int c1_per,
+                                                           const int32_t* c1_desc, const uint8_t* c1_ring, WgradAllArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char wg_smem[];
     // grid order: conv1, conv2, conv3, fc1, small reductions -- the longest workgroups first (the grid can exceed what is
     // resident at once, and what starts late should be short)
     const int blk = blockIdx.x;
-    // the four boundaries in one scalar load (read one by one, each is a load-wait-branch step of its own)
-    const int f1 = a.first[1], f2 = a.first[2], f3 = a.first[3], f4 = a.first[4];
-    asm volatile("" :: "s"(f1), "s"(f2), "s"(f3), "s"(f4));
     if (blk < f1) {
-        wgrad_conv_block<WgConv1>(a.c1, blk, 0, wg_smem);
+        WgConvArgs c1;
+        c1.dz = c1_dz; c1.in = c1_in; c1.n = c1_n; c1.per = c1_per; c1.desc = c1_desc; c1.ring = c1_ring;
+        c1.partial = a.c1.partial; c1.bias_partial = a.c1.bias_partial;
+        wgrad_conv_block<WgConv1>(c1, blk, 0, wg_smem);
     } else if (blk < f2) {
         wgrad_conv_block<WgConv2>(a.c2, (blk - f1) / WgConv2::CS, (blk - f1) % WgConv2::CS, wg_smem);
     } else if (blk < f3) {
