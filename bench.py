@@ -268,7 +268,6 @@ class Workload:
         """`steps` benchmark steps: the trainer thread and the sampler (this) thread run concurrently
         between synchronisation points, as in Algorithm 1 (no host synchronisation with the GPU).
         part = "train" / "act" runs only that side (same sync schedule), for the alone-vs-overlapped figures."""
-        import threading
         done = 0
         while done < steps:
             if part != "both":
@@ -283,23 +282,44 @@ class Workload:
             if self.train_steps % self.sync_every == 0:
                 self.sync_point()
             n = min(steps - done, self.sync_every - self.train_steps % self.sync_every)
-            err = []
-
-            def trainer():
-                try:
-                    self.train_part(n)
-                except Exception as e:      # noqa: BLE001
-                    err.append(e)
-
-            t = threading.Thread(target=trainer)
-            t.start()
+            self._trainer_submit(n)
             self.act_part(n)
-            t.join()
-            if err:
-                raise err[0]
+            self._trainer_wait()
             done += n
 
+    # The trainer thread lives as long as the workload (as Algorithm 1's trainer thread does): starting a thread per
+    # call would put its start-up inside every timed region, which shows in short runs.
+    def _trainer_loop(self):
+        while True:
+            n = self._trainer_tasks.get()
+            if n is None:
+                return
+            try:
+                self.train_part(n)
+            except Exception as e:      # noqa: BLE001
+                self._trainer_err.append(e)
+            self._trainer_done.set()
+
+    def _trainer_submit(self, n):
+        import queue
+        import threading
+        if getattr(self, "_trainer_thread", None) is None:
+            self._trainer_tasks, self._trainer_done, self._trainer_err = queue.SimpleQueue(), threading.Event(), []
+            self._trainer_thread = threading.Thread(target=self._trainer_loop, daemon=True)
+            self._trainer_thread.start()
+        self._trainer_done.clear()
+        self._trainer_tasks.put(n)
+
+    def _trainer_wait(self):
+        self._trainer_done.wait()
+        if self._trainer_err:
+            raise self._trainer_err.pop()
+
     def close(self):
+        if getattr(self, "_trainer_thread", None) is not None:
+            self._trainer_tasks.put(None)
+            self._trainer_thread.join()
+            self._trainer_thread = None
         self.torch.cuda.synchronize()
         self.P.replay_destroy(self.rb)
         self.P.dqn_destroy(self.ctx)
