@@ -47,7 +47,9 @@ def check_actions(acts, q_ref, eps, seed, step, tol):
 
 
 @pytest.mark.parametrize("precision", [P.DQN_PRECISION_FP32, P.DQN_PRECISION_BF16])
-@pytest.mark.parametrize("A,W", [(4, 1), (6, 8), (18, 37)])
+# W = 32 is the largest round the small-batch fc1 kernel takes, 33 the smallest for the large-batch one, 64 a whole
+# number of its 32-row tiles (the W of the batch-256 sweep point), 37 a ragged one
+@pytest.mark.parametrize("A,W", [(4, 1), (6, 8), (18, 32), (18, 33), (18, 37), (18, 64)])
 def test_act_parity(precision, A, W):
     seed = 211101264
     cfg = make_cfg(A, max_envs=64, precision=precision, seed=seed)
