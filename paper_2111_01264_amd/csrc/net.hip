@@ -149,7 +149,8 @@ constexpr int kWgSlices1 = 128, kWgSlices23 = 44;
 // Smallest minibatch handled through descriptors.  Below it the assembled states are the faster form: the byte gather
 // rides for free in the previous step's head kernel (which leaves most of the chip idle at small batches), and the
 // fused conv kernel starts on states that are contiguous and cache-warm instead of after a descriptor round trip
-// (batch 32: 56.9 us per train step through descriptors, 55.5 us through assembled states; batch 128: 75.6 against 77.7).
+// (per train step through descriptors / through assembled states: batch 32: 52.4 / 51.8 us, batch 64: 62.8 / 62.9,
+// batch 96: 64.9 / 67.1, batch 128: 68.1 / 72.0).
 constexpr int kDescMinBatch = 96;
 constexpr size_t kWgOff1 = 0, kWgOff2 = kWgMaxSplits1 * 32 * 256, kWgOff3 = kWgOff2 + kWgMaxSplits * 64 * 512;
 constexpr size_t kWgTotal = kWgOff3 + kWgMaxSplits * 64 * 576;
