@@ -132,7 +132,15 @@ static_assert(kTowerXBytes <= kTowerXchgBytes, "the state buffer overlays the ex
 // tower_blocks, x[0], x[1], desc, ring, w1[0]): the first 14 dwords of the kernel arguments are preloaded into scalar
 // registers when a wavefront starts (build option amdgpu-kernarg-preload-count), while a field of the struct is a load
 // from cold memory in front of everything that depends on it.
-template <bool DESC>
+//
+// PARTS = 3: one item is a THIRD of a sample's work -- output rows 0-2 / 3-4 / 5-6 of conv3, with the rows of conv2 (0-4 /
+// 3-6 / 5-8) and conv1 (0-11 / 6-15 / 10-19) they depend on -- and every workgroup runs exactly one item.  A round of a few
+// synchronized samplers (Section 4) or a minibatch of 32 leaves most of the chip idle while each sample's chain of layers
+// takes its seven microseconds on one compute unit; in thirds the chain is conv1 in one pass instead of two (at most eight
+// pixel tiles for eight wavefronts), two pixel tiles of conv2 instead of three and one of conv3 instead of two.  Every
+// output element is computed by the same instructions in the same order as with PARTS = 1 (rows that two parts both need
+// are computed twice), so the results are equal bit for bit.
+template <bool DESC, int PARTS>
 __global__ __launch_bounds__(kTowerThreads) void conv_tower_kernel(int n_, int groups_, int per_, int tower_blocks_, const uint8_t* x0_,
                                                                    const uint8_t* x1_, const int32_t* desc_, const uint8_t* ring_,
                                                                    const _Float16* w1_0_, TowerArgs a)
@@ -158,9 +166,17 @@ __global__ __launch_bounds__(kTowerThreads) void conv_tower_kernel(int n_, int g
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lp = lane & 31, kg = lane >> 5;
     const int nt = wave >> 2, kq = wave & 3;
+    static_assert(PARTS == 1 || PARTS == 3, "whole samples, or thirds");
     const int total = n_ * groups_;
-    const int first = blockIdx.x * per_, last = min(total, first + per_);
+    // PARTS = 3: workgroup j runs part j % 3 of item j / 3 (the host launches 3 * total workgroups, per_ = 1)
+    const int part = PARTS == 1 ? 0 : static_cast<int>(blockIdx.x % PARTS);
+    const int first = PARTS == 1 ? blockIdx.x * per_ : static_cast<int>(blockIdx.x / PARTS), last = PARTS == 1 ? min(total, first + per_) : min(total, first + 1);
     if (first >= last) return;
+    // first row and pixel count of this part in each layer's output (whole sample: all of it)
+    const int r1_lo = PARTS == 1 ? 0 : (part == 0 ? 0 : part == 1 ? 6 : 10), n1 = PARTS == 1 ? 400 : (part == 0 ? 240 : 200);
+    const int r2_lo = PARTS == 1 ? 0 : (part == 0 ? 0 : part == 1 ? 3 : 5), n2 = PARTS == 1 ? 81 : (part == 0 ? 45 : 36);
+    const int r3_lo = PARTS == 1 ? 0 : (part == 0 ? 0 : part == 1 ? 3 : 5), n3 = PARTS == 1 ? 49 : (part == 0 ? 21 : 14);
+    constexpr int T2 = PARTS == 1 ? 3 : 2, T3 = PARTS == 1 ? 2 : 1;   // pixel tiles of conv2 / conv3 per wavefront
 
     // The state of item (g_, b_), 16 bytes per lane and load (the last load is clamped, not predicated);
     // named registers rather than an array, which the compiler would keep in scratch memory.  With a descriptor table
@@ -275,8 +291,8 @@ __global__ __launch_bounds__(kTowerThreads) void conv_tower_kernel(int n_, int g
                 f32x16 acc[NT];
 #pragma unroll
                 for (int t = 0; t < NT; ++t) {
-                    const int px = (wave + 8 * t) * 32 + lp;
-                    const int pc = px < 400 ? px : 399;
+                    const int lpx = (wave + 8 * t) * 32 + lp;
+                    const int pc = r1_lo * 20 + (lpx < n1 ? lpx : n1 - 1);
                     base[t] = sX + (4 * (pc / 20) + kg) * 84 + 4 * (pc % 20);
 #pragma unroll
                     for (int v = 0; v < 16; ++v) acc[t][v] = 0.f;
@@ -314,8 +330,8 @@ __global__ __launch_bounds__(kTowerThreads) void conv_tower_kernel(int n_, int g
                 // output stage: scale, bias, ReLU -> LDS (+ global); rows 8q + 4kg .. + 3 are channels of this lane's pixel
 #pragma unroll
                 for (int t = 0; t < NT; ++t) {
-                    const int px = (wave + 8 * t) * 32 + lp;
-                    if (px < 400) {
+                    const int lpx = (wave + 8 * t) * 32 + lp, px = r1_lo * 20 + lpx;
+                    if (lpx < n1) {
                         constexpr float kScale = 16777216.f / 255.f;
 #pragma unroll
                         for (int q = 0; q < 4; ++q) {
@@ -329,18 +345,18 @@ __global__ __launch_bounds__(kTowerThreads) void conv_tower_kernel(int n_, int g
                     }
                 }
             };
-            if (wave < 5) run(std::integral_constant<int, 2>{}); else run(std::integral_constant<int, 1>{});   // 13 tiles
+            if (PARTS == 1 && wave < 5) run(std::integral_constant<int, 2>{}); else run(std::integral_constant<int, 1>{});   // 13 tiles (a third: at most 8)
         }
         __syncthreads();
 
         // ---- conv2: k = (p, q, c); this quarter is filter row p = kq; k-step k covers q = k / 2, channels 16 * (k % 2) + 8 * kg .. + 7
         {
-            f32x16 acc[3];
-            const T* base[3];
+            f32x16 acc[T2];
+            const T* base[T2];
 #pragma unroll
-            for (int t = 0; t < 3; ++t) {
-                const int px = t * 32 + lp;
-                const int pc = px < 81 ? px : 80;
+            for (int t = 0; t < T2; ++t) {
+                const int lpx = t * 32 + lp;
+                const int pc = r2_lo * 9 + (lpx < n2 ? lpx : n2 - 1);
                 base[t] = sA1 + ((2 * (pc / 9) + kq) * 20 + 2 * (pc % 9)) * kTowerP1 + kg * 8;
 #pragma unroll
                 for (int v = 0; v < 16; ++v) acc[t][v] = 0.f;
@@ -355,17 +371,20 @@ __global__ __launch_bounds__(kTowerThreads) void conv_tower_kernel(int n_, int g
 #pragma unroll
                 for (int u = 0; u < D; ++u) ring[u] = fetch(u);
 #pragma unroll
-                for (int step = 0; step < 24; ++step) {
+                for (int step = 0; step < 8 * T2; ++step) {
                     const V8 cur = ring[step % D];
-                    if (step + D < 24) ring[step % D] = fetch(step + D);
+                    if (step + D < 8 * T2) ring[step % D] = fetch(step + D);
                     mma_32x32x16(acc[step / 8], wf2[step % 8], cur);
-                    if (new_group && step >= 4 && step < 22 && (step & 1) == 0) wf3[(step - 4) >> 1] = *reinterpret_cast<const V8*>(p3 + ((step - 4) >> 1) * 512);   // conv3's
+                    // conv3's fragments: nine requests spread over the stream (every other step of 24, every step of 16)
+                    constexpr int W3_FIRST = T2 == 3 ? 4 : 3, W3_EVERY = T2 == 3 ? 2 : 1;
+                    if (new_group && step >= W3_FIRST && (step - W3_FIRST) % W3_EVERY == 0 && (step - W3_FIRST) / W3_EVERY < 9)
+                        wf3[(step - W3_FIRST) / W3_EVERY] = *reinterpret_cast<const V8*>(p3 + ((step - W3_FIRST) / W3_EVERY) * 512);
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
             float4* xc = sXchg + static_cast<size_t>(nt * 3) * (4 * 3 * 64);
 #pragma unroll
-            for (int t = 0; t < 3; ++t) {
+            for (int t = 0; t < T2; ++t) {
                 float4* x = xc + t * (4 * 3 * 64);
                 if (kq == 0) tower_send<0>(x, acc[t], lane); else if (kq == 1) tower_send<1>(x, acc[t], lane);
                 else if (kq == 2) tower_send<2>(x, acc[t], lane); else tower_send<3>(x, acc[t], lane);
@@ -375,13 +394,13 @@ __global__ __launch_bounds__(kTowerThreads) void conv_tower_kernel(int n_, int g
             const int ch = nt * 32 + 8 * kq + 4 * kg;
             const float4 bv = *reinterpret_cast<const float4*>(sB2 + ch);
 #pragma unroll
-            for (int t = 0; t < 3; ++t) {
+            for (int t = 0; t < T2; ++t) {
                 const float4* x = xc + t * (4 * 3 * 64);
                 float4 v;
                 if (kq == 0) v = tower_finish<0>(x, acc[t], lane, bv); else if (kq == 1) v = tower_finish<1>(x, acc[t], lane, bv);
                 else if (kq == 2) v = tower_finish<2>(x, acc[t], lane, bv); else v = tower_finish<3>(x, acc[t], lane, bv);
-                const int px = t * 32 + lp;
-                if (px < 81) {
+                const int lpx = t * 32 + lp, px = r2_lo * 9 + lpx;
+                if (lpx < n2) {
                     store4<T>(sA2 + px * kTowerP2 + ch, v.x, v.y, v.z, v.w);
                     if (g2) store4<T>(g2 + (static_cast<size_t>(b) * 81 + px) * 64 + ch, v.x, v.y, v.z, v.w);
                 }
@@ -391,12 +410,12 @@ __global__ __launch_bounds__(kTowerThreads) void conv_tower_kernel(int n_, int g
 
         // ---- conv3: k = (p, q, c); k-step ks = 9 * kq + k covers tap ks / 4, channels 16 * (ks % 4) + 8 * kg .. + 7
         {
-            f32x16 acc[2];
-            const T* base[2];
+            f32x16 acc[T3];
+            const T* base[T3];
 #pragma unroll
-            for (int t = 0; t < 2; ++t) {
-                const int px = t * 32 + lp;
-                const int pc = px < 49 ? px : 48;
+            for (int t = 0; t < T3; ++t) {
+                const int lpx = t * 32 + lp;
+                const int pc = r3_lo * 7 + (lpx < n3 ? lpx : n3 - 1);
                 base[t] = sA2 + ((pc / 7) * 9 + pc % 7) * kTowerP2 + kg * 8;
 #pragma unroll
                 for (int v = 0; v < 16; ++v) acc[t][v] = 0.f;
@@ -408,16 +427,16 @@ __global__ __launch_bounds__(kTowerThreads) void conv_tower_kernel(int n_, int g
 #pragma unroll
                 for (int u = 0; u < D; ++u) ring[u] = fetch(u);
 #pragma unroll
-                for (int step = 0; step < 18; ++step) {
+                for (int step = 0; step < 9 * T3; ++step) {
                     const V8 cur = ring[step % D];
-                    if (step + D < 18) ring[step % D] = fetch(step + D);
+                    if (step + D < 9 * T3) ring[step % D] = fetch(step + D);
                     mma_32x32x16(acc[step / 9], wf3[step % 9], cur);
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
             float4* xc = sXchg + static_cast<size_t>(nt * 3) * (4 * 3 * 64);
 #pragma unroll
-            for (int t = 0; t < 2; ++t) {
+            for (int t = 0; t < T3; ++t) {
                 float4* x = xc + t * (4 * 3 * 64);
                 if (kq == 0) tower_send<0>(x, acc[t], lane); else if (kq == 1) tower_send<1>(x, acc[t], lane);
                 else if (kq == 2) tower_send<2>(x, acc[t], lane); else tower_send<3>(x, acc[t], lane);
@@ -426,13 +445,13 @@ __global__ __launch_bounds__(kTowerThreads) void conv_tower_kernel(int n_, int g
             const int ch = nt * 32 + 8 * kq + 4 * kg;
             const float4 bv = *reinterpret_cast<const float4*>(sB3 + ch);
 #pragma unroll
-            for (int t = 0; t < 2; ++t) {
+            for (int t = 0; t < T3; ++t) {
                 const float4* x = xc + t * (4 * 3 * 64);
                 float4 v;
                 if (kq == 0) v = tower_finish<0>(x, acc[t], lane, bv); else if (kq == 1) v = tower_finish<1>(x, acc[t], lane, bv);
                 else if (kq == 2) v = tower_finish<2>(x, acc[t], lane, bv); else v = tower_finish<3>(x, acc[t], lane, bv);
-                const int px = t * 32 + lp;
-                if (px < 49) store4<T>(a.act3[g] + (static_cast<size_t>(b) * 49 + px) * 64 + ch, v.x, v.y, v.z, v.w);
+                const int lpx = t * 32 + lp, px = r3_lo * 7 + lpx;
+                if (lpx < n3) store4<T>(a.act3[g] + (static_cast<size_t>(b) * 49 + px) * 64 + ch, v.x, v.y, v.z, v.w);
             }
         }
         __syncthreads();   // the exchange block is read until here; its head is the next item's state buffer
