@@ -73,6 +73,13 @@ template <int KH> __device__ inline float4 tower_sum_half(const float4* theirs, 
 
 // The arguments are TowerBwdArgs' fields one by one, in the order a workgroup needs them: the first 14 dwords of the
 // kernel arguments are preloaded into scalar registers when a wavefront starts (see conv_tower_kernel).
+//
+// PARTS = 5: an item is a FIFTH of a sample -- rows 2 j, 2 j + 1 of every parity class of dz1 (four rows of dz1) with the
+// two or three rows of dz2 they depend on -- and every workgroup runs exactly one item: one pixel tile per stage instead of
+// three and four.  For minibatches that leave most of the chip idle (see conv_tower_kernel's PARTS); every element is
+// computed by the same instructions in the same order as with PARTS = 1, rows of dz2 that two parts need are computed and
+// stored by both.
+template <int PARTS>
 __global__ __launch_bounds__(kTowerThreads) void conv_tower_bwd_kernel(int n_, int per_, const bf16_t* dz3_, const bf16_t* w3d_, const bf16_t* w2d_,
                                                                        const bf16_t* act2_, const bf16_t* act1_, bf16_t* dz2_, bf16_t* dz1_)
 {
@@ -87,8 +94,14 @@ __global__ __launch_bounds__(kTowerThreads) void conv_tower_bwd_kernel(int n_, i
     const int lp = lane & 31, kg = lane >> 5;
     const int nt = wave >> 2, kq = wave & 3;     // conv3 stage
     const int cls = wave >> 1, kh = wave & 1;    // conv2 stage: class (py, px) = (cls >> 1, cls & 1)
-    const int first = blockIdx.x * per_, last = min(n_, first + per_);
+    static_assert(PARTS == 1 || PARTS == 5, "whole samples, or fifths");
+    const int part = PARTS == 1 ? 0 : static_cast<int>(blockIdx.x % PARTS);
+    const int first = PARTS == 1 ? blockIdx.x * per_ : static_cast<int>(blockIdx.x / PARTS), last = PARTS == 1 ? min(n_, first + per_) : min(n_, first + 1);
     if (first >= last) return;
+    // this part's rows: [y_lo, y_lo + 2) of each parity class of dz1 (20 pixels), rows [r2_lo, y_lo + 2) of dz2
+    const int y_lo = PARTS == 1 ? 0 : 2 * part, nc = PARTS == 1 ? 100 : 20;
+    const int r2_lo = PARTS == 1 ? 0 : (part == 0 ? 0 : 2 * part - 1), n2 = PARTS == 1 ? 81 : (part == 0 || part == 4 ? 18 : 27);   // rows 2 part - 1 .. 2 part + 1 of dz2's nine
+    constexpr int T3 = PARTS == 1 ? 3 : 1, T2 = PARTS == 1 ? 4 : 1;   // pixel tiles per wavefront: conv3 stage, conv2 stage
 
     // a sample's dz3: 49 pixels x 128 bytes = 392 vectors, one per thread, fetched one sample ahead.  The first sample's is
     // requested before the weights: loads return in order, and behind 139 KB of fragments the staging below waited ~1 us
@@ -125,17 +138,17 @@ __global__ __launch_bounds__(kTowerThreads) void conv_tower_bwd_kernel(int n_, i
         if (tid < 392) *reinterpret_cast<uint4*>(sP3 + my_dst) = xv;
         if (b + 1 < last && tid < 392) xv = reinterpret_cast<const uint4*>(dz3_ + static_cast<size_t>(b + 1) * 3136)[tid];
         // ReLU masks of both stages: requested now, used after the exchanges
-        uint2 m2[3], m1[4][2];
+        uint2 m2[T3], m1[T2][2];
         {
             const int ch = nt * 32 + 8 * kq + 4 * kg;
 #pragma unroll
-            for (int t = 0; t < 3; ++t) {
-                const int px = t * 32 + lp;
-                m2[t] = *reinterpret_cast<const uint2*>(act2_ + (static_cast<size_t>(b) * 81 + (px < 81 ? px : 80)) * 64 + ch);
+            for (int t = 0; t < T3; ++t) {
+                const int lpx = t * 32 + lp;
+                m2[t] = *reinterpret_cast<const uint2*>(act2_ + (static_cast<size_t>(b) * 81 + r2_lo * 9 + (lpx < n2 ? lpx : n2 - 1)) * 64 + ch);
             }
 #pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                const int px = t * 32 + lp, pc = px < 100 ? px : 99;
+            for (int t = 0; t < T2; ++t) {
+                const int lpx = t * 32 + lp, pc = y_lo * 10 + (lpx < nc ? lpx : nc - 1);
                 const int pix = (2 * (pc / 10) + (cls >> 1)) * 20 + 2 * (pc % 10) + (cls & 1);
 #pragma unroll
                 for (int h = 0; h < 2; ++h)
@@ -146,11 +159,11 @@ __global__ __launch_bounds__(kTowerThreads) void conv_tower_bwd_kernel(int n_, i
 
         // ---- conv3 data gradient: 81 pixels = 3 tiles, channel tile nt, k-quarter kq (9 k-steps) ------------
         {
-            f32x16 acc[3];
-            const T* base[3];
+            f32x16 acc[T3];
+            const T* base[T3];
 #pragma unroll
-            for (int t = 0; t < 3; ++t) {
-                const int px = t * 32 + lp, pc = px < 81 ? px : 80;
+            for (int t = 0; t < T3; ++t) {
+                const int lpx = t * 32 + lp, pc = r2_lo * 9 + (lpx < n2 ? lpx : n2 - 1);
                 base[t] = sP3 + ((pc / 9 + 2) * 11 + pc % 9 + 2) * kTbPitch + kg * 8;
 #pragma unroll
                 for (int v = 0; v < 16; ++v) acc[t][v] = 0.f;
@@ -162,16 +175,16 @@ __global__ __launch_bounds__(kTowerThreads) void conv_tower_bwd_kernel(int n_, i
 #pragma unroll
                 for (int u = 0; u < D; ++u) ring[u] = fetch(u);
 #pragma unroll
-                for (int step = 0; step < 27; ++step) {
+                for (int step = 0; step < 9 * T3; ++step) {
                     const V8 cur = ring[step % D];
-                    if (step + D < 27) ring[step % D] = fetch(step + D);
+                    if (step + D < 9 * T3) ring[step % D] = fetch(step + D);
                     mma_32x32x16(acc[step / 9], wf3[step % 9], cur);
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
             float4* xc = sXchg + static_cast<size_t>(nt * 3) * (4 * 3 * 64);
 #pragma unroll
-            for (int t = 0; t < 3; ++t) {
+            for (int t = 0; t < T3; ++t) {
                 float4* x = xc + t * (4 * 3 * 64);
                 if (kq == 0) tower_send<0>(x, acc[t], lane); else if (kq == 1) tower_send<1>(x, acc[t], lane);
                 else if (kq == 2) tower_send<2>(x, acc[t], lane); else tower_send<3>(x, acc[t], lane);
@@ -179,13 +192,13 @@ __global__ __launch_bounds__(kTowerThreads) void conv_tower_bwd_kernel(int n_, i
             __syncthreads();
             const int ch = nt * 32 + 8 * kq + 4 * kg;
 #pragma unroll
-            for (int t = 0; t < 3; ++t) {
+            for (int t = 0; t < T3; ++t) {
                 const float4* x = xc + t * (4 * 3 * 64);
                 float4 v;
                 if (kq == 0) v = tower_sum<0>(x, acc[t], lane); else if (kq == 1) v = tower_sum<1>(x, acc[t], lane);
                 else if (kq == 2) v = tower_sum<2>(x, acc[t], lane); else v = tower_sum<3>(x, acc[t], lane);
-                const int px = t * 32 + lp;
-                if (px < 81) {
+                const int lpx = t * 32 + lp, px = r2_lo * 9 + lpx;
+                if (lpx < n2) {
                     // ReLU mask: a bf16 activation is positive iff its bit pattern is in 0x0001 .. 0x7FFF (no NaNs here)
                     const uint32_t lo = m2[t].x, hi = m2[t].y;
                     const float v0 = static_cast<int16_t>(lo & 0xFFFF) > 0 ? v.x : 0.f, v1 = static_cast<int16_t>(lo >> 16) > 0 ? v.y : 0.f;
@@ -199,11 +212,11 @@ __global__ __launch_bounds__(kTowerThreads) void conv_tower_bwd_kernel(int n_, i
 
         // ---- conv2 data gradient: class (py, px), 100 pixels = 4 tiles, k-half kh (8 k-steps) --------------------
         {
-            f32x16 acc[4];
-            const T* base[4];
+            f32x16 acc[T2];
+            const T* base[T2];
 #pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                const int px = t * 32 + lp, pc = px < 100 ? px : 99;
+            for (int t = 0; t < T2; ++t) {
+                const int lpx = t * 32 + lp, pc = y_lo * 10 + (lpx < nc ? lpx : nc - 1);
                 // k-step 8 * kh + k: tap (p2, q2) = (kh, k / 4), channels 16 * (k % 4) + 8 * kg .. + 7 of dz2 at (y2 - p2, x2 - q2)
                 base[t] = sP2 + ((pc / 10 + 1 - kh) * 11 + pc % 10 + 1) * kTbPitch + kg * 8;
 #pragma unroll
@@ -219,9 +232,9 @@ __global__ __launch_bounds__(kTowerThreads) void conv_tower_bwd_kernel(int n_, i
 #pragma unroll
                 for (int u = 0; u < D; ++u) ring[u] = fetch(u);
 #pragma unroll
-                for (int step = 0; step < 32; ++step) {
+                for (int step = 0; step < 8 * T2; ++step) {
                     const V8 cur = ring[step % D];
-                    if (step + D < 32) ring[step % D] = fetch(step + D);
+                    if (step + D < 8 * T2) ring[step % D] = fetch(step + D);
                     mma_32x32x16(acc[step / 8], wf2[step % 8], cur);
                     __builtin_amdgcn_sched_barrier(0);
                 }
@@ -230,18 +243,18 @@ __global__ __launch_bounds__(kTowerThreads) void conv_tower_bwd_kernel(int n_, i
             float4* mine = sXchg + static_cast<size_t>(wave) * (4 * 64 * 2);
             const float4* theirs = sXchg + static_cast<size_t>(wave ^ 1) * (4 * 64 * 2);
 #pragma unroll
-            for (int t = 0; t < 4; ++t) {
+            for (int t = 0; t < T2; ++t) {
                 if (kh) tower_send_half<1>(mine + t * 128, acc[t], lane); else tower_send_half<0>(mine + t * 128, acc[t], lane);
             }
             __syncthreads();
 #pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                const int px = t * 32 + lp;
+            for (int t = 0; t < T2; ++t) {
+                const int lpx = t * 32 + lp, px = y_lo * 10 + lpx;
 #pragma unroll
                 for (int h = 0; h < 2; ++h) {
                     float4 v;
                     if (kh) v = tower_sum_half<1>(theirs + t * 128, acc[t], lane, h); else v = tower_sum_half<0>(theirs + t * 128, acc[t], lane, h);
-                    if (px < 100) {
+                    if (lpx < nc) {
                         const int pix = (2 * (px / 10) + (cls >> 1)) * 20 + 2 * (px % 10) + (cls & 1);
                         const uint32_t lo = m1[t][h].x, hi = m1[t][h].y;
                         store4<T>(dz1_ + (static_cast<size_t>(b) * 400 + pix) * 32 + 8 * (2 * kh + h) + 4 * kg,

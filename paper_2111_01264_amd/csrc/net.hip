@@ -189,7 +189,9 @@ static hipError_t raise_lds_limits()
         if (result == hipSuccess)
             result = hipFuncSetAttribute(reinterpret_cast<const void*>(conv_tower_kernel<true, 1>), hipFuncAttributeMaxDynamicSharedMemorySize, kTowerSmem);
         if (result == hipSuccess)
-            result = hipFuncSetAttribute(reinterpret_cast<const void*>(conv_tower_bwd_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, kTowerBwdSmem);
+            result = hipFuncSetAttribute(reinterpret_cast<const void*>(conv_tower_bwd_kernel<1>), hipFuncAttributeMaxDynamicSharedMemorySize, kTowerBwdSmem);
+        if (result == hipSuccess)
+            result = hipFuncSetAttribute(reinterpret_cast<const void*>(conv_tower_bwd_kernel<5>), hipFuncAttributeMaxDynamicSharedMemorySize, kTowerBwdSmem);
     });
     return result;
 }
@@ -479,11 +481,17 @@ static int train_impl(dqn_ctx* c, const uint8_t* s, const int32_t* a, const floa
         ta.dz3 = dz3; ta.act2 = act2; ta.act1 = act1; ta.w3d = bsh + kBshW3; ta.w2d = bsh + kBshW2;
         ta.dz2 = dz2; ta.dz1 = dz1; ta.n = B;
         DQN_HIP(raise_lds_limits());
-        const int grid = B < c->num_cus ? B : c->num_cus;
-        ta.per = (B + grid - 1) / grid;
+        // small minibatches: five workgroups per sample (a fifth of its rows each) while that fits the chip
+        const bool fifths = 5 * B <= c->num_cus;
+        const int grid = fifths ? 5 * B : (B < c->num_cus ? B : c->num_cus);
+        ta.per = fifths ? 1 : (B + grid - 1) / grid;
         const ProfPair pr = prof_pair(c, K_TOWER_BWD);
-        launch_timed(conv_tower_bwd_kernel, dim3(grid), dim3(kTowerThreads), kTowerBwdSmem, st, pr.begin, pr.end, ta.n, ta.per, ta.dz3, ta.w3d, ta.w2d, ta.act2,
-                     ta.act1, ta.dz2, ta.dz1);
+        if (fifths)
+            launch_timed(conv_tower_bwd_kernel<5>, dim3(grid), dim3(kTowerThreads), kTowerBwdSmem, st, pr.begin, pr.end, ta.n, ta.per, ta.dz3, ta.w3d, ta.w2d,
+                         ta.act2, ta.act1, ta.dz2, ta.dz1);
+        else
+            launch_timed(conv_tower_bwd_kernel<1>, dim3(grid), dim3(kTowerThreads), kTowerBwdSmem, st, pr.begin, pr.end, ta.n, ta.per, ta.dz3, ta.w3d, ta.w2d,
+                         ta.act2, ta.act1, ta.dz2, ta.dz1);
         DQN_LAUNCH_CHECK();
     } else {
         {   // conv3 data gradient through conv2's ReLU
