@@ -139,7 +139,8 @@ static_assert(kTowerXBytes <= kTowerXchgBytes, "the state buffer overlays the ex
 // takes its seven microseconds on one compute unit; in thirds the chain is conv1 in one pass instead of two (at most eight
 // pixel tiles for eight wavefronts), two pixel tiles of conv2 instead of three and one of conv3 instead of two.  Every
 // output element is computed by the same instructions in the same order as with PARTS = 1 (rows that two parts both need
-// are computed twice), so the results are equal bit for bit.
+// are computed twice), so the results are equal bit for bit.  PARTS = 7, for a single round of samplers: one output row of
+// conv3 per workgroup (three rows of conv2: one pixel tile, eight rows of conv1: five tiles).
 template <bool DESC, int PARTS>
 __global__ __launch_bounds__(kTowerThreads) void conv_tower_kernel(int n_, int groups_, int per_, int tower_blocks_, const uint8_t* x0_,
                                                                    const uint8_t* x1_, const int32_t* desc_, const uint8_t* ring_,
@@ -166,17 +167,20 @@ __global__ __launch_bounds__(kTowerThreads) void conv_tower_kernel(int n_, int g
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lp = lane & 31, kg = lane >> 5;
     const int nt = wave >> 2, kq = wave & 3;
-    static_assert(PARTS == 1 || PARTS == 3, "whole samples, or thirds");
+    static_assert(PARTS == 1 || PARTS == 3 || PARTS == 7, "whole samples, thirds, or sevenths");
     const int total = n_ * groups_;
     // PARTS = 3: workgroup j runs part j % 3 of item j / 3 (the host launches 3 * total workgroups, per_ = 1)
     const int part = PARTS == 1 ? 0 : static_cast<int>(blockIdx.x % PARTS);
     const int first = PARTS == 1 ? blockIdx.x * per_ : static_cast<int>(blockIdx.x / PARTS), last = PARTS == 1 ? min(total, first + per_) : min(total, first + 1);
     if (first >= last) return;
     // first row and pixel count of this part in each layer's output (whole sample: all of it)
-    const int r1_lo = PARTS == 1 ? 0 : (part == 0 ? 0 : part == 1 ? 6 : 10), n1 = PARTS == 1 ? 400 : (part == 0 ? 240 : 200);
-    const int r2_lo = PARTS == 1 ? 0 : (part == 0 ? 0 : part == 1 ? 3 : 5), n2 = PARTS == 1 ? 81 : (part == 0 ? 45 : 36);
-    const int r3_lo = PARTS == 1 ? 0 : (part == 0 ? 0 : part == 1 ? 3 : 5), n3 = PARTS == 1 ? 49 : (part == 0 ? 21 : 14);
-    constexpr int T2 = PARTS == 1 ? 3 : 2, T3 = PARTS == 1 ? 2 : 1;   // pixel tiles of conv2 / conv3 per wavefront
+    // (conv3 rows [r, r') need conv2 rows [r, r' + 2), and those need conv1 rows [2 r, 2 r' + 6))
+    const int r3_lo = PARTS == 1 ? 0 : PARTS == 7 ? part : (part == 0 ? 0 : part == 1 ? 3 : 5);
+    const int r2_lo = r3_lo, r1_lo = 2 * r3_lo;
+    const int n3 = PARTS == 1 ? 49 : PARTS == 7 ? 7 : (part == 0 ? 21 : 14);
+    const int n2 = PARTS == 1 ? 81 : PARTS == 7 ? 27 : (part == 0 ? 45 : 36);
+    const int n1 = PARTS == 1 ? 400 : PARTS == 7 ? 160 : (part == 0 ? 240 : 200);
+    constexpr int T2 = PARTS == 1 ? 3 : PARTS == 3 ? 2 : 1, T3 = PARTS == 1 ? 2 : 1;   // pixel tiles of conv2 / conv3 per wavefront
 
     // The state of item (g_, b_), 16 bytes per lane and load (the last load is clamped, not predicated);
     // named registers rather than an array, which the compiler would keep in scratch memory.  With a descriptor table
@@ -375,10 +379,11 @@ __global__ __launch_bounds__(kTowerThreads) void conv_tower_kernel(int n_, int g
                     const V8 cur = ring[step % D];
                     if (step + D < 8 * T2) ring[step % D] = fetch(step + D);
                     mma_32x32x16(acc[step / 8], wf2[step % 8], cur);
-                    // conv3's fragments: nine requests spread over the stream (every other step of 24, every step of 16)
-                    constexpr int W3_FIRST = T2 == 3 ? 4 : 3, W3_EVERY = T2 == 3 ? 2 : 1;
+                    // conv3's fragments: nine requests spread over the stream (every other step of 24, every step of 16 or 8)
+                    constexpr int W3_FIRST = T2 == 3 ? 4 : T2 == 2 ? 3 : 0, W3_EVERY = T2 == 3 ? 2 : 1;
                     if (new_group && step >= W3_FIRST && (step - W3_FIRST) % W3_EVERY == 0 && (step - W3_FIRST) / W3_EVERY < 9)
                         wf3[(step - W3_FIRST) / W3_EVERY] = *reinterpret_cast<const V8*>(p3 + ((step - W3_FIRST) / W3_EVERY) * 512);
+                    if (T2 == 1 && new_group && step == 7) wf3[8] = *reinterpret_cast<const V8*>(p3 + 8 * 512);   // eight steps, nine fragments
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }

@@ -187,6 +187,8 @@ static hipError_t raise_lds_limits()
         if (result == hipSuccess)
             result = hipFuncSetAttribute(reinterpret_cast<const void*>(conv_tower_kernel<false, 3>), hipFuncAttributeMaxDynamicSharedMemorySize, kTowerSmem);
         if (result == hipSuccess)
+            result = hipFuncSetAttribute(reinterpret_cast<const void*>(conv_tower_kernel<false, 7>), hipFuncAttributeMaxDynamicSharedMemorySize, kTowerSmem);
+        if (result == hipSuccess)
             result = hipFuncSetAttribute(reinterpret_cast<const void*>(conv_tower_kernel<true, 1>), hipFuncAttributeMaxDynamicSharedMemorySize, kTowerSmem);
         if (result == hipSuccess)
             result = hipFuncSetAttribute(reinterpret_cast<const void*>(conv_tower_bwd_kernel<1>), hipFuncAttributeMaxDynamicSharedMemorySize, kTowerBwdSmem);
@@ -283,12 +285,13 @@ static int forward_to_fc1(dqn_ctx* c, hipStream_t st, Workspace& ws, int groups,
         a.n = n; a.groups = groups;
         if (src) { a.desc = src->desc; a.ring = src->ring; a.s_out = src->s_out; }
         DQN_HIP(raise_lds_limits());
-        // Few items (a round of synchronized samplers, a minibatch of 32): three workgroups per item, one third of its
-        // output rows each, while that still fits the chip -- the chain of layers of one sample is what the launch waits for
+        // Few items (a round of synchronized samplers, a minibatch of 32): seven or three workgroups per item, a seventh or
+        // a third of its output rows each, while that still fits the chip -- the chain of layers of one sample is what the
+        // launch waits for
         const int total = n * groups;
-        const bool thirds = !a.desc && 3 * total <= c->num_cus;
-        const int grid = thirds ? 3 * total : (total < c->num_cus ? total : c->num_cus);
-        a.per = thirds ? 1 : (total + grid - 1) / grid;
+        const int parts = a.desc ? 1 : (7 * total <= c->num_cus ? 7 : (3 * total <= c->num_cus ? 3 : 1));
+        const int grid = parts > 1 ? parts * total : (total < c->num_cus ? total : c->num_cus);
+        a.per = parts > 1 ? 1 : (total + grid - 1) / grid;
         a.tower_blocks = grid;
         a.push.L = 0;
         if (push) a.push = *push;
@@ -296,7 +299,8 @@ static int forward_to_fc1(dqn_ctx* c, hipStream_t st, Workspace& ws, int groups,
         // (the leading arguments repeat the fields a workgroup needs first: see the kernel)
         const dim3 g3(grid + a.push.L), b3(kTowerThreads);
         if (a.desc) launch_timed(conv_tower_kernel<true, 1>, g3, b3, kTowerSmem, st, pr.begin, pr.end, a.n, a.groups, a.per, a.tower_blocks, a.x[0], a.x[1], a.desc, a.ring, a.w1[0], a);
-        else if (thirds) launch_timed(conv_tower_kernel<false, 3>, g3, b3, kTowerSmem, st, pr.begin, pr.end, a.n, a.groups, a.per, a.tower_blocks, a.x[0], a.x[1], a.desc, a.ring, a.w1[0], a);
+        else if (parts == 7) launch_timed(conv_tower_kernel<false, 7>, g3, b3, kTowerSmem, st, pr.begin, pr.end, a.n, a.groups, a.per, a.tower_blocks, a.x[0], a.x[1], a.desc, a.ring, a.w1[0], a);
+        else if (parts == 3) launch_timed(conv_tower_kernel<false, 3>, g3, b3, kTowerSmem, st, pr.begin, pr.end, a.n, a.groups, a.per, a.tower_blocks, a.x[0], a.x[1], a.desc, a.ring, a.w1[0], a);
         else launch_timed(conv_tower_kernel<false, 1>, g3, b3, kTowerSmem, st, pr.begin, pr.end, a.n, a.groups, a.per, a.tower_blocks, a.x[0], a.x[1], a.desc, a.ring, a.w1[0], a);
         DQN_LAUNCH_CHECK();
     } else {
