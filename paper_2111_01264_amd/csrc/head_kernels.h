@@ -270,14 +270,28 @@ __global__ __launch_bounds__(256) void head_fwd_kernel(const float* partial_, in
     // Tail: wavefront 0, 32 lanes per row (kHeadRows = 2), lane k owns action k.  argmax with the lowest index
     // among equal values (the tie rule of the greedy policy, Section 2.1), as a butterfly over the 32 lanes.
     static_assert(kHeadRows == 2 && kMaxActions <= 32, "tail layout: one wavefront, 32 lanes per row");
-    auto argmax_lowest = [&](float v, int k) {   // every lane of the row returns the winner
+    // "Better" is a total order on (value, index), so the pairs may meet in any tree: inside a row of sixteen lanes through
+    // the lane-permuting moves of the vector unit (neighbours, pairs, mirrored halves of eight, mirrored sixteen -- a few
+    // cycles each), across the two sixteens through one cross-lane exchange (ten of those in a row were 0.6 us of a 3 us kernel).
+    auto argmax_lowest = [&](float v, int k) {   // lanes 0 .. 15 of the row return the winner
         int best = k;
-#pragma unroll
-        for (int m = 16; m >= 1; m >>= 1) {
-            const float ov = __shfl_xor(v, m, 32);
-            const int ob = __shfl_xor(best, m, 32);
+        auto meet = [&](float ov, int ob) {
             if (ov > v || (ov == v && ob < best)) { v = ov; best = ob; }
-        }
+        };
+#define DQN_ARGMAX_DPP(ctrl)                                                                                              \
+        meet(__builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), ctrl, 0xF, 0xF, false)), \
+             __builtin_amdgcn_update_dpp(0, best, ctrl, 0xF, 0xF, false))
+        DQN_ARGMAX_DPP(0xB1);    // quad_perm [1, 0, 3, 2]: lane ^ 1
+        DQN_ARGMAX_DPP(0x4E);    // quad_perm [2, 3, 0, 1]: lane ^ 2
+        DQN_ARGMAX_DPP(0x141);   // row_half_mirror: lane i of eight <-> 7 - i (the other quad)
+        DQN_ARGMAX_DPP(0x140);   // row_mirror: lane i of sixteen <-> 15 - i (the other eight)
+#undef DQN_ARGMAX_DPP
+        // the other sixteen of the row: its result is read from its first lane (16, or 48 for the second row) -- a scalar
+        // broadcast, where a cross-lane exchange costs ten times as much.  Only the FIRST sixteen lanes of a row end up with
+        // the row's winner; the callers use lane 0 of the row.
+        const int hv = lane < 32 ? __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 16) : __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 48);
+        const int hb = lane < 32 ? __builtin_amdgcn_readlane(best, 16) : __builtin_amdgcn_readlane(best, 48);
+        meet(__builtin_bit_cast(float, hv), hb);
         return best;
     };
     const int trow = lane >> 5, tk = lane & 31;    // tail row / action of this lane (wavefront 0 only)
