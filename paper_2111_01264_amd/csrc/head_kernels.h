@@ -223,7 +223,12 @@ __global__ __launch_bounds__(256) void head_fwd_kernel(const float* partial_, in
                     float w[4];
                     load4<T>(static_cast<const T*>(w2_0_) + static_cast<size_t>(act_taken) * 512 + hf0, w);
                     w2row = make_float4(w[0], w[1], w[2], w[3]);
-                } else draw = philox_draw(a.seed, kTagAct, a.act_step, static_cast<uint32_t>(row0 + trow_));
+                } else {
+                    draw = philox_draw(a.seed, kTagAct, a.act_step, static_cast<uint32_t>(row0 + trow_));
+                    // computed HERE, under the slices' latency (left alone, the compiler moves the ten rounds into the
+                    // tail, where only lane 0 of a row uses them and nothing hides them)
+                    asm volatile("" :: "v"(draw.x[0]), "v"(draw.x[1]));
+                }
             }
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
