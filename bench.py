@@ -72,12 +72,12 @@ _TOWER_BWD_SRC = (_C + "conv_tower_bwd.h", _C + "conv_tower.h", _C + "conv_ws.h"
 TRAFFIC = {
     ("rmsprop", 32, "bf16"): (66.16e6, _RMS_SRC, "04b098e8e5afd762a19a4e8bad05d9ea95f77a45", "profiles/hbm_traffic_b32.txt"),
     ("wgrad_all", 32, "bf16"): (25.63e6, _WG_SRC, "0a99a0aeb00340b719a0eaf1e2dca707da54d3b6", "profiles/hbm_traffic_b32.txt"),
-    ("conv_tower", 32, "bf16"): (10.26e6, _TOWER_SRC, "445bb1c4f94e9c05b280d543826bbcfc38a745fc", "profiles/hbm_traffic_b32.txt"),
-    ("conv_tower_bwd", 32, "bf16"): (4.78e6, _TOWER_BWD_SRC, "05dd299e14a023dbd2c78cd76c39e5e67c6d70b6", "profiles/hbm_traffic_b32.txt"),
+    ("conv_tower", 32, "bf16"): (10.26e6, _TOWER_SRC, "b0874bb25d0a1959b7edaf5b96e267f8279aa4cd", "profiles/hbm_traffic_b32.txt"),
+    ("conv_tower_bwd", 32, "bf16"): (4.78e6, _TOWER_BWD_SRC, "bb4819da911de89f68019999026c0078f3c48051", "profiles/hbm_traffic_b32.txt"),
     ("rmsprop", 256, "bf16"): (71.34e6, _RMS_SRC, "04b098e8e5afd762a19a4e8bad05d9ea95f77a45", "profiles/hbm_traffic_b256.txt"),
     ("wgrad_all", 256, "bf16"): (85.73e6, _WG_SRC, "0a99a0aeb00340b719a0eaf1e2dca707da54d3b6", "profiles/hbm_traffic_b256.txt"),
-    ("conv_tower", 256, "bf16"): (24.22e6, _TOWER_SRC, "445bb1c4f94e9c05b280d543826bbcfc38a745fc", "profiles/hbm_traffic_b256.txt"),
-    ("conv_tower_bwd", 256, "bf16"): (21.25e6, _TOWER_BWD_SRC, "05dd299e14a023dbd2c78cd76c39e5e67c6d70b6", "profiles/hbm_traffic_b256.txt"),
+    ("conv_tower", 256, "bf16"): (24.22e6, _TOWER_SRC, "b0874bb25d0a1959b7edaf5b96e267f8279aa4cd", "profiles/hbm_traffic_b256.txt"),
+    ("conv_tower_bwd", 256, "bf16"): (21.25e6, _TOWER_BWD_SRC, "bb4819da911de89f68019999026c0078f3c48051", "profiles/hbm_traffic_b256.txt"),
 }
 
 

@@ -31,6 +31,8 @@
 //   The four k-quarters of a channel tile meet through LDS: wavefront (nt, q) finishes accumulator rows
 //   4q .. 4q + 3 of each 16 and receives them from the other three, added in k order.
 // act1 / act2 also go to global memory when the backward pass will need them.
+// With few items (an act step, a small minibatch) an item is one band of a sample's output rows instead of a whole
+// sample, and one workgroup runs one item: see PARTS at the kernel.
 #pragma once
 #include <type_traits>
 
